@@ -1,0 +1,195 @@
+/*
+ * po.h -- C ABI of libpo: single-output-token ("prefill-only") transformer inference on
+ * one AMD MI355X (gfx950).
+ *
+ * The operation (paper Sections 1, 2.2, 4): a request is a token sequence plus a short
+ * list of acceptable output tokens; the engine runs ONLY the prefill phase, in one
+ * forward pass, and returns the next-token distribution at the last position, either
+ * as logits over the vocabulary or as log-probabilities restricted to the acceptable
+ * tokens (whose probabilities sum to 1).  Because nothing is decoded, only the K/V of
+ * the layer currently being computed is kept (abstract, Section 1); the position-wise
+ * layers run chunk by chunk over tokens so their intermediates stay small while
+ * attention runs over the whole sequence in one call ("hybrid prefilling", Section 4.2);
+ * chunk outputs are written straight into preallocated buffers and same-shape outputs
+ * overwrite their inputs (Section 4.3).  Requests run one at a time (Section 6.1).
+ *
+ * Model: a Llama-style pre-norm decoder (RMSNorm, rotary embedding with the rotate-half
+ * pairing (i, i + head_dim/2) and angle pos * theta^(-2i/head_dim), causal grouped-query
+ * attention with query head h reading KV head h / (n_q_heads / n_kv_heads), SwiGLU MLP,
+ * untied LM head, optional QKV bias).  Position of token i is i.
+ *
+ * Conventions
+ *   - every call returns a po_status; nothing is written to outputs on error.
+ *   - pointers are HOST pointers unless the name starts with dev_.
+ *   - the caller owns every buffer it passes, including the two device arenas
+ *     (dev_weights, dev_workspace) which must stay alive and untouched by others for
+ *     the life of the context; the library owns only the po_ctx.
+ *   - all device work of a context is issued on the HIP stream given to po_create;
+ *     po_prefill returns after that stream has been synchronised.
+ *   - a context is not re-entrant: one call at a time per context.
+ *   - weights are given in the checkpoint layout [out_features, in_features], row-major,
+ *     in the model's storage dtype (float for PO_F32; bf16 bit patterns for PO_BF16).
+ */
+#ifndef PO_H_
+#define PO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PO_OK = 0,
+    PO_ERR_INVALID_ARG = 1,        /* NULL pointer, non-positive size, bad enum value      */
+    PO_ERR_BAD_CONFIG = 2,         /* model shape the kernels do not support               */
+    PO_ERR_NOT_LOADED = 3,         /* po_prefill before every tensor was loaded            */
+    PO_ERR_TOO_LONG = 4,           /* len > max_input_len given to po_create               */
+    PO_ERR_TOKEN_RANGE = 5,        /* a token or candidate id outside [0, vocab_size)      */
+    PO_ERR_WORKSPACE_TOO_SMALL = 6,/* an arena smaller than po_workspace_bytes reports     */
+    PO_ERR_OOM = 7,                /* host allocation failed                               */
+    PO_ERR_DEVICE = 8              /* a HIP call failed (message via po_last_device_error) */
+} po_status;
+
+typedef enum { PO_F32 = 0, PO_BF16 = 1 } po_dtype;
+
+/* Tensor kinds for po_load_tensor.  Per-layer kinds take layer in [0, n_layers);
+ * global kinds (EMBED, FINAL_NORM, LM_HEAD) take layer = -1. */
+typedef enum {
+    PO_T_EMBED = 0,       /* [vocab, d_model]                    */
+    PO_T_ATTN_NORM = 1,   /* [d_model]   gain of the norm before attention */
+    PO_T_WQ = 2,          /* [n_q_heads*head_dim, d_model]       */
+    PO_T_WK = 3,          /* [n_kv_heads*head_dim, d_model]      */
+    PO_T_WV = 4,          /* [n_kv_heads*head_dim, d_model]      */
+    PO_T_BQ = 5,          /* [n_q_heads*head_dim]   (qkv_bias=1) */
+    PO_T_BK = 6,          /* [n_kv_heads*head_dim]  (qkv_bias=1) */
+    PO_T_BV = 7,          /* [n_kv_heads*head_dim]  (qkv_bias=1) */
+    PO_T_WO = 8,          /* [d_model, n_q_heads*head_dim]       */
+    PO_T_MLP_NORM = 9,    /* [d_model]   gain of the norm before the MLP */
+    PO_T_WG = 10,         /* [ffn_dim, d_model]   gate projection */
+    PO_T_WU = 11,         /* [ffn_dim, d_model]   up projection   */
+    PO_T_WD = 12,         /* [d_model, ffn_dim]   down projection */
+    PO_T_FINAL_NORM = 13, /* [d_model]                            */
+    PO_T_LM_HEAD = 14,    /* [vocab, d_model]                     */
+    PO_T_COUNT = 15
+} po_tensor_kind;
+
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab_size;
+    float rms_eps, rope_theta;
+    int32_t dtype;     /* po_dtype: storage and activation type; accumulation is fp32 */
+    int32_t qkv_bias;  /* 0 | 1 */
+} po_model_config;
+
+typedef struct {
+    double last_prefill_ms;       /* device time of the last po_prefill (HIP events)      */
+    double last_attention_ms;     /* ... of which attention kernels (0 unless timing on)  */
+    double last_linear_ms;        /* ... of which GEMM kernels      (0 unless timing on)  */
+    uint64_t weights_bytes;       /* size of the weight arena in use                      */
+    uint64_t workspace_bytes;     /* size of the activation arena in use (peak; static)   */
+    int64_t last_len;             /* tokens in the last request                           */
+} po_stats;
+
+typedef struct po_ctx po_ctx;
+
+/* Sizes of the two device arenas for a model, a maximum input length and a chunk size
+ * (Section 3: the user declares the maximum input length up front and memory is sized
+ * from it).  Closed form; needs no GPU.  workspace = residual stream + Q/O + ONE layer
+ * of K/V + one chunk of position-wise intermediates + rotary table + logits. */
+po_status po_workspace_bytes(const po_model_config* cfg, int64_t max_input_len, int32_t mlp_chunk,
+                             size_t* weights_bytes, size_t* workspace_bytes);
+
+/* Creates a context over caller-provided device memory (256-byte aligned) and a HIP
+ * stream (hipStream_t passed as void*; NULL = the default stream).  mlp_chunk is the
+ * number of tokens per chunk of the position-wise layers (Section 4.2), >= 1. */
+po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t mlp_chunk,
+                    void* dev_weights, size_t weights_bytes,
+                    void* dev_workspace, size_t workspace_bytes,
+                    void* hip_stream, po_ctx** out);
+
+/* Copies one tensor from host memory into the weight arena (re-laid out for the
+ * kernels).  bytes must equal the tensor's size in the model dtype.  Synchronous. */
+po_status po_load_tensor(po_ctx* ctx, int32_t tensor_kind, int32_t layer,
+                         const void* host_data, size_t bytes);
+
+/* 1 when every tensor the configuration needs has been loaded, else 0. */
+int32_t po_is_loaded(const po_ctx* ctx);
+
+/* One prefill-only request.  tokens[len] int32 in [0, vocab); cand_ids[n_cand] are the
+ * acceptable tokens (may be NULL/0).  out_logits (fp32 [vocab]) and out_cand_logprobs
+ * (fp32 [n_cand], log-softmax restricted to the candidates) may each be NULL.  Ranges
+ * are validated on the host before any launch. */
+po_status po_prefill(po_ctx* ctx, const int32_t* tokens, int64_t len,
+                     const int32_t* cand_ids, int32_t n_cand,
+                     float* out_logits, float* out_cand_logprobs);
+
+/* n_req independent requests run one after another (Section 6.1: no batching);
+ * tokens_concat holds them back to back, lens[n_req] their lengths.  Outputs are
+ * [n_req, vocab] and [n_req, n_cand].  Bit-identical to n_req po_prefill calls. */
+po_status po_prefill_batch(po_ctx* ctx, const int32_t* tokens_concat, const int64_t* lens,
+                           int32_t n_req, const int32_t* cand_ids, int32_t n_cand,
+                           float* out_logits, float* out_cand_logprobs);
+
+/* When on, po_prefill brackets attention and GEMM launches with HIP events so that
+ * po_get_stats can split the time (adds event overhead; off by default). */
+po_status po_set_phase_timing(po_ctx* ctx, int32_t on);
+
+po_status po_get_stats(const po_ctx* ctx, po_stats* out);
+
+void po_destroy(po_ctx* ctx);
+
+const char* po_strerror(po_status s);
+
+/* Text of the last HIP error seen by this thread ("" if none). */
+const char* po_last_device_error(void);
+
+/* ------------------------------------------------------------------------------------
+ * Single-kernel entry points.  Each runs ONE step of the path on DEVICE buffers the
+ * caller owns, asynchronously on `hip_stream`, so a step can be checked against its
+ * definition and timed at the exact shapes the full path uses.  dtype is a po_dtype
+ * (activation and weight storage; all reductions accumulate in fp32).
+ * ---------------------------------------------------------------------------------- */
+
+/* y[r, :] = x[r, :] * rsqrt(mean(x[r,:]^2) + eps) * g   (rows x d). */
+po_status po_op_rmsnorm(int32_t dtype, const void* dev_x, const void* dev_g, void* dev_y,
+                        int64_t rows, int32_t d, float eps, void* hip_stream);
+
+/* Position-wise linear layer of Section 4: C[M, N] = A[M, K] * W[N, K]^T (+ residual).
+ * dev_residual may be NULL, or a [M, N] tensor added before the store (may alias dev_c). */
+po_status po_op_linear(int32_t dtype, const void* dev_a, const void* dev_w, void* dev_c,
+                       const void* dev_residual, int64_t M, int32_t N, int32_t K, void* hip_stream);
+
+/* Gate/up projection with the SiLU-multiply of the MLP (Section 4.1's MLP figure):
+ * H[M, F] = silu(A Wg^T) * (A Wu^T); dev_wgu is [2F, K] in the library's interleaved
+ * order (see po_op_pack_gate_up); dev_scratch must hold M*2F elements for PO_F32 and may
+ * be NULL for PO_BF16. */
+po_status po_op_gate_up_silu(int32_t dtype, const void* dev_a, const void* dev_wgu, void* dev_h,
+                             void* dev_scratch, int64_t M, int32_t F, int32_t K, void* hip_stream);
+
+/* Packs Wg [F, K] and Wu [F, K] (device) into the interleaved [2F, K] order the gate/up
+ * kernel reads. */
+po_status po_op_pack_gate_up(int32_t dtype, const void* dev_wg, const void* dev_wu, void* dev_wgu,
+                             int32_t F, int32_t K, void* hip_stream);
+
+/* Causal grouped-query attention over one whole sequence (Section 4.2: attention is not
+ * chunked).  q [N, Hq, hd] (already rotated), k [N, Hkv, hd] (rotated), v [N, Hkv, hd];
+ * o [N, Hq, hd] may alias q.  dev_scratch: PO_BF16 needs Hkv*hd*round_up(N,64) elements
+ * (a transposed copy of V); PO_F32 needs none (NULL). */
+po_status po_op_attention(int32_t dtype, const void* dev_q, const void* dev_k, const void* dev_v,
+                          void* dev_o, void* dev_scratch, int64_t N, int32_t n_q_heads,
+                          int32_t n_kv_heads, int32_t head_dim, void* hip_stream);
+
+/* Rotary embedding in place on x [N, H, hd] for positions 0..N-1 (angles formed in
+ * double precision). */
+po_status po_op_rope(int32_t dtype, void* dev_x, int64_t N, int32_t n_heads, int32_t head_dim,
+                     float theta, void* hip_stream);
+
+/* Last-position LM head: logits[V] = x[d] . W[V, d]^T  (fp32 output). */
+po_status po_op_lm_head(int32_t dtype, const void* dev_x, const void* dev_w, float* dev_logits,
+                        int32_t V, int32_t d, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PO_H_ */

@@ -1,0 +1,288 @@
+"""ctypes binding over libpo.so: the same names as include/po.h, argument marshalling only.
+
+PyTorch appears here solely as the provider of device memory (the two arenas) and of the
+HIP stream handle; every step of the path runs inside libpo's own kernels.  If libpo.so is
+missing, loading fails with an error: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpo.so")
+
+PO_OK = 0
+PO_ERR_INVALID_ARG = 1
+PO_ERR_BAD_CONFIG = 2
+PO_ERR_NOT_LOADED = 3
+PO_ERR_TOO_LONG = 4
+PO_ERR_TOKEN_RANGE = 5
+PO_ERR_WORKSPACE_TOO_SMALL = 6
+PO_ERR_OOM = 7
+PO_ERR_DEVICE = 8
+
+PO_F32, PO_BF16 = 0, 1
+
+EXPORTS = [
+    "po_workspace_bytes", "po_create", "po_load_tensor", "po_is_loaded", "po_prefill",
+    "po_prefill_batch", "po_set_phase_timing", "po_get_stats", "po_destroy", "po_strerror",
+    "po_last_device_error", "po_op_rmsnorm", "po_op_linear", "po_op_gate_up_silu",
+    "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head",
+]
+
+
+class ModelConfigC(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn_dim", C.c_int32),
+                ("vocab_size", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float),
+                ("dtype", C.c_int32), ("qkv_bias", C.c_int32)]
+
+
+class StatsC(C.Structure):
+    _fields_ = [("last_prefill_ms", C.c_double), ("last_attention_ms", C.c_double),
+                ("last_linear_ms", C.c_double), ("weights_bytes", C.c_uint64),
+                ("workspace_bytes", C.c_uint64), ("last_len", C.c_int64)]
+
+
+class PoError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(what)
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libpo.so (built in-tree by paper_2505_07203_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it first (python -m paper_2505_07203_amd.build); "
+            "there is no fallback implementation")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
+    L.po_workspace_bytes.argtypes = [C.POINTER(ModelConfigC), i64, i32, C.POINTER(sz), C.POINTER(sz)]
+    L.po_create.argtypes = [C.POINTER(ModelConfigC), i64, i32, vp, sz, vp, sz, vp, C.POINTER(vp)]
+    L.po_load_tensor.argtypes = [vp, i32, i32, vp, sz]
+    L.po_is_loaded.argtypes = [vp]
+    L.po_prefill.argtypes = [vp, vp, i64, vp, i32, vp, vp]
+    L.po_prefill_batch.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
+    L.po_set_phase_timing.argtypes = [vp, i32]
+    L.po_get_stats.argtypes = [vp, C.POINTER(StatsC)]
+    L.po_destroy.argtypes = [vp]
+    L.po_destroy.restype = None
+    L.po_strerror.argtypes = [i32]
+    L.po_strerror.restype = C.c_char_p
+    L.po_last_device_error.argtypes = []
+    L.po_last_device_error.restype = C.c_char_p
+    L.po_op_rmsnorm.argtypes = [i32, vp, vp, vp, i64, i32, f32, vp]
+    L.po_op_linear.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, vp]
+    L.po_op_gate_up_silu.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, vp]
+    L.po_op_pack_gate_up.argtypes = [i32, vp, vp, vp, i32, i32, vp]
+    L.po_op_attention.argtypes = [i32, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
+    L.po_op_rope.argtypes = [i32, vp, i64, i32, i32, f32, vp]
+    L.po_op_lm_head.argtypes = [i32, vp, vp, vp, i32, i32, vp]
+    for name in EXPORTS:
+        if name not in ("po_destroy", "po_strerror", "po_last_device_error"):
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def check(status: int) -> None:
+    if status != PO_OK:
+        L = lib()
+        msg = L.po_strerror(status).decode()
+        if status == PO_ERR_DEVICE:
+            msg += ": " + L.po_last_device_error().decode()
+        raise PoError(status, f"libpo: {msg} (status {status})")
+
+
+def config_c(cfg) -> ModelConfigC:
+    return ModelConfigC(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                        cfg.ffn_dim, cfg.vocab_size, cfg.rms_eps, cfg.rope_theta, cfg.dtype,
+                        cfg.qkv_bias)
+
+
+def po_workspace_bytes(cfg, max_input_len: int, mlp_chunk: int):
+    """-> (weights_bytes, workspace_bytes); closed form, needs no GPU."""
+    w, s = C.c_size_t(0), C.c_size_t(0)
+    cc = config_c(cfg)
+    check(lib().po_workspace_bytes(C.byref(cc), max_input_len, mlp_chunk, C.byref(w), C.byref(s)))
+    return w.value, s.value
+
+
+def _host_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class Context:
+    """A po_ctx over two torch-allocated device arenas on the current stream."""
+
+    def __init__(self, cfg, max_input_len: int, mlp_chunk: int, device: str = "cuda:0"):
+        import torch
+        self.cfg = cfg
+        self.max_input_len = int(max_input_len)
+        self.mlp_chunk = int(mlp_chunk)
+        wb, sb = po_workspace_bytes(cfg, max_input_len, mlp_chunk)
+        self.weights_bytes, self.workspace_bytes = wb, sb
+        self._torch = torch
+        self.device = torch.device(device)
+        # plumbing only: raw byte arenas and the stream handle
+        self._w = torch.empty(wb, dtype=torch.uint8, device=self.device)
+        self._ws = torch.empty(sb, dtype=torch.uint8, device=self.device)
+        with torch.cuda.device(self.device):
+            self.stream = torch.cuda.current_stream().cuda_stream
+        h = C.c_void_p()
+        cc = config_c(cfg)
+        check(lib().po_create(C.byref(cc), self.max_input_len, self.mlp_chunk, self._w.data_ptr(), wb,
+                              self._ws.data_ptr(), sb, self.stream, C.byref(h)))
+        self._h = h
+
+    # -- same names as the C ABI ---------------------------------------------------------
+    def po_load_tensor(self, kind: int, layer: int, host: np.ndarray) -> None:
+        a = np.ascontiguousarray(host)
+        check(lib().po_load_tensor(self._h, kind, layer, _host_ptr(a), a.nbytes))
+
+    def po_is_loaded(self) -> bool:
+        return bool(lib().po_is_loaded(self._h))
+
+    def po_prefill(self, tokens: np.ndarray, cand: Optional[Sequence[int]] = None,
+                   want_logits: bool = True):
+        """-> (logits float32[V] or None, candidate log-probs float32[n_cand] or None)"""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        n_cand = 0 if cand is None else len(cand)
+        cand_a = None if cand is None else np.ascontiguousarray(cand, dtype=np.int32)
+        logits = np.empty(self.cfg.vocab_size, dtype=np.float32) if want_logits else None
+        lp = np.empty(n_cand, dtype=np.float32) if n_cand else None
+        check(lib().po_prefill(self._h, _host_ptr(tok), tok.shape[0], _host_ptr(cand_a), n_cand,
+                               _host_ptr(logits), _host_ptr(lp)))
+        return logits, lp
+
+    def po_prefill_batch(self, token_lists: Sequence[np.ndarray], cand: Optional[Sequence[int]] = None,
+                         want_logits: bool = False):
+        lens = np.array([len(t) for t in token_lists], dtype=np.int64)
+        tok = np.ascontiguousarray(np.concatenate([np.asarray(t, dtype=np.int32) for t in token_lists]))
+        n_req = len(token_lists)
+        n_cand = 0 if cand is None else len(cand)
+        cand_a = None if cand is None else np.ascontiguousarray(cand, dtype=np.int32)
+        logits = np.empty((n_req, self.cfg.vocab_size), dtype=np.float32) if want_logits else None
+        lp = np.empty((n_req, n_cand), dtype=np.float32) if n_cand else None
+        check(lib().po_prefill_batch(self._h, _host_ptr(tok), _host_ptr(lens), n_req, _host_ptr(cand_a),
+                                     n_cand, _host_ptr(logits), _host_ptr(lp)))
+        return logits, lp
+
+    def po_set_phase_timing(self, on: bool) -> None:
+        check(lib().po_set_phase_timing(self._h, 1 if on else 0))
+
+    def po_get_stats(self) -> dict:
+        s = StatsC()
+        check(lib().po_get_stats(self._h, C.byref(s)))
+        return {n: getattr(s, n) for n, _ in StatsC._fields_}
+
+    def po_destroy(self) -> None:
+        if getattr(self, "_h", None):
+            lib().po_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.po_destroy()
+        except Exception:
+            pass
+
+    # -- convenience: load a whole synthetic model from the seeded generator ----------------
+    def load_synthetic(self, seed: int, threads: int = 8) -> None:
+        from . import inputs as I
+        for kind, layer, arr in I.iter_model_tensors(self.cfg, seed, threads=threads):
+            self.po_load_tensor(kind, layer, arr)
+        if not self.po_is_loaded():
+            raise RuntimeError("model not fully loaded")
+
+
+# ---- single-kernel entry points on torch device tensors (pointers only) ---------------------
+
+def _dt(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return PO_F32
+    if t.dtype == torch.bfloat16:
+        return PO_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def po_op_rmsnorm(x, g, eps: float):
+    import torch
+    y = torch.empty_like(x)
+    check(lib().po_op_rmsnorm(_dt(x), x.data_ptr(), g.data_ptr(), y.data_ptr(), x.shape[0], x.shape[1], eps, _stream()))
+    return y
+
+
+def po_op_linear(a, w, residual=None, out=None):
+    import torch
+    M, K = a.shape
+    N = w.shape[0]
+    c = out if out is not None else torch.empty((M, N), dtype=a.dtype, device=a.device)
+    check(lib().po_op_linear(_dt(a), a.data_ptr(), w.data_ptr(), c.data_ptr(),
+                             None if residual is None else residual.data_ptr(), M, N, K, _stream()))
+    return c
+
+
+def po_op_pack_gate_up(wg, wu):
+    import torch
+    F, K = wg.shape
+    out = torch.empty((2 * F, K), dtype=wg.dtype, device=wg.device)
+    check(lib().po_op_pack_gate_up(_dt(wg), wg.data_ptr(), wu.data_ptr(), out.data_ptr(), F, K, _stream()))
+    return out
+
+
+def po_op_gate_up_silu(a, wgu):
+    import torch
+    M, K = a.shape
+    F = wgu.shape[0] // 2
+    h = torch.empty((M, F), dtype=a.dtype, device=a.device)
+    scratch = torch.empty((M, 2 * F), dtype=a.dtype, device=a.device) if a.dtype == torch.float32 else None
+    check(lib().po_op_gate_up_silu(_dt(a), a.data_ptr(), wgu.data_ptr(), h.data_ptr(),
+                                   None if scratch is None else scratch.data_ptr(), M, F, K, _stream()))
+    return h
+
+
+def po_op_attention(q, k, v, out=None):
+    """q [N,Hq,hd], k/v [N,Hkv,hd] (rotated) -> o [N,Hq,hd]; out may be q itself."""
+    import torch
+    N, Hq, hd = q.shape
+    Hkv = k.shape[1]
+    o = out if out is not None else torch.empty_like(q)
+    scratch = None
+    if q.dtype == torch.bfloat16:
+        scratch = torch.empty(Hkv * hd * ((N + 63) // 64 * 64), dtype=q.dtype, device=q.device)
+    check(lib().po_op_attention(_dt(q), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                None if scratch is None else scratch.data_ptr(), N, Hq, Hkv, hd, _stream()))
+    return o
+
+
+def po_op_rope(x, theta: float):
+    """in place on x [N, H, hd]"""
+    N, H, hd = x.shape
+    check(lib().po_op_rope(_dt(x), x.data_ptr(), N, H, hd, theta, _stream()))
+    return x
+
+
+def po_op_lm_head(x, w):
+    import torch
+    V, d = w.shape
+    z = torch.empty(V, dtype=torch.float32, device=w.device)
+    check(lib().po_op_lm_head(_dt(x), x.data_ptr(), w.data_ptr(), z.data_ptr(), V, d, _stream()))
+    return z

@@ -1,0 +1,605 @@
+// libpo host side: the C ABI of include/po.h, the arena layouts and the forward driver
+// (layer loop, token-chunk loop, one HIP stream, no device<->host synchronisation inside
+// a request except the final one).
+#include "../../include/po.h"
+#include "po_internal.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+using namespace po;
+
+namespace {
+
+thread_local char g_dev_err[512] = "";
+
+#define PO_HIP(expr)                                                                           \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) {                                                                \
+            snprintf(g_dev_err, sizeof(g_dev_err), "%s: %s (%s:%d)", #expr, hipGetErrorString(e_), \
+                     __FILE__, __LINE__);                                                      \
+            return PO_ERR_DEVICE;                                                              \
+        }                                                                                      \
+    } while (0)
+
+constexpr size_t ALIGN = 256;
+constexpr int MAX_CAND = 4096;
+constexpr int GU_INTERLEAVE_BF16 = 32;   // rows per gate/up block in the packed bf16 weight
+
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct LayerOff {
+    size_t attn_norm, wqkv, bqkv, wo, mlp_norm, wgu, wd;
+};
+
+struct Layout {
+    // weights arena
+    size_t embed, final_norm, lm_head;
+    std::vector<LayerOff> layers;
+    size_t weights_bytes;
+    // workspace arena
+    size_t tokens, X, Q, K, V, Vt, Xn, H, GU, rope_cos, rope_sin, logits, xn_last, cand, cand_lp;
+    size_t workspace_bytes;
+    int64_t ldv;
+    int chunk;          // effective chunk = min(mlp_chunk, max_len)
+};
+
+po_status validate_config(const po_model_config* c) {
+    if (!c) return PO_ERR_INVALID_ARG;
+    if (c->dtype != PO_F32 && c->dtype != PO_BF16) return PO_ERR_INVALID_ARG;
+    if (c->qkv_bias != 0 && c->qkv_bias != 1) return PO_ERR_INVALID_ARG;
+    if (c->n_layers < 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
+        c->ffn_dim <= 0 || c->vocab_size <= 0)
+        return PO_ERR_INVALID_ARG;
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return PO_ERR_INVALID_ARG;
+    if (c->n_q_heads % c->n_kv_heads != 0) return PO_ERR_BAD_CONFIG;
+    if (c->d_model % 8 != 0 || c->ffn_dim % 8 != 0) return PO_ERR_BAD_CONFIG;
+    const int hd = c->head_dim;
+    if (c->dtype == PO_F32) {
+        if (hd != 32 && hd != 64 && hd != 128) return PO_ERR_BAD_CONFIG;
+    } else {
+        const int qd = c->n_q_heads * hd, kvd = c->n_kv_heads * hd;
+        if (!attention_mfma_supported(c->n_q_heads, c->n_kv_heads, hd)) return PO_ERR_BAD_CONFIG;
+        if (!gemm_mfma_supported(qd + 2 * kvd, c->d_model)) return PO_ERR_BAD_CONFIG;
+        if (!gemm_mfma_supported(c->d_model, qd)) return PO_ERR_BAD_CONFIG;
+        if (c->ffn_dim % GU_INTERLEAVE_BF16 != 0) return PO_ERR_BAD_CONFIG;
+        if (!gemm_mfma_supported(2 * c->ffn_dim, c->d_model)) return PO_ERR_BAD_CONFIG;
+        if (!gemm_mfma_supported(c->d_model, c->ffn_dim)) return PO_ERR_BAD_CONFIG;
+    }
+    return PO_OK;
+}
+
+po_status make_layout(const po_model_config* c, int64_t max_len, int32_t mlp_chunk, Layout* L) {
+    po_status st = validate_config(c);
+    if (st != PO_OK) return st;
+    if (max_len <= 0 || mlp_chunk <= 0) return PO_ERR_INVALID_ARG;
+    if (max_len > (int64_t)1 << 24) return PO_ERR_TOO_LONG;
+    const size_t esz = c->dtype == PO_F32 ? 4 : 2;
+    const size_t d = c->d_model, F = c->ffn_dim, V = c->vocab_size;
+    const size_t qd = (size_t)c->n_q_heads * c->head_dim, kvd = (size_t)c->n_kv_heads * c->head_dim;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    L->embed = take(V * d * esz);
+    L->final_norm = take(d * esz);
+    L->lm_head = take(V * d * esz);
+    L->layers.resize(c->n_layers);
+    for (int l = 0; l < c->n_layers; ++l) {
+        LayerOff& o = L->layers[l];
+        o.attn_norm = take(d * esz);
+        o.wqkv = take((qd + 2 * kvd) * d * esz);
+        o.bqkv = c->qkv_bias ? take((qd + 2 * kvd) * esz) : 0;
+        o.wo = take(d * qd * esz);
+        o.mlp_norm = take(d * esz);
+        o.wgu = take(2 * F * d * esz);
+        o.wd = take(d * F * esz);
+    }
+    L->weights_bytes = off;
+
+    const size_t N = (size_t)max_len;
+    const size_t C = (size_t)(mlp_chunk < max_len ? mlp_chunk : max_len);
+    L->chunk = (int)C;
+    L->ldv = round_up64(max_len, 64);
+    off = 0;
+    L->tokens = take(N * 4);
+    L->X = take(N * d * esz);
+    L->Q = take(N * qd * esz);
+    L->K = take(N * kvd * esz);
+    L->V = take(N * kvd * esz);
+    L->Vt = c->dtype == PO_BF16 ? take(kvd * (size_t)L->ldv * esz) : 0;
+    L->Xn = take(C * d * esz);
+    L->H = take(C * F * esz);
+    L->GU = c->dtype == PO_F32 ? take(C * 2 * F * esz) : 0;
+    L->rope_cos = take(N * (c->head_dim / 2) * 4);
+    L->rope_sin = take(N * (c->head_dim / 2) * 4);
+    L->logits = take(V * 4);
+    L->xn_last = take(d * esz);
+    L->cand = take(MAX_CAND * 4);
+    L->cand_lp = take(MAX_CAND * 4);
+    L->workspace_bytes = off;
+    return PO_OK;
+}
+
+}  // namespace
+
+struct po_ctx {
+    po_model_config cfg;
+    int64_t max_len;
+    int32_t mlp_chunk;
+    Layout lay;
+    unsigned char* w;      // weights arena (device)
+    unsigned char* ws;     // workspace arena (device)
+    hipStream_t stream;
+    std::vector<uint32_t> loaded;     // per layer bitmask of tensor kinds; index n_layers = globals
+    hipEvent_t ev_start, ev_stop;
+    bool phase_timing;
+    std::vector<hipEvent_t> ev_pool;  // pairs
+    std::vector<int> ev_kind;         // per pair: 0 attention, 1 linear
+    size_t ev_used;
+    po_stats stats;
+};
+
+namespace {
+
+uint32_t required_layer_mask(const po_model_config& c) {
+    uint32_t m = (1u << PO_T_ATTN_NORM) | (1u << PO_T_WQ) | (1u << PO_T_WK) | (1u << PO_T_WV) | (1u << PO_T_WO) |
+                 (1u << PO_T_MLP_NORM) | (1u << PO_T_WG) | (1u << PO_T_WU) | (1u << PO_T_WD);
+    if (c.qkv_bias) m |= (1u << PO_T_BQ) | (1u << PO_T_BK) | (1u << PO_T_BV);
+    return m;
+}
+constexpr uint32_t GLOBAL_MASK = (1u << PO_T_EMBED) | (1u << PO_T_FINAL_NORM) | (1u << PO_T_LM_HEAD);
+
+// RAII-less helper: records an event pair around a launch when phase timing is on
+struct PhaseTimer {
+    po_ctx* c;
+    bool on;
+    size_t idx;
+    PhaseTimer(po_ctx* ctx, int kind) : c(ctx), on(ctx->phase_timing), idx(0) {
+        if (!on) return;
+        if (c->ev_used + 2 > c->ev_pool.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+            c->ev_pool.push_back(a);
+            c->ev_pool.push_back(b);
+            c->ev_kind.push_back(kind);
+        }
+        idx = c->ev_used;
+        c->ev_kind[idx / 2] = kind;
+        c->ev_used += 2;
+        (void)hipEventRecord(c->ev_pool[idx], c->stream);
+    }
+    ~PhaseTimer() {
+        if (on) (void)hipEventRecord(c->ev_pool[idx + 1], c->stream);
+    }
+};
+
+// one request on the device; tokens already validated
+po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32_t* cand, int32_t n_cand,
+                      float* out_logits, float* out_lp) {
+    const po_model_config& m = c->cfg;
+    const Layout& L = c->lay;
+    const int dt = m.dtype;
+    const size_t esz = dt == PO_F32 ? 4 : 2;
+    const int d = m.d_model, F = m.ffn_dim, hd = m.head_dim;
+    const int qd = m.n_q_heads * hd, kvd = m.n_kv_heads * hd;
+    hipStream_t s = c->stream;
+    unsigned char* ws = c->ws;
+    int32_t* d_tok = (int32_t*)(ws + L.tokens);
+    unsigned char* X = ws + L.X;
+    unsigned char* Q = ws + L.Q;
+    unsigned char* K = ws + L.K;
+    unsigned char* V = ws + L.V;
+    unsigned char* Xn = ws + L.Xn;
+    unsigned char* H = ws + L.H;
+    const float* rc = (const float*)(ws + L.rope_cos);
+    const float* rs = (const float*)(ws + L.rope_sin);
+    float* d_logits = (float*)(ws + L.logits);
+    const int C = L.chunk;
+
+    c->ev_used = 0;
+    PO_HIP(hipMemcpyAsync(d_tok, tokens, (size_t)len * 4, hipMemcpyHostToDevice, s));
+    if (n_cand > 0) PO_HIP(hipMemcpyAsync(ws + L.cand, cand, (size_t)n_cand * 4, hipMemcpyHostToDevice, s));
+    PO_HIP(hipEventRecord(c->ev_start, s));
+    launch_embed(dt, d_tok, c->w + L.embed, X, len, d, s);
+
+    for (int l = 0; l < m.n_layers; ++l) {
+        const LayerOff& o = L.layers[l];
+        const unsigned char* wqkv = c->w + o.wqkv;
+        const unsigned char* bqkv = m.qkv_bias ? c->w + o.bqkv : nullptr;
+        // ---- position-wise part before attention, chunk by chunk: norm -> QKV projection
+        for (int64_t c0 = 0; c0 < len; c0 += C) {
+            const int64_t rows = (len - c0 < C) ? len - c0 : C;
+            launch_rmsnorm(dt, X + (size_t)c0 * d * esz, c->w + o.attn_norm, Xn, rows, d, m.rms_eps, s);
+            PhaseTimer pt(c, 1);
+            if (dt == PO_BF16) {
+                GemmSeg segs[3] = {{Q + (size_t)c0 * qd * esz, qd, qd},
+                                   {K + (size_t)c0 * kvd * esz, kvd, qd + kvd},
+                                   {V + (size_t)c0 * kvd * esz, kvd, qd + 2 * kvd}};
+                launch_gemm_mfma(EPI_STORE, (const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, segs, 3,
+                                 (const bf16_t*)bqkv, nullptr, 0, rows, qd + 2 * kvd, d, s);
+            } else {
+                launch_gemm_basic(dt, Xn, d, wqkv, d, Q + (size_t)c0 * qd * esz, qd, bqkv, nullptr, 0, rows, qd, d, s);
+                launch_gemm_basic(dt, Xn, d, wqkv + (size_t)qd * d * esz, d, K + (size_t)c0 * kvd * esz, kvd,
+                                  bqkv ? bqkv + (size_t)qd * esz : nullptr, nullptr, 0, rows, kvd, d, s);
+                launch_gemm_basic(dt, Xn, d, wqkv + (size_t)(qd + kvd) * d * esz, d, V + (size_t)c0 * kvd * esz, kvd,
+                                  bqkv ? bqkv + (size_t)(qd + kvd) * esz : nullptr, nullptr, 0, rows, kvd, d, s);
+            }
+        }
+        launch_rope(dt, Q, qd, rc, rs, len, m.n_q_heads, hd, s);
+        launch_rope(dt, K, kvd, rc, rs, len, m.n_kv_heads, hd, s);
+        // ---- attention over the whole sequence in one call; O overwrites Q
+        {
+            PhaseTimer pt(c, 0);
+            if (dt == PO_BF16) {
+                bf16_t* Vt = (bf16_t*)(ws + L.Vt);
+                launch_v_transpose((const bf16_t*)V, Vt, len, kvd, L.ldv, s);
+                launch_attention_mfma((const bf16_t*)Q, (const bf16_t*)K, Vt, L.ldv, (bf16_t*)Q, len, m.n_q_heads,
+                                      m.n_kv_heads, hd, s);
+            } else {
+                launch_attention_basic(dt, Q, K, V, Q, len, m.n_q_heads, m.n_kv_heads, hd, s);
+            }
+        }
+        // ---- position-wise part after attention, chunk by chunk, residual stream in place
+        for (int64_t c0 = 0; c0 < len; c0 += C) {
+            const int64_t rows = (len - c0 < C) ? len - c0 : C;
+            unsigned char* Xc = X + (size_t)c0 * d * esz;
+            const unsigned char* Oc = Q + (size_t)c0 * qd * esz;
+            if (dt == PO_BF16) {
+                GemmSeg xs = {Xc, d, d};
+                {
+                    PhaseTimer pt(c, 1);
+                    launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)Oc, qd, (const bf16_t*)(c->w + o.wo), qd, &xs, 1,
+                                     nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
+                }
+                launch_rmsnorm(dt, Xc, c->w + o.mlp_norm, Xn, rows, d, m.rms_eps, s);
+                PhaseTimer pt(c, 1);
+                GemmSeg hs = {H, F, F};
+                launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)Xn, d, (const bf16_t*)(c->w + o.wgu), d, &hs, 1, nullptr,
+                                 nullptr, 0, rows, 2 * F, d, s);
+                launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)H, F, (const bf16_t*)(c->w + o.wd), F, &xs, 1, nullptr,
+                                 (const bf16_t*)Xc, d, rows, d, F, s);
+            } else {
+                unsigned char* GU = ws + L.GU;
+                {
+                    PhaseTimer pt(c, 1);
+                    launch_gemm_basic(dt, Oc, qd, c->w + o.wo, qd, Xc, d, nullptr, Xc, d, rows, d, qd, s);
+                }
+                launch_rmsnorm(dt, Xc, c->w + o.mlp_norm, Xn, rows, d, m.rms_eps, s);
+                PhaseTimer pt(c, 1);
+                launch_gemm_basic(dt, Xn, d, c->w + o.wgu, d, GU, 2 * F, nullptr, nullptr, 0, rows, 2 * F, d, s);
+                launch_silu_mul(dt, GU, H, rows, F, s);
+                launch_gemm_basic(dt, H, F, c->w + o.wd, F, Xc, d, nullptr, Xc, d, rows, d, F, s);
+            }
+        }
+    }
+    // ---- last position only: final norm, LM head, candidate log-probs
+    launch_rmsnorm(dt, X + (size_t)(len - 1) * d * esz, c->w + L.final_norm, ws + L.xn_last, 1, d, m.rms_eps, s);
+    launch_lm_head(dt, ws + L.xn_last, c->w + L.lm_head, d_logits, m.vocab_size, d, s);
+    if (n_cand > 0)
+        launch_cand_logprobs(d_logits, (const int32_t*)(ws + L.cand), n_cand, (float*)(ws + L.cand_lp), s);
+    PO_HIP(hipEventRecord(c->ev_stop, s));
+    PO_HIP(hipGetLastError());
+    if (out_logits)
+        PO_HIP(hipMemcpyAsync(out_logits, d_logits, (size_t)m.vocab_size * 4, hipMemcpyDeviceToHost, s));
+    if (out_lp && n_cand > 0)
+        PO_HIP(hipMemcpyAsync(out_lp, ws + L.cand_lp, (size_t)n_cand * 4, hipMemcpyDeviceToHost, s));
+    PO_HIP(hipStreamSynchronize(s));
+    float ms = 0.f;
+    PO_HIP(hipEventElapsedTime(&ms, c->ev_start, c->ev_stop));
+    c->stats.last_prefill_ms = ms;
+    c->stats.last_len = len;
+    c->stats.last_attention_ms = 0;
+    c->stats.last_linear_ms = 0;
+    for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, c->ev_pool[i], c->ev_pool[i + 1]) == hipSuccess) {
+            if (c->ev_kind[i / 2] == 0) c->stats.last_attention_ms += t;
+            else c->stats.last_linear_ms += t;
+        }
+    }
+    return PO_OK;
+}
+
+po_status validate_request(const po_ctx* c, const int32_t* tokens, int64_t len, const int32_t* cand, int32_t n_cand) {
+    if (!tokens || len <= 0 || n_cand < 0 || (n_cand > 0 && !cand) || n_cand > MAX_CAND) return PO_ERR_INVALID_ARG;
+    if (len > c->max_len) return PO_ERR_TOO_LONG;
+    const int32_t V = c->cfg.vocab_size;
+    for (int64_t i = 0; i < len; ++i)
+        if (tokens[i] < 0 || tokens[i] >= V) return PO_ERR_TOKEN_RANGE;
+    for (int32_t i = 0; i < n_cand; ++i)
+        if (cand[i] < 0 || cand[i] >= V) return PO_ERR_TOKEN_RANGE;
+    return PO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+po_status po_workspace_bytes(const po_model_config* cfg, int64_t max_input_len, int32_t mlp_chunk,
+                             size_t* weights_bytes, size_t* workspace_bytes) {
+    if (!cfg || !weights_bytes || !workspace_bytes) return PO_ERR_INVALID_ARG;
+    Layout L;
+    po_status st = make_layout(cfg, max_input_len, mlp_chunk, &L);
+    if (st != PO_OK) return st;
+    *weights_bytes = L.weights_bytes;
+    *workspace_bytes = L.workspace_bytes;
+    return PO_OK;
+}
+
+po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t mlp_chunk, void* dev_weights,
+                    size_t weights_bytes, void* dev_workspace, size_t workspace_bytes, void* hip_stream,
+                    po_ctx** out) {
+    if (!cfg || !out || !dev_weights || !dev_workspace) return PO_ERR_INVALID_ARG;
+    if (((uintptr_t)dev_weights % ALIGN) || ((uintptr_t)dev_workspace % ALIGN)) return PO_ERR_INVALID_ARG;
+    po_ctx* c = new (std::nothrow) po_ctx();
+    if (!c) return PO_ERR_OOM;
+    po_status st = make_layout(cfg, max_input_len, mlp_chunk, &c->lay);
+    if (st != PO_OK) { delete c; return st; }
+    if (weights_bytes < c->lay.weights_bytes || workspace_bytes < c->lay.workspace_bytes) {
+        delete c;
+        return PO_ERR_WORKSPACE_TOO_SMALL;
+    }
+    c->cfg = *cfg;
+    c->max_len = max_input_len;
+    c->mlp_chunk = mlp_chunk;
+    c->w = (unsigned char*)dev_weights;
+    c->ws = (unsigned char*)dev_workspace;
+    c->stream = (hipStream_t)hip_stream;
+    c->loaded.assign(cfg->n_layers + 1, 0u);
+    c->phase_timing = false;
+    c->ev_used = 0;
+    memset(&c->stats, 0, sizeof(c->stats));
+    c->stats.weights_bytes = c->lay.weights_bytes;
+    c->stats.workspace_bytes = c->lay.workspace_bytes;
+    c->ev_start = c->ev_stop = nullptr;
+    if (hipEventCreate(&c->ev_start) != hipSuccess || hipEventCreate(&c->ev_stop) != hipSuccess) {
+        snprintf(g_dev_err, sizeof(g_dev_err), "hipEventCreate failed");
+        if (c->ev_start) (void)hipEventDestroy(c->ev_start);
+        delete c;
+        return PO_ERR_DEVICE;
+    }
+    // rotary table for every position up to max_input_len (angles in fp64 on the device)
+    launch_rope_table((float*)(c->ws + c->lay.rope_cos), (float*)(c->ws + c->lay.rope_sin), max_input_len,
+                      cfg->head_dim, cfg->rope_theta, c->stream);
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) {
+        snprintf(g_dev_err, sizeof(g_dev_err), "rope table: %s", hipGetErrorString(e));
+        po_destroy(c);
+        return PO_ERR_DEVICE;
+    }
+    *out = c;
+    return PO_OK;
+}
+
+po_status po_load_tensor(po_ctx* c, int32_t kind, int32_t layer, const void* host, size_t bytes) {
+    if (!c || !host || kind < 0 || kind >= PO_T_COUNT) return PO_ERR_INVALID_ARG;
+    const po_model_config& m = c->cfg;
+    const bool is_global = kind == PO_T_EMBED || kind == PO_T_FINAL_NORM || kind == PO_T_LM_HEAD;
+    if (is_global ? layer != -1 : (layer < 0 || layer >= m.n_layers)) return PO_ERR_INVALID_ARG;
+    if (!m.qkv_bias && (kind == PO_T_BQ || kind == PO_T_BK || kind == PO_T_BV)) return PO_ERR_INVALID_ARG;
+    const size_t esz = m.dtype == PO_F32 ? 4 : 2;
+    const size_t d = m.d_model, F = m.ffn_dim, V = m.vocab_size;
+    const size_t qd = (size_t)m.n_q_heads * m.head_dim, kvd = (size_t)m.n_kv_heads * m.head_dim;
+    const Layout& L = c->lay;
+    size_t want = 0, off = 0;
+    const LayerOff* o = is_global ? nullptr : &L.layers[layer];
+    switch (kind) {
+        case PO_T_EMBED: want = V * d; off = L.embed; break;
+        case PO_T_FINAL_NORM: want = d; off = L.final_norm; break;
+        case PO_T_LM_HEAD: want = V * d; off = L.lm_head; break;
+        case PO_T_ATTN_NORM: want = d; off = o->attn_norm; break;
+        case PO_T_MLP_NORM: want = d; off = o->mlp_norm; break;
+        case PO_T_WQ: want = qd * d; off = o->wqkv; break;
+        case PO_T_WK: want = kvd * d; off = o->wqkv + qd * d * esz; break;
+        case PO_T_WV: want = kvd * d; off = o->wqkv + (qd + kvd) * d * esz; break;
+        case PO_T_BQ: want = qd; off = o->bqkv; break;
+        case PO_T_BK: want = kvd; off = o->bqkv + qd * esz; break;
+        case PO_T_BV: want = kvd; off = o->bqkv + (qd + kvd) * esz; break;
+        case PO_T_WO: want = d * qd; off = o->wo; break;
+        case PO_T_WG: want = F * d; off = o->wgu; break;
+        case PO_T_WU: want = F * d; off = o->wgu; break;
+        case PO_T_WD: want = d * F; off = o->wd; break;
+        default: return PO_ERR_INVALID_ARG;
+    }
+    if (bytes != want * esz) return PO_ERR_INVALID_ARG;
+    if (kind == PO_T_WG || kind == PO_T_WU) {
+        // gate and up rows are interleaved in blocks of `il` rows so that one GEMM tile
+        // holds a feature's gate and up values together (fp32 path: il = F, i.e. [Wg; Wu])
+        const size_t il = m.dtype == PO_BF16 ? GU_INTERLEAVE_BF16 : F;
+        const size_t blk = il * d * esz;
+        unsigned char* dst = c->w + off + (kind == PO_T_WU ? blk : 0);
+        PO_HIP(hipMemcpy2D(dst, 2 * blk, host, blk, blk, F / il, hipMemcpyHostToDevice));
+    } else {
+        PO_HIP(hipMemcpy(c->w + off, host, bytes, hipMemcpyHostToDevice));
+    }
+    c->loaded[is_global ? m.n_layers : layer] |= 1u << kind;
+    return PO_OK;
+}
+
+int32_t po_is_loaded(const po_ctx* c) {
+    if (!c) return 0;
+    const uint32_t need = required_layer_mask(c->cfg);
+    for (int l = 0; l < c->cfg.n_layers; ++l)
+        if ((c->loaded[l] & need) != need) return 0;
+    return (c->loaded[c->cfg.n_layers] & GLOBAL_MASK) == GLOBAL_MASK ? 1 : 0;
+}
+
+po_status po_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32_t* cand_ids, int32_t n_cand,
+                     float* out_logits, float* out_cand_logprobs) {
+    if (!c) return PO_ERR_INVALID_ARG;
+    po_status st = validate_request(c, tokens, len, cand_ids, n_cand);
+    if (st != PO_OK) return st;
+    if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
+    return run_prefill(c, tokens, len, cand_ids, n_cand, out_logits, out_cand_logprobs);
+}
+
+po_status po_prefill_batch(po_ctx* c, const int32_t* tokens_concat, const int64_t* lens, int32_t n_req,
+                           const int32_t* cand_ids, int32_t n_cand, float* out_logits, float* out_cand_logprobs) {
+    if (!c || !tokens_concat || !lens || n_req <= 0) return PO_ERR_INVALID_ARG;
+    // validate everything before the first launch: no partial output on error
+    int64_t off = 0;
+    for (int32_t r = 0; r < n_req; ++r) {
+        if (lens[r] <= 0) return PO_ERR_INVALID_ARG;
+        po_status st = validate_request(c, tokens_concat + off, lens[r], cand_ids, n_cand);
+        if (st != PO_OK) return st;
+        off += lens[r];
+    }
+    if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
+    off = 0;
+    double total_ms = 0, att_ms = 0, lin_ms = 0;
+    for (int32_t r = 0; r < n_req; ++r) {
+        po_status st = run_prefill(c, tokens_concat + off, lens[r], cand_ids, n_cand,
+                                   out_logits ? out_logits + (size_t)r * c->cfg.vocab_size : nullptr,
+                                   out_cand_logprobs ? out_cand_logprobs + (size_t)r * n_cand : nullptr);
+        if (st != PO_OK) return st;
+        total_ms += c->stats.last_prefill_ms;
+        att_ms += c->stats.last_attention_ms;
+        lin_ms += c->stats.last_linear_ms;
+        off += lens[r];
+    }
+    c->stats.last_prefill_ms = total_ms;
+    c->stats.last_attention_ms = att_ms;
+    c->stats.last_linear_ms = lin_ms;
+    c->stats.last_len = off;
+    return PO_OK;
+}
+
+po_status po_set_phase_timing(po_ctx* c, int32_t on) {
+    if (!c) return PO_ERR_INVALID_ARG;
+    c->phase_timing = on != 0;
+    return PO_OK;
+}
+
+po_status po_get_stats(const po_ctx* c, po_stats* out) {
+    if (!c || !out) return PO_ERR_INVALID_ARG;
+    *out = c->stats;
+    return PO_OK;
+}
+
+void po_destroy(po_ctx* c) {
+    if (!c) return;
+    if (c->ev_start) (void)hipEventDestroy(c->ev_start);
+    if (c->ev_stop) (void)hipEventDestroy(c->ev_stop);
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    delete c;
+}
+
+const char* po_strerror(po_status s) {
+    switch (s) {
+        case PO_OK: return "ok";
+        case PO_ERR_INVALID_ARG: return "invalid argument";
+        case PO_ERR_BAD_CONFIG: return "model configuration not supported by the kernels";
+        case PO_ERR_NOT_LOADED: return "weights not fully loaded";
+        case PO_ERR_TOO_LONG: return "input longer than max_input_len";
+        case PO_ERR_TOKEN_RANGE: return "token or candidate id outside [0, vocab_size)";
+        case PO_ERR_WORKSPACE_TOO_SMALL: return "device arena smaller than po_workspace_bytes reports";
+        case PO_ERR_OOM: return "host allocation failed";
+        case PO_ERR_DEVICE: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+const char* po_last_device_error(void) { return g_dev_err; }
+
+// ------------------------------------------------------------------ single-kernel entry points
+
+static inline bool bad_dtype(int32_t dt) { return dt != PO_F32 && dt != PO_BF16; }
+
+po_status po_op_rmsnorm(int32_t dtype, const void* x, const void* g, void* y, int64_t rows, int32_t d, float eps,
+                        void* stream) {
+    if (bad_dtype(dtype) || !x || !g || !y || rows <= 0 || d <= 0 || d % 8) return PO_ERR_INVALID_ARG;
+    launch_rmsnorm(dtype, x, g, y, rows, d, eps, (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_linear(int32_t dtype, const void* a, const void* w, void* cc, const void* residual, int64_t M,
+                       int32_t N, int32_t K, void* stream) {
+    if (bad_dtype(dtype) || !a || !w || !cc || M <= 0 || N <= 0 || K <= 0) return PO_ERR_INVALID_ARG;
+    if (dtype == PO_BF16) {
+        if (!gemm_mfma_supported(N, K)) return PO_ERR_BAD_CONFIG;
+        GemmSeg seg = {cc, N, N};
+        launch_gemm_mfma(residual ? EPI_RESIDUAL : EPI_STORE, (const bf16_t*)a, K, (const bf16_t*)w, K, &seg, 1,
+                         nullptr, (const bf16_t*)residual, N, M, N, K, (hipStream_t)stream);
+    } else {
+        launch_gemm_basic(dtype, a, K, w, K, cc, N, nullptr, residual, N, M, N, K, (hipStream_t)stream);
+    }
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_gate_up_silu(int32_t dtype, const void* a, const void* wgu, void* h, void* scratch, int64_t M,
+                             int32_t F, int32_t K, void* stream) {
+    if (bad_dtype(dtype) || !a || !wgu || !h || M <= 0 || F <= 0 || K <= 0) return PO_ERR_INVALID_ARG;
+    if (dtype == PO_BF16) {
+        if (F % GU_INTERLEAVE_BF16 || !gemm_mfma_supported(2 * F, K)) return PO_ERR_BAD_CONFIG;
+        GemmSeg seg = {h, F, F};
+        launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)a, K, (const bf16_t*)wgu, K, &seg, 1, nullptr, nullptr, 0, M,
+                         2 * F, K, (hipStream_t)stream);
+    } else {
+        if (!scratch) return PO_ERR_INVALID_ARG;
+        launch_gemm_basic(dtype, a, K, wgu, K, scratch, 2 * F, nullptr, nullptr, 0, M, 2 * F, K, (hipStream_t)stream);
+        launch_silu_mul(dtype, scratch, h, M, F, (hipStream_t)stream);
+    }
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_pack_gate_up(int32_t dtype, const void* wg, const void* wu, void* wgu, int32_t F, int32_t K,
+                             void* stream) {
+    if (bad_dtype(dtype) || !wg || !wu || !wgu || F <= 0 || K <= 0 || K % 8) return PO_ERR_INVALID_ARG;
+    if (dtype == PO_BF16 && F % GU_INTERLEAVE_BF16) return PO_ERR_BAD_CONFIG;
+    launch_pack_gate_up(dtype, wg, wu, wgu, F, K, dtype == PO_BF16 ? GU_INTERLEAVE_BF16 : F, (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* o, void* scratch,
+                          int64_t N, int32_t Hq, int32_t Hkv, int32_t hd, void* stream) {
+    if (bad_dtype(dtype) || !q || !k || !v || !o || N <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return PO_ERR_INVALID_ARG;
+    if (N > (int64_t)1 << 24) return PO_ERR_TOO_LONG;
+    if (dtype == PO_BF16) {
+        if (!attention_mfma_supported(Hq, Hkv, hd)) return PO_ERR_BAD_CONFIG;
+        if (!scratch) return PO_ERR_INVALID_ARG;
+        const int64_t ldv = round_up64(N, 64);
+        launch_v_transpose((const bf16_t*)v, (bf16_t*)scratch, N, Hkv * hd, ldv, (hipStream_t)stream);
+        launch_attention_mfma((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)scratch, ldv, (bf16_t*)o, N, Hq, Hkv,
+                              hd, (hipStream_t)stream);
+    } else {
+        if (hd != 32 && hd != 64 && hd != 128) return PO_ERR_BAD_CONFIG;
+        launch_attention_basic(dtype, q, k, v, o, N, Hq, Hkv, hd, (hipStream_t)stream);
+    }
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_rope(int32_t dtype, void* x, int64_t N, int32_t H, int32_t hd, float theta, void* stream) {
+    if (bad_dtype(dtype) || !x || N <= 0 || H <= 0 || hd <= 0 || hd % 2 || !(theta > 0.f)) return PO_ERR_INVALID_ARG;
+    float* tab = nullptr;
+    const size_t half_bytes = (size_t)N * (hd / 2) * 4;
+    PO_HIP(hipMalloc((void**)&tab, 2 * half_bytes));
+    launch_rope_table(tab, tab + (size_t)N * (hd / 2), N, hd, theta, (hipStream_t)stream);
+    launch_rope(dtype, x, (int64_t)H * hd, tab, tab + (size_t)N * (hd / 2), N, H, hd, (hipStream_t)stream);
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    (void)hipFree(tab);
+    PO_HIP(e);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_lm_head(int32_t dtype, const void* x, const void* w, float* logits, int32_t V, int32_t d,
+                        void* stream) {
+    if (bad_dtype(dtype) || !x || !w || !logits || V <= 0 || d <= 0 || d % 8) return PO_ERR_INVALID_ARG;
+    launch_lm_head(dtype, x, w, logits, V, d, (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

@@ -1,0 +1,73 @@
+// Internal declarations shared by the translation units of libpo (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace po {
+
+typedef uint16_t bf16_t;   // bf16 bit pattern as stored in HBM
+
+// ---- scalar conversions ---------------------------------------------------------------
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// fp32 -> bf16, round-to-nearest-even (v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(bf16_t, h);
+}
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return bf2f(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f2bf(v); }
+
+static inline int64_t round_up64(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// ---- launchers: "basic" kernels, any dtype (dtype: 0 = fp32, 1 = bf16) ----------------
+void launch_embed(int dtype, const int32_t* tok, const void* E, void* X, int64_t n, int d, hipStream_t s);
+void launch_rmsnorm(int dtype, const void* x, const void* g, void* y, int64_t rows, int d, float eps,
+                    hipStream_t s);
+// cos/sin table [n, hd/2] each, angles formed in fp64
+void launch_rope_table(float* cos_t, float* sin_t, int64_t n, int hd, float theta, hipStream_t s);
+// in-place rotate-half RoPE on x[n, H, hd] (row stride ld elements)
+void launch_rope(int dtype, void* x, int64_t ld, const float* cos_t, const float* sin_t, int64_t n,
+                 int H, int hd, hipStream_t s);
+// fp32-accumulating tiled GEMM  C[M,N] = A[M,K] W[N,K]^T (+bias[N]) (+R[M,N])
+void launch_gemm_basic(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, void* C,
+                       int64_t ldc, const void* bias, const void* R, int64_t ldr, int64_t M, int N,
+                       int K, hipStream_t s);
+// H[M,F] = silu(GU[:, :F]) * GU[:, F:]   (GU row stride 2F)
+void launch_silu_mul(int dtype, const void* GU, void* H, int64_t M, int F, hipStream_t s);
+// fp32-path attention (one thread per query row), o may alias q
+void launch_attention_basic(int dtype, const void* q, const void* k, const void* v, void* o, int64_t N,
+                            int Hq, int Hkv, int hd, hipStream_t s);
+// logits[V] = x[d] . W[V,d]^T
+void launch_lm_head(int dtype, const void* x, const void* W, float* logits, int V, int d, hipStream_t s);
+// lp[i] = logits[cand[i]] - logsumexp_j logits[cand[j]]
+void launch_cand_logprobs(const float* logits, const int32_t* cand, int n_cand, float* lp, hipStream_t s);
+// interleave gate/up rows in blocks of `il` rows: dst rows [2b*il, 2b*il+il) = Wg block b, next il = Wu block b
+void launch_pack_gate_up(int dtype, const void* wg, const void* wu, void* wgu, int F, int K, int il,
+                         hipStream_t s);
+
+// ---- launchers: bf16 MFMA kernels ------------------------------------------------------
+struct GemmSeg {           // one destination column segment of a GEMM output
+    void* ptr;             // base of the destination (element [row 0, col 0 of the segment])
+    int64_t ld;            // row stride in elements
+    int col_end;           // exclusive end column (in GEMM N coordinates) of this segment
+};
+enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SILU_MUL = 2 };
+// C = A[M,K] W[N,K]^T with bf16 MFMA.  EPI_STORE: up to 3 column segments, optional bias[N] (bf16).
+// EPI_RESIDUAL: seg[0] only; R added in fp32 (R may alias the destination).
+// EPI_SILU_MUL: W rows interleaved gate/up in blocks of 32; writes H[M, N/2] to seg[0].
+void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw,
+                      const GemmSeg* segs, int nseg, const bf16_t* bias, const bf16_t* R, int64_t ldr,
+                      int64_t M, int N, int K, hipStream_t s);
+// Vt[Hkv*hd][ldv] = transpose of V[n, Hkv*hd]; columns n..round_up(n,64)-1 are zero-filled
+void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int64_t ldv, hipStream_t s);
+// causal GQA flash attention; q [N,Hq,hd], k [N,Hkv,hd], vt [Hkv*hd][ldv]; o may alias q
+void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
+                           int64_t N, int Hq, int Hkv, int hd, hipStream_t s);
+bool gemm_mfma_supported(int N, int K);
+bool attention_mfma_supported(int Hq, int Hkv, int hd);
+
+}  // namespace po

@@ -1,0 +1,129 @@
+"""Host-side checks that need no GPU: the library loads and exports every symbol the header
+declares, the closed-form arena sizes, argument validation that happens before any launch,
+and the size arithmetic the paper prints."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2505_07203_amd import binding as B
+from paper_2505_07203_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "po.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(po_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = header_symbols()
+    assert len(names) >= 18
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_strerror_is_distinct_per_status():
+    L = B.lib()
+    msgs = {L.po_strerror(s).decode() for s in range(9)}
+    assert len(msgs) == 9
+
+
+def expected_workspace(cfg, n, c):
+    """The closed form: residual stream + Q/O + ONE layer of K/V (+ V^T copy for bf16) + one
+    chunk of position-wise intermediates + rotary table + logits (each rounded up to 256 B)."""
+    esz = 4 if cfg.dtype == I.F32 else 2
+    al = lambda b: (b + 255) // 256 * 256
+    c = min(c, n)
+    parts = [n * 4, n * cfg.d_model * esz, n * cfg.q_dim * esz, n * cfg.kv_dim * esz, n * cfg.kv_dim * esz]
+    if cfg.dtype == I.BF16:
+        parts.append(cfg.kv_dim * ((n + 63) // 64 * 64) * esz)
+    parts += [c * cfg.d_model * esz, c * cfg.ffn_dim * esz]
+    if cfg.dtype == I.F32:
+        parts.append(c * 2 * cfg.ffn_dim * esz)
+    parts += [n * (cfg.head_dim // 2) * 4] * 2
+    parts += [cfg.vocab_size * 4, cfg.d_model * esz, 4096 * 4, 4096 * 4]
+    return sum(al(p) for p in parts)
+
+
+@pytest.mark.parametrize("name", list(I.WORKLOADS))
+def test_workspace_closed_form(name):
+    w = I.WORKLOADS[name]
+    cfg = w["cfg"]
+    n = int(I.workload_lengths(name).max())
+    wb, sb = B.po_workspace_bytes(cfg, n, w["chunk"])
+    assert sb == expected_workspace(cfg, n, w["chunk"])
+    esz = 4 if cfg.dtype == I.F32 else 2
+    params = 2 * cfg.vocab_size * cfg.d_model + cfg.d_model + cfg.n_layers * (
+        2 * cfg.d_model + (cfg.q_dim + 2 * cfg.kv_dim) * cfg.d_model + cfg.d_model * cfg.q_dim
+        + 3 * cfg.ffn_dim * cfg.d_model)
+    assert params * esz <= wb <= params * esz + 256 * (3 + 7 * cfg.n_layers)
+
+
+def test_activation_footprint_slope_is_one_layer_of_kv():
+    """Only the current layer's K/V is resident (abstract / Section 1): the per-token slope
+    of the workspace must not grow with the number of layers."""
+    cfg = I.LLAMA8B
+    _, s1 = B.po_workspace_bytes(cfg, 65536, 4096)
+    _, s2 = B.po_workspace_bytes(cfg, 131072, 4096)
+    slope = (s2 - s1) / 65536
+    # X + Q/O + K + V + V^T (bf16) + rotary table + token id
+    assert slope == 2 * (4096 + 4096 + 3 * 1024) + 2 * 4 * 64 + 4
+    _, s3 = B.po_workspace_bytes(cfg.replace(n_layers=64), 131072, 4096)
+    assert s3 == s2
+    all_layer_kv = 2 * cfg.n_layers * cfg.kv_dim * 2
+    assert slope < all_layer_kv / 5
+
+
+def test_paper_size_arithmetic():
+    vals = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "paper_sizes.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split(";")[0].split("=")
+            vals[k.strip()] = float(v)
+    cfg = I.LLAMA8B
+    assert 2 * cfg.ffn_dim == vals["mlp_intermediate_numbers_per_token"]
+    assert 2 * cfg.ffn_dim / (2 * cfg.kv_dim) == vals["mlp_over_one_layer_kv_ratio"]
+    kv_bytes = 100000 * cfg.n_layers * 2 * cfg.kv_dim * 2
+    assert abs(kv_bytes / 2 ** 30 - vals["all_layer_kv_gb_for_100000_tokens"]) < 1.5
+    assert I.workload_lengths("llama8b_32k")[0] == vals["profiled_prefill_tokens"]
+
+
+def test_bad_arguments_rejected_before_any_launch():
+    L = B.lib()
+    w, s = C.c_size_t(), C.c_size_t()
+    cc = B.config_c(I.TINY)
+    assert L.po_workspace_bytes(None, 512, 512, C.byref(w), C.byref(s)) == B.PO_ERR_INVALID_ARG
+    assert L.po_workspace_bytes(C.byref(cc), 0, 512, C.byref(w), C.byref(s)) == B.PO_ERR_INVALID_ARG
+    assert L.po_workspace_bytes(C.byref(cc), 512, 0, C.byref(w), C.byref(s)) == B.PO_ERR_INVALID_ARG
+    assert L.po_workspace_bytes(C.byref(cc), 1 << 30, 512, C.byref(w), C.byref(s)) == B.PO_ERR_TOO_LONG
+    bad = B.config_c(I.TINY.replace(n_kv_heads=3))
+    assert L.po_workspace_bytes(C.byref(bad), 512, 512, C.byref(w), C.byref(s)) == B.PO_ERR_BAD_CONFIG
+    bad = B.config_c(I.TINY.replace(dtype=7))
+    assert L.po_workspace_bytes(C.byref(bad), 512, 512, C.byref(w), C.byref(s)) == B.PO_ERR_INVALID_ARG
+    bad = B.config_c(I.LLAMA8B.replace(head_dim=96))
+    assert L.po_workspace_bytes(C.byref(bad), 512, 512, C.byref(w), C.byref(s)) == B.PO_ERR_BAD_CONFIG
+    bad = B.config_c(I.LLAMA8B.replace(ffn_dim=14336 + 8))
+    assert L.po_workspace_bytes(C.byref(bad), 512, 512, C.byref(w), C.byref(s)) == B.PO_ERR_BAD_CONFIG
+    # po_create: misaligned or too-small arenas are refused before any HIP call
+    h = C.c_void_p()
+    assert L.po_create(C.byref(cc), 512, 512, 256 + 8, 1 << 30, 4096, 1 << 30, None, C.byref(h)) == B.PO_ERR_INVALID_ARG
+    assert L.po_create(C.byref(cc), 512, 512, 4096, 16, 8192, 1 << 30, None, C.byref(h)) == B.PO_ERR_WORKSPACE_TOO_SMALL
+    assert L.po_create(C.byref(cc), 512, 512, None, 1 << 30, 8192, 1 << 30, None, C.byref(h)) == B.PO_ERR_INVALID_ARG
+    # NULL context
+    assert L.po_prefill(None, None, 1, None, 0, None, None) == B.PO_ERR_INVALID_ARG
+    assert L.po_is_loaded(None) == 0
+    assert L.po_get_stats(None, None) == B.PO_ERR_INVALID_ARG
+    L.po_destroy(None)
+    # single-kernel entry points validate too
+    assert L.po_op_linear(B.PO_BF16, 4096, 4096, 4096, None, 8, 48, 64, None) == B.PO_ERR_BAD_CONFIG
+    assert L.po_op_linear(3, 4096, 4096, 4096, None, 8, 64, 64, None) == B.PO_ERR_INVALID_ARG
+    assert L.po_op_attention(B.PO_BF16, 4096, 4096, 4096, 4096, 4096, 8, 4, 2, 96, None) == B.PO_ERR_BAD_CONFIG
+    assert L.po_op_attention(B.PO_BF16, 4096, 4096, 4096, 4096, 4096, 8, 4, 3, 128, None) == B.PO_ERR_INVALID_ARG
