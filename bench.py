@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Prefill throughput of libpo on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: every request
+of the workload goes through po_prefill (embedding -> L x [norm, QKV, RoPE, attention over
+the whole sequence, O-proj, norm, chunked SwiGLU MLP] -> last-row norm + LM head -> label
+log-probs).  Default workload: the Llama-3-8B-shaped bf16 model on one 32768-token request,
+MLP chunk 4096 (the configuration the headline metric is quoted on).
+
+Prints ONE JSON line (see the keys below).  `value` is tokens/s with weights and workspace
+resident in HBM; the only host traffic inside the timed region is the 128 KiB of token ids
+going in and the logits coming out.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+import numpy as np
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
+PEAK_HBM_GBS = 8000.0
+
+
+def flop_model(cfg, lens, last_row_lm_head=True):
+    """Algorithmic flops: causal half of attention only, LM head on the last row only."""
+    lin = att = 0.0
+    per_tok = 2.0 * (cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) + cfg.q_dim * cfg.d_model
+                     + 3 * cfg.d_model * cfg.ffn_dim)
+    for n in lens:
+        n = float(n)
+        lin += cfg.n_layers * per_tok * n + 2.0 * cfg.d_model * cfg.vocab_size
+        att += cfg.n_layers * 4.0 * cfg.q_dim * n * (n + 1) / 2
+    return lin, att
+
+
+def cpu_baseline(cfg, wseed, tseed, full_lens, sample_layers, sample_tokens):
+    """Times the oracle as it stands on a bounded slice of the same workload (first
+    `sample_layers` layers x first `sample_tokens` tokens) and scales by the flop model."""
+    from oracle import prefill_oracle as O
+    import helpers as H
+    from paper_2505_07203_amd import inputs as I
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    scfg = cfg.replace(n_layers=sample_layers)
+    tokens = I.make_tokens(cfg, tseed, sample_tokens)
+    # only the embedding rows the sample reads are widened to fp64 (same values, less memory)
+    embed = I.stored_to_f64(I.make_tensor(cfg, wseed, I.KIND_EMBED, -1)[tokens])
+    layers = [H.oracle_layer(cfg, wseed, l) for l in range(sample_layers)]
+    t0 = time.perf_counter()
+    O.forward_hidden(np.arange(sample_tokens), embed, layers, scfg)
+    dt = time.perf_counter() - t0
+    lin_s, att_s = flop_model(scfg, [sample_tokens])
+    lin_s -= 2.0 * cfg.d_model * cfg.vocab_size          # the slice stops before the LM head
+    lin_f, att_f = flop_model(cfg, full_lens)
+    full_time = dt * (lin_f + att_f) / (lin_s + att_s)
+    return {"value": float(sum(full_lens)) / full_time, "unit": "tokens/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"fp64 numpy oracle, first {sample_layers} layer(s) x first {sample_tokens} tokens of the "
+                      f"same workload: {dt:.2f} s measured, extrapolated to the full workload by the flop model"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama8b_32k")
+    ap.add_argument("--layers", type=int, default=0, help="debug: override the layer count (invalidates the metric)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-phase-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (requests are independent; more GPUs run more "
+              "independent engine instances); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_07203_amd import binding as B
+    from paper_2505_07203_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    w = I.WORKLOADS[args.workload]
+    cfg = w["cfg"]
+    if args.layers:
+        cfg = cfg.replace(n_layers=args.layers)
+    lens = [int(x) for x in I.workload_lengths(args.workload)]
+    cand = I.label_ids(cfg)
+    reqs = [I.make_tokens(cfg, w["tseed"], n, request=i) for i, n in enumerate(lens)]
+
+    t0 = time.perf_counter()
+    ctx = B.Context(cfg, max(lens), w["chunk"])
+    ctx.load_synthetic(w["wseed"], threads=16)
+    load_s = time.perf_counter() - t0
+    ctx.po_set_phase_timing(not args.no_phase_timing)
+
+    def step():
+        att = lin = 0.0
+        for t in reqs:
+            ctx.po_prefill(t, cand, want_logits=len(reqs) == 1)
+            st = ctx.po_get_stats()
+            att += st["last_attention_ms"]
+            lin += st["last_linear_ms"]
+        return att, lin
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    att_ms = lin_ms = 0.0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        a, l = step()
+        att_ms += a
+        lin_ms += l
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens = sum(lens)
+    value = tokens * args.steps / elapsed
+    lin_f, att_f = flop_model(cfg, lens)
+    lm_head_f = 2.0 * cfg.d_model * cfg.vocab_size * len(lens)
+    gemm_f = lin_f - lm_head_f                  # flops that run in the MFMA GEMM kernel
+    att_ms /= args.steps
+    lin_ms /= args.steps
+    chunk = w["chunk"]
+    gemm_launches = sum(cfg.n_layers * 4 * ((n + chunk - 1) // chunk) for n in lens)
+    free_b, total_b = torch.cuda.mem_get_info()
+
+    out = {
+        "metric": "prefill tokens/s on 1 MI355X (8B-shape, 32k ctx)" if args.workload == "llama8b_32k" and not args.layers
+                  else f"prefill tokens/s on 1 MI355X ({args.workload})",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == I.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": cfg.n_layers, "d_model": cfg.d_model,
+                   "requests": len(lens), "tokens": tokens, "mlp_chunk": chunk,
+                   "weights": "random-init N(0,0.02), seeded"},
+        "end_to_end": {"algorithmic_tflop": (lin_f + att_f) / 1e12,
+                       "achieved_tflops": (lin_f + att_f) / 1e12 / (ms_per_step / 1e3),
+                       "frac_of_bf16_mfma_peak": (lin_f + att_f) / 1e12 / (ms_per_step / 1e3) / PEAK_BF16_TFLOPS},
+        "peak_hbm_bytes": {"weights_arena": ctx.weights_bytes, "workspace_arena": ctx.workspace_bytes,
+                           "device_in_use_after_run": int(total_b - free_b)},
+        "load_seconds": load_s,
+    }
+    if lin_ms > 0:
+        ach = gemm_f / 1e12 / (lin_ms / 1e3)
+        out["roofline"] = {"kernel": "gemm_bf16_mfma_kernel (QKV, O-proj, gate/up+SiLU, down; all launches)",
+                           "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                           "launches_per_step": gemm_launches, "avg_launch_ms": lin_ms / gemm_launches,
+                           "flop_per_launch_avg": gemm_f / gemm_launches}
+        ach_a = att_f / 1e12 / (att_ms / 1e3)
+        out["roofline_attention"] = {"kernel": "attn_fwd_kernel (+ V transpose), one launch per layer",
+                                     "bound": "mfma", "achieved": ach_a, "peak": PEAK_BF16_TFLOPS,
+                                     "unit": "TFLOP/s", "frac": ach_a / PEAK_BF16_TFLOPS,
+                                     "avg_launch_ms": att_ms / (cfg.n_layers * len(lens))}
+    ctx.po_destroy()
+    del ctx
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, w["wseed"], w["tseed"], lens, 1, 1024)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

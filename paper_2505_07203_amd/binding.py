@@ -66,6 +66,11 @@ def lib() -> C.CDLL:
         raise FileNotFoundError(
             f"{LIB_PATH} not found: build it first (python -m paper_2505_07203_amd.build); "
             "there is no fallback implementation")
+    # The arenas and the stream come from PyTorch, so libpo must bind to the SAME HIP runtime
+    # PyTorch uses (its wheel ships its own libamdhip64 with the same soname): importing torch
+    # first makes the loader resolve libpo's dependency to that already-loaded copy.  Loading
+    # libpo first would pull in a second, unrelated runtime that knows none of torch's pointers.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, i64, sz, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
     L.po_workspace_bytes.argtypes = [C.POINTER(ModelConfigC), i64, i32, C.POINTER(sz), C.POINTER(sz)]

@@ -357,8 +357,10 @@ po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t m
     c->stats.weights_bytes = c->lay.weights_bytes;
     c->stats.workspace_bytes = c->lay.workspace_bytes;
     c->ev_start = c->ev_stop = nullptr;
-    if (hipEventCreate(&c->ev_start) != hipSuccess || hipEventCreate(&c->ev_stop) != hipSuccess) {
-        snprintf(g_dev_err, sizeof(g_dev_err), "hipEventCreate failed");
+    hipError_t ee = hipEventCreate(&c->ev_start);
+    if (ee == hipSuccess) ee = hipEventCreate(&c->ev_stop);
+    if (ee != hipSuccess) {
+        snprintf(g_dev_err, sizeof(g_dev_err), "hipEventCreate: %s", hipGetErrorString(ee));
         if (c->ev_start) (void)hipEventDestroy(c->ev_start);
         delete c;
         return PO_ERR_DEVICE;
