@@ -88,35 +88,35 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
     const bf16_t* kbase = k + (int64_t)kvh * HD + kseg * 8;
     const bf16_t* vbase = vt + (int64_t)kvh * HD * ldv + vseg * 8;
     const int64_t krs = (int64_t)Hkv * HD;
+    // Prefetch registers: filled and drained unconditionally (the last iteration re-loads the
+    // final tile into the idle stage) so that they stay in VGPRs.
     uint4 rk[KLD], rv[VLD];
-    auto gload = [&](int j) {
-        const int kv0 = j * BNK;
-#pragma unroll
-        for (int i = 0; i < KLD; ++i) {
-            const int row = min(kv0 + krow0 + (NT / KSEG) * i, N - 1);
-            rk[i] = *(const uint4*)(kbase + (int64_t)row * krs);
-        }
-#pragma unroll
-        for (int i = 0; i < VLD; ++i) {
-            const int row = vrow0 + (NT / 8) * i;
-            rv[i] = *(const uint4*)(vbase + (int64_t)row * ldv + kv0);
-        }
-    };
-    auto sstore = [&](int stage) {
-        unsigned char* sk = smem + stage * STAGE_BYTES;
-        unsigned char* sv = sk + TILE_BYTES;
-#pragma unroll
-        for (int i = 0; i < KLD; ++i) {
-            const int row = krow0 + (NT / KSEG) * i;
-            const int ps = (KSEG == 16) ? (kseg ^ (row & 15)) : (kseg ^ swz8(row));
-            *(uint4*)(sk + row * (HD * 2) + (ps << 4)) = rk[i];
-        }
-#pragma unroll
-        for (int i = 0; i < VLD; ++i) {
-            const int row = vrow0 + (NT / 8) * i;
-            *(uint4*)(sv + row * 128 + ((vseg ^ swz8(row)) << 4)) = rv[i];
-        }
-    };
+#define PO_GLOAD(j_)                                                                   \
+    {                                                                                  \
+        const int kv0_ = (j_) * BNK;                                                   \
+        _Pragma("unroll") for (int i = 0; i < KLD; ++i) {                              \
+            const int row_ = min(kv0_ + krow0 + (NT / KSEG) * i, N - 1);               \
+            rk[i] = *(const uint4*)(kbase + (int64_t)row_ * krs);                      \
+        }                                                                              \
+        _Pragma("unroll") for (int i = 0; i < VLD; ++i) {                              \
+            const int row_ = vrow0 + (NT / 8) * i;                                     \
+            rv[i] = *(const uint4*)(vbase + (int64_t)row_ * ldv + kv0_);               \
+        }                                                                              \
+    }
+#define PO_SSTORE(stage_)                                                              \
+    {                                                                                  \
+        unsigned char* sk_ = smem + (stage_) * STAGE_BYTES;                            \
+        unsigned char* sv_ = sk_ + TILE_BYTES;                                         \
+        _Pragma("unroll") for (int i = 0; i < KLD; ++i) {                              \
+            const int row_ = krow0 + (NT / KSEG) * i;                                  \
+            const int ps_ = (KSEG == 16) ? (kseg ^ (row_ & 15)) : (kseg ^ swz8(row_)); \
+            *(uint4*)(sk_ + row_ * (HD * 2) + (ps_ << 4)) = rk[i];                     \
+        }                                                                              \
+        _Pragma("unroll") for (int i = 0; i < VLD; ++i) {                              \
+            const int row_ = vrow0 + (NT / 8) * i;                                     \
+            *(uint4*)(sv_ + row_ * 128 + ((vseg ^ swz8(row_)) << 4)) = rv[i];          \
+        }                                                                              \
+    }
 
     // K fragment rows: MFMA row i of a 32-key tile holds key pi(i) (bits 2,3 swapped)
     const int pk = (l31 & 0x13) | ((l31 & 4) << 1) | ((l31 & 8) >> 1);
@@ -134,12 +134,11 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) { mrow[qt] = -1.0e30f; lrow[qt] = 0.f; }
 
-    gload(0);
-    sstore(0);
+    PO_GLOAD(0);
+    PO_SSTORE(0);
     __syncthreads();
     for (int j = 0; j < n_kv_blk; ++j) {
-        const bool more = j + 1 < n_kv_blk;
-        if (more) gload(j + 1);
+        PO_GLOAD(min(j + 1, n_kv_blk - 1));
         if (j < n_kv_wave) {
             const unsigned char* sk = smem + (j & 1) * STAGE_BYTES;
             const unsigned char* sv = sk + TILE_BYTES;
@@ -229,9 +228,11 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
                 }
             }
         }
-        if (more) sstore((j + 1) & 1);
+        PO_SSTORE((j + 1) & 1);
         __syncthreads();
     }
+#undef PO_GLOAD
+#undef PO_SSTORE
 
     // ---- normalise and store: lane = query row, registers = head-dim rows
 #pragma unroll

@@ -88,24 +88,27 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     }
     const int st_off = lrow * 128 + ((lseg ^ swz8(lrow)) << 4);   // + 64*i rows = + 8192 i bytes
 
+    // The prefetch registers are plain locals filled and drained unconditionally (the last
+    // iteration re-loads the final K slice into the idle LDS stage): no branches around the
+    // loads, so they stay in VGPRs and their latency hides behind the MFMA work.
     uint4 ra[4], rw[4];
-    auto gload = [&](int kt) {
-        const int k0 = kt * BK;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ra[i] = *(const uint4*)(ga[i] + k0);
-            rw[i] = *(const uint4*)(gw[i] + k0);
-        }
-    };
-    auto sstore = [&](int stage) {
-        unsigned char* sa = smem + stage * STAGE_BYTES;
-        unsigned char* sw = sa + TILE_BYTES;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *(uint4*)(sa + st_off + i * 8192) = ra[i];
-            *(uint4*)(sw + st_off + i * 8192) = rw[i];
-        }
-    };
+#define PO_GLOAD(kt_)                                              \
+    {                                                              \
+        const int k0_ = (kt_) * BK;                                \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {            \
+            ra[i] = *(const uint4*)(ga[i] + k0_);                  \
+            rw[i] = *(const uint4*)(gw[i] + k0_);                  \
+        }                                                          \
+    }
+#define PO_SSTORE(stage_)                                          \
+    {                                                              \
+        unsigned char* sa_ = smem + (stage_) * STAGE_BYTES;        \
+        unsigned char* sw_ = sa_ + TILE_BYTES;                     \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {            \
+            *(uint4*)(sa_ + st_off + i * 8192) = ra[i];            \
+            *(uint4*)(sw_ + st_off + i * 8192) = rw[i];            \
+        }                                                          \
+    }
 
     f32x16 acc[4][2];
 #pragma unroll
@@ -121,12 +124,11 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     const int w_row_off = (wn * 64 + l31) * 128;
 
     const int KT = p.K / BK;
-    gload(0);
-    sstore(0);
+    PO_GLOAD(0);
+    PO_SSTORE(0);
     __syncthreads();
     for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 1 < KT;
-        if (more) gload(kt + 1);
+        PO_GLOAD(min(kt + 1, KT - 1));
         const unsigned char* sa = smem + (kt & 1) * STAGE_BYTES;
         const unsigned char* sw = sa + TILE_BYTES;
 #pragma unroll
@@ -143,9 +145,11 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
                 for (int ni = 0; ni < 2; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], wf[ni], acc[mi][ni], 0, 0, 0);
         }
-        if (more) sstore((kt + 1) & 1);
+        PO_SSTORE((kt + 1) & 1);
         __syncthreads();
     }
+#undef PO_GLOAD
+#undef PO_SSTORE
 
     // ---- epilogue.  Accumulator layout of a 32x32 tile: lane holds column (lane & 31),
     // register r holds row 8*(r/4) + 4*(lane/32) + (r%4).
