@@ -185,6 +185,29 @@ po_status po_op_attention(int32_t dtype, const void* dev_q, const void* dev_k, c
 po_status po_op_rope(int32_t dtype, void* dev_x, int64_t N, int32_t n_heads, int32_t head_dim,
                      float theta, void* hip_stream);
 
+/* cos/sin tables, fp32 [n, head_dim/2] each, of pos * theta^(-2i/head_dim) for positions
+ * 0..n-1 (angles formed in double precision). */
+po_status po_op_rope_table(float* dev_cos, float* dev_sin, int64_t n, int32_t head_dim, float theta,
+                           void* hip_stream);
+
+/* PO_BF16 only.  Builds the packed QKV weight [(Hq+2Hkv)*hd, K] (and bias, if the three bias
+ * pointers are given) the fused projection reads, from Wq [Hq*hd, K], Wk, Wv [Hkv*hd, K]:
+ * rows are concatenated and, inside every Q and K head, reordered so that the two halves of
+ * a rotary pair land in one accumulator lane. */
+po_status po_op_pack_qkv(const void* dev_wq, const void* dev_wk, const void* dev_wv, void* dev_wqkv,
+                         const void* dev_bq, const void* dev_bk, const void* dev_bv, void* dev_bqkv,
+                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t K, void* hip_stream);
+
+/* PO_BF16 only.  The fused step before attention for M consecutive tokens starting at
+ * sequence position pos0: [Q|K|V] = A Wqkv^T (+bias), rotary embedding applied to Q and K in
+ * fp32 before rounding; q [M, Hq*hd] and k [M, Hkv*hd] are written row-major, V is written
+ * transposed into columns pos0..pos0+M-1 of vt [Hkv*hd][ldv] (the layout the attention
+ * kernel reads).  dev_bqkv may be NULL. */
+po_status po_op_qkv_rope(const void* dev_a, const void* dev_wqkv, const void* dev_bqkv, void* dev_q, void* dev_k,
+                         void* dev_vt, int64_t ldv, const float* dev_cos, const float* dev_sin, int64_t pos0,
+                         int64_t M, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t K,
+                         void* hip_stream);
+
 /* Last-position LM head: logits[V] = x[d] . W[V, d]^T  (fp32 output). */
 po_status po_op_lm_head(int32_t dtype, const void* dev_x, const void* dev_w, float* dev_logits,
                         int32_t V, int32_t d, void* hip_stream);

@@ -31,7 +31,8 @@ EXPORTS = [
     "po_workspace_bytes", "po_create", "po_load_tensor", "po_is_loaded", "po_prefill",
     "po_prefill_batch", "po_set_phase_timing", "po_get_stats", "po_destroy", "po_strerror",
     "po_last_device_error", "po_op_rmsnorm", "po_op_linear", "po_op_gate_up_silu",
-    "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head",
+    "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head", "po_op_rope_table",
+    "po_op_pack_qkv", "po_op_qkv_rope",
 ]
 
 
@@ -94,6 +95,9 @@ def lib() -> C.CDLL:
     L.po_op_attention.argtypes = [i32, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
     L.po_op_rope.argtypes = [i32, vp, i64, i32, i32, f32, vp]
     L.po_op_lm_head.argtypes = [i32, vp, vp, vp, i32, i32, vp]
+    L.po_op_rope_table.argtypes = [vp, vp, i64, i32, f32, vp]
+    L.po_op_pack_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    L.po_op_qkv_rope.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i32, i32, i32, i32, vp]
     for name in EXPORTS:
         if name not in ("po_destroy", "po_strerror", "po_last_device_error"):
             getattr(L, name).restype = i32
@@ -291,3 +295,38 @@ def po_op_lm_head(x, w):
     z = torch.empty(V, dtype=torch.float32, device=w.device)
     check(lib().po_op_lm_head(_dt(x), x.data_ptr(), w.data_ptr(), z.data_ptr(), V, d, _stream()))
     return z
+
+
+def po_op_rope_table(n: int, head_dim: int, theta: float):
+    import torch
+    cos = torch.empty((n, head_dim // 2), dtype=torch.float32, device="cuda")
+    sin = torch.empty_like(cos)
+    check(lib().po_op_rope_table(cos.data_ptr(), sin.data_ptr(), n, head_dim, theta, _stream()))
+    return cos, sin
+
+
+def po_op_pack_qkv(wq, wk, wv, n_q_heads: int, n_kv_heads: int, head_dim: int, bq=None, bk=None, bv=None):
+    import torch
+    K = wq.shape[1]
+    rows = (n_q_heads + 2 * n_kv_heads) * head_dim
+    wqkv = torch.empty((rows, K), dtype=wq.dtype, device=wq.device)
+    bqkv = torch.empty(rows, dtype=wq.dtype, device=wq.device) if bq is not None else None
+    p = lambda t: None if t is None else t.data_ptr()
+    check(lib().po_op_pack_qkv(wq.data_ptr(), wk.data_ptr(), wv.data_ptr(), wqkv.data_ptr(), p(bq), p(bk), p(bv),
+                               p(bqkv), n_q_heads, n_kv_heads, head_dim, K, _stream()))
+    return wqkv, bqkv
+
+
+def po_op_qkv_rope(a, wqkv, bqkv, cos, sin, n_q_heads: int, n_kv_heads: int, head_dim: int, pos0: int = 0,
+                   vt=None):
+    """-> q [M, Hq*hd], k [M, Hkv*hd] (rotated), vt [Hkv*hd, ldv] with columns pos0..pos0+M-1 written"""
+    import torch
+    M, K = a.shape
+    q = torch.empty((M, n_q_heads * head_dim), dtype=a.dtype, device=a.device)
+    k = torch.empty((M, n_kv_heads * head_dim), dtype=a.dtype, device=a.device)
+    if vt is None:
+        vt = torch.zeros((n_kv_heads * head_dim, (pos0 + M + 63) // 64 * 64), dtype=a.dtype, device=a.device)
+    check(lib().po_op_qkv_rope(a.data_ptr(), wqkv.data_ptr(), None if bqkv is None else bqkv.data_ptr(),
+                               q.data_ptr(), k.data_ptr(), vt.data_ptr(), vt.shape[1], cos.data_ptr(),
+                               sin.data_ptr(), pos0, M, n_q_heads, n_kv_heads, head_dim, K, _stream()))
+    return q, k, vt

@@ -426,4 +426,32 @@ void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int6
     hipLaunchKernelGGL(v_transpose_kernel, grid, dim3(256), 0, s, V, Vt, n, kv_dim, ldv);
 }
 
+// ------------------------------------------------------------------ rotary row packing (bf16)
+// swap row blocks [32,64) and [64,96) of every 128-row head, in place
+__global__ void __launch_bounds__(256) pack_rope_rows_kernel(bf16_t* W, int64_t row_elems) {
+    const int head = blockIdx.y, r = blockIdx.x;       // r in [0, 32)
+    bf16_t* a = W + ((int64_t)head * 128 + 32 + r) * row_elems;
+    bf16_t* b = W + ((int64_t)head * 128 + 64 + r) * row_elems;
+    for (int64_t i = threadIdx.x; i < row_elems; i += 256) {
+        const bf16_t t = a[i];
+        a[i] = b[i];
+        b[i] = t;
+    }
+}
+
+void launch_pack_rope_rows(bf16_t* W, int n_heads, int hd, int64_t row_elems, hipStream_t s) {
+    if (hd != 128 || n_heads <= 0) return;
+    hipLaunchKernelGGL(pack_rope_rows_kernel, dim3(32, (unsigned)n_heads), dim3(256), 0, s, W, row_elems);
+}
+
+__global__ void __launch_bounds__(64) vt_pad_zero_kernel(bf16_t* Vt, int64_t ldv, int64_t n, int pad) {
+    if ((int)threadIdx.x < pad) Vt[(int64_t)blockIdx.x * ldv + n + threadIdx.x] = 0;
+}
+
+void launch_vt_pad_zero(bf16_t* Vt, int rows, int64_t ldv, int64_t n, hipStream_t s) {
+    const int pad = (int)(round_up64(n, 64) - n);
+    if (pad <= 0 || rows <= 0) return;
+    hipLaunchKernelGGL(vt_pad_zero_kernel, dim3((unsigned)rows), dim3(64), 0, s, Vt, ldv, n, pad);
+}
+
 }  // namespace po

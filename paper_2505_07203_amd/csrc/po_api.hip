@@ -109,7 +109,7 @@ po_status make_layout(const po_model_config* c, int64_t max_len, int32_t mlp_chu
     L->X = take(N * d * esz);
     L->Q = take(N * qd * esz);
     L->K = take(N * kvd * esz);
-    L->V = take(N * kvd * esz);
+    L->V = c->dtype == PO_F32 ? take(N * kvd * esz) : 0;   // bf16: V lives only as V^T
     L->Vt = c->dtype == PO_BF16 ? take(kvd * (size_t)L->ldv * esz) : 0;
     L->Xn = take(C * d * esz);
     L->H = take(C * F * esz);
@@ -205,6 +205,8 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
     if (n_cand > 0) PO_HIP(hipMemcpyAsync(ws + L.cand, cand, (size_t)n_cand * 4, hipMemcpyHostToDevice, s));
     PO_HIP(hipEventRecord(c->ev_start, s));
     launch_embed(dt, d_tok, c->w + L.embed, X, len, d, s);
+    // the last key tile of the attention reads V^T up to the next multiple of 64 positions
+    if (dt == PO_BF16) launch_vt_pad_zero((bf16_t*)(ws + L.Vt), kvd, L.ldv, len, s);
 
     for (int l = 0; l < m.n_layers; ++l) {
         const LayerOff& o = L.layers[l];
@@ -216,11 +218,10 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
             launch_rmsnorm(dt, X + (size_t)c0 * d * esz, c->w + o.attn_norm, Xn, rows, d, m.rms_eps, s);
             PhaseTimer pt(c, 1);
             if (dt == PO_BF16) {
-                GemmSeg segs[3] = {{Q + (size_t)c0 * qd * esz, qd, qd},
-                                   {K + (size_t)c0 * kvd * esz, kvd, qd + kvd},
-                                   {V + (size_t)c0 * kvd * esz, kvd, qd + 2 * kvd}};
-                launch_gemm_mfma(EPI_STORE, (const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, segs, 3,
-                                 (const bf16_t*)bqkv, nullptr, 0, rows, qd + 2 * kvd, d, s);
+                // one GEMM: RoPE applied to Q and K in the epilogue, V written as V^T
+                launch_gemm_qkv_rope((const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, (const bf16_t*)bqkv,
+                                     (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
+                                     (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, rows, qd, kvd, hd, d, s);
             } else {
                 launch_gemm_basic(dt, Xn, d, wqkv, d, Q + (size_t)c0 * qd * esz, qd, bqkv, nullptr, 0, rows, qd, d, s);
                 launch_gemm_basic(dt, Xn, d, wqkv + (size_t)qd * d * esz, d, K + (size_t)c0 * kvd * esz, kvd,
@@ -229,16 +230,16 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
                                   bqkv ? bqkv + (size_t)(qd + kvd) * esz : nullptr, nullptr, 0, rows, kvd, d, s);
             }
         }
-        launch_rope(dt, Q, qd, rc, rs, len, m.n_q_heads, hd, s);
-        launch_rope(dt, K, kvd, rc, rs, len, m.n_kv_heads, hd, s);
+        if (dt == PO_F32) {
+            launch_rope(dt, Q, qd, rc, rs, len, m.n_q_heads, hd, s);
+            launch_rope(dt, K, kvd, rc, rs, len, m.n_kv_heads, hd, s);
+        }
         // ---- attention over the whole sequence in one call; O overwrites Q
         {
             PhaseTimer pt(c, 0);
             if (dt == PO_BF16) {
-                bf16_t* Vt = (bf16_t*)(ws + L.Vt);
-                launch_v_transpose((const bf16_t*)V, Vt, len, kvd, L.ldv, s);
-                launch_attention_mfma((const bf16_t*)Q, (const bf16_t*)K, Vt, L.ldv, (bf16_t*)Q, len, m.n_q_heads,
-                                      m.n_kv_heads, hd, s);
+                launch_attention_mfma((const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)(ws + L.Vt), L.ldv,
+                                      (bf16_t*)Q, len, m.n_q_heads, m.n_kv_heads, hd, s);
             } else {
                 launch_attention_basic(dt, Q, K, V, Q, len, m.n_q_heads, m.n_kv_heads, hd, s);
             }
@@ -249,19 +250,17 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
             unsigned char* Xc = X + (size_t)c0 * d * esz;
             const unsigned char* Oc = Q + (size_t)c0 * qd * esz;
             if (dt == PO_BF16) {
-                GemmSeg xs = {Xc, d, d};
                 {
                     PhaseTimer pt(c, 1);
-                    launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)Oc, qd, (const bf16_t*)(c->w + o.wo), qd, &xs, 1,
-                                     nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
+                    launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)Oc, qd, (const bf16_t*)(c->w + o.wo), qd,
+                                     (bf16_t*)Xc, d, nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
                 }
                 launch_rmsnorm(dt, Xc, c->w + o.mlp_norm, Xn, rows, d, m.rms_eps, s);
                 PhaseTimer pt(c, 1);
-                GemmSeg hs = {H, F, F};
-                launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)Xn, d, (const bf16_t*)(c->w + o.wgu), d, &hs, 1, nullptr,
-                                 nullptr, 0, rows, 2 * F, d, s);
-                launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)H, F, (const bf16_t*)(c->w + o.wd), F, &xs, 1, nullptr,
-                                 (const bf16_t*)Xc, d, rows, d, F, s);
+                launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)Xn, d, (const bf16_t*)(c->w + o.wgu), d, (bf16_t*)H, F,
+                                 nullptr, nullptr, 0, rows, 2 * F, d, s);
+                launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)H, F, (const bf16_t*)(c->w + o.wd), F, (bf16_t*)Xc, d,
+                                 nullptr, (const bf16_t*)Xc, d, rows, d, F, s);
             } else {
                 unsigned char* GU = ws + L.GU;
                 {
@@ -419,6 +418,15 @@ po_status po_load_tensor(po_ctx* c, int32_t kind, int32_t layer, const void* hos
         PO_HIP(hipMemcpy2D(dst, 2 * blk, host, blk, blk, F / il, hipMemcpyHostToDevice));
     } else {
         PO_HIP(hipMemcpy(c->w + off, host, bytes, hipMemcpyHostToDevice));
+        if (m.dtype == PO_BF16 && (kind == PO_T_WQ || kind == PO_T_WK || kind == PO_T_BQ || kind == PO_T_BK)) {
+            // rotary partners (i, i + head_dim/2) are brought into one 64-row group so that the
+            // QKV GEMM can rotate them in its epilogue (see launch_pack_rope_rows)
+            const bool is_bias = kind == PO_T_BQ || kind == PO_T_BK;
+            const int heads = (kind == PO_T_WQ || kind == PO_T_BQ) ? m.n_q_heads : m.n_kv_heads;
+            launch_pack_rope_rows((bf16_t*)(c->w + off), heads, m.head_dim, is_bias ? 1 : (int64_t)d, c->stream);
+            PO_HIP(hipStreamSynchronize(c->stream));
+            PO_HIP(hipGetLastError());
+        }
     }
     c->loaded[is_global ? m.n_layers : layer] |= 1u << kind;
     return PO_OK;
@@ -526,8 +534,7 @@ po_status po_op_linear(int32_t dtype, const void* a, const void* w, void* cc, co
     if (bad_dtype(dtype) || !a || !w || !cc || M <= 0 || N <= 0 || K <= 0) return PO_ERR_INVALID_ARG;
     if (dtype == PO_BF16) {
         if (!gemm_mfma_supported(N, K)) return PO_ERR_BAD_CONFIG;
-        GemmSeg seg = {cc, N, N};
-        launch_gemm_mfma(residual ? EPI_RESIDUAL : EPI_STORE, (const bf16_t*)a, K, (const bf16_t*)w, K, &seg, 1,
+        launch_gemm_mfma(residual ? EPI_RESIDUAL : EPI_STORE, (const bf16_t*)a, K, (const bf16_t*)w, K, (bf16_t*)cc, N,
                          nullptr, (const bf16_t*)residual, N, M, N, K, (hipStream_t)stream);
     } else {
         launch_gemm_basic(dtype, a, K, w, K, cc, N, nullptr, residual, N, M, N, K, (hipStream_t)stream);
@@ -541,8 +548,7 @@ po_status po_op_gate_up_silu(int32_t dtype, const void* a, const void* wgu, void
     if (bad_dtype(dtype) || !a || !wgu || !h || M <= 0 || F <= 0 || K <= 0) return PO_ERR_INVALID_ARG;
     if (dtype == PO_BF16) {
         if (F % GU_INTERLEAVE_BF16 || !gemm_mfma_supported(2 * F, K)) return PO_ERR_BAD_CONFIG;
-        GemmSeg seg = {h, F, F};
-        launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)a, K, (const bf16_t*)wgu, K, &seg, 1, nullptr, nullptr, 0, M,
+        launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)a, K, (const bf16_t*)wgu, K, (bf16_t*)h, F, nullptr, nullptr, 0, M,
                          2 * F, K, (hipStream_t)stream);
     } else {
         if (!scratch) return PO_ERR_INVALID_ARG;
@@ -591,6 +597,52 @@ po_status po_op_rope(int32_t dtype, void* x, int64_t N, int32_t H, int32_t hd, f
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(tab);
     PO_HIP(e);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_rope_table(float* cos_t, float* sin_t, int64_t n, int32_t hd, float theta, void* stream) {
+    if (!cos_t || !sin_t || n <= 0 || hd <= 0 || hd % 2 || !(theta > 0.f)) return PO_ERR_INVALID_ARG;
+    launch_rope_table(cos_t, sin_t, n, hd, theta, (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_pack_qkv(const void* wq, const void* wk, const void* wv, void* wqkv, const void* bq, const void* bk,
+                         const void* bv, void* bqkv, int32_t Hq, int32_t Hkv, int32_t hd, int32_t K, void* stream) {
+    if (!wq || !wk || !wv || !wqkv || Hq <= 0 || Hkv <= 0 || K <= 0) return PO_ERR_INVALID_ARG;
+    if (hd != 64 && hd != 128) return PO_ERR_BAD_CONFIG;
+    const bool has_bias = bq || bk || bv;
+    if (has_bias && !(bq && bk && bv && bqkv)) return PO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t qd = (size_t)Hq * hd, kvd = (size_t)Hkv * hd, rb = (size_t)K * 2;
+    unsigned char* w = (unsigned char*)wqkv;
+    PO_HIP(hipMemcpyAsync(w, wq, qd * rb, hipMemcpyDeviceToDevice, s));
+    PO_HIP(hipMemcpyAsync(w + qd * rb, wk, kvd * rb, hipMemcpyDeviceToDevice, s));
+    PO_HIP(hipMemcpyAsync(w + (qd + kvd) * rb, wv, kvd * rb, hipMemcpyDeviceToDevice, s));
+    launch_pack_rope_rows((bf16_t*)w, Hq, hd, K, s);
+    launch_pack_rope_rows((bf16_t*)(w + qd * rb), Hkv, hd, K, s);
+    if (has_bias) {
+        unsigned char* b = (unsigned char*)bqkv;
+        PO_HIP(hipMemcpyAsync(b, bq, qd * 2, hipMemcpyDeviceToDevice, s));
+        PO_HIP(hipMemcpyAsync(b + qd * 2, bk, kvd * 2, hipMemcpyDeviceToDevice, s));
+        PO_HIP(hipMemcpyAsync(b + (qd + kvd) * 2, bv, kvd * 2, hipMemcpyDeviceToDevice, s));
+        launch_pack_rope_rows((bf16_t*)b, Hq, hd, 1, s);
+        launch_pack_rope_rows((bf16_t*)(b + qd * 2), Hkv, hd, 1, s);
+    }
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_qkv_rope(const void* a, const void* wqkv, const void* bqkv, void* q, void* k, void* vt, int64_t ldv,
+                         const float* cos_t, const float* sin_t, int64_t pos0, int64_t M, int32_t Hq, int32_t Hkv,
+                         int32_t hd, int32_t K, void* stream) {
+    if (!a || !wqkv || !q || !k || !vt || !cos_t || !sin_t || M <= 0 || pos0 < 0 || Hq <= 0 || Hkv <= 0 || K <= 0)
+        return PO_ERR_INVALID_ARG;
+    if ((hd != 64 && hd != 128) || !gemm_mfma_supported((Hq + 2 * Hkv) * hd, K)) return PO_ERR_BAD_CONFIG;
+    if (ldv < pos0 + M || ldv % 8) return PO_ERR_INVALID_ARG;
+    launch_gemm_qkv_rope((const bf16_t*)a, K, (const bf16_t*)wqkv, K, (const bf16_t*)bqkv, (bf16_t*)q, (bf16_t*)k,
+                         (bf16_t*)vt, ldv, cos_t, sin_t, pos0, M, Hq * hd, Hkv * hd, hd, K, (hipStream_t)stream);
     PO_HIP(hipGetLastError());
     return PO_OK;
 }

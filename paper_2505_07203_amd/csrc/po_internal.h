@@ -50,18 +50,27 @@ void launch_pack_gate_up(int dtype, const void* wg, const void* wu, void* wgu, i
                          hipStream_t s);
 
 // ---- launchers: bf16 MFMA kernels ------------------------------------------------------
-struct GemmSeg {           // one destination column segment of a GEMM output
-    void* ptr;             // base of the destination (element [row 0, col 0 of the segment])
-    int64_t ld;            // row stride in elements
-    int col_end;           // exclusive end column (in GEMM N coordinates) of this segment
-};
-enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SILU_MUL = 2 };
-// C = A[M,K] W[N,K]^T with bf16 MFMA.  EPI_STORE: up to 3 column segments, optional bias[N] (bf16).
-// EPI_RESIDUAL: seg[0] only; R added in fp32 (R may alias the destination).
-// EPI_SILU_MUL: W rows interleaved gate/up in blocks of 32; writes H[M, N/2] to seg[0].
-void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw,
-                      const GemmSeg* segs, int nseg, const bf16_t* bias, const bf16_t* R, int64_t ldr,
-                      int64_t M, int N, int K, hipStream_t s);
+enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SILU_MUL = 2, EPI_QKV_ROPE = 3 };
+// C[M,N] = A[M,K] W[N,K]^T with bf16 MFMA, fp32 accumulation.
+//   EPI_STORE    : C = acc (+ bias[N], bf16)
+//   EPI_RESIDUAL : C = acc + R  (added in fp32; R may alias C)
+//   EPI_SILU_MUL : W rows interleaved gate/up in blocks of 32; C[M, N/2] = silu(gate) * up
+void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* C, int64_t ldc,
+                      const bf16_t* bias, const bf16_t* R, int64_t ldr, int64_t M, int N, int K, hipStream_t s);
+// Fused QKV projection: [Q|K|V] = A Wqkv^T (+bias), rotary embedding applied to Q and K in
+// the fp32 epilogue, V written transposed.  Wqkv (and bias) rows must be in the packed order
+// of launch_pack_rope_rows.  Q, K point at the first row of this call (row stride qd / kvd);
+// Vt is the base of V^T [kvd][ldv] and the call writes columns pos0 .. pos0+M-1.
+void launch_gemm_qkv_rope(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
+                          bf16_t* Q, bf16_t* K, bf16_t* Vt, int64_t ldv, const float* rope_cos,
+                          const float* rope_sin, int64_t pos0, int64_t M, int qd, int kvd, int hd, int Kdim,
+                          hipStream_t s);
+// In place: within every head of `hd` rows (hd == 128 only; hd == 64 is already in order)
+// swap row blocks [32,64) and [64,96), so that rotary partners i and i + hd/2 sit 32 rows
+// apart inside one 64-row group.  row_elems = elements per row (1 for a bias vector).
+void launch_pack_rope_rows(bf16_t* W, int n_heads, int hd, int64_t row_elems, hipStream_t s);
+// zero columns [n, round_up(n,64)) of V^T [rows][ldv]
+void launch_vt_pad_zero(bf16_t* Vt, int rows, int64_t ldv, int64_t n, hipStream_t s);
 // Vt[Hkv*hd][ldv] = transpose of V[n, Hkv*hd]; columns n..round_up(n,64)-1 are zero-filled
 void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int64_t ldv, hipStream_t s);
 // causal GQA flash attention; q [N,Hq,hd], k [N,Hkv,hd], vt [Hkv*hd][ldv]; o may alias q

@@ -41,9 +41,11 @@ def expected_workspace(cfg, n, c):
     esz = 4 if cfg.dtype == I.F32 else 2
     al = lambda b: (b + 255) // 256 * 256
     c = min(c, n)
-    parts = [n * 4, n * cfg.d_model * esz, n * cfg.q_dim * esz, n * cfg.kv_dim * esz, n * cfg.kv_dim * esz]
-    if cfg.dtype == I.BF16:
+    parts = [n * 4, n * cfg.d_model * esz, n * cfg.q_dim * esz, n * cfg.kv_dim * esz]
+    if cfg.dtype == I.BF16:       # V is kept transposed only
         parts.append(cfg.kv_dim * ((n + 63) // 64 * 64) * esz)
+    else:
+        parts.append(n * cfg.kv_dim * esz)
     parts += [c * cfg.d_model * esz, c * cfg.ffn_dim * esz]
     if cfg.dtype == I.F32:
         parts.append(c * 2 * cfg.ffn_dim * esz)
@@ -73,8 +75,8 @@ def test_activation_footprint_slope_is_one_layer_of_kv():
     _, s1 = B.po_workspace_bytes(cfg, 65536, 4096)
     _, s2 = B.po_workspace_bytes(cfg, 131072, 4096)
     slope = (s2 - s1) / 65536
-    # X + Q/O + K + V + V^T (bf16) + rotary table + token id
-    assert slope == 2 * (4096 + 4096 + 3 * 1024) + 2 * 4 * 64 + 4
+    # X + Q/O + K + V^T (bf16) + rotary table + token id
+    assert slope == 2 * (4096 + 4096 + 2 * 1024) + 2 * 4 * 64 + 4
     _, s3 = B.po_workspace_bytes(cfg.replace(n_layers=64), 131072, 4096)
     assert s3 == s2
     all_layer_kv = 2 * cfg.n_layers * cfg.kv_dim * 2

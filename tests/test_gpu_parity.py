@@ -266,3 +266,31 @@ def test_errors_leave_outputs_untouched():
     assert e.value.status == B.PO_ERR_INVALID_ARG
     z, _ = ctx.po_prefill(tok)       # still usable afterwards
     assert np.isfinite(z).all()
+
+
+@pytest.mark.parametrize("Hq,Hkv,hd,K,M,pos0,bias", [(4, 2, 128, 256, 300, 0, 0), (8, 2, 64, 128, 257, 64, 1),
+                                                     (2, 1, 128, 64, 70, 4096 - 70, 1)])
+def test_op_qkv_rope(Hq, Hkv, hd, K, M, pos0, bias):
+    """The fused step before attention (projection + rotary embedding + transposed V) against
+    its definition: plain matmuls, oracle rope at the true positions, V untouched."""
+    rng = np.random.default_rng(Hq * hd + M)
+    qd, kvd = Hq * hd, Hkv * hd
+    a = rand_stored(rng, (M, K), I.BF16)
+    wq, wk, wv = (rand_stored(rng, (n, K), I.BF16, 0.1) for n in (qd, kvd, kvd))
+    bq, bk, bv = (rand_stored(rng, (n,), I.BF16, 0.5) if bias else None for n in (qd, kvd, kvd))
+    A = I.stored_to_f64(a)
+    pos = np.arange(pos0, pos0 + M)
+    lin = lambda w, b: A @ I.stored_to_f64(w).T + (I.stored_to_f64(b) if b is not None else 0.0)
+    q_ref = O.rope(lin(wq, bq).reshape(M, Hq, hd), pos, 500000.0).reshape(M, qd)
+    k_ref = O.rope(lin(wk, bk).reshape(M, Hkv, hd), pos, 500000.0).reshape(M, kvd)
+    v_ref = lin(wv, bv)
+    dev = lambda t: None if t is None else to_dev(t)
+    wqkv, bqkv = B.po_op_pack_qkv(to_dev(wq), to_dev(wk), to_dev(wv), Hq, Hkv, hd, dev(bq), dev(bk), dev(bv))
+    cos, sin = B.po_op_rope_table(pos0 + M, hd, 500000.0)
+    q, k, vt = B.po_op_qkv_rope(to_dev(a), wqkv, bqkv, cos, sin, Hq, Hkv, hd, pos0=pos0)
+    for got, ref in ((from_dev(q), q_ref), (from_dev(k), k_ref), (from_dev(vt)[:, pos0:pos0 + M].T, v_ref)):
+        assert np.max(np.abs(got - ref)) <= 6e-3 * np.max(np.abs(ref))
+    # columns of V^T outside [pos0, pos0 + M) are not touched
+    outside = np.ones(vt.shape[1], dtype=bool)
+    outside[pos0:pos0 + M] = False
+    assert np.all(from_dev(vt)[:, outside] == 0)
