@@ -88,34 +88,44 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
     const bf16_t* kbase = k + (int64_t)kvh * HD + kseg * 8;
     const bf16_t* vbase = vt + (int64_t)kvh * HD * ldv + vseg * 8;
     const int64_t krs = (int64_t)Hkv * HD;
-    // Prefetch registers: filled and drained unconditionally (the last iteration re-loads the
-    // final tile into the idle stage) so that they stay in VGPRs.
-    uint4 rk[KLD], rv[VLD];
-#define PO_GLOAD(j_)                                                                   \
-    {                                                                                  \
-        const int kv0_ = (j_) * BNK;                                                   \
-        _Pragma("unroll") for (int i = 0; i < KLD; ++i) {                              \
-            const int row_ = min(kv0_ + krow0 + (NT / KSEG) * i, N - 1);               \
-            rk[i] = *(const uint4*)(kbase + (int64_t)row_ * krs);                      \
-        }                                                                              \
-        _Pragma("unroll") for (int i = 0; i < VLD; ++i) {                              \
-            const int row_ = vrow0 + (NT / 8) * i;                                     \
-            rv[i] = *(const uint4*)(vbase + (int64_t)row_ * ldv + kv0_);               \
-        }                                                                              \
+    // Prefetch registers, plain scalars so that they stay in VGPRs: set r holds the tile that
+    // goes to LDS next, set n the one after it (prefetch distance 2, which covers the HBM/L2
+    // latency of the K/V stream).  Loads are unconditional; tile indices clamp to the last tile.
+    uint4 rk0, rk1, rk2, rk3, rv0, rv1, rv2, rv3, nk0, nk1, nk2, nk3, nv0, nv1, nv2, nv3;
+    rk1 = rv1 = nk1 = nv1 = rk2 = rk3 = rv2 = rv3 = nk2 = nk3 = nv2 = nv3 = make_uint4(0, 0, 0, 0);
+#define PO_KLOAD(i_) (*(const uint4*)(kbase + (int64_t)min(kv0_ + krow0 + (NT / KSEG) * (i_), N - 1) * krs))
+#define PO_VLOAD(i_) (*(const uint4*)(vbase + (int64_t)(vrow0 + (NT / 8) * (i_)) * ldv + kv0_))
+#define PO_GLOAD(P, j_)                                       \
+    {                                                         \
+        const int kv0_ = min((j_), n_kv_blk - 1) * BNK;       \
+        P##k0 = PO_KLOAD(0);                                  \
+        if (KLD > 1) P##k1 = PO_KLOAD(1);                     \
+        if (KLD > 2) { P##k2 = PO_KLOAD(2); P##k3 = PO_KLOAD(3); } \
+        P##v0 = PO_VLOAD(0);                                  \
+        if (VLD > 1) P##v1 = PO_VLOAD(1);                     \
+        if (VLD > 2) { P##v2 = PO_VLOAD(2); P##v3 = PO_VLOAD(3); } \
     }
-#define PO_SSTORE(stage_)                                                              \
-    {                                                                                  \
-        unsigned char* sk_ = smem + (stage_) * STAGE_BYTES;                            \
-        unsigned char* sv_ = sk_ + TILE_BYTES;                                         \
-        _Pragma("unroll") for (int i = 0; i < KLD; ++i) {                              \
-            const int row_ = krow0 + (NT / KSEG) * i;                                  \
-            const int ps_ = (KSEG == 16) ? (kseg ^ (row_ & 15)) : (kseg ^ swz8(row_)); \
-            *(uint4*)(sk_ + row_ * (HD * 2) + (ps_ << 4)) = rk[i];                     \
-        }                                                                              \
-        _Pragma("unroll") for (int i = 0; i < VLD; ++i) {                              \
-            const int row_ = vrow0 + (NT / 8) * i;                                     \
-            *(uint4*)(sv_ + row_ * 128 + ((vseg ^ swz8(row_)) << 4)) = rv[i];          \
-        }                                                                              \
+#define PO_KST(i_, val_)                                                                         \
+    {                                                                                            \
+        const int row_ = krow0 + (NT / KSEG) * (i_);                                             \
+        const int ps_ = (KSEG == 16) ? (kseg ^ (row_ & 15)) : (kseg ^ swz8(row_));               \
+        *(uint4*)(sk_ + row_ * (HD * 2) + (ps_ << 4)) = val_;                                    \
+    }
+#define PO_VST(i_, val_)                                                                         \
+    {                                                                                            \
+        const int row_ = vrow0 + (NT / 8) * (i_);                                                \
+        *(uint4*)(sv_ + row_ * 128 + ((vseg ^ swz8(row_)) << 4)) = val_;                         \
+    }
+#define PO_SSTORE(stage_)                                      \
+    {                                                          \
+        unsigned char* sk_ = smem + (stage_) * STAGE_BYTES;    \
+        unsigned char* sv_ = sk_ + TILE_BYTES;                 \
+        PO_KST(0, rk0);                                        \
+        if (KLD > 1) PO_KST(1, rk1);                           \
+        if (KLD > 2) { PO_KST(2, rk2); PO_KST(3, rk3); }       \
+        PO_VST(0, rv0);                                        \
+        if (VLD > 1) PO_VST(1, rv1);                           \
+        if (VLD > 2) { PO_VST(2, rv2); PO_VST(3, rv3); }       \
     }
 
     // K fragment rows: MFMA row i of a 32-key tile holds key pi(i) (bits 2,3 swapped)
@@ -134,11 +144,12 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) { mrow[qt] = -1.0e30f; lrow[qt] = 0.f; }
 
-    PO_GLOAD(0);
+    PO_GLOAD(r, 0);
     PO_SSTORE(0);
+    PO_GLOAD(r, 1);
+    PO_GLOAD(n, 2);
     __syncthreads();
     for (int j = 0; j < n_kv_blk; ++j) {
-        PO_GLOAD(min(j + 1, n_kv_blk - 1));
         if (j < n_kv_wave) {
             const unsigned char* sk = smem + (j & 1) * STAGE_BYTES;
             const unsigned char* sv = sk + TILE_BYTES;
@@ -228,11 +239,18 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
                 }
             }
         }
-        PO_SSTORE((j + 1) & 1);
+        PO_SSTORE((j + 1) & 1);              // tile j+1 (loaded two iterations ago)
+        rk0 = nk0; rk1 = nk1; rk2 = nk2; rk3 = nk3;
+        rv0 = nv0; rv1 = nv1; rv2 = nv2; rv3 = nv3;
+        PO_GLOAD(n, j + 3);
         __syncthreads();
     }
 #undef PO_GLOAD
 #undef PO_SSTORE
+#undef PO_KLOAD
+#undef PO_VLOAD
+#undef PO_KST
+#undef PO_VST
 
     // ---- normalise and store: lane = query row, registers = head-dim rows
 #pragma unroll
@@ -282,8 +300,8 @@ bool attention_mfma_supported(int Hq, int Hkv, int hd) {
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N,
                            int Hq, int Hkv, int hd, hipStream_t s) {
     if (N <= 0) return;
-    if (hd == 128) launch_t<128, 2, 4>(q, k, vt, ldv, o, N, Hq, Hkv, s);
-    else if (hd == 64) launch_t<64, 2, 4>(q, k, vt, ldv, o, N, Hq, Hkv, s);
+    if (hd == 128) launch_t<128, 1, 8>(q, k, vt, ldv, o, N, Hq, Hkv, s);
+    else if (hd == 64) launch_t<64, 1, 8>(q, k, vt, ldv, o, N, Hq, Hkv, s);
 }
 
 }  // namespace po
