@@ -3,17 +3,28 @@
 //   C[M, N] = A[M, K] * W[N, K]^T        A: activations (token-major), W: weights in the
 //                                        checkpoint layout [out, in]; both K-contiguous.
 //
-// Block tile 256 x 256 x 64, 512 threads = 8 wavefronts arranged 2 (M) x 4 (N); each
-// wavefront owns a 128 x 64 patch = 4 x 2 MFMA 32x32x16 tiles (128 fp32 accumulators per
-// lane).  Operand tiles go global -> registers -> LDS (16-byte segments, XOR-swizzled so
-// that both the 16-byte row writes and the MFMA fragment reads are bank-conflict free),
-// double-buffered in LDS with one barrier per K slice: the global loads of slice k+1 are
-// in flight while slice k is multiplied.
-//
-// Workgroups are dispatched round-robin over the 8 XCDs (each with a private L2), so the
-// block id is first split into (XCD, local index) and every XCD walks a contiguous range
-// of output tiles in groups of 4 M-tiles x consecutive N-tiles: the 32 tiles resident on
-// one XCD then share 4 activation panels and 8 weight panels through that XCD's L2.
+// Design (what bounds it: the matrix pipe, then LDS read bandwidth):
+//  * Block tile 256 x 256, 256 threads = 4 wavefronts (one per SIMD) arranged 2 x 2; each
+//    wavefront owns a 128 x 128 patch = 4 x 4 MFMA 32x32x16 tiles (256 fp32 accumulators per
+//    lane).  The large per-wavefront patch is what keeps LDS traffic down: 8 fragment reads
+//    feed 16 MFMAs per k-step (0.5 KiB of LDS reads per MFMA).
+//  * K is consumed in slices of 32.  Operand slices go straight from global memory into
+//    LDS (global_load_lds, 16 bytes per lane, no staging registers) through a ring of four
+//    32 KiB stages: the loads of slice k+4 are issued while slice k is multiplied, which
+//    covers HBM latency; one workgroup barrier per slice hands a stage over.
+//  * LDS layout: 64-byte rows (32 bf16), the four 16-byte segments of a row XOR-swizzled
+//    with (row >> 2) & 3, so that the MFMA fragment reads (16 lanes = 16 consecutive rows,
+//    same logical segment) touch 16 distinct 16-byte bank groups.  The DMA writes a
+//    wavefront's 64 x 16 bytes contiguously, so the swizzle is applied on the global side:
+//    lane l of a load fetches logical segment (l & 3) ^ swizzle(row).
+//  * Workgroups are dispatched round-robin over the 8 XCDs (each with a private L2), so the
+//    block id is first split into (XCD, local index) and every XCD walks a contiguous range
+//    of output tiles in groups of 4 M-tiles x consecutive N-tiles: the 32 tiles resident on
+//    one XCD share 4 activation panels and 8 weight panels through that XCD's L2.
+//  * The MFMA is issued as (W fragment) x (A fragment)^T: in an accumulator tile a lane
+//    holds ONE token row and four consecutive output features per register quad, so the
+//    epilogues (bias, residual add in fp32, SiLU-multiply of gate/up pairs, rotary embedding
+//    of Q/K pairs, transposed store of V) work on whole lanes and move 8 bytes at a time.
 //
 // A row's K reduction order is fixed by the kernel and independent of how M is tiled or
 // chunked, which is what makes the chunk-by-chunk evaluation of Section 4.2 bit-exact.
@@ -28,11 +39,12 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int NTHREADS = 512;
-constexpr int TILE_BYTES = BM * BK * 2;            // 32 KiB per operand per stage
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + W
-constexpr int SMEM_BYTES = 2 * STAGE_BYTES;        // double buffer: 128 KiB
+constexpr int BM = 256, BN = 256, BK = 32;
+constexpr int NTHREADS = 256;
+constexpr int NSTAGE = 4;
+constexpr int OPER_BYTES = BM * BK * 2;            // 16 KiB per operand per stage
+constexpr int STAGE_BYTES = 2 * OPER_BYTES;        // A + W
+constexpr int SMEM_BYTES = NSTAGE * STAGE_BYTES;   // 128 KiB
 constexpr int GROUP_M = 4;
 
 struct GemmParams {
@@ -53,11 +65,115 @@ struct GemmParams {
     int qd, kvd, hd;     // EPI_QKV_ROPE: segment widths and head size
 };
 
-// 16-byte segment swizzle inside a 128-byte tile row: a bijection on the 8 segments for
-// any 8 consecutive rows, and rows r, r+8 land in different (row parity, segment) slots.
-__device__ __forceinline__ int swz8(int row) { return (row & 7) ^ ((row >> 3) & 1); }
-
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
+    uint2 w;
+    w.x = (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+    w.y = (uint32_t)f2bf(c) | ((uint32_t)f2bf(d) << 16);
+    return w;
+}
+
+// Epilogue of one 64-column patch of one token row.  c0 / c1 are the accumulator tiles of
+// the patch's two 32-column sub-tiles; the lane holds features 8*(r/4) + 4*lhi + (r%4) of
+// each.  cb = first GEMM column of the patch (a multiple of 64).
+template <int EPI>
+__device__ __forceinline__ void epilogue_patch(const GemmParams& p, int row, int cb, int lhi, const f32x16& c0,
+                                               const f32x16& c1) {
+    if (EPI == EPI_SILU_MUL) {
+        // sub-tile 0 = gate, sub-tile 1 = up of the same 32 features (weight rows interleaved)
+        bf16_t* drow = p.dst + (int64_t)row * p.ld + cb / 2 + 4 * lhi;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+            *(uint2*)(drow + 8 * g4) =
+                pack4(silu_f(c0[4 * g4]) * c1[4 * g4], silu_f(c0[4 * g4 + 1]) * c1[4 * g4 + 1],
+                      silu_f(c0[4 * g4 + 2]) * c1[4 * g4 + 2], silu_f(c0[4 * g4 + 3]) * c1[4 * g4 + 3]);
+    } else if (EPI == EPI_QKV_ROPE) {
+        const int half = p.hd >> 1;
+        if (cb < p.qd + p.kvd) {
+            // Q or K patch: sub-tile 0 holds rotary index i, sub-tile 1 holds i + hd/2 (the
+            // weight rows were packed that way), so a pair sits in one lane, same register.
+            const bool is_q = cb < p.qd;
+            const int c = is_q ? cb : cb - p.qd;
+            const int head = c / p.hd;
+            const int patch = (c - head * p.hd) >> 6;
+            const int i0 = patch * 32 + 4 * lhi;             // rotary index of register quad 0
+            bf16_t* drow = (is_q ? p.dst + (int64_t)row * p.qd : p.dst_k + (int64_t)row * p.kvd) + head * p.hd + i0;
+            const float* ct = p.rope_cos + (p.pos0 + row) * half + i0;
+            const float* st = p.rope_sin + (p.pos0 + row) * half + i0;
+            const bf16_t* bp = p.bias ? p.bias + cb + 4 * lhi : nullptr;
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const float4 cs = *(const float4*)(ct + 8 * g4);
+                const float4 sn = *(const float4*)(st + 8 * g4);
+                const float cv[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
+                float lo[4], hi[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float a = c0[4 * g4 + e], b = c1[4 * g4 + e];
+                    if (bp) { a += bf2f(bp[8 * g4 + e]); b += bf2f(bp[32 + 8 * g4 + e]); }
+                    lo[e] = a * cv[e] - b * sv[e];
+                    hi[e] = b * cv[e] + a * sv[e];
+                }
+                *(uint2*)(drow + 8 * g4) = pack4(lo[0], lo[1], lo[2], lo[3]);
+                *(uint2*)(drow + half + 8 * g4) = pack4(hi[0], hi[1], hi[2], hi[3]);
+            }
+        } else {
+            // V patch: stored transposed, V^T[feature][position]; consecutive lanes are
+            // consecutive positions.
+            const int f0 = cb - p.qd - p.kvd + 4 * lhi;
+            bf16_t* dcol = p.dst_vt + p.pos0 + row;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int f = f0 + 8 * (r >> 2) + (r & 3);
+                float v0 = c0[r], v1 = c1[r];
+                if (p.bias) { v0 += bf2f(p.bias[p.qd + p.kvd + f]); v1 += bf2f(p.bias[p.qd + p.kvd + f + 32]); }
+                dcol[(int64_t)f * p.ldv] = f2bf(v0);
+                dcol[(int64_t)(f + 32) * p.ldv] = f2bf(v1);
+            }
+        }
+    } else {
+        // (N is a multiple of 64, so a patch is either wholly inside or wholly outside)
+        // The residual may alias the destination (in-place update of the residual stream):
+        // all eight 8-byte pieces of this lane are read before the first one is written,
+        // so the loads are issued back to back instead of one per store.
+        uint2 rw[2][4];
+        if (EPI == EPI_RESIDUAL) {
+            const bf16_t* rrow = p.R + (int64_t)row * p.ldr + cb + 4 * lhi;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) rw[ni][g4] = *(const uint2*)(rrow + ni * 32 + 8 * g4);
+        }
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const f32x16& cc = ni ? c1 : c0;
+            const int col = cb + ni * 32 + 4 * lhi;
+            bf16_t* drow = p.dst + (int64_t)row * p.ld + col;
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                float v[4] = {cc[4 * g4], cc[4 * g4 + 1], cc[4 * g4 + 2], cc[4 * g4 + 3]};
+                if (EPI == EPI_STORE && p.bias) {
+                    const uint2 bw = *(const uint2*)(p.bias + col + 8 * g4);
+                    v[0] += __uint_as_float(bw.x << 16); v[1] += __uint_as_float(bw.x & 0xffff0000u);
+                    v[2] += __uint_as_float(bw.y << 16); v[3] += __uint_as_float(bw.y & 0xffff0000u);
+                }
+                if (EPI == EPI_RESIDUAL) {
+                    v[0] += __uint_as_float(rw[ni][g4].x << 16); v[1] += __uint_as_float(rw[ni][g4].x & 0xffff0000u);
+                    v[2] += __uint_as_float(rw[ni][g4].y << 16); v[3] += __uint_as_float(rw[ni][g4].y & 0xffff0000u);
+                }
+                *(uint2*)(drow + 8 * g4) = pack4(v[0], v[1], v[2], v[3]);
+            }
+        }
+    }
+}
+
+// Stage hand-over: wait until this wavefront's global->LDS loads of the NEXT slice have
+// landed (all but the 16 youngest, i.e. the two slices after it, may stay in flight) and its
+// own LDS reads have returned, then meet the other wavefronts.  A plain __syncthreads() would
+// also wait for every load in flight and so cancel the prefetch distance; the "memory"
+// clobber keeps the compiler from moving LDS accesses across the barrier.
+#define PO_HANDOVER() asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
 template <int EPI>
 __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmParams p) {
@@ -78,205 +194,113 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, lhi = lane >> 5;
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave >> 1, wn = wave & 1;
 
-    // ---- global -> register staging: thread owns segment `lseg` of rows lrow + 64 i
-    const int lseg = tid & 7, lrow = tid >> 3;
+    // ---- global -> LDS map.  Load instruction i (0..3) of wavefront w fills rows
+    // (w*4 + i)*16 .. +15 of an operand slice: lane l -> row + l/4, physical segment l & 3,
+    // which holds logical segment (l & 3) ^ ((row >> 2) & 3).
     const bf16_t* ga[4];
     const bf16_t* gw[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int ra = min(m0 + lrow + 64 * i, p.M - 1);
-        const int rw = min(n0 + lrow + 64 * i, p.N - 1);
-        ga[i] = p.A + (int64_t)ra * p.lda + lseg * 8;
-        gw[i] = p.W + (int64_t)rw * p.ldw + lseg * 8;
+        const int row = (wave * 4 + i) * 16 + (lane >> 2);
+        const int lseg = (lane & 3) ^ ((row >> 2) & 3);
+        ga[i] = p.A + (int64_t)min(m0 + row, p.M - 1) * p.lda + lseg * 8;
+        gw[i] = p.W + (int64_t)min(n0 + row, p.N - 1) * p.ldw + lseg * 8;
     }
-    const int st_off = lrow * 128 + ((lseg ^ swz8(lrow)) << 4);   // + 64*i rows = + 8192 i bytes
-
-    // Two register sets hold the next two K slices (prefetch distance 2): the loads of slice
-    // k+2 / k+3 are in flight while slice k is multiplied, which covers HBM latency.  Loads
-    // and LDS stores are unconditional (slice indices clamp to the last slice, whose extra
-    // copies land in an LDS stage nobody reads again), so the sets stay in VGPRs.
-    uint4 a0_0, a0_1, a0_2, a0_3, w0_0, w0_1, w0_2, w0_3;     // register set 0
-    uint4 a1_0, a1_1, a1_2, a1_3, w1_0, w1_1, w1_2, w1_3;     // register set 1
-#define PO_GLOAD(S, kt_)                                           \
-    {                                                              \
-        const int k0_ = min((kt_), KT - 1) * BK;                   \
-        a##S##_0 = *(const uint4*)(ga[0] + k0_);                   \
-        w##S##_0 = *(const uint4*)(gw[0] + k0_);                   \
-        a##S##_1 = *(const uint4*)(ga[1] + k0_);                   \
-        w##S##_1 = *(const uint4*)(gw[1] + k0_);                   \
-        a##S##_2 = *(const uint4*)(ga[2] + k0_);                   \
-        w##S##_2 = *(const uint4*)(gw[2] + k0_);                   \
-        a##S##_3 = *(const uint4*)(ga[3] + k0_);                   \
-        w##S##_3 = *(const uint4*)(gw[3] + k0_);                   \
-    }
-#define PO_SSTORE(S, stage_)                                       \
-    {                                                              \
-        unsigned char* sa_ = smem + (stage_) * STAGE_BYTES + st_off; \
-        unsigned char* sw_ = sa_ + TILE_BYTES;                     \
-        *(uint4*)(sa_) = a##S##_0;                                 \
-        *(uint4*)(sw_) = w##S##_0;                                 \
-        *(uint4*)(sa_ + 8192) = a##S##_1;                          \
-        *(uint4*)(sw_ + 8192) = w##S##_1;                          \
-        *(uint4*)(sa_ + 16384) = a##S##_2;                         \
-        *(uint4*)(sw_ + 16384) = w##S##_2;                         \
-        *(uint4*)(sa_ + 24576) = a##S##_3;                         \
-        *(uint4*)(sw_ + 24576) = w##S##_3;                         \
-    }
-#define PO_COMPUTE(stage_)                                                                               \
-    {                                                                                                    \
-        const unsigned char* sa = smem + (stage_) * STAGE_BYTES;                                         \
-        const unsigned char* sw = sa + TILE_BYTES;                                                       \
-        _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                               \
-            const int seg_off = (((kk * 2 + lhi) ^ fsw) << 4);                                           \
-            bf16x8 af[4], wf[2];                                                                         \
-            _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                             \
-                af[mi] = *(const bf16x8*)(sa + a_row_off + mi * 4096 + seg_off);                         \
-            _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                                             \
-                wf[ni] = *(const bf16x8*)(sw + w_row_off + ni * 4096 + seg_off);                         \
-            _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                             \
-                _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                                         \
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], af[mi], acc[mi][ni], 0, 0, 0); \
-        }                                                                                                \
+    const int KT = p.K / BK;
+#define PO_ISSUE(kt_)                                                                                         \
+    {                                                                                                         \
+        const int t_ = min((kt_), KT - 1);                                                                    \
+        unsigned char* sa_ = smem + ((kt_) & (NSTAGE - 1)) * STAGE_BYTES + wave * 4096;                       \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                       \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ga[i] + t_ * BK), \
+                                             (__attribute__((address_space(3))) void*)(sa_ + i * 1024), 16, 0, 0); \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gw[i] + t_ * BK), \
+                                             (__attribute__((address_space(3))) void*)(sa_ + OPER_BYTES + i * 1024), 16, 0, 0); \
+        }                                                                                                     \
     }
 
-    f32x16 acc[4][2];
+    f32x16 acc[4][4];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    // fragment read offsets (bytes) for k-step 0; k-step kk toggles segment bits
-    const int fsw = swz8(l31);
-    const int a_row_off = (wm * 128 + l31) * 128;
-    const int w_row_off = (wn * 64 + l31) * 128;
-    const int KT = p.K / BK;
+    // fragment read offsets: row l31 of a 32-row tile, logical segment kk*2 + lhi
+    const int fsw = (l31 >> 2) & 3;
+    int f_off[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) f_off[kk] = l31 * 64 + (((kk * 2 + lhi) ^ fsw) << 4);
+    const int a_base = wm * 128 * 64;
+    const int w_base = OPER_BYTES + wn * 128 * 64;
 
-    PO_GLOAD(0, 0);
-    PO_SSTORE(0, 0);
-    PO_GLOAD(0, 1);
-    PO_GLOAD(1, 2);
-    __syncthreads();
-    for (int kt = 0; kt + 1 < KT; kt += 2) {
-        PO_COMPUTE(0);                       // slice kt
-        PO_SSTORE(0, 1);              // slice kt+1
-        PO_GLOAD(0, kt + 3);
-        __syncthreads();
-        PO_COMPUTE(1);                       // slice kt+1
-        PO_SSTORE(1, 0);              // slice kt+2
-        PO_GLOAD(1, kt + 4);
-        __syncthreads();
+    // Software pipeline inside the wavefront (there is only one per SIMD, so nothing else
+    // hides LDS latency): the fragments of the next k-step are requested BEFORE the 16 MFMAs of
+    // the current one are issued, and the slice barrier sits between the two k-steps of a
+    // slice, so each batch of fragment reads has a 16-MFMA block to hide behind:
+    //   16 MFMA (kt, 0) with reads (kt, k-step 1) issued inside | hand-over barrier |
+    //   DMA slice kt+4 | 16 MFMA (kt, 1) with reads (kt+1, k-step 0) issued inside
+    bf16x8 af0[4], wf0[4], af1[4], wf1[4];
+#define PO_FRAGS(AF, WF, st_, kk_)                                                                  \
+    {                                                                                               \
+        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                            \
+            AF[mi] = *(const bf16x8*)((st_) + a_base + mi * 2048 + f_off[kk_]);                     \
+        _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                            \
+            WF[ni] = *(const bf16x8*)((st_) + w_base + ni * 2048 + f_off[kk_]);                     \
     }
-    if (KT & 1) PO_COMPUTE(0);               // odd slice count: the last slice sits in stage 0
-#undef PO_GLOAD
-#undef PO_SSTORE
-#undef PO_COMPUTE
+#define PO_MFMA(AF, WF, lo_, hi_)                                                                  \
+    {                                                                                               \
+        _Pragma("unroll") for (int t = (lo_); t < (hi_); ++t)                                       \
+            acc[t >> 2][t & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[t & 3], AF[t >> 2], acc[t >> 2][t & 3], 0, 0, 0); \
+    }
+    PO_ISSUE(0);
+    PO_ISSUE(1);
+    PO_ISSUE(2);
+    PO_ISSUE(3);
+    asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");     // slice 0 has landed
+    PO_FRAGS(af0, wf0, smem, 0);
+    for (int kt = 0; kt < KT; ++kt) {
+        const unsigned char* st = smem + (kt & (NSTAGE - 1)) * STAGE_BYTES;
+        const unsigned char* stn = smem + ((kt + 1) & (NSTAGE - 1)) * STAGE_BYTES;
+        // (the fragment reads are issued a few MFMAs INTO the block that precedes their use:
+        // the wait the compiler places in front of a block then only covers reads that have
+        // had the rest of the previous block to complete)
+        PO_MFMA(af0, wf0, 0, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        PO_FRAGS(af1, wf1, st, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        PO_MFMA(af0, wf0, 4, 16);
+        __builtin_amdgcn_sched_barrier(0);
+        PO_HANDOVER();            // slice kt+1 has landed; everybody is done reading slice kt
+        PO_ISSUE(kt + 4);         // into the stage slice kt occupied
+        PO_MFMA(af1, wf1, 0, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        PO_FRAGS(af0, wf0, stn, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        PO_MFMA(af1, wf1, 4, 16);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#undef PO_ISSUE
+#undef PO_FRAGS
+#undef PO_MFMA
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the clamped tail loads
 
-    // ---- epilogue.  The MFMA is issued as (W fragment) x (A fragment)^T, so in a 32x32
-    // accumulator tile a lane holds ONE token row (lane & 31) and register r holds feature
-    // 8*(r/4) + 4*(lane/32) + (r%4): four consecutive features per register quad, which are
-    // combined, rounded and moved with 8-byte accesses.
+    // ---- epilogue: lane = token row, 64-column patches
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
         const int row = m0 + wm * 128 + mi * 32 + l31;
         if (row >= p.M) continue;
-        const int cb = n0 + wn * 64;                 // first column of this wavefront's patch
-        if (cb >= p.N) continue;
-        if (EPI == EPI_SILU_MUL) {
-            bf16_t* drow = p.dst + (int64_t)row * p.ld + cb / 2 + 4 * lhi;
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                float h[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) h[e] = silu_f(acc[mi][0][4 * g4 + e]) * acc[mi][1][4 * g4 + e];
-                uint2 w;
-                w.x = (uint32_t)f2bf(h[0]) | ((uint32_t)f2bf(h[1]) << 16);
-                w.y = (uint32_t)f2bf(h[2]) | ((uint32_t)f2bf(h[3]) << 16);
-                *(uint2*)(drow + 8 * g4) = w;
-            }
-        } else if (EPI == EPI_QKV_ROPE) {
-            const int half = p.hd >> 1;
-            if (cb < p.qd + p.kvd) {
-                // Q or K patch: sub-tile 0 holds rotary index i, sub-tile 1 holds i + hd/2 (the
-                // weight rows were packed that way), so a pair sits in one lane, same register.
-                const bool is_q = cb < p.qd;
-                const int c = is_q ? cb : cb - p.qd;
-                const int head = c / p.hd;
-                const int patch = (c - head * p.hd) >> 6;
-                const int i0 = patch * 32 + 4 * lhi;             // rotary index of register quad 0
-                bf16_t* drow = (is_q ? p.dst + (int64_t)row * p.qd : p.dst_k + (int64_t)row * p.kvd) +
-                               head * p.hd + i0;
-                const float* ct = p.rope_cos + (p.pos0 + row) * half + i0;
-                const float* st = p.rope_sin + (p.pos0 + row) * half + i0;
-                const bf16_t* bp = p.bias ? p.bias + cb + 4 * lhi : nullptr;
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const float4 cs = *(const float4*)(ct + 8 * g4);
-                    const float4 sn = *(const float4*)(st + 8 * g4);
-                    const float cv[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
-                    float lo[4], hi[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float a = acc[mi][0][4 * g4 + e], b = acc[mi][1][4 * g4 + e];
-                        if (bp) { a += bf2f(bp[8 * g4 + e]); b += bf2f(bp[32 + 8 * g4 + e]); }
-                        lo[e] = a * cv[e] - b * sv[e];
-                        hi[e] = b * cv[e] + a * sv[e];
-                    }
-                    uint2 w;
-                    w.x = (uint32_t)f2bf(lo[0]) | ((uint32_t)f2bf(lo[1]) << 16);
-                    w.y = (uint32_t)f2bf(lo[2]) | ((uint32_t)f2bf(lo[3]) << 16);
-                    *(uint2*)(drow + 8 * g4) = w;
-                    w.x = (uint32_t)f2bf(hi[0]) | ((uint32_t)f2bf(hi[1]) << 16);
-                    w.y = (uint32_t)f2bf(hi[2]) | ((uint32_t)f2bf(hi[3]) << 16);
-                    *(uint2*)(drow + half + 8 * g4) = w;
-                }
-            } else {
-                // V patch: stored transposed, V^T[feature][position]; consecutive lanes are
-                // consecutive positions.
-                const int f0 = cb - p.qd - p.kvd + 4 * lhi;
-                bf16_t* dcol = p.dst_vt + p.pos0 + row;
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int f = f0 + ni * 32 + 8 * (r >> 2) + (r & 3);
-                        float v = acc[mi][ni][r];
-                        if (p.bias) v += bf2f(p.bias[p.qd + p.kvd + f]);
-                        dcol[(int64_t)f * p.ldv] = f2bf(v);
-                    }
-            }
-        } else {
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const int col = cb + ni * 32 + 4 * lhi;
-                if (cb + ni * 32 >= p.N) continue;
-                bf16_t* drow = p.dst + (int64_t)row * p.ld + col;
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    float v[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][4 * g4 + e];
-                    if (EPI == EPI_STORE && p.bias) {
-                        const uint2 bw = *(const uint2*)(p.bias + col + 8 * g4);
-                        v[0] += __uint_as_float(bw.x << 16); v[1] += __uint_as_float(bw.x & 0xffff0000u);
-                        v[2] += __uint_as_float(bw.y << 16); v[3] += __uint_as_float(bw.y & 0xffff0000u);
-                    }
-                    if (EPI == EPI_RESIDUAL) {
-                        const uint2 rw = *(const uint2*)(p.R + (int64_t)row * p.ldr + col + 8 * g4);
-                        v[0] += __uint_as_float(rw.x << 16); v[1] += __uint_as_float(rw.x & 0xffff0000u);
-                        v[2] += __uint_as_float(rw.y << 16); v[3] += __uint_as_float(rw.y & 0xffff0000u);
-                    }
-                    uint2 w;
-                    w.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
-                    w.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
-                    *(uint2*)(drow + 8 * g4) = w;
-                }
-            }
+        for (int pt = 0; pt < 2; ++pt) {
+            const int cb = n0 + wn * 128 + pt * 64;
+            if (cb >= p.N) continue;
+            epilogue_patch<EPI>(p, row, cb, lhi, acc[mi][2 * pt], acc[mi][2 * pt + 1]);
         }
     }
 }
@@ -294,11 +318,7 @@ void launch_t(const GemmParams& p, hipStream_t s) {
     hipLaunchKernelGGL(gemm_bf16_mfma_kernel<EPI>, dim3((unsigned)(per_xcd * 8)), dim3(NTHREADS), SMEM_BYTES, s, p);
 }
 
-}  // namespace
-
-bool gemm_mfma_supported(int N, int K) { return K > 0 && K % BK == 0 && N > 0 && N % 32 == 0; }
-
-static GemmParams base_params(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, int64_t M, int N, int K) {
+GemmParams base_params(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, int64_t M, int N, int K) {
     GemmParams p;
     memset(&p, 0, sizeof(p));
     p.A = A; p.W = W; p.lda = lda; p.ldw = ldw;
@@ -307,6 +327,12 @@ static GemmParams base_params(const bf16_t* A, int64_t lda, const bf16_t* W, int
     p.nt = (N + BN - 1) / BN;
     return p;
 }
+
+}  // namespace
+
+// K must be a multiple of 64 (two 32-wide slices keep the 16-byte segments whole), N of 64
+// (the epilogues work on 64-column patches).
+bool gemm_mfma_supported(int N, int K) { return K > 0 && K % 64 == 0 && N > 0 && N % 64 == 0; }
 
 void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* C, int64_t ldc,
                       const bf16_t* bias, const bf16_t* R, int64_t ldr, int64_t M, int N, int K, hipStream_t s) {

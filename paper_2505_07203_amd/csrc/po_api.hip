@@ -79,6 +79,8 @@ po_status make_layout(const po_model_config* c, int64_t max_len, int32_t mlp_chu
     if (st != PO_OK) return st;
     if (max_len <= 0 || mlp_chunk <= 0) return PO_ERR_INVALID_ARG;
     if (max_len > (int64_t)1 << 24) return PO_ERR_TOO_LONG;
+    // the bf16 attention addresses one layer of K (and V^T) with 32-bit byte offsets
+    if (c->dtype == PO_BF16 && (max_len + 64) * c->n_kv_heads * c->head_dim * 2 >= ((int64_t)1 << 32)) return PO_ERR_TOO_LONG;
     const size_t esz = c->dtype == PO_F32 ? 4 : 2;
     const size_t d = c->d_model, F = c->ffn_dim, V = c->vocab_size;
     const size_t qd = (size_t)c->n_q_heads * c->head_dim, kvd = (size_t)c->n_kv_heads * c->head_dim;
@@ -575,6 +577,7 @@ po_status po_op_attention(int32_t dtype, const void* q, const void* k, const voi
     if (dtype == PO_BF16) {
         if (!attention_mfma_supported(Hq, Hkv, hd)) return PO_ERR_BAD_CONFIG;
         if (!scratch) return PO_ERR_INVALID_ARG;
+        if ((N + 64) * Hkv * hd * 2 >= ((int64_t)1 << 32)) return PO_ERR_TOO_LONG;
         const int64_t ldv = round_up64(N, 64);
         launch_v_transpose((const bf16_t*)v, (bf16_t*)scratch, N, Hkv * hd, ldv, (hipStream_t)stream);
         launch_attention_mfma((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)scratch, ldv, (bf16_t*)o, N, Hq, Hkv,
