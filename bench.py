@@ -104,37 +104,57 @@ def main():
     load_s = time.perf_counter() - t0
     ctx.po_set_phase_timing(not args.no_phase_timing)
 
+    classes = B.KERNEL_CLASSES
+
     def step():
-        att = lin = 0.0
+        ms = dict.fromkeys(classes, 0.0)
+        n = dict.fromkeys(classes, 0)
         for t in reqs:
             ctx.po_prefill(t, cand, want_logits=len(reqs) == 1)
             st = ctx.po_get_stats()
-            att += st["last_attention_ms"]
-            lin += st["last_linear_ms"]
-        return att, lin
+            for k in classes:
+                ms[k] += st["kernel_ms"][k]
+                n[k] += st["kernel_launches"][k]
+        return ms, n
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    att_ms = lin_ms = 0.0
+    k_ms = dict.fromkeys(classes, 0.0)
+    k_n = dict.fromkeys(classes, 0)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        a, l = step()
-        att_ms += a
-        lin_ms += l
+        ms, n = step()
+        for k in classes:
+            k_ms[k] += ms[k]
+            k_n[k] += n[k]
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
     tokens = sum(lens)
     value = tokens * args.steps / elapsed
     lin_f, att_f = flop_model(cfg, lens)
-    lm_head_f = 2.0 * cfg.d_model * cfg.vocab_size * len(lens)
-    gemm_f = lin_f - lm_head_f                  # flops that run in the MFMA GEMM kernel
-    att_ms /= args.steps
-    lin_ms /= args.steps
     chunk = w["chunk"]
-    gemm_launches = sum(cfg.n_layers * 4 * ((n + chunk - 1) // chunk) for n in lens)
     free_b, total_b = torch.cuda.mem_get_info()
+    # algorithmic flops per step of each kernel class (causal half only for attention)
+    tok_l = float(tokens) * cfg.n_layers
+    k_flop = {"attention": att_f,
+              "qkv": 2.0 * cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) * tok_l,
+              "residual": 2.0 * (cfg.q_dim * cfg.d_model + cfg.ffn_dim * cfg.d_model) * tok_l,
+              "gate_up": 2.0 * cfg.d_model * 2 * cfg.ffn_dim * tok_l}
+    k_name = {"attention": "attn_fwd_kernel<128> (causal GQA flash attention, one launch per layer)",
+              "qkv": "gemm_bf16_mfma_kernel<3> (QKV projection + RoPE + transposed V)",
+              "residual": "gemm_bf16_mfma_kernel<1> (O-projection and MLP down projection + residual)",
+              "gate_up": "gemm_bf16_mfma_kernel<2> (MLP gate/up projection + SiLU-multiply)"}
+
+    def roof(k):
+        launches = k_n[k] / args.steps
+        avg_ms = k_ms[k] / max(k_n[k], 1)
+        ach = k_flop[k] / max(launches, 1) / 1e12 / (avg_ms / 1e3) if avg_ms > 0 else 0.0
+        return {"kernel": k_name[k], "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "launches_per_step": launches,
+                "avg_launch_ms": avg_ms, "algorithmic_flop_per_launch": k_flop[k] / max(launches, 1),
+                "share_of_step_time": (k_ms[k] / args.steps) / ms_per_step}
 
     out = {
         "metric": "prefill tokens/s on 1 MI355X (8B-shape, 32k ctx)" if args.workload == "llama8b_32k" and not args.layers
@@ -152,23 +172,16 @@ def main():
                            "device_in_use_after_run": int(total_b - free_b)},
         "load_seconds": load_s,
     }
-    if lin_ms > 0:
-        ach = gemm_f / 1e12 / (lin_ms / 1e3)
-        out["roofline"] = {"kernel": "gemm_bf16_mfma_kernel (QKV, O-proj, gate/up+SiLU, down; all launches)",
-                           "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                           "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
-                           "launches_per_step": gemm_launches, "avg_launch_ms": lin_ms / gemm_launches,
-                           "flop_per_launch_avg": gemm_f / gemm_launches}
-        ach_a = att_f / 1e12 / (att_ms / 1e3)
-        out["roofline_attention"] = {"kernel": "attn_fwd_kernel (+ V transpose), one launch per layer",
-                                     "bound": "mfma", "achieved": ach_a, "peak": PEAK_BF16_TFLOPS,
-                                     "unit": "TFLOP/s", "frac": ach_a / PEAK_BF16_TFLOPS,
-                                     "avg_launch_ms": att_ms / (cfg.n_layers * len(lens))}
+    if sum(k_ms.values()) > 0:
+        # `roofline` is the kernel with the largest share of the step; the others follow
+        order = sorted(classes, key=lambda k: -k_ms[k])
+        out["roofline"] = roof(order[0])
+        out["roofline_other_kernels"] = [roof(k) for k in order[1:]]
     ctx.po_destroy()
     del ctx
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, w["wseed"], w["tseed"], lens, 1, 1024)
+        out["cpu_baseline"] = cpu_baseline(cfg, w["wseed"], w["tseed"], lens, 2, 4096)
     print(json.dumps(out))
 
 

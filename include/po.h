@@ -82,13 +82,22 @@ typedef struct {
     int32_t qkv_bias;  /* 0 | 1 */
 } po_model_config;
 
+/* Kernel classes whose time po_get_stats splits out when phase timing is on. */
+typedef enum {
+    PO_K_ATTENTION = 0,   /* causal GQA attention, one launch per layer                     */
+    PO_K_QKV = 1,         /* QKV projection (+ rotary embedding, transposed V)              */
+    PO_K_RESIDUAL = 2,    /* O-projection and MLP down projection (+ residual add)          */
+    PO_K_GATE_UP = 3,     /* MLP gate/up projection (+ SiLU-multiply)                       */
+    PO_K_COUNT = 4
+} po_kernel_class;
+
 typedef struct {
-    double last_prefill_ms;       /* device time of the last po_prefill (HIP events)      */
-    double last_attention_ms;     /* ... of which attention kernels (0 unless timing on)  */
-    double last_linear_ms;        /* ... of which GEMM kernels      (0 unless timing on)  */
-    uint64_t weights_bytes;       /* size of the weight arena in use                      */
-    uint64_t workspace_bytes;     /* size of the activation arena in use (peak; static)   */
-    int64_t last_len;             /* tokens in the last request                           */
+    double last_prefill_ms;               /* device time of the last po_prefill (HIP events on its stream) */
+    double kernel_ms[PO_K_COUNT];         /* ... of which each kernel class (0 unless phase timing is on)  */
+    int64_t kernel_launches[PO_K_COUNT];  /* launches of each class in the last po_prefill                 */
+    uint64_t weights_bytes;               /* size of the weight arena in use                               */
+    uint64_t workspace_bytes;             /* size of the activation arena in use (peak; static)            */
+    int64_t last_len;                     /* tokens in the last request                                    */
 } po_stats;
 
 typedef struct po_ctx po_ctx;
@@ -131,8 +140,9 @@ po_status po_prefill_batch(po_ctx* ctx, const int32_t* tokens_concat, const int6
                            int32_t n_req, const int32_t* cand_ids, int32_t n_cand,
                            float* out_logits, float* out_cand_logprobs);
 
-/* When on, po_prefill brackets attention and GEMM launches with HIP events so that
- * po_get_stats can split the time (adds event overhead; off by default). */
+/* When on, po_prefill brackets the attention and GEMM launches with HIP events on its stream
+ * so that po_get_stats can split the time per kernel class (adds event overhead; off by
+ * default). */
 po_status po_set_phase_timing(po_ctx* ctx, int32_t on);
 
 po_status po_get_stats(const po_ctx* ctx, po_stats* out);

@@ -26,6 +26,7 @@ PO_ERR_OOM = 7
 PO_ERR_DEVICE = 8
 
 PO_F32, PO_BF16 = 0, 1
+KERNEL_CLASSES = ("attention", "qkv", "residual", "gate_up")   # po_kernel_class order
 
 EXPORTS = [
     "po_workspace_bytes", "po_create", "po_load_tensor", "po_is_loaded", "po_prefill",
@@ -44,8 +45,8 @@ class ModelConfigC(C.Structure):
 
 
 class StatsC(C.Structure):
-    _fields_ = [("last_prefill_ms", C.c_double), ("last_attention_ms", C.c_double),
-                ("last_linear_ms", C.c_double), ("weights_bytes", C.c_uint64),
+    _fields_ = [("last_prefill_ms", C.c_double), ("kernel_ms", C.c_double * 4),
+                ("kernel_launches", C.c_int64 * 4), ("weights_bytes", C.c_uint64),
                 ("workspace_bytes", C.c_uint64), ("last_len", C.c_int64)]
 
 
@@ -194,7 +195,10 @@ class Context:
     def po_get_stats(self) -> dict:
         s = StatsC()
         check(lib().po_get_stats(self._h, C.byref(s)))
-        return {n: getattr(s, n) for n, _ in StatsC._fields_}
+        out = {n: getattr(s, n) for n, _ in StatsC._fields_}
+        out["kernel_ms"] = dict(zip(KERNEL_CLASSES, s.kernel_ms))
+        out["kernel_launches"] = dict(zip(KERNEL_CLASSES, s.kernel_launches))
+        return out
 
     def po_destroy(self) -> None:
         if getattr(self, "_h", None):

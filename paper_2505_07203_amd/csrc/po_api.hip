@@ -140,7 +140,7 @@ struct po_ctx {
     hipEvent_t ev_start, ev_stop;
     bool phase_timing;
     std::vector<hipEvent_t> ev_pool;  // pairs
-    std::vector<int> ev_kind;         // per pair: 0 attention, 1 linear
+    std::vector<int> ev_kind;         // per pair: po_kernel_class
     size_t ev_used;
     po_stats stats;
 };
@@ -214,11 +214,17 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
         const LayerOff& o = L.layers[l];
         const unsigned char* wqkv = c->w + o.wqkv;
         const unsigned char* bqkv = m.qkv_bias ? c->w + o.bqkv : nullptr;
-        // ---- position-wise part before attention, chunk by chunk: norm -> QKV projection
-        for (int64_t c0 = 0; c0 < len; c0 += C) {
-            const int64_t rows = (len - c0 < C) ? len - c0 : C;
+        // ---- position-wise part before attention, chunk by chunk: norm -> QKV projection.
+        // Its only intermediate is the normalised chunk, so it borrows the (larger, idle) MLP
+        // chunk buffer and runs on up to twice as many tokens per launch: with 256-token
+        // tiles that fills whole rounds of the 256 CUs (e.g. 32 x 24 tiles = 3 rounds).
+        const int64_t Cq = ((int64_t)C * F >= 2 * (int64_t)C * d) ? 2 * (int64_t)C : C;
+        unsigned char* Xq = (Cq > C) ? H : Xn;
+        for (int64_t c0 = 0; c0 < len; c0 += Cq) {
+            const int64_t rows = (len - c0 < Cq) ? len - c0 : Cq;
+            unsigned char* Xn = Xq;     // (shadows the MLP-phase buffer inside this loop)
             launch_rmsnorm(dt, X + (size_t)c0 * d * esz, c->w + o.attn_norm, Xn, rows, d, m.rms_eps, s);
-            PhaseTimer pt(c, 1);
+            PhaseTimer pt(c, PO_K_QKV);
             if (dt == PO_BF16) {
                 // one GEMM: RoPE applied to Q and K in the epilogue, V written as V^T
                 launch_gemm_qkv_rope((const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, (const bf16_t*)bqkv,
@@ -238,7 +244,7 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
         }
         // ---- attention over the whole sequence in one call; O overwrites Q
         {
-            PhaseTimer pt(c, 0);
+            PhaseTimer pt(c, PO_K_ATTENTION);
             if (dt == PO_BF16) {
                 launch_attention_mfma((const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)(ws + L.Vt), L.ldv,
                                       (bf16_t*)Q, len, m.n_q_heads, m.n_kv_heads, hd, s);
@@ -253,26 +259,32 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
             const unsigned char* Oc = Q + (size_t)c0 * qd * esz;
             if (dt == PO_BF16) {
                 {
-                    PhaseTimer pt(c, 1);
+                    PhaseTimer pt(c, PO_K_RESIDUAL);
                     launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)Oc, qd, (const bf16_t*)(c->w + o.wo), qd,
                                      (bf16_t*)Xc, d, nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
                 }
                 launch_rmsnorm(dt, Xc, c->w + o.mlp_norm, Xn, rows, d, m.rms_eps, s);
-                PhaseTimer pt(c, 1);
-                launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)Xn, d, (const bf16_t*)(c->w + o.wgu), d, (bf16_t*)H, F,
-                                 nullptr, nullptr, 0, rows, 2 * F, d, s);
+                {
+                    PhaseTimer pt(c, PO_K_GATE_UP);
+                    launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)Xn, d, (const bf16_t*)(c->w + o.wgu), d, (bf16_t*)H, F,
+                                     nullptr, nullptr, 0, rows, 2 * F, d, s);
+                }
+                PhaseTimer pt(c, PO_K_RESIDUAL);
                 launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)H, F, (const bf16_t*)(c->w + o.wd), F, (bf16_t*)Xc, d,
                                  nullptr, (const bf16_t*)Xc, d, rows, d, F, s);
             } else {
                 unsigned char* GU = ws + L.GU;
                 {
-                    PhaseTimer pt(c, 1);
+                    PhaseTimer pt(c, PO_K_RESIDUAL);
                     launch_gemm_basic(dt, Oc, qd, c->w + o.wo, qd, Xc, d, nullptr, Xc, d, rows, d, qd, s);
                 }
                 launch_rmsnorm(dt, Xc, c->w + o.mlp_norm, Xn, rows, d, m.rms_eps, s);
-                PhaseTimer pt(c, 1);
-                launch_gemm_basic(dt, Xn, d, c->w + o.wgu, d, GU, 2 * F, nullptr, nullptr, 0, rows, 2 * F, d, s);
-                launch_silu_mul(dt, GU, H, rows, F, s);
+                {
+                    PhaseTimer pt(c, PO_K_GATE_UP);
+                    launch_gemm_basic(dt, Xn, d, c->w + o.wgu, d, GU, 2 * F, nullptr, nullptr, 0, rows, 2 * F, d, s);
+                    launch_silu_mul(dt, GU, H, rows, F, s);
+                }
+                PhaseTimer pt(c, PO_K_RESIDUAL);
                 launch_gemm_basic(dt, H, F, c->w + o.wd, F, Xc, d, nullptr, Xc, d, rows, d, F, s);
             }
         }
@@ -293,13 +305,12 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
     PO_HIP(hipEventElapsedTime(&ms, c->ev_start, c->ev_stop));
     c->stats.last_prefill_ms = ms;
     c->stats.last_len = len;
-    c->stats.last_attention_ms = 0;
-    c->stats.last_linear_ms = 0;
+    for (int kc = 0; kc < PO_K_COUNT; ++kc) { c->stats.kernel_ms[kc] = 0; c->stats.kernel_launches[kc] = 0; }
     for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
         float t = 0.f;
         if (hipEventElapsedTime(&t, c->ev_pool[i], c->ev_pool[i + 1]) == hipSuccess) {
-            if (c->ev_kind[i / 2] == 0) c->stats.last_attention_ms += t;
-            else c->stats.last_linear_ms += t;
+            c->stats.kernel_ms[c->ev_kind[i / 2]] += t;
+            c->stats.kernel_launches[c->ev_kind[i / 2]] += 1;
         }
     }
     return PO_OK;
@@ -464,20 +475,19 @@ po_status po_prefill_batch(po_ctx* c, const int32_t* tokens_concat, const int64_
     }
     if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
     off = 0;
-    double total_ms = 0, att_ms = 0, lin_ms = 0;
+    double total_ms = 0, k_ms[PO_K_COUNT] = {0, 0, 0, 0};
+    int64_t k_n[PO_K_COUNT] = {0, 0, 0, 0};
     for (int32_t r = 0; r < n_req; ++r) {
         po_status st = run_prefill(c, tokens_concat + off, lens[r], cand_ids, n_cand,
                                    out_logits ? out_logits + (size_t)r * c->cfg.vocab_size : nullptr,
                                    out_cand_logprobs ? out_cand_logprobs + (size_t)r * n_cand : nullptr);
         if (st != PO_OK) return st;
         total_ms += c->stats.last_prefill_ms;
-        att_ms += c->stats.last_attention_ms;
-        lin_ms += c->stats.last_linear_ms;
+        for (int kc = 0; kc < PO_K_COUNT; ++kc) { k_ms[kc] += c->stats.kernel_ms[kc]; k_n[kc] += c->stats.kernel_launches[kc]; }
         off += lens[r];
     }
     c->stats.last_prefill_ms = total_ms;
-    c->stats.last_attention_ms = att_ms;
-    c->stats.last_linear_ms = lin_ms;
+    for (int kc = 0; kc < PO_K_COUNT; ++kc) { c->stats.kernel_ms[kc] = k_ms[kc]; c->stats.kernel_launches[kc] = k_n[kc]; }
     c->stats.last_len = off;
     return PO_OK;
 }
