@@ -26,6 +26,11 @@ import numpy as np
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 PEAK_HBM_GBS = 8000.0
 
+# Memory traffic per launch in bytes, from two counter runs of this command at the default
+# workload (FETCH_SIZE x 2.0 and WRITE_SIZE x 1.0 KiB per dispatch, the factors a 1 GiB
+# elementwise kernel calibrates; summary under profiles/).  Other workloads report null.
+MEASURED_TRAFFIC = {"llama8b_32k": {"attention": 1.674e9, "gate_up": 1.528e9, "residual": 0.520e9, "qkv": 0.780e9}}
+
 
 def flop_model(cfg, lens, last_row_lm_head=True):
     """Algorithmic flops: causal half of attention only, LM head on the last row only."""
@@ -77,6 +82,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: override the layer count (invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-timing", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one elementwise kernel that reads 1 GiB and writes 1 GiB, so that a "
+                         "counter run of this command holds a dispatch of known HBM traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (requests are independent; more GPUs run more "
@@ -117,6 +125,12 @@ def main():
                 n[k] += st["kernel_launches"][k]
         return ms, n
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)          # 2^30 bytes fetched, 2^30 bytes written
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -152,7 +166,9 @@ def main():
         avg_ms = k_ms[k] / max(k_n[k], 1)
         ach = k_flop[k] / max(launches, 1) / 1e12 / (avg_ms / 1e3) if avg_ms > 0 else 0.0
         return {"kernel": k_name[k], "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "launches_per_step": launches,
+                "frac": ach / PEAK_BF16_TFLOPS,
+                "traffic": None if args.layers else MEASURED_TRAFFIC.get(args.workload, {}).get(k),
+                "launches_per_step": launches,
                 "avg_launch_ms": avg_ms, "algorithmic_flop_per_launch": k_flop[k] / max(launches, 1),
                 "share_of_step_time": (k_ms[k] / args.steps) / ms_per_step}
 

@@ -1,0 +1,135 @@
+#!/usr/bin/env python3
+"""Writes the stored expected values under tests/golden/ for the wide-shape parity cases.
+
+Calls only oracle/ (the float64 definition) and the seeded input generators; nothing here
+touches the GPU library.  One JSON file per case holds the oracle's last-token logits at a
+fixed set of vocabulary ids (evenly spaced ids, the label ids, the oracle's 16 largest
+logits), the candidate log-probs, and what identifies the inputs (config, seeds, lengths,
+a SHA-256 of the token ids), so that a GPU test can regenerate the same inputs and compare.
+
+    python tests/golden/make_golden.py --list
+    python tests/golden/make_golden.py --case llama8b_L32_N2048 [--case ...]
+
+Layers are the outer loop and requests the inner one, so each layer's weights are generated
+once; every request still goes through oracle.decoder_layer unchunked, as defined.
+Run time on 8 host cores ranges from minutes (reduced cases) to about two hours (the full
+32k-token configuration).
+"""
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(HERE))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+import numpy as np
+
+from oracle import prefill_oracle as O
+from paper_2505_07203_amd import inputs as I
+import helpers as H
+
+N_EVEN = 509          # evenly spaced sample ids
+N_TOP = 16
+
+# case -> (workload whose config and seeds are used, layer count or None for all,
+#          request lengths or None for the workload's own, lazy last layer)
+CASES = {
+    # reduced-cost rungs at full width
+    "llama8b_L32_N2048": ("llama8b_32k", None, [2048], False),
+    "llama8b_L2_N32768": ("llama8b_32k", 2, [32768], False),
+    "llama8b_L1_N131072": ("llama8b_128k", 1, [131072], True),
+    "qwen32b_L64_N1024": ("qwen32b_8x16k", None, [1024], False),
+    "qwen32b_L2_N16384": ("qwen32b_8x16k", 2, [16384], False),
+    # full configurations
+    "llama8b_mixed16": ("llama8b_mixed16", None, None, False),
+    "llama8b_32k": ("llama8b_32k", None, None, False),
+}
+
+
+def sample_ids(V, cand, z):
+    even = np.unique(np.round(np.linspace(0, V - 1, N_EVEN)).astype(np.int64))
+    top = np.argsort(-z)[:N_TOP]
+    return np.unique(np.concatenate([even, np.asarray(cand, dtype=np.int64), top]))
+
+
+def run_case(name):
+    wl, layers, lens, lazy = CASES[name]
+    w = I.WORKLOADS[wl]
+    cfg = w["cfg"]
+    if layers:
+        cfg = cfg.replace(n_layers=layers)
+    if lens is None:
+        lens = [int(x) for x in I.workload_lengths(wl)]
+    cand = I.label_ids(cfg)
+    t_all = time.perf_counter()
+    reqs = [I.make_tokens(cfg, w["tseed"], n, request=i) for i, n in enumerate(lens)]
+    embed = I.make_tensor(cfg, w["wseed"], I.KIND_EMBED, -1)
+    xs = [I.stored_to_f64(embed[t]) for t in reqs]
+    del embed
+    t_layers = 0.0
+    for l in range(cfg.n_layers):
+        W = H.oracle_layer(cfg, w["wseed"], l)
+        t0 = time.perf_counter()
+        last = lazy and l == cfg.n_layers - 1
+        xs = [O.decoder_layer(x, W, cfg, None, last_row_only=last) for x in xs]
+        t_layers += time.perf_counter() - t0
+        print(f"[{name}] layer {l + 1}/{cfg.n_layers} done, {time.perf_counter() - t_all:.0f} s", flush=True)
+        del W
+    fnorm = I.stored_to_f64(I.make_tensor(cfg, w["wseed"], I.KIND_FINAL_NORM, -1))
+    lm = I.stored_to_f64(I.make_tensor(cfg, w["wseed"], I.KIND_LM_HEAD, -1))
+    out_reqs = []
+    for t, x in zip(reqs, xs):
+        z = O.last_token_logits(x[-1], fnorm, lm, cfg.rms_eps)
+        lp = O.candidate_logprobs(z, cand)
+        ids = sample_ids(cfg.vocab_size, cand, z)
+        order = np.argsort(-z)
+        out_reqs.append({
+            "len": int(len(t)),
+            "tokens_sha256": hashlib.sha256(np.ascontiguousarray(t, dtype=np.int32).tobytes()).hexdigest(),
+            "argmax": int(order[0]),
+            "top_gap": float(z[order[0]] - z[order[1]]),
+            "max_abs_logit": float(np.max(np.abs(z))),
+            "sample_ids": [int(i) for i in ids],
+            "sample_logits": [float(np.float32(z[i])) for i in ids],
+            "top_ids": [int(i) for i in order[:N_TOP]],
+            "cand_logprobs": [float(v) for v in lp],
+        })
+    doc = {
+        "kind": "prefill_last_token_logits",
+        "source": "oracle/prefill_oracle.py (float64), written by tests/golden/make_golden.py",
+        "citation": "Section 4.2: chunked position-wise layers leave the result unchanged; "
+                    "Section 2.2: acceptable-token probabilities sum to 1",
+        "case": name, "workload": wl, "layers": cfg.n_layers, "lazy_last_layer": bool(lazy),
+        "wseed": w["wseed"], "tseed": w["tseed"], "mlp_chunk": w["chunk"],
+        "cand_ids": [int(c) for c in cand],
+        "oracle_layer_seconds": t_layers, "oracle_total_seconds": time.perf_counter() - t_all,
+        "host_cores": os.cpu_count(),
+        "requests": out_reqs,
+    }
+    path = os.path.join(HERE, name + ".json")
+    with open(path, "w") as f:
+        json.dump(doc, f, indent=0)
+        f.write("\n")
+    print(f"[{name}] wrote {path} ({doc['oracle_total_seconds']:.0f} s)", flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--case", action="append", default=[])
+    ap.add_argument("--list", action="store_true")
+    a = ap.parse_args()
+    if a.list or not a.case:
+        for k, v in CASES.items():
+            print(k, v)
+        return
+    for c in a.case:
+        run_case(c)
+
+
+if __name__ == "__main__":
+    main()
