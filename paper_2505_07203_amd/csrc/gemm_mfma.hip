@@ -201,28 +201,34 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
 
     // ---- global -> LDS map.  Load instruction i (0..3) of wavefront w fills rows
     // (w*4 + i)*16 .. +15 of an operand slice: lane l -> row + l/4, physical segment l & 3,
-    // which holds logical segment (l & 3) ^ ((row >> 2) & 3).
-    const bf16_t* ga[4];
-    const bf16_t* gw[4];
+    // which holds logical segment (l & 3) ^ ((row >> 2) & 3).  Addresses are a wavefront-uniform
+    // 64-bit base (tile origin + slice) plus a 32-bit per-lane byte offset that never changes,
+    // so issuing a load costs no vector arithmetic.
+    const unsigned char* sA = (const unsigned char*)(p.A + (int64_t)m0 * p.lda);
+    const unsigned char* sW = (const unsigned char*)(p.W + (int64_t)n0 * p.ldw);
+    uint32_t voa[4], vow[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = (wave * 4 + i) * 16 + (lane >> 2);
         const int lseg = (lane & 3) ^ ((row >> 2) & 3);
-        ga[i] = p.A + (int64_t)min(m0 + row, p.M - 1) * p.lda + lseg * 8;
-        gw[i] = p.W + (int64_t)min(n0 + row, p.N - 1) * p.ldw + lseg * 8;
+        voa[i] = (uint32_t)min(row, p.M - 1 - m0) * (uint32_t)(p.lda * 2) + lseg * 16;
+        vow[i] = (uint32_t)min(row, p.N - 1 - n0) * (uint32_t)(p.ldw * 2) + lseg * 16;
     }
     const int KT = p.K / BK;
-#define PO_ISSUE(kt_)                                                                                         \
+    // one 16-byte-per-lane load of operand slice kt_: j_ = 0..3 activations, 4..7 weights
+#define PO_DMA(kt_, j_)                                                                                       \
     {                                                                                                         \
         const int t_ = min((kt_), KT - 1);                                                                    \
-        unsigned char* sa_ = smem + ((kt_) & (NSTAGE - 1)) * STAGE_BYTES + wave * 4096;                       \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                       \
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ga[i] + t_ * BK), \
-                                             (__attribute__((address_space(3))) void*)(sa_ + i * 1024), 16, 0, 0); \
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gw[i] + t_ * BK), \
-                                             (__attribute__((address_space(3))) void*)(sa_ + OPER_BYTES + i * 1024), 16, 0, 0); \
-        }                                                                                                     \
+        unsigned char* sa_ = smem + ((kt_) & (NSTAGE - 1)) * STAGE_BYTES + wave * 4096 + ((j_) & 3) * 1024 +  \
+                             ((j_) >> 2) * OPER_BYTES;                                                        \
+        const unsigned char* b_ = ((j_) >> 2 ? sW : sA) + t_ * (BK * 2);                                      \
+        asm volatile("" : "+s"(b_));  /* slice base stays scalar: address = SGPR pair + 32-bit lane offset */ \
+        const unsigned char* g_ = b_ + ((j_) >> 2 ? vow[(j_) & 3] : voa[(j_) & 3]);                           \
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g_,                  \
+                                         (__attribute__((address_space(3))) void*)sa_, 16, 0, 0);             \
     }
+#define PO_ISSUE(kt_)                                                                                         \
+    { _Pragma("unroll") for (int j = 0; j < 8; ++j) PO_DMA(kt_, j) }
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -240,55 +246,73 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     const int a_base = wm * 128 * 64;
     const int w_base = OPER_BYTES + wn * 128 * 64;
 
-    // Software pipeline inside the wavefront (there is only one per SIMD, so nothing else
-    // hides LDS latency): the fragments of the next k-step are requested BEFORE the 16 MFMAs of
-    // the current one are issued, and the slice barrier sits between the two k-steps of a
-    // slice, so each batch of fragment reads has a 16-MFMA block to hide behind:
-    //   16 MFMA (kt, 0) with reads (kt, k-step 1) issued inside | hand-over barrier |
-    //   DMA slice kt+4 | 16 MFMA (kt, 1) with reads (kt+1, k-step 0) issued inside
+    // Software pipeline inside the wavefront.  There is only one wavefront per SIMD, so every
+    // cycle it spends issuing something other than an MFMA while the matrix pipe is empty is
+    // lost, and the four wavefronts run in lockstep, so whatever they issue together queues
+    // up in the CU's single address unit.  Memory instructions are therefore issued ONE AT A
+    // TIME between MFMAs (a 32x32x16 MFMA keeps the pipe busy for 32 cycles) and the eight
+    // global->LDS loads of a slice are spread over two 16-MFMA blocks, one per four MFMAs:
+    //   block A(kt): 16 MFMA (kt, k-step 0); 8 fragment reads of (kt, k-step 1);
+    //                loads 4..7 (weights) of slice kt+3
+    //   hand-over barrier: slice kt+1 has landed, nobody reads slice kt's stage any more
+    //   block B(kt): 16 MFMA (kt, k-step 1); 8 fragment reads of (kt+1, k-step 0);
+    //                loads 0..3 (activations) of slice kt+4, into the stage slice kt occupied
+    // At the hand-over the loads issued after those of slice kt+1 are exactly the 16 of
+    // slices kt+2 and kt+3.
     bf16x8 af0[4], wf0[4], af1[4], wf1[4];
-#define PO_FRAGS(AF, WF, st_, kk_)                                                                  \
+#define PO_FRAG1(AF, WF, st_, kk_, j_)                                                              \
     {                                                                                               \
-        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                            \
-            AF[mi] = *(const bf16x8*)((st_) + a_base + mi * 2048 + f_off[kk_]);                     \
-        _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                            \
-            WF[ni] = *(const bf16x8*)((st_) + w_base + ni * 2048 + f_off[kk_]);                     \
+        if ((j_) < 4) AF[(j_) & 3] = *(const bf16x8*)((st_) + a_base + ((j_) & 3) * 2048 + f_off[kk_]); \
+        else          WF[(j_) & 3] = *(const bf16x8*)((st_) + w_base + ((j_) & 3) * 2048 + f_off[kk_]); \
     }
-#define PO_MFMA(AF, WF, lo_, hi_)                                                                  \
-    {                                                                                               \
-        _Pragma("unroll") for (int t = (lo_); t < (hi_); ++t)                                       \
-            acc[t >> 2][t & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[t & 3], AF[t >> 2], acc[t >> 2][t & 3], 0, 0, 0); \
-    }
+#define PO_MFMA1(AF, WF, t_)                                                                        \
+    acc[(t_) >> 2][(t_) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[(t_) & 3], AF[(t_) >> 2], acc[(t_) >> 2][(t_) & 3], 0, 0, 0);
+    // slot t of a block: fragment read number, or -1 (reads go in the order of first use:
+    // MFMA t needs AF[t >> 2] and WF[t & 3])
+#define PO_READ_SLOT(t_) ((t_) == 0 ? 0 : (t_) == 1 ? 4 : (t_) == 3 ? 5 : (t_) == 4 ? 6 : (t_) == 5 ? 7 : \
+                          (t_) == 7 ? 1 : (t_) == 8 ? 2 : (t_) == 9 ? 3 : -1)
     PO_ISSUE(0);
     PO_ISSUE(1);
     PO_ISSUE(2);
-    PO_ISSUE(3);
-    asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");     // slice 0 has landed
-    PO_FRAGS(af0, wf0, smem, 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) PO_DMA(3, j);
+    asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");     // slice 0 has landed
+#pragma unroll
+    for (int j = 0; j < 8; ++j) PO_FRAG1(af0, wf0, smem, 0, j);
     for (int kt = 0; kt < KT; ++kt) {
         const unsigned char* st = smem + (kt & (NSTAGE - 1)) * STAGE_BYTES;
         const unsigned char* stn = smem + ((kt + 1) & (NSTAGE - 1)) * STAGE_BYTES;
-        // (the fragment reads are issued a few MFMAs INTO the block that precedes their use:
-        // the wait the compiler places in front of a block then only covers reads that have
-        // had the rest of the previous block to complete)
-        PO_MFMA(af0, wf0, 0, 4);
-        __builtin_amdgcn_sched_barrier(0);
-        PO_FRAGS(af1, wf1, st, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        PO_MFMA(af0, wf0, 4, 16);
-        __builtin_amdgcn_sched_barrier(0);
-        PO_HANDOVER();            // slice kt+1 has landed; everybody is done reading slice kt
-        PO_ISSUE(kt + 4);         // into the stage slice kt occupied
-        PO_MFMA(af1, wf1, 0, 4);
-        __builtin_amdgcn_sched_barrier(0);
-        PO_FRAGS(af0, wf0, stn, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        PO_MFMA(af1, wf1, 4, 16);
-        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            PO_MFMA1(af0, wf0, t);
+            __builtin_amdgcn_sched_barrier(0);
+            if (PO_READ_SLOT(t) >= 0) {
+                PO_FRAG1(af1, wf1, st, 1, PO_READ_SLOT(t));
+                __builtin_amdgcn_sched_barrier(0);
+            } else if ((t & 3) == 2) {
+                PO_DMA(kt + 3, 4 + (t >> 2));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        PO_HANDOVER();
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            PO_MFMA1(af1, wf1, t);
+            __builtin_amdgcn_sched_barrier(0);
+            if (PO_READ_SLOT(t) >= 0) {
+                PO_FRAG1(af0, wf0, stn, 0, PO_READ_SLOT(t));
+                __builtin_amdgcn_sched_barrier(0);
+            } else if ((t & 3) == 2) {
+                PO_DMA(kt + 4, t >> 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
     }
+#undef PO_READ_SLOT
 #undef PO_ISSUE
-#undef PO_FRAGS
-#undef PO_MFMA
+#undef PO_DMA
+#undef PO_FRAG1
+#undef PO_MFMA1
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the clamped tail loads
 
     // ---- epilogue: lane = token row, 64-column patches

@@ -6,6 +6,19 @@ masked explicitly.  It exists only to pin oracle/prefill_oracle.py (tests/test_o
 it imports neither the oracle nor the HIP binding.  Usable for N <= ~16, d <= ~32.
 """
 import math
+import struct
+
+
+def bf16_scalar(v):
+    """Nearest bfloat16 of a Python float, ties to even, by way of the float32 bit pattern
+    (pure-Python counterpart of the oracle's array rounding)."""
+    (u,) = struct.unpack("<I", struct.pack("<f", v))     # struct rounds to float32, ties to even
+    low = u & 0xFFFF
+    u >>= 16
+    if low > 0x8000 or (low == 0x8000 and (u & 1)):
+        u += 1
+    (out,) = struct.unpack("<f", struct.pack("<I", (u << 16) & 0xFFFFFFFF))
+    return out
 
 
 def _dot(a, b):
@@ -37,10 +50,15 @@ def _rope_vec(u, t, theta):
     return out
 
 
-def forward_last_logits(tokens, embed, layers, final_norm, lm_head, cfg):
+def forward_last_logits(tokens, embed, layers, final_norm, lm_head, cfg, store=None):
     """tokens: list[int]; embed/lm_head: nested lists [V][d]; layers: list of dicts of
     nested lists keyed like the oracle ("attn_norm","wq","wk","wv","wo","mlp_norm","wg",
-    "wu","wd", optional "bq","bk","bv").  Returns (logits list [V], hidden rows [N][d])."""
+    "wu","wd", optional "bq","bk","bv").  Returns (logits list [V], hidden rows [N][d]).
+    `store` (optional scalar function) is applied to every element of the tensors kept
+    between operators: both normalised activations, rotated Q and K, V, the attention
+    output, the gated MLP intermediate and the residual stream after each update."""
+    def st(vec):
+        return vec if store is None else [store(e) for e in vec]
     N = len(tokens)
     hd, Hq, Hkv = cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads
     G = Hq // Hkv
@@ -50,17 +68,17 @@ def forward_last_logits(tokens, embed, layers, final_norm, lm_head, cfg):
         k = [[None] * Hkv for _ in range(N)]
         v = [[None] * Hkv for _ in range(N)]
         for t in range(N):
-            a = _rmsnorm(x[t], W["attn_norm"], cfg.rms_eps)
+            a = st(_rmsnorm(x[t], W["attn_norm"], cfg.rms_eps))
             qf, kf, vf = _matvec(W["wq"], a), _matvec(W["wk"], a), _matvec(W["wv"], a)
             if cfg.qkv_bias:
                 qf = [p + b for p, b in zip(qf, W["bq"])]
                 kf = [p + b for p, b in zip(kf, W["bk"])]
                 vf = [p + b for p, b in zip(vf, W["bv"])]
             for h in range(Hq):
-                q[t][h] = _rope_vec(qf[h * hd:(h + 1) * hd], t, cfg.rope_theta)
+                q[t][h] = st(_rope_vec(qf[h * hd:(h + 1) * hd], t, cfg.rope_theta))
             for c in range(Hkv):
-                k[t][c] = _rope_vec(kf[c * hd:(c + 1) * hd], t, cfg.rope_theta)
-                v[t][c] = vf[c * hd:(c + 1) * hd]
+                k[t][c] = st(_rope_vec(kf[c * hd:(c + 1) * hd], t, cfg.rope_theta))
+                v[t][c] = st(vf[c * hd:(c + 1) * hd])
         for t in range(N):
             o = []
             for h in range(Hq):
@@ -78,12 +96,12 @@ def forward_last_logits(tokens, embed, layers, final_norm, lm_head, cfg):
                     for j in range(hd):
                         oh[j] += p * v[s][c][j]
                 o += oh
-            att = _matvec(W["wo"], o)
-            x[t] = [xi + ai for xi, ai in zip(x[t], att)]
-            m = _rmsnorm(x[t], W["mlp_norm"], cfg.rms_eps)
+            att = _matvec(W["wo"], st(o))
+            x[t] = st([xi + ai for xi, ai in zip(x[t], att)])
+            m = st(_rmsnorm(x[t], W["mlp_norm"], cfg.rms_eps))
             gate, up = _matvec(W["wg"], m), _matvec(W["wu"], m)
-            hmid = [gv / (1.0 + math.exp(-gv)) * uv for gv, uv in zip(gate, up)]
+            hmid = st([gv / (1.0 + math.exp(-gv)) * uv for gv, uv in zip(gate, up)])
             y = _matvec(W["wd"], hmid)
-            x[t] = [xi + yi for xi, yi in zip(x[t], y)]
-    xn = _rmsnorm(x[N - 1], final_norm, cfg.rms_eps)
+            x[t] = st([xi + yi for xi, yi in zip(x[t], y)])
+    xn = st(_rmsnorm(x[N - 1], final_norm, cfg.rms_eps))
     return _matvec(lm_head, xn), x

@@ -1,11 +1,19 @@
 """Wide-shape parity: libpo against stored float64-oracle results (tests/golden/*.json).
 
-Each file was written by tests/golden/make_golden.py from oracle/ alone.  The inputs are
+Each file was written by tests/golden/make_golden.py from oracle/ alone and holds two
+evaluations of the definition: "exact" (nothing rounded) and "stored_bf16" (every tensor kept
+between operators rounded to bfloat16, as a bf16 model stores them).  The inputs are
 regenerated here from the recorded seeds (and checked against the recorded SHA-256 of the
 token ids), run through po_prefill at the recorded chunk size, and compared at the stored
-vocabulary ids.  Bar (bf16 path): max|got - oracle| / max|oracle| <= 2e-2 over the stored
-ids (normalised by the oracle's largest logit over the whole vocabulary), the same top-1
-token, the same preferred label, and the label log-prob difference within 2e-2 * max|oracle|.
+vocabulary ids.
+
+Bar (bf16 path), with err(a, b) = max|a - b| / max|oracle logit over the vocabulary|:
+  * against "stored_bf16": err <= 2e-2, the same top-1 token, the same preferred label, the
+    label log-prob difference within 2e-2 * max|oracle|;
+  * against "exact": err <= max(2e-2, 2 * err(stored_bf16, exact)).  A deep randomly
+    initialised decoder amplifies each 2^-9 rounding of a stored activation; how far ANY
+    bf16-storing evaluation lands from the exact one is measured by the oracle's own two
+    evaluations, and the GPU path may not be further away than twice that.
 
 Top-1 rule: when the oracle's own gap between its two largest logits is below the error the
 tolerance allows (2 * 2e-2 * max|oracle|) several answers are correct; then the GPU's
@@ -32,6 +40,30 @@ def _load(path):
         return json.load(f)
 
 
+def _err(z, block):
+    ids = np.asarray(block["sample_ids"])
+    ref = np.asarray(block["sample_logits"], dtype=np.float64)
+    return float(np.max(np.abs(z[ids].astype(np.float64) - ref)) / block["max_abs_logit"])
+
+
+def _check_block(case, i, z, lp, block, tol):
+    scale = block["max_abs_logit"]
+    err = _err(z, block)
+    assert err <= tol, (case, i, err, tol)
+    top = int(np.argmax(z))
+    if block["top_gap"] >= 2 * tol * scale:
+        assert top == block["argmax"], (case, i, top, block["argmax"])
+    else:
+        ref_by_id = dict(zip(block["sample_ids"], block["sample_logits"]))
+        ok = [j for j in block["top_ids"] if ref_by_id[block["argmax"]] - ref_by_id[j] <= 2 * tol * scale]
+        assert top in ok, (case, i, top, ok)
+    ref_lp = np.asarray(block["cand_logprobs"])
+    assert abs((lp[0] - lp[1]) - (ref_lp[0] - ref_lp[1])) <= tol * scale
+    if abs(ref_lp[0] - ref_lp[1]) > 2 * tol * scale:
+        assert int(np.argmax(lp)) == int(np.argmax(ref_lp))
+    return err
+
+
 @pytest.mark.parametrize("path", GOLDEN, ids=[os.path.basename(p)[:-5] for p in GOLDEN])
 def test_against_stored_oracle(path):
     from paper_2505_07203_amd import binding as B
@@ -50,23 +82,17 @@ def test_against_stored_oracle(path):
             t = I.make_tokens(cfg, doc["tseed"], r["len"], request=i)
             assert hashlib.sha256(np.ascontiguousarray(t, dtype=np.int32).tobytes()).hexdigest() == r["tokens_sha256"]
             z, lp = ctx.po_prefill(t, cand, want_logits=True)
-            ids = np.asarray(r["sample_ids"])
-            ref = np.asarray(r["sample_logits"], dtype=np.float64)
-            scale = r["max_abs_logit"]
-            err = float(np.max(np.abs(z[ids].astype(np.float64) - ref)) / scale)
-            print(f"{doc['case']} request {i} len {r['len']}: normalised max error {err:.3e}")
-            assert err <= TOL, (doc["case"], i, err)
-            top = int(np.argmax(z))
-            if r["top_gap"] >= 2 * TOL * scale:
-                assert top == r["argmax"], (doc["case"], i, top, r["argmax"])
-            else:
-                ref_by_id = dict(zip(r["sample_ids"], r["sample_logits"]))
-                ok = [j for j in r["top_ids"] if ref_by_id[r["argmax"]] - ref_by_id[j] <= 2 * TOL * scale]
-                assert top in ok, (doc["case"], i, top, ok)
-            ref_lp = np.asarray(r["cand_logprobs"])
-            assert abs((lp[0] - lp[1]) - (ref_lp[0] - ref_lp[1])) <= TOL * scale
-            if abs(ref_lp[0] - ref_lp[1]) > 2 * TOL * scale:
-                assert int(np.argmax(lp)) == int(np.argmax(ref_lp))
             assert abs(float(np.sum(np.exp(lp.astype(np.float64)))) - 1.0) < 1e-5
+            ex, sb = r["exact"], r["stored_bf16"]
+            # what storing activations in bf16 costs by itself, from the oracle's two evaluations
+            common = sorted(set(ex["sample_ids"]) & set(sb["sample_ids"]))
+            e_by, s_by = dict(zip(ex["sample_ids"], ex["sample_logits"])), dict(zip(sb["sample_ids"], sb["sample_logits"]))
+            storage_dev = max(abs(e_by[j] - s_by[j]) for j in common) / ex["max_abs_logit"]
+            err_s = _check_block(doc["case"], i, z, lp, sb, TOL)
+            tol_exact = max(TOL, 2 * storage_dev)
+            err_e = _err(z, ex)
+            print(f"{doc['case']} request {i} len {r['len']}: err vs stored_bf16 {err_s:.3e}, vs exact {err_e:.3e} "
+                  f"(oracle stored-vs-exact {storage_dev:.3e})")
+            assert err_e <= tol_exact, (doc["case"], i, err_e, tol_exact)
     finally:
         ctx.po_destroy()

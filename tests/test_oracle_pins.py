@@ -59,6 +59,42 @@ def test_whole_forward_matches_scalar_brute_force(bias, hq, hkv):
     assert np.max(np.abs(z)) > 0.1
 
 
+def test_stored_precision_mode_matches_scalar_brute_force():
+    """The optional bf16 storage of activations: same rounding points, second implementation."""
+    cfg = micro_cfg(qkv_bias=1, n_q_heads=4, n_kv_heads=2, d_model=16, head_dim=8)
+    embed, layers, fnorm, lm = micro_weights(cfg, seed=8, scale=12.0)
+    tokens = I.make_tokens(cfg, 12, 9)
+    z, _ = O.prefill(tokens, embed, layers, fnorm, lm, cfg, store=O.round_bf16)
+    xs = O.forward_hidden(tokens, embed, layers, cfg, store=O.round_bf16)
+    z_exact, _ = O.prefill(tokens, embed, layers, fnorm, lm, cfg)
+    as_lists = [{k: v.tolist() for k, v in W.items()} for W in layers]
+    z_bf, x_bf = BF.forward_last_logits([int(t) for t in tokens], embed.tolist(), as_lists,
+                                        fnorm.tolist(), lm.tolist(), cfg, store=BF.bf16_scalar)
+    assert np.max(np.abs(np.array(x_bf) - xs)) < 1e-11
+    assert np.max(np.abs(np.array(z_bf) - z)) < 1e-11
+    # the residual stream that comes out is bf16-representable, and the mode is not a no-op
+    assert np.array_equal(O.round_bf16(xs), xs)
+    assert 1e-4 < np.max(np.abs(z - z_exact)) / np.max(np.abs(z_exact)) < 5e-2
+    # store=None and an identity function are the plain definition
+    z_id, _ = O.prefill(tokens, embed, layers, fnorm, lm, cfg, store=lambda t: t)
+    assert np.array_equal(z_id, z_exact)
+
+
+def test_round_bf16_matches_torch_and_ties_to_even():
+    import torch
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.normal(0, 1, 4096), rng.normal(0, 1e-3, 1024), rng.normal(0, 1e4, 1024),
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.0e38, 1e-40])])
+    want = torch.from_numpy(x).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.round_bf16(x)
+    assert np.array_equal(got, want)
+    # 1 + 2^-8 lies half-way between 1 and 1 + 2^-7: ties go to the even significand (1.0);
+    # 1 + 3*2^-8 lies half-way between 1 + 2^-7 and 1 + 2^-6: goes up to the even one
+    assert O.round_bf16(np.array([1.00390625]))[0] == 1.0
+    assert O.round_bf16(np.array([1.01171875]))[0] == 1.015625
+    assert [BF.bf16_scalar(float(v)) for v in x[:512]] == [float(v) for v in got[:512]]
+
+
 # ------------------------------------------------------------------ library routines
 
 def test_attention_matches_torch_sdpa():
