@@ -15,8 +15,9 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hi
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result"]
 
 
-# attention: max() of finite-or--inf scores needs no NaN canonicalisation
-EXTRA_FLAGS = {"attn_mfma.hip": ["-fno-honor-nans"]}
+# attention: max() of finite-or--inf scores needs no NaN canonicalisation; MFMA builtins write
+# architectural registers (the softmax reads them), see the register-file note in the kernel
+EXTRA_FLAGS = {"attn_mfma.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src: str) -> str:

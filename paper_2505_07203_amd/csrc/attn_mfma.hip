@@ -273,6 +273,376 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
     }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Head dimension 128: 64 query rows per wavefront, one wavefront per SIMD.
+//
+// The kernel above reads one 1 KiB LDS fragment per MFMA (32 query rows per wavefront), which
+// at full matrix rate is the whole LDS bandwidth of the CU.  Here a wavefront owns TWO
+// 32-row query tiles, so every K and V^T fragment feeds two MFMAs.  With 4 wavefronts x 64
+// rows there is a single wavefront per SIMD, so the softmax arithmetic has to run in the
+// shadow of the SAME wavefront's MFMAs; the loop is software-pipelined over blocks of 32 keys:
+//
+//   iteration i, first half : 16 MFMA  S(i+1) = K(i+1) Q^T      | VALU: P(i) = exp2(S(i) - m)
+//   iteration i, second half: 16 MFMA  O^T += V^T(i) P(i)^T      | VALU: block max of S(i+1),
+//                                                                        row sums of P(i)
+// MFMAs and their LDS fragment reads are written one by one with a slice of the vector work
+// behind each (scheduling fences keep that order).
+//
+// Reference exponent instead of a running maximum.  Every vector instruction issued between
+// MFMAs delays the next MFMA by a few cycles (measured: the two do not overlap within a
+// wavefront), so the per-score instruction count is what bounds this kernel, and the block
+// maximum of the usual online softmax is 18 instructions per block that only guard the number
+// range.  Here a query row keeps ONE reference r (the maximum over its first 32 keys, which
+// include key 0) and accumulates p = exp2(s - r) in fp32 as it stands: softmax is invariant to
+// r, bf16 has the fp32 exponent range, so p > 1 is harmless.  The row sum is watched instead:
+// when it passes 2^40 the sums and accumulators are multiplied by an exact power of two and
+// r moves by that exponent (rare: not once with the workloads here).  Terms below 2^-126
+// relative to r underflow exactly as they would against the true maximum once it is larger.
+// A score more than 87 (in log2 units; 60 nats) above everything seen before it, within a
+// single block, would overflow before the watch sees it; scores of that size do not come out
+// of bf16 attention inputs of the kind this path serves.
+//
+// K (64 keys x 256 B) and V^T (128 rows x 128 B) tiles go global -> LDS directly
+// (global_load_lds, 16 B per lane) through a ring of four 32 KiB stages, three tiles ahead;
+// the XOR swizzles of the kernel above are applied on the global side of the copy.  One
+// workgroup barrier per 64-key tile hands a stage over.
+constexpr int A64_STAGE = 2 * 64 * 128 * 2;     // K tile + V^T tile
+constexpr int A64_NSTAGE = 4;
+
+__device__ __forceinline__ float half_swap_max(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+__global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const bf16_t* __restrict__ k,
+                                                         const bf16_t* __restrict__ vt, int64_t ldv, bf16_t* o, int N,
+                                                         int Hq, int Hkv, float sc_log2e, int nqt, int hpx) {
+    constexpr int HD = 128, KS = 8, HT = 4;
+    constexpr int TILE_BYTES = 64 * HD * 2;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    int qtile, head;
+    if (hpx > 0) {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        qtile = nqt - 1 - j / hpx;
+        head = xcd * hpx + j % hpx;
+    } else {
+        qtile = nqt - 1 - (int)(blockIdx.x / Hq);
+        head = blockIdx.x % Hq;
+    }
+    const int kvh = head / (Hq / Hkv);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l31 = lane & 31, lhi = lane >> 5;
+    const int qb = qtile * 256;
+    const int qw = qb + wave * 64;
+    const int blk_last = min(N, qb + 256) - 1;
+    const int n_tiles = blk_last / 64 + 1;                       // 64-key tiles the workgroup streams
+    const int nkb_w = (qw < N) ? (min(N, qw + 64) - 1) / 32 + 1 : 0;   // 32-key blocks this wavefront needs
+
+    // ---- Q fragments (B operand: lane = query column, 8 consecutive head-dim values)
+    bf16x8 qf[2][KS];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const int qrow = min(qw + qt * 32 + l31, N - 1);
+        const bf16_t* qp = q + ((int64_t)qrow * Hq + head) * HD + lhi * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const uint4 t = *(const uint4*)(qp + ks * 16);
+            qf[qt][ks] = __builtin_bit_cast(bf16x8, t);
+        }
+    }
+
+    // ---- global -> LDS copy maps.  K: round jj (0..3) of wavefront w fills rows jj*16 + w*4 .. +3
+    // (16 lanes per 256-byte row); V^T: round jj fills rows jj*32 + w*8 .. +7 (8 lanes per row).
+    // Lane l writes physical segment l % 16 (l % 8), so it fetches the logical segment that the
+    // swizzle maps there.
+    const int krow_l = wave * 4 + (lane >> 4);
+    const uint32_t kcol = (uint32_t)(((lane & 15) ^ (krow_l & 15)) << 4);
+    const uint32_t krs2 = (uint32_t)(Hkv * HD * 2);
+    const uint32_t klane = (uint32_t)krow_l * krs2 + kcol;
+    const int vrow_l = wave * 8 + (lane >> 3);
+    const uint32_t voff_v = (uint32_t)vrow_l * (uint32_t)(ldv * 2) + (uint32_t)(((lane & 7) ^ swz8(vrow_l)) << 4);
+    // K goes through a buffer resource that ends with the last position: rows of the last, ragged tile
+    // beyond it read as zero (they are masked keys) instead of needing a clamp per load.
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(k + (int64_t)kvh * HD), 0, (int)((uint32_t)(N - 1) * krs2 + 256u), 0x00020000);
+    const unsigned char* vg = (const unsigned char*)(vt + (int64_t)kvh * HD * ldv);
+#define PO_DMA(tile_, jj_)                                                                                     \
+    {                                                                                                          \
+        const int kv0_ = min((tile_), n_tiles - 1) * 64;                                                       \
+        unsigned char* dst_ = smem + ((tile_) & (A64_NSTAGE - 1)) * A64_STAGE +                                \
+                              ((jj_) < 4 ? ((jj_) * 16 + wave * 4) * 256 : TILE_BYTES + (((jj_) - 4) * 32 + wave * 8) * 128); \
+        if ((jj_) < 4) {                                                                                       \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (__attribute__((address_space(3))) void*)dst_, 16,  \
+                                                     klane, (kv0_ + (jj_) * 16) * krs2, 0, 0);                  \
+        } else {                                                                                               \
+            const unsigned char* b_ = vg + (int64_t)((jj_) - 4) * 32 * (ldv * 2) + kv0_ * 2;                   \
+            asm volatile("" : "+s"(b_));                                                                       \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b_ + voff_v),     \
+                                             (__attribute__((address_space(3))) void*)dst_, 16, 0, 0);         \
+        }                                                                                                      \
+    }
+
+    // ---- LDS fragment addresses
+    const int pk = (l31 & 0x13) | ((l31 & 4) << 1) | ((l31 & 8) >> 1);   // K rows read permuted (see above)
+    uint32_t koff[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = pk * 256 + (((ks * 2 + lhi) ^ (pk & 15)) << 4);
+    uint32_t vofs[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int j2 = 0; j2 < 2; ++j2) vofs[a][j2] = TILE_BYTES + l31 * 128 + (((a * 4 + j2 * 2 + lhi) ^ swz8(l31)) << 4);
+
+    f32x16 oacc[HT][2];
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[ht][qt][r] = 0.f;
+    float mb[2], lrow[2] = {0.f, 0.f};      // reference exponents (log2 domain) and row sums per query tile
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+    // causal mask of a 32-key block on the accumulators of one query tile
+#define PO_MASK(S, kb_, qt_)                                                                     \
+    {                                                                                            \
+        const int qidx_ = qw + (qt_) * 32 + l31;                                                 \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                         \
+            const int key_ = (kb_) * 32 + (r & 7) + 8 * lhi + 16 * (r >> 3);                     \
+            if (key_ > qidx_) S[qt_][r] = -INFINITY;                                             \
+        }                                                                                        \
+    }
+#define PO_BLOCKMAX(S, qt_, out_)                                                                \
+    {                                                                                            \
+        float m0_ = fmaxf(fmaxf(S[qt_][0], S[qt_][1]), S[qt_][2]);                               \
+        float m1_ = fmaxf(fmaxf(S[qt_][3], S[qt_][4]), S[qt_][5]);                               \
+        m0_ = fmaxf(fmaxf(m0_, S[qt_][6]), S[qt_][7]);                                           \
+        m1_ = fmaxf(fmaxf(m1_, S[qt_][8]), S[qt_][9]);                                           \
+        m0_ = fmaxf(fmaxf(m0_, S[qt_][10]), S[qt_][11]);                                         \
+        m1_ = fmaxf(fmaxf(m1_, S[qt_][12]), S[qt_][13]);                                         \
+        m0_ = fmaxf(fmaxf(m0_, S[qt_][14]), S[qt_][15]);                                         \
+        out_ = half_swap_max(fmaxf(m0_, m1_));                                                   \
+    }
+
+    // ---- prologue: three tiles in flight, S(0), reference maxima
+    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(0, jj);
+    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(1, jj);
+    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(2, jj);
+    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");      // Q fragments and tile 0 have landed
+
+    f32x16 sa[2], sb[2];
+    bf16x8 pf[2][2], fr[4];
+    {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 kf = *(const bf16x8*)(smem + koff[ks]);
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                if (ks == 0) {
+                    const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    sa[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][ks], z, 0, 0, 0);
+                } else {
+                    sa[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][ks], sa[qt], 0, 0, 0);
+                }
+            }
+        }
+        if (31 > qw) { PO_MASK(sa, 0, 0); PO_MASK(sa, 0, 1); }
+        float m0, m1;
+        PO_BLOCKMAX(sa, 0, m0);
+        PO_BLOCKMAX(sa, 1, m1);
+        mb[0] = m0 * sc_log2e;
+        mb[1] = m1 * sc_log2e;
+    }
+
+    // Register files.  The vector ALU reaches only the 256 architectural registers; S must live there
+    // (softmax), the O^T accumulators (128 registers, touched by MFMAs only) must not.  The compiler puts
+    // the results of ALL MFMA builtins of a function in one file or the other, so the S products use the
+    // builtin (built with -amdgpu-mfma-vgpr-form: architectural registers) and the O^T products are
+    // written as an instruction with accumulation-register constraints.  The compiler does not know that
+    // instruction's latency, so before the vector ALU reads O^T (rescale, epilogue) the pipe is drained
+    // by hand; MFMA-to-MFMA accumulation on the same registers needs no software wait.
+#define PO_MFMA_ACC(ACC, A_, B_) \
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(A_), "v"(B_))
+#define PO_MFMA_DRAIN() asm volatile("s_nop 15\n\ts_nop 15" ::: "memory")
+    // One iteration over key block i_: SC holds S(i_), SN receives S(i_+1).  It is a chain of 16 steps,
+    // each one LDS fragment feeding two MFMAs (steps 0..7: K rows of block i_+1 at KST_/KA_; steps 8..15:
+    // V^T of block i_ at VST_/VA_, 16-key half outermost); the fragment of step c+3 is requested right
+    // after the first MFMA of step c, into the register step c-1 has just finished with (steps 13..15
+    // request the first three K fragments of the next iteration, at NKST_/NKA_).
+    //   BAR_: the hand-over barrier sits between the two halves of this iteration.
+    //   DMA_T_/DMA_J0_: four global->LDS loads ride on steps 9, 11, 13, 15.
+    // The compiler waits for ALL LDS reads in flight before an MFMA written as an instruction (it does
+    // not work out which read feeds it).  Three fragment reads are in flight at the first MFMA of a step
+    // and LDS reads return in order, so an explicit wait for "all but the two youngest" in front of it
+    // is exact, and the compiler, which does account for explicit waits, then adds none.
+#define PO_FRAG_ADDR(c_, KST_, KA_, VST_, VA_, NKST_, NKA_)                                                     \
+    ((c_) < 8 ? (KST_) + (KA_) * 8192 + koff[(c_) & 7]                                                          \
+              : (c_) < 16 ? (VST_) + (((c_) - 8) & 3) * 4096 + vofs[VA_][((c_) - 8) >> 2]                       \
+                          : (NKST_) + (NKA_) * 8192 + koff[(c_) & 7])
+#define PO_WAIT_LGKM2() __builtin_amdgcn_s_waitcnt(0xC27F)     /* lgkmcnt(2), other counters untouched */
+#define PO_ITER(i_, SC, SN, KST_, KA_, VST_, VA_, NKST_, NKA_, BAR_, DMA_T_, DMA_J0_, MASK_)                    \
+    {                                                                                                           \
+        const float mb0_ = mb[0], mb1_ = mb[1];                                                                 \
+        _Pragma("unroll") for (int c = 0; c < 16; ++c) {                                                        \
+            if (c == 8) {                                                                                       \
+                if (MASK_) {                                                                                    \
+                    PO_MASK(SN, (i_) + 1, 0);                                                                   \
+                    PO_MASK(SN, (i_) + 1, 1);                                                                   \
+                }                                                                                               \
+                if (BAR_) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");                         \
+                __builtin_amdgcn_sched_barrier(0);                                                              \
+            }                                                                                                   \
+            PO_WAIT_LGKM2();                                                                                    \
+            __builtin_amdgcn_sched_barrier(0);                                                                  \
+            _Pragma("unroll") for (int qt = 0; qt < 2; ++qt) {                                                  \
+                if (c < 8) {                                                                                    \
+                    if (c == 0) {                                                                               \
+                        const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
+                        SN[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[c & 3], qf[qt][c & 7], z_, 0, 0, 0); \
+                    } else {                                                                                    \
+                        SN[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[c & 3], qf[qt][c & 7], SN[qt], 0, 0, 0); \
+                    }                                                                                           \
+                } else {                                                                                        \
+                    PO_MFMA_ACC(oacc[(c - 8) & 3][qt], fr[c & 3], pf[qt][(c - 8) >> 2]);                        \
+                }                                                                                               \
+                __builtin_amdgcn_sched_barrier(0);                                                              \
+                if (qt == 0) {                                                                                  \
+                    fr[(c + 3) & 3] = *(const bf16x8*)PO_FRAG_ADDR(c + 3, KST_, KA_, VST_, VA_, NKST_, NKA_);   \
+                    __builtin_amdgcn_sched_barrier(0);                                                          \
+                }                                                                                               \
+                /* Probabilities of S(i), two at a time behind an MFMA.  The exponential is a quarter-rate       \
+                   instruction: 32 of them cost as many cycles as the 16 MFMAs of a half, so 24 go into the     \
+                   first half (slots 0..7: the 16 values the first four V^T steps need; slots 8, 10, 12, 14:    \
+                   query tile 0, registers 8..15) and the last 8 (query tile 1, registers 8..15, needed from    \
+                   V^T step 4 on) into the first MFMA slots of the second half. */                              \
+                const int slot_ = 2 * c + qt;                    /* 0..31 over the iteration */                 \
+                const int e_ = slot_ < 8 ? (slot_ < 4 ? 2 * slot_ : 16 + 2 * (slot_ - 4))                       \
+                             : (slot_ < 16 ? ((slot_ & 1) ? -1 : 8 + (slot_ - 8))                               \
+                             : ((slot_ < 24 && !(slot_ & 1)) ? 24 + (slot_ - 16) : -1));                        \
+                if (e_ >= 0) {                                                                                  \
+                    const int pq_ = e_ >> 4, pr_ = e_ & 15;                                                     \
+                    const float mb_ = pq_ ? mb1_ : mb0_;                                                        \
+                    const float p0_ = __builtin_amdgcn_exp2f(fmaf(SC[pq_][pr_], sc_log2e, -mb_));               \
+                    const float p1_ = __builtin_amdgcn_exp2f(fmaf(SC[pq_][pr_ + 1], sc_log2e, -mb_));           \
+                    pf[pq_][pr_ >> 3][pr_ & 7] = (__bf16)p0_;                                                   \
+                    pf[pq_][pr_ >> 3][(pr_ & 7) + 1] = (__bf16)p1_;                                             \
+                }                                                                                               \
+                if (c >= 8) {                                                                                   \
+                    const int c_ = (c - 8) * 2 + qt;             /* 0..15 */                                    \
+                    if (c_ == 8 || c_ == 9) {                                                                   \
+                        const int sq_ = c_ - 8;                                                                 \
+                        float l_ = lrow[sq_];                                                                   \
+                        _Pragma("unroll") for (int h2 = 0; h2 < 2; ++h2)                                        \
+                        _Pragma("unroll") for (int e2 = 0; e2 < 4; ++e2) {                                      \
+                            const bf16x2 pr2_ = {pf[sq_][h2][2 * e2], pf[sq_][h2][2 * e2 + 1]};                 \
+                            l_ = __builtin_amdgcn_fdot2_f32_bf16(pr2_, ones, l_, false);                        \
+                        }                                                                                       \
+                        lrow[sq_] = l_;                                                                         \
+                    }                                                                                           \
+                    if ((c_ & 3) == 3) { PO_DMA(DMA_T_, (DMA_J0_) + (c_ >> 2)); }                               \
+                }                                                                                               \
+                __builtin_amdgcn_sched_barrier(0);                                                              \
+            }                                                                                                   \
+        }                                                                                                       \
+        /* ---- renormalise when a row sum has grown past 2^40 (rare; see the note on the reference) */         \
+        if (__any(lrow[0] > 0x1p40f || lrow[1] > 0x1p40f)) {                                                    \
+            int e0_ = ilogbf(half_swap_sum(lrow[0])), e1_ = ilogbf(half_swap_sum(lrow[1]));                     \
+            asm volatile("" : "+v"(e0_), "+v"(e1_));   /* keeps the rescale inside this rarely taken branch */  \
+            PO_MFMA_DRAIN();                                                                                    \
+            const float a0_ = ldexpf(1.0f, -e0_), a1_ = ldexpf(1.0f, -e1_);                                     \
+            mb[0] += (float)e0_;                                                                                \
+            mb[1] += (float)e1_;                                                                                \
+            lrow[0] *= a0_;                                                                                     \
+            lrow[1] *= a1_;                                                                                     \
+            _Pragma("unroll") for (int ht = 0; ht < HT; ++ht)                                                   \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) { oacc[ht][0][r] *= a0_; oacc[ht][1][r] *= a1_; }    \
+        }                                                                                                       \
+    }
+
+    // Pair j = key blocks 2j, 2j+1 (one 64-key tile).  Block 2j multiplies with K of block 2j+1 (tile j,
+    // second half) and V^T of block 2j (tile j, first half); block 2j+1 with K of block 2j+2 (tile j+1,
+    // first half) and V^T of block 2j+1.  Hand-over between the halves of block 2j: tile j+1 has landed
+    // (the 8 loads of tile j+2 may still be in flight) and every wavefront is done with tile j-1, whose
+    // stage the loads of tile j+3 overwrite: its K rows ride on the rest of block 2j, its V^T rows on
+    // block 2j+1.  The causal mask touches S(i+1) only in the last three blocks of a wavefront
+    // (i + 1 >= qw / 32), so the loop is split by pair into: no mask | second block masked | both masked |
+    // nothing left to compute (the wavefront still copies its share and meets the barriers).
+#define PO_PAIR(M0_, M1_)                                                                          \
+    {                                                                                              \
+        const unsigned char* st = smem + (j & (A64_NSTAGE - 1)) * A64_STAGE;                       \
+        const unsigned char* stn = smem + ((j + 1) & (A64_NSTAGE - 1)) * A64_STAGE;                \
+        PO_ITER(2 * j, sa, sb, st, 1, st, 0, stn, 0, 1, j + 3, 0, M0_);                            \
+        PO_ITER(2 * j + 1, sb, sa, stn, 0, st, 1, stn, 1, 0, j + 3, 4, M1_);                       \
+    }
+    const int wt = qw >> 6;                      // pair that holds this wavefront's first query row
+    const int j_last = (nkb_w > 0) ? wt : -1;    // last pair with work
+    fr[0] = *(const bf16x8*)(smem + 8192 + koff[0]);      // K fragments 0, 1, 2 of block 1
+    fr[1] = *(const bf16x8*)(smem + 8192 + koff[1]);
+    fr[2] = *(const bf16x8*)(smem + 8192 + koff[2]);
+    int j = 0;
+    for (; j < j_last - 1; ++j) PO_PAIR(0, 0);
+    if (j == j_last - 1) { PO_PAIR(0, 1); ++j; }
+    if (j == j_last) { PO_PAIR(1, 1); ++j; }
+    for (; j < n_tiles; ++j) {
+        asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+        _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(j + 3, jj);
+    }
+#undef PO_PAIR
+#undef PO_FRAG_ADDR
+#undef PO_WAIT_LGKM2
+#undef PO_ITER
+#undef PO_DMA
+#undef PO_MASK
+#undef PO_BLOCKMAX
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    PO_MFMA_DRAIN();
+#undef PO_MFMA_ACC
+#undef PO_MFMA_DRAIN
+
+    // ---- normalise and store: lane = query row, registers = head-dim rows
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const float inv = 1.0f / half_swap_sum(lrow[qt]);
+        const int qrow = qw + qt * 32 + l31;
+        if (qrow < N) {
+            bf16_t* op = o + ((int64_t)qrow * Hq + head) * HD + 4 * lhi;
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    uint2 w;
+                    w.x = (uint32_t)f2bf(oacc[ht][qt][rg * 4 + 0] * inv) | ((uint32_t)f2bf(oacc[ht][qt][rg * 4 + 1] * inv) << 16);
+                    w.y = (uint32_t)f2bf(oacc[ht][qt][rg * 4 + 2] * inv) | ((uint32_t)f2bf(oacc[ht][qt][rg * 4 + 3] * inv) << 16);
+                    *(uint2*)(op + ht * 32 + rg * 8) = w;
+                }
+        }
+    }
+}
+
+void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
+                  int Hkv, hipStream_t s) {
+    constexpr int SMEM = A64_NSTAGE * A64_STAGE;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)attn_fwd64_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+        attr_set = true;
+    }
+    const int nqt = (int)((N + 255) / 256);
+    const int hpx = (Hq % 8 == 0) ? Hq / 8 : 0;
+    const float sc_log2e = (float)(1.4426950408889634 / sqrt(128.0));
+    hipLaunchKernelGGL(attn_fwd64_kernel, dim3((unsigned)(nqt * Hq)), dim3(256), SMEM, s, q, k, vt, ldv, o, (int)N, Hq,
+                       Hkv, sc_log2e, nqt, hpx);
+}
+
 template <int HD, int QT, int NW>
 void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
               int Hkv, hipStream_t s) {
@@ -300,7 +670,7 @@ bool attention_mfma_supported(int Hq, int Hkv, int hd) {
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N,
                            int Hq, int Hkv, int hd, hipStream_t s) {
     if (N <= 0) return;
-    if (hd == 128) launch_t<128, 1, 8>(q, k, vt, ldv, o, N, Hq, Hkv, s);
+    if (hd == 128) launch_fwd64(q, k, vt, ldv, o, N, Hq, Hkv, s);
     else if (hd == 64) launch_t<64, 1, 8>(q, k, vt, ldv, o, N, Hq, Hkv, s);
 }
 
