@@ -1,0 +1,174 @@
+"""Parity at the sizes and launch configurations the benchmark times (Llama-3-8B shape, 32768
+tokens, MLP chunk 4096): outputs the oracle can compute one by one, and properties that hold
+at any size.
+
+  * attention over the whole 32768-token sequence in one launch: sampled query rows (first
+    and last rows of tiles, rows next to the diagonal, the last row) against the oracle's
+    definition evaluated for exactly those rows;
+  * the three fused GEMMs at their benchmark shapes: whole sampled rows (every column tile)
+    and whole sampled columns (every row tile) against float64 matrix products;
+  * the whole path: bit-identical logits across MLP chunk sizes and across repeated runs.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_07203_amd import binding as B
+from paper_2505_07203_amd import inputs as I
+from oracle import prefill_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+
+
+def bf16_dev(x32: np.ndarray):
+    """float32 array -> (device bf16 tensor, the same values as float64)"""
+    bits = I.f32_to_bf16_bits(x32)
+    t = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return t, I.stored_to_f64(bits)
+
+
+def host64(t) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+# ------------------------------------------------------------------ attention, 32768 tokens
+
+def test_attention_32k_sampled_rows():
+    N, Hq, Hkv, hd = 32768, 32, 8, 128
+    rng = np.random.default_rng(32768)
+    q, q64 = bf16_dev(rng.standard_normal((N, Hq, hd), dtype=np.float32))
+    k, k64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    rows = np.array([0, 1, 31, 32, 63, 64, 65, 127, 255, 256, 257, 319, 4095, 4096, 12345, 16383, 16384,
+                     20000, 32511, 32512, 32575, 32703, 32766, 32767])
+    ref = O.causal_gqa_attention(q64, k64, v64, query_rows=rows)
+    del q64
+    got = host64(B.po_op_attention(q, k, v)[torch.from_numpy(rows).cuda()])
+    err = np.max(np.abs(got - ref), axis=(1, 2)) / np.max(np.abs(ref))
+    print("attention N=32768, per sampled row:", " ".join(f"{r}:{e:.1e}" for r, e in zip(rows, err)))
+    assert np.max(err) <= 1.5e-2
+
+
+def test_attention_large_scores_renormalise():
+    """Scores far above the first key block's maximum: the running sums pass the
+    renormalisation threshold many times."""
+    N, Hq, Hkv, hd = 2048, 8, 2, 128
+    rng = np.random.default_rng(7)
+    qs = rng.standard_normal((N, Hq, hd), dtype=np.float32)
+    ks = rng.standard_normal((N, Hkv, hd), dtype=np.float32)
+    # growing key norm: later keys score higher and higher than the early ones
+    ks *= (1.0 + 7.0 * np.arange(N, dtype=np.float32) / N)[:, None, None]
+    qs *= 3.0
+    q, q64 = bf16_dev(qs)
+    k, k64 = bf16_dev(ks)
+    v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    ref = O.causal_gqa_attention(q64, k64, v64)
+    got = host64(B.po_op_attention(q, k, v))
+    assert np.all(np.isfinite(got))
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    print(f"attention with large scores: {err:.3e}")
+    assert err <= 1.5e-2
+
+
+# ------------------------------------------------------------------ GEMMs at benchmark shapes
+
+ROWS = np.array([0, 1, 255, 256, 257, 2047, 4094, 4095])
+
+
+def _check_rows_cols(got, ref_rows, ref_cols, rows, cols, tol):
+    scale = max(np.max(np.abs(ref_rows)), np.max(np.abs(ref_cols)))
+    e_r = np.max(np.abs(got[rows] - ref_rows)) / scale
+    e_c = np.max(np.abs(got[:, cols] - ref_cols)) / scale
+    assert e_r <= tol and e_c <= tol, (e_r, e_c)
+    return max(e_r, e_c)
+
+
+def test_gemm_residual_benchmark_shapes():
+    """O-projection (K = 4096) and MLP down projection (K = 14336) with the residual added in place."""
+    for M, N, K in ((4096, 4096, 4096), (4096, 4096, 14336)):
+        rng = np.random.default_rng(K)
+        a, a64 = bf16_dev(rng.standard_normal((M, K), dtype=np.float32))
+        w, w64 = bf16_dev(rng.standard_normal((N, K), dtype=np.float32) * 0.02)
+        r, r64 = bf16_dev(rng.standard_normal((M, N), dtype=np.float32))
+        cols = np.array([0, 63, 64, 255, 256, 2049, 4032, 4095])
+        ref_rows = a64[ROWS] @ w64.T + r64[ROWS]
+        ref_cols = a64 @ w64[cols].T + r64[:, cols]
+        B.po_op_linear(a, w, residual=r, out=r)
+        e = _check_rows_cols(host64(r), ref_rows, ref_cols, ROWS, cols, 6e-3)
+        print(f"residual GEMM {M}x{N}x{K}: {e:.2e}")
+
+
+def test_gemm_gate_up_silu_benchmark_shape():
+    M, F, K = 4096, 14336, 4096
+    rng = np.random.default_rng(F)
+    a, a64 = bf16_dev(rng.standard_normal((M, K), dtype=np.float32))
+    wg, g64 = bf16_dev(rng.standard_normal((F, K), dtype=np.float32) * 0.02)
+    wu, u64 = bf16_dev(rng.standard_normal((F, K), dtype=np.float32) * 0.02)
+    cols = np.array([0, 31, 32, 63, 64, 7000, 14304, 14335])
+
+    def mlp_act(x, gw, uw):
+        gate, up = x @ gw.T, x @ uw.T
+        return gate / (1 + np.exp(-gate)) * up
+    ref_rows = mlp_act(a64[ROWS], g64, u64)
+    ref_cols = mlp_act(a64, g64[cols], u64[cols])
+    got = host64(B.po_op_gate_up_silu(a, B.po_op_pack_gate_up(wg, wu)))
+    e = _check_rows_cols(got, ref_rows, ref_cols, ROWS, cols, 6e-3)
+    print(f"gate/up GEMM {M}x{2 * F}x{K}: {e:.2e}")
+
+
+def test_gemm_qkv_rope_benchmark_shape():
+    """8192-row QKV projection with RoPE at positions 24576 .. 32767, V written transposed."""
+    M, Hq, Hkv, hd, K, pos0 = 8192, 32, 8, 128, 4096, 24576
+    theta = 500000.0
+    rng = np.random.default_rng(M)
+    a, a64 = bf16_dev(rng.standard_normal((M, K), dtype=np.float32))
+    wq, q64 = bf16_dev(rng.standard_normal((Hq * hd, K), dtype=np.float32) * 0.02)
+    wk, k64 = bf16_dev(rng.standard_normal((Hkv * hd, K), dtype=np.float32) * 0.02)
+    wv, v64 = bf16_dev(rng.standard_normal((Hkv * hd, K), dtype=np.float32) * 0.02)
+    rows = np.array([0, 1, 255, 256, 4095, 4096, 8190, 8191])
+    pos = pos0 + rows
+    ref_q = O.rope((a64[rows] @ q64.T).reshape(len(rows), Hq, hd), pos, theta)
+    ref_k = O.rope((a64[rows] @ k64.T).reshape(len(rows), Hkv, hd), pos, theta)
+    ref_v = a64[rows] @ v64.T
+    cos, sin = B.po_op_rope_table(pos0 + M, hd, theta)
+    wqkv, _ = B.po_op_pack_qkv(wq, wk, wv, Hq, Hkv, hd)
+    q, k, vt = B.po_op_qkv_rope(a, wqkv, None, cos, sin, Hq, Hkv, hd, pos0=pos0)
+    gq = host64(q).reshape(M, Hq, hd)[rows]
+    gk = host64(k).reshape(M, Hkv, hd)[rows]
+    gv = host64(vt)[:, pos].T if vt.shape[1] > M else host64(vt)[:, rows].T
+    for name, g, r in (("q", gq, ref_q), ("k", gk, ref_k), ("v", gv, ref_v)):
+        e = np.max(np.abs(g - r)) / np.max(np.abs(r))
+        print(f"qkv+rope {name}: {e:.2e}")
+        assert e <= 6e-3, (name, e)
+
+
+# ------------------------------------------------------------------ whole path at 32768 tokens
+
+def test_full_path_32k_bitwise_properties():
+    """Two layers of the 8B shape on the benchmark's 32768 tokens: logits identical bit for bit for MLP
+    chunks 4096 (the benchmark's), 8192 and 3000 (ragged last chunk), and across repeated runs."""
+    w = I.WORKLOADS["llama8b_32k"]
+    cfg = w["cfg"].replace(n_layers=2)
+    tokens = I.make_tokens(cfg, w["tseed"], 32768, request=0)
+    cand = I.label_ids(cfg)
+    outs = []
+    for chunk in (4096, 8192, 3000):
+        ctx = B.Context(cfg, 32768, chunk)
+        try:
+            ctx.load_synthetic(w["wseed"], threads=16)
+            z, lp = ctx.po_prefill(tokens, cand, want_logits=True)
+            if chunk == 4096:
+                z2, lp2 = ctx.po_prefill(tokens, cand, want_logits=True)
+                assert np.array_equal(z, z2) and np.array_equal(lp, lp2)
+            outs.append((z, lp))
+        finally:
+            ctx.po_destroy()
+    assert np.all(np.isfinite(outs[0][0]))
+    for z, lp in outs[1:]:
+        assert np.array_equal(z, outs[0][0]) and np.array_equal(lp, outs[0][1])
