@@ -156,7 +156,8 @@ def main():
               "qkv": 2.0 * cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) * tok_l,
               "residual": 2.0 * (cfg.q_dim * cfg.d_model + cfg.ffn_dim * cfg.d_model) * tok_l,
               "gate_up": 2.0 * cfg.d_model * 2 * cfg.ffn_dim * tok_l}
-    k_name = {"attention": "attn_fwd_kernel<128> (causal GQA flash attention, one launch per layer)",
+    k_name = {"attention": ("attn_fwd64_kernel" if cfg.head_dim == 128 else "attn_fwd_kernel<64>") +
+                           " (causal GQA flash attention, one launch per layer)",
               "qkv": "gemm_bf16_mfma_kernel<3> (QKV projection + RoPE + transposed V)",
               "residual": "gemm_bf16_mfma_kernel<1> (O-projection and MLP down projection + residual)",
               "gate_up": "gemm_bf16_mfma_kernel<2> (MLP gate/up projection + SiLU-multiply)"}
