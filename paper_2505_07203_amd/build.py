@@ -17,7 +17,11 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hi
 
 # attention: max() of finite-or--inf scores needs no NaN canonicalisation; MFMA builtins write
 # architectural registers (the softmax reads them), see the register-file note in the kernel
-EXTRA_FLAGS = {"attn_mfma.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+# the software-pipelined loop bodies are written as fully unrolled loops far larger than the default
+# limit up to which "#pragma unroll" is honoured (past it the loop silently stays and every register
+# array indexed by its counter moves to scratch memory)
+EXTRA_FLAGS = {"attn_mfma.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+                                 "-mllvm", "-pragma-unroll-threshold=1048576"]}
 
 
 def _compile(src: str) -> str:

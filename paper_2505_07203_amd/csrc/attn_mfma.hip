@@ -283,9 +283,8 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
 // rows there is a single wavefront per SIMD, so the softmax arithmetic has to run in the
 // shadow of the SAME wavefront's MFMAs; the loop is software-pipelined over blocks of 32 keys:
 //
-//   iteration i, first half : 16 MFMA  S(i+1) = K(i+1) Q^T      | VALU: P(i) = exp2(S(i) - m)
-//   iteration i, second half: 16 MFMA  O^T += V^T(i) P(i)^T      | VALU: block max of S(i+1),
-//                                                                        row sums of P(i)
+//   iteration i, first half : 16 MFMA  S(i+1) = K(i+1) Q^T      | VALU: 24 of the 32 P(i) = exp2(S(i) - r)
+//   iteration i, second half: 16 MFMA  O^T += V^T(i) P(i)^T      | VALU: the other 8, row sums of P(i)
 // MFMAs and their LDS fragment reads are written one by one with a slice of the vector work
 // behind each (scheduling fences keep that order).
 //
@@ -303,12 +302,16 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
 // single block, would overflow before the watch sees it; scores of that size do not come out
 // of bf16 attention inputs of the kind this path serves.
 //
+// LDS holds the K tiles of the four stages in its first 64 KiB and the V^T tiles in the second: with
+// the stage number known at compile time (main loop unrolled over the four stages) every fragment
+// address is a fixed per-lane register plus an immediate offset below 64 KiB.
 // K (64 keys x 256 B) and V^T (128 rows x 128 B) tiles go global -> LDS directly
 // (global_load_lds, 16 B per lane) through a ring of four 32 KiB stages, three tiles ahead;
 // the XOR swizzles of the kernel above are applied on the global side of the copy.  One
 // workgroup barrier per 64-key tile hands a stage over.
-constexpr int A64_STAGE = 2 * 64 * 128 * 2;     // K tile + V^T tile
+constexpr int A64_TILE = 64 * 128 * 2;          // one K tile or one V^T tile: 16 KiB
 constexpr int A64_NSTAGE = 4;
+constexpr int A64_VBASE = A64_NSTAGE * A64_TILE; // LDS: the four K tiles, then the four V^T tiles
 
 __device__ __forceinline__ float half_swap_max(float x) {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -374,20 +377,23 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
     // beyond it read as zero (they are masked keys) instead of needing a clamp per load.
     const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(k + (int64_t)kvh * HD), 0, (int)((uint32_t)(N - 1) * krs2 + 256u), 0x00020000);
-    const unsigned char* vg = (const unsigned char*)(vt + (int64_t)kvh * HD * ldv);
-#define PO_DMA(tile_, jj_)                                                                                     \
+    // (V^T of this KV head: 128 rows of ldv positions; its columns are always inside the row)
+    const __amdgpu_buffer_rsrc_t vrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(vt + (int64_t)kvh * HD * ldv), 0, (int)((uint32_t)HD * (uint32_t)(ldv * 2)), 0x00020000);
+    const uint32_t vrow32 = (uint32_t)(32 * ldv * 2);
+    // load jj_ (0..3: K rows, 4..7: V^T rows) of tile tile_ into stage stg_
+#define PO_DMA(tile_, stg_, jj_)                                                                               \
     {                                                                                                          \
         const int kv0_ = min((tile_), n_tiles - 1) * 64;                                                       \
-        unsigned char* dst_ = smem + ((tile_) & (A64_NSTAGE - 1)) * A64_STAGE +                                \
-                              ((jj_) < 4 ? ((jj_) * 16 + wave * 4) * 256 : TILE_BYTES + (((jj_) - 4) * 32 + wave * 8) * 128); \
         if ((jj_) < 4) {                                                                                       \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (__attribute__((address_space(3))) void*)dst_, 16,  \
-                                                     klane, (kv0_ + (jj_) * 16) * krs2, 0, 0);                  \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                          \
+                krsrc, (__attribute__((address_space(3))) void*)(smem + (stg_) * A64_TILE + ((jj_) * 16 + wave * 4) * 256), \
+                16, klane, (kv0_ + (jj_) * 16) * krs2, 0, 0);                                                  \
         } else {                                                                                               \
-            const unsigned char* b_ = vg + (int64_t)((jj_) - 4) * 32 * (ldv * 2) + kv0_ * 2;                   \
-            asm volatile("" : "+s"(b_));                                                                       \
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b_ + voff_v),     \
-                                             (__attribute__((address_space(3))) void*)dst_, 16, 0, 0);         \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                          \
+                vrsrc, (__attribute__((address_space(3))) void*)(smem + A64_VBASE + (stg_) * A64_TILE +        \
+                                                                 (((jj_) - 4) * 32 + wave * 8) * 128),          \
+                16, voff_v, ((jj_) - 4) * vrow32 + kv0_ * 2, 0, 0);                                            \
         }                                                                                                      \
     }
 
@@ -400,7 +406,7 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int j2 = 0; j2 < 2; ++j2) vofs[a][j2] = TILE_BYTES + l31 * 128 + (((a * 4 + j2 * 2 + lhi) ^ swz8(l31)) << 4);
+        for (int j2 = 0; j2 < 2; ++j2) vofs[a][j2] = l31 * 128 + (((a * 4 + j2 * 2 + lhi) ^ swz8(l31)) << 4);
 
     f32x16 oacc[HT][2];
 #pragma unroll
@@ -434,9 +440,9 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
     }
 
     // ---- prologue: three tiles in flight, S(0), reference maxima
-    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(0, jj);
-    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(1, jj);
-    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(2, jj);
+    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(0, 0, jj);
+    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(1, 1, jj);
+    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(2, 2, jj);
     asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");      // Q fragments and tile 0 have landed
 
     f32x16 sa[2], sb[2];
@@ -489,9 +495,21 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
               : (c_) < 16 ? (VST_) + (((c_) - 8) & 3) * 4096 + vofs[VA_][((c_) - 8) >> 2]                       \
                           : (NKST_) + (NKA_) * 8192 + koff[(c_) & 7])
 #define PO_WAIT_LGKM2() __builtin_amdgcn_s_waitcnt(0xC27F)     /* lgkmcnt(2), other counters untouched */
-#define PO_ITER(i_, SC, SN, KST_, KA_, VST_, VA_, NKST_, NKA_, BAR_, DMA_T_, DMA_J0_, MASK_)                    \
+    // job whose exponentials are issued in MFMA slot s_ (-1: none), and the first of its two values
+#define PO_JOB_AT(s_) ((s_) < 0 ? -1 : (s_) < 8 ? (s_) : (s_) < 16 ? (((s_) & 1) ? -1 : 8 + ((s_) - 8) / 2) \
+                       : (((s_) < 24 && !((s_) & 1)) ? 12 + ((s_) - 16) / 2 : -1))
+#define PO_JOB_E(n_) ((n_) < 4 ? 2 * (n_) : (n_) < 8 ? 16 + 2 * ((n_) - 4) : (n_) < 12 ? 8 + 2 * ((n_) - 8) : 24 + 2 * ((n_) - 12))
+#define PO_EXP_ARG(n_, SC, mb0_, mb1_)                                                             \
+    {                                                                                              \
+        const int e_ = PO_JOB_E((n_) & 15);                                                        \
+        const float mb_ = (e_ >> 4) ? mb1_ : mb0_;                                                 \
+        ea_[(n_) & 15][0] = fmaf(SC[e_ >> 4][e_ & 15], sc_log2e, -mb_);                            \
+        ea_[(n_) & 15][1] = fmaf(SC[e_ >> 4][(e_ & 15) + 1], sc_log2e, -mb_);                      \
+    }
+#define PO_ITER(i_, SC, SN, KST_, KA_, VST_, VA_, NKST_, NKA_, BAR_, DMA_T_, DMA_S_, DMA_J0_, MASK_)            \
     {                                                                                                           \
         const float mb0_ = mb[0], mb1_ = mb[1];                                                                 \
+        float ea_[16][2];                                                                                       \
         _Pragma("unroll") for (int c = 0; c < 16; ++c) {                                                        \
             if (c == 8) {                                                                                       \
                 if (MASK_) {                                                                                    \
@@ -519,36 +537,41 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
                     fr[(c + 3) & 3] = *(const bf16x8*)PO_FRAG_ADDR(c + 3, KST_, KA_, VST_, VA_, NKST_, NKA_);   \
                     __builtin_amdgcn_sched_barrier(0);                                                          \
                 }                                                                                               \
-                /* Probabilities of S(i), two at a time behind an MFMA.  The exponential is a quarter-rate       \
-                   instruction: 32 of them cost as many cycles as the 16 MFMAs of a half, so 24 go into the     \
-                   first half (slots 0..7: the 16 values the first four V^T steps need; slots 8, 10, 12, 14:    \
-                   query tile 0, registers 8..15) and the last 8 (query tile 1, registers 8..15, needed from    \
-                   V^T step 4 on) into the first MFMA slots of the second half. */                              \
+                /* Probabilities of S(i): 16 jobs of two values (one packed conversion each).  The            \
+                   exponential is a quarter-rate instruction, so 12 jobs go into the first half (slots 0..7:    \
+                   the 16 values the first four V^T steps need; slots 8, 10, 12, 14: query tile 0, registers    \
+                   8..15) and 4 (query tile 1, registers 8..15, needed from V^T step 4 on) into slots 16, 18,   \
+                   20, 22.  Each job is spread over three MFMA slots (exponent arguments | exponentials |       \
+                   conversion) so that no instruction waits for the one issued just before it. */               \
                 const int slot_ = 2 * c + qt;                    /* 0..31 over the iteration */                 \
-                const int e_ = slot_ < 8 ? (slot_ < 4 ? 2 * slot_ : 16 + 2 * (slot_ - 4))                       \
-                             : (slot_ < 16 ? ((slot_ & 1) ? -1 : 8 + (slot_ - 8))                               \
-                             : ((slot_ < 24 && !(slot_ & 1)) ? 24 + (slot_ - 16) : -1));                        \
-                if (e_ >= 0) {                                                                                  \
-                    const int pq_ = e_ >> 4, pr_ = e_ & 15;                                                     \
-                    const float mb_ = pq_ ? mb1_ : mb0_;                                                        \
-                    const float p0_ = __builtin_amdgcn_exp2f(fmaf(SC[pq_][pr_], sc_log2e, -mb_));               \
-                    const float p1_ = __builtin_amdgcn_exp2f(fmaf(SC[pq_][pr_ + 1], sc_log2e, -mb_));           \
-                    pf[pq_][pr_ >> 3][pr_ & 7] = (__bf16)p0_;                                                   \
-                    pf[pq_][pr_ >> 3][(pr_ & 7) + 1] = (__bf16)p1_;                                             \
+                {                                                                                               \
+                    const int na_ = PO_JOB_AT(slot_ + 1), nb_ = PO_JOB_AT(slot_), nc_ = PO_JOB_AT(slot_ - 1);   \
+                    if (slot_ == 0) { PO_EXP_ARG(0, SC, mb0_, mb1_); }                                          \
+                    if (na_ > 0) { PO_EXP_ARG(na_, SC, mb0_, mb1_); }                                           \
+                    if (nb_ >= 0) {                                                                             \
+                        ea_[nb_ & 15][0] = __builtin_amdgcn_exp2f(ea_[nb_ & 15][0]);                            \
+                        ea_[nb_ & 15][1] = __builtin_amdgcn_exp2f(ea_[nb_ & 15][1]);                            \
+                    }                                                                                           \
+                    if (nc_ >= 0) {                                                                             \
+                        const int e_ = PO_JOB_E(nc_ & 15);                                                      \
+                        pf[e_ >> 4][(e_ & 15) >> 3][e_ & 7] = (__bf16)ea_[nc_ & 15][0];                         \
+                        pf[e_ >> 4][(e_ & 15) >> 3][(e_ & 7) + 1] = (__bf16)ea_[nc_ & 15][1];                   \
+                    }                                                                                           \
                 }                                                                                               \
                 if (c >= 8) {                                                                                   \
                     const int c_ = (c - 8) * 2 + qt;             /* 0..15 */                                    \
                     if (c_ == 8 || c_ == 9) {                                                                   \
                         const int sq_ = c_ - 8;                                                                 \
-                        float l_ = lrow[sq_];                                                                   \
+                        /* four independent chains: a dependent dot product waits about 6 cycles */             \
+                        float l_[4] = {lrow[sq_], 0.f, 0.f, 0.f};                                               \
                         _Pragma("unroll") for (int h2 = 0; h2 < 2; ++h2)                                        \
                         _Pragma("unroll") for (int e2 = 0; e2 < 4; ++e2) {                                      \
                             const bf16x2 pr2_ = {pf[sq_][h2][2 * e2], pf[sq_][h2][2 * e2 + 1]};                 \
-                            l_ = __builtin_amdgcn_fdot2_f32_bf16(pr2_, ones, l_, false);                        \
+                            l_[e2] = __builtin_amdgcn_fdot2_f32_bf16(pr2_, ones, l_[e2], false);                \
                         }                                                                                       \
-                        lrow[sq_] = l_;                                                                         \
+                        lrow[sq_] = (l_[0] + l_[1]) + (l_[2] + l_[3]);                                          \
                     }                                                                                           \
-                    if ((c_ & 3) == 3) { PO_DMA(DMA_T_, (DMA_J0_) + (c_ >> 2)); }                               \
+                    if ((c_ & 3) == 3) { PO_DMA(DMA_T_, DMA_S_, (DMA_J0_) + (c_ >> 2)); }                       \
                 }                                                                                               \
                 __builtin_amdgcn_sched_barrier(0);                                                              \
             }                                                                                                   \
@@ -576,12 +599,15 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
     // block 2j+1.  The causal mask touches S(i+1) only in the last three blocks of a wavefront
     // (i + 1 >= qw / 32), so the loop is split by pair into: no mask | second block masked | both masked |
     // nothing left to compute (the wavefront still copies its share and meets the barriers).
-#define PO_PAIR(M0_, M1_)                                                                          \
+    // s_ = j & 3: the stage of tile j (a literal in the unrolled main loop, so that every LDS address
+    // below is a lane register plus an immediate)
+#define PO_PAIR(s_, M0_, M1_)                                                                      \
     {                                                                                              \
-        const unsigned char* st = smem + (j & (A64_NSTAGE - 1)) * A64_STAGE;                       \
-        const unsigned char* stn = smem + ((j + 1) & (A64_NSTAGE - 1)) * A64_STAGE;                \
-        PO_ITER(2 * j, sa, sb, st, 1, st, 0, stn, 0, 1, j + 3, 0, M0_);                            \
-        PO_ITER(2 * j + 1, sb, sa, stn, 0, st, 1, stn, 1, 0, j + 3, 4, M1_);                       \
+        const unsigned char* kst = smem + (s_) * A64_TILE;                                         \
+        const unsigned char* kstn = smem + (((s_) + 1) & 3) * A64_TILE;                            \
+        const unsigned char* vst = smem + A64_VBASE + (s_) * A64_TILE;                             \
+        PO_ITER(2 * j, sa, sb, kst, 1, vst, 0, kstn, 0, 1, j + 3, ((s_) + 3) & 3, 0, M0_);         \
+        PO_ITER(2 * j + 1, sb, sa, kstn, 0, vst, 1, kstn, 1, 0, j + 3, ((s_) + 3) & 3, 4, M1_);    \
     }
     const int wt = qw >> 6;                      // pair that holds this wavefront's first query row
     const int j_last = (nkb_w > 0) ? wt : -1;    // last pair with work
@@ -589,17 +615,30 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
     fr[1] = *(const bf16x8*)(smem + 8192 + koff[1]);
     fr[2] = *(const bf16x8*)(smem + 8192 + koff[2]);
     int j = 0;
-    for (; j < j_last - 1; ++j) PO_PAIR(0, 0);
-    if (j == j_last - 1) { PO_PAIR(0, 1); ++j; }
-    if (j == j_last) { PO_PAIR(1, 1); ++j; }
+    for (; j + 4 <= j_last - 1; j += 4) {
+        PO_PAIR(0, 0, 0);
+        ++j;
+        PO_PAIR(1, 0, 0);
+        ++j;
+        PO_PAIR(2, 0, 0);
+        ++j;
+        PO_PAIR(3, 0, 0);
+        j -= 3;
+    }
+    for (; j < j_last - 1; ++j) PO_PAIR(j & 3, 0, 0);
+    if (j == j_last - 1) { PO_PAIR(j & 3, 0, 1); ++j; }
+    if (j == j_last) { PO_PAIR(j & 3, 1, 1); ++j; }
     for (; j < n_tiles; ++j) {
         asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
-        _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(j + 3, jj);
+        _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) PO_DMA(j + 3, (j + 3) & 3, jj);
     }
 #undef PO_PAIR
 #undef PO_FRAG_ADDR
 #undef PO_WAIT_LGKM2
 #undef PO_ITER
+#undef PO_JOB_AT
+#undef PO_JOB_E
+#undef PO_EXP_ARG
 #undef PO_DMA
 #undef PO_MASK
 #undef PO_BLOCKMAX
@@ -630,7 +669,7 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
 
 void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
                   int Hkv, hipStream_t s) {
-    constexpr int SMEM = A64_NSTAGE * A64_STAGE;
+    constexpr int SMEM = 2 * A64_NSTAGE * A64_TILE;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void*)attn_fwd64_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
