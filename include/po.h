@@ -109,6 +109,14 @@ typedef struct po_ctx po_ctx;
 po_status po_workspace_bytes(const po_model_config* cfg, int64_t max_input_len, int32_t mlp_chunk,
                              size_t* weights_bytes, size_t* workspace_bytes);
 
+/* Largest maximum input length whose two arenas fit in hbm_budget_bytes (the quantity the
+ * paper's evaluation calls maximum input length, Section 7.2 / its MIL table): the largest
+ * N with weights_bytes + workspace_bytes(N) <= budget, found by bisection on the closed
+ * form above; needs no GPU.  PO_ERR_OOM if not even one token fits; *max_len is capped at
+ * the longest sequence the kernels address (2^24 tokens, or less for wide KV rows). */
+po_status po_max_input_len(const po_model_config* cfg, int32_t mlp_chunk, size_t hbm_budget_bytes,
+                           int64_t* max_len);
+
 /* Creates a context over caller-provided device memory (256-byte aligned) and a HIP
  * stream (hipStream_t passed as void*; NULL = the default stream).  mlp_chunk is the
  * number of tokens per chunk of the position-wise layers (Section 4.2), >= 1. */
@@ -139,6 +147,18 @@ po_status po_prefill(po_ctx* ctx, const int32_t* tokens, int64_t len,
 po_status po_prefill_batch(po_ctx* ctx, const int32_t* tokens_concat, const int64_t* lens,
                            int32_t n_req, const int32_t* cand_ids, int32_t n_cand,
                            float* out_logits, float* out_cand_logprobs);
+
+/* Profile run (Section 3: at start-up the engine forwards a fake request of the declared
+ * maximum input length and sizes what is left of the GPU from it).  Fills the activation
+ * arena with a byte pattern, runs one request of `len` copies of token 0 (len <= the
+ * context's max_input_len; weights must be loaded), and reports the device time of that
+ * request and the measured high-water mark of the arena: the offset one past the highest
+ * byte the run changed.  The footprint is static, so the mark must come out as the closed
+ * form of po_workspace_bytes for the context's max_input_len, less the unused tail of the
+ * candidate buffers at the arena's end (sized for the largest candidate list; the fake
+ * request uses two); that is what this call lets a caller check.  Synchronous; overwrites
+ * the arena (the rotary table, the only content that outlives a request, is rebuilt). */
+po_status po_profile(po_ctx* ctx, int64_t len, double* elapsed_ms, size_t* touched_bytes);
 
 /* When on, po_prefill brackets the attention and GEMM launches with HIP events on its stream
  * so that po_get_stats can split the time per kernel class (adds event overhead; off by

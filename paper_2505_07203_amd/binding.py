@@ -33,7 +33,7 @@ EXPORTS = [
     "po_prefill_batch", "po_set_phase_timing", "po_get_stats", "po_destroy", "po_strerror",
     "po_last_device_error", "po_op_rmsnorm", "po_op_linear", "po_op_gate_up_silu",
     "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head", "po_op_rope_table",
-    "po_op_pack_qkv", "po_op_qkv_rope",
+    "po_op_pack_qkv", "po_op_qkv_rope", "po_max_input_len", "po_profile",
 ]
 
 
@@ -76,6 +76,8 @@ def lib() -> C.CDLL:
     L = C.CDLL(LIB_PATH)
     vp, i32, i64, sz, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
     L.po_workspace_bytes.argtypes = [C.POINTER(ModelConfigC), i64, i32, C.POINTER(sz), C.POINTER(sz)]
+    L.po_max_input_len.argtypes = [C.POINTER(ModelConfigC), i32, sz, C.POINTER(i64)]
+    L.po_profile.argtypes = [vp, i64, C.POINTER(C.c_double), C.POINTER(sz)]
     L.po_create.argtypes = [C.POINTER(ModelConfigC), i64, i32, vp, sz, vp, sz, vp, C.POINTER(vp)]
     L.po_load_tensor.argtypes = [vp, i32, i32, vp, sz]
     L.po_is_loaded.argtypes = [vp]
@@ -127,6 +129,14 @@ def po_workspace_bytes(cfg, max_input_len: int, mlp_chunk: int):
     cc = config_c(cfg)
     check(lib().po_workspace_bytes(C.byref(cc), max_input_len, mlp_chunk, C.byref(w), C.byref(s)))
     return w.value, s.value
+
+
+def po_max_input_len(cfg, mlp_chunk: int, hbm_budget_bytes: int) -> int:
+    """Largest maximum input length whose arenas fit the budget; closed form, needs no GPU."""
+    n = C.c_int64(0)
+    cc = config_c(cfg)
+    check(lib().po_max_input_len(C.byref(cc), mlp_chunk, hbm_budget_bytes, C.byref(n)))
+    return n.value
 
 
 def _host_ptr(a: Optional[np.ndarray]):
@@ -188,6 +198,12 @@ class Context:
         check(lib().po_prefill_batch(self._h, _host_ptr(tok), _host_ptr(lens), n_req, _host_ptr(cand_a),
                                      n_cand, _host_ptr(logits), _host_ptr(lp)))
         return logits, lp
+
+    def po_profile(self, length: int):
+        """-> (device ms of a fake request of `length` tokens, measured high-water mark of the arena)"""
+        ms, touched = C.c_double(0), C.c_size_t(0)
+        check(lib().po_profile(self._h, length, C.byref(ms), C.byref(touched)))
+        return ms.value, touched.value
 
     def po_set_phase_timing(self, on: bool) -> None:
         check(lib().po_set_phase_timing(self._h, 1 if on else 0))

@@ -454,4 +454,29 @@ void launch_vt_pad_zero(bf16_t* Vt, int rows, int64_t ldv, int64_t n, hipStream_
     hipLaunchKernelGGL(vt_pad_zero_kernel, dim3((unsigned)rows), dim3(64), 0, s, Vt, ldv, n, pad);
 }
 
+// Highest 32-bit word of an arena that differs from a fill pattern: per-thread strided scan,
+// wavefront/workgroup maximum, one 64-bit atomic maximum per workgroup.  *out must start at 0 and
+// receives (index of that word + 1), or stays 0 when nothing differs.
+__global__ void __launch_bounds__(256) high_water_kernel(const uint32_t* ws, size_t n_words, uint32_t pattern,
+                                                         unsigned long long* out) {
+    __shared__ unsigned long long part[4];
+    unsigned long long best = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (size_t)gridDim.x * 256)
+        if (ws[i] != pattern) best = i + 1;       // indices grow along the scan
+    for (int off = 32; off > 0; off >>= 1) {
+        const unsigned long long o = __shfl_xor(best, off);
+        best = o > best ? o : best;
+    }
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) best = part[w] > best ? part[w] : best;
+        if (best) atomicMax(out, best);
+    }
+}
+
+void launch_high_water(const void* ws, size_t bytes, uint32_t pattern, unsigned long long* out, hipStream_t s) {
+    hipLaunchKernelGGL(high_water_kernel, dim3(2048), dim3(256), 0, s, (const uint32_t*)ws, bytes / 4, pattern, out);
+}
+
 }  // namespace po

@@ -343,6 +343,32 @@ po_status po_workspace_bytes(const po_model_config* cfg, int64_t max_input_len, 
     return PO_OK;
 }
 
+po_status po_max_input_len(const po_model_config* cfg, int32_t mlp_chunk, size_t hbm_budget_bytes,
+                           int64_t* max_len) {
+    if (!cfg || !max_len) return PO_ERR_INVALID_ARG;
+    Layout L;
+    po_status st = make_layout(cfg, 1, mlp_chunk, &L);
+    if (st != PO_OK) return st;
+    if (L.weights_bytes + L.workspace_bytes > hbm_budget_bytes) return PO_ERR_OOM;
+    // longest length the kernels address (make_layout accepts every length up to it and none beyond)
+    int64_t ok = 1, bad = ((int64_t)1 << 24) + 1;
+    while (bad - ok > 1) {
+        const int64_t mid = ok + (bad - ok) / 2;
+        if (make_layout(cfg, mid, mlp_chunk, &L) == PO_OK) ok = mid; else bad = mid;
+    }
+    // the footprint is non-decreasing in the length: bisect on [1, ok]
+    int64_t lo = 1, hi = ok;
+    st = make_layout(cfg, hi, mlp_chunk, &L);
+    if (st == PO_OK && L.weights_bytes + L.workspace_bytes <= hbm_budget_bytes) { *max_len = hi; return PO_OK; }
+    while (hi - lo > 1) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        st = make_layout(cfg, mid, mlp_chunk, &L);
+        if (st == PO_OK && L.weights_bytes + L.workspace_bytes <= hbm_budget_bytes) lo = mid; else hi = mid;
+    }
+    *max_len = lo;
+    return PO_OK;
+}
+
 po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t mlp_chunk, void* dev_weights,
                     size_t weights_bytes, void* dev_workspace, size_t workspace_bytes, void* hip_stream,
                     po_ctx** out) {
@@ -490,6 +516,39 @@ po_status po_prefill_batch(po_ctx* c, const int32_t* tokens_concat, const int64_
     for (int kc = 0; kc < PO_K_COUNT; ++kc) { c->stats.kernel_ms[kc] = k_ms[kc]; c->stats.kernel_launches[kc] = k_n[kc]; }
     c->stats.last_len = off;
     return PO_OK;
+}
+
+po_status po_profile(po_ctx* c, int64_t len, double* elapsed_ms, size_t* touched_bytes) {
+    if (!c || len <= 0) return PO_ERR_INVALID_ARG;
+    if (len > c->max_len) return PO_ERR_TOO_LONG;
+    if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
+    const size_t ws_bytes = c->lay.workspace_bytes;
+    unsigned long long* d_mark = nullptr;
+    if (hipMalloc(&d_mark, sizeof(unsigned long long)) != hipSuccess) return PO_ERR_OOM;
+    std::vector<int32_t> tokens((size_t)len, 0);
+    const int32_t cand[2] = {0, c->cfg.vocab_size - 1};
+    float lp[2];
+    po_status st = PO_ERR_DEVICE;
+    if (hipMemsetAsync(c->ws, 0xA5, ws_bytes, c->stream) == hipSuccess &&
+        hipMemsetAsync(d_mark, 0, sizeof(unsigned long long), c->stream) == hipSuccess) {
+        // the rotary table is the one thing in the arena that outlives a request: rebuild it
+        launch_rope_table((float*)(c->ws + c->lay.rope_cos), (float*)(c->ws + c->lay.rope_sin), c->max_len,
+                          c->cfg.head_dim, c->cfg.rope_theta, c->stream);
+        st = run_prefill(c, tokens.data(), len, cand, 2, nullptr, lp);
+        if (st == PO_OK) {
+            launch_high_water(c->ws, ws_bytes, 0xA5A5A5A5u, d_mark, c->stream);
+            unsigned long long mark = 0;
+            if (hipMemcpyAsync(&mark, d_mark, sizeof(mark), hipMemcpyDeviceToHost, c->stream) == hipSuccess &&
+                hipStreamSynchronize(c->stream) == hipSuccess) {
+                if (elapsed_ms) *elapsed_ms = c->stats.last_prefill_ms;
+                if (touched_bytes) *touched_bytes = (size_t)mark * 4;
+            } else {
+                st = PO_ERR_DEVICE;
+            }
+        }
+    }
+    (void)hipFree(d_mark);
+    return st;
 }
 
 po_status po_set_phase_timing(po_ctx* c, int32_t on) {

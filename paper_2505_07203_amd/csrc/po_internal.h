@@ -71,6 +71,7 @@ void launch_gemm_qkv_rope(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int6
 void launch_pack_rope_rows(bf16_t* W, int n_heads, int hd, int64_t row_elems, hipStream_t s);
 // zero columns [n, round_up(n,64)) of V^T [rows][ldv]
 void launch_vt_pad_zero(bf16_t* Vt, int rows, int64_t ldv, int64_t n, hipStream_t s);
+void launch_high_water(const void* ws, size_t bytes, uint32_t pattern, unsigned long long* out, hipStream_t s);
 // Vt[Hkv*hd][ldv] = transpose of V[n, Hkv*hd]; columns n..round_up(n,64)-1 are zero-filled
 void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int64_t ldv, hipStream_t s);
 // causal GQA flash attention; q [N,Hq,hd], k [N,Hkv,hd], vt [Hkv*hd][ldv]; o may alias q

@@ -83,6 +83,34 @@ def test_activation_footprint_slope_is_one_layer_of_kv():
     assert slope < all_layer_kv / 5
 
 
+@pytest.mark.parametrize("cfg,chunk", [(I.LLAMA8B, 4096), (I.QWEN32B, 4096), (I.TINY, 512)])
+def test_max_input_len_is_the_largest_length_that_fits(cfg, chunk):
+    """Section 3 / the paper's maximum-input-length metric: bisection on the closed form."""
+    for budget in (24e9, 40e9, 80e9, 288e9):
+        budget = int(budget)
+        wb1, sb1 = B.po_workspace_bytes(cfg, 1, chunk)
+        if wb1 + sb1 > budget:
+            with pytest.raises(B.PoError):
+                B.po_max_input_len(cfg, chunk, budget)
+            continue
+        n = B.po_max_input_len(cfg, chunk, budget)
+        wb, sb = B.po_workspace_bytes(cfg, n, chunk)
+        assert wb + sb <= budget
+        if n < (1 << 24):
+            try:
+                wb2, sb2 = B.po_workspace_bytes(cfg, n + 1, chunk)
+                assert wb2 + sb2 > budget
+            except B.PoError:
+                pass            # n is the longest sequence the kernels address
+    # the 8B shape in the 24 GB of the paper's smallest GPU: (budget - weights - chunk scratch) / slope
+    if cfg is I.LLAMA8B:
+        n = B.po_max_input_len(cfg, chunk, int(24e9))
+        wb, _ = B.po_workspace_bytes(cfg, 1, chunk)
+        assert abs(n - (24e9 - wb - 2 * 4096 * (4096 + 14336) - 4 * 128256) / 20996) < 2000
+        # all-layer KV + unchunked MLP would pay 249856 bytes per token instead of 20996
+        assert n > 10 * (24e9 - wb) / 249856 * 0.9
+
+
 def test_paper_size_arithmetic():
     vals = {}
     for line in open(os.path.join(ROOT, "tests", "golden", "paper_sizes.txt")):

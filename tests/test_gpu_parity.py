@@ -294,3 +294,25 @@ def test_op_qkv_rope(Hq, Hkv, hd, K, M, pos0, bias):
     outside = np.ones(vt.shape[1], dtype=bool)
     outside[pos0:pos0 + M] = False
     assert np.all(from_dev(vt)[:, outside] == 0)
+
+
+def test_profile_run_measures_the_static_footprint():
+    """Section 3's profile run: a fake request of the maximum length; the arena's measured high-water
+    mark is the closed form (static arenas), whatever the request length."""
+    cfg = I.TINY.replace(dtype=I.BF16, ffn_dim=704)
+    ctx = make_ctx(cfg, 31, 1000, 256)
+    try:
+        tokens = I.make_tokens(cfg, 5, 200)
+        z0, lp0 = ctx.po_prefill(tokens, I.label_ids(cfg))
+        for n in (1000, 37):
+            ms, touched = ctx.po_profile(n)
+            assert ms > 0
+            # (the arena ends with the candidate log-prob buffer, sized for 4096 candidates; 2 are used)
+            assert ctx.workspace_bytes - 4096 * 4 - 256 <= touched <= ctx.workspace_bytes
+        with pytest.raises(B.PoError):
+            ctx.po_profile(1001)
+        # the arena is scratch: the same request before and after the profile runs, bit for bit
+        z1, lp1 = ctx.po_prefill(tokens, I.label_ids(cfg))
+        assert np.array_equal(z0, z1) and np.array_equal(lp0, lp1)
+    finally:
+        ctx.po_destroy()
