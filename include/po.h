@@ -160,6 +160,13 @@ po_status po_prefill_batch(po_ctx* ctx, const int32_t* tokens_concat, const int6
  * the arena (the rotary table, the only content that outlives a request, is rebuilt). */
 po_status po_profile(po_ctx* ctx, int64_t len, double* elapsed_ms, size_t* touched_bytes);
 
+/* Last-layer shortcut, on by default.  A prefill-only request produces one token (Section 1),
+ * so nothing reads the last layer's output except at the last position: with the shortcut
+ * the last layer still forms K and V for every position, but runs attention only for the
+ * row block that holds the last position and the O-projection and MLP only for that row.
+ * Logits and log-probs are bit-identical with the shortcut on and off. */
+po_status po_set_lazy_last_layer(po_ctx* ctx, int32_t on);
+
 /* When on, po_prefill brackets the attention and GEMM launches with HIP events on its stream
  * so that po_get_stats can split the time per kernel class (adds event overhead; off by
  * default). */

@@ -33,7 +33,7 @@ EXPORTS = [
     "po_prefill_batch", "po_set_phase_timing", "po_get_stats", "po_destroy", "po_strerror",
     "po_last_device_error", "po_op_rmsnorm", "po_op_linear", "po_op_gate_up_silu",
     "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head", "po_op_rope_table",
-    "po_op_pack_qkv", "po_op_qkv_rope", "po_max_input_len", "po_profile",
+    "po_op_pack_qkv", "po_op_qkv_rope", "po_max_input_len", "po_profile", "po_set_lazy_last_layer",
 ]
 
 
@@ -84,6 +84,7 @@ def lib() -> C.CDLL:
     L.po_prefill.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.po_prefill_batch.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
     L.po_set_phase_timing.argtypes = [vp, i32]
+    L.po_set_lazy_last_layer.argtypes = [vp, i32]
     L.po_get_stats.argtypes = [vp, C.POINTER(StatsC)]
     L.po_destroy.argtypes = [vp]
     L.po_destroy.restype = None
@@ -204,6 +205,9 @@ class Context:
         ms, touched = C.c_double(0), C.c_size_t(0)
         check(lib().po_profile(self._h, length, C.byref(ms), C.byref(touched)))
         return ms.value, touched.value
+
+    def po_set_lazy_last_layer(self, on: bool) -> None:
+        check(lib().po_set_lazy_last_layer(self._h, 1 if on else 0))
 
     def po_set_phase_timing(self, on: bool) -> None:
         check(lib().po_set_phase_timing(self._h, 1 if on else 0))

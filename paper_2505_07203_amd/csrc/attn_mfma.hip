@@ -668,7 +668,7 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
 }
 
 void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
-                  int Hkv, hipStream_t s) {
+                  int Hkv, int64_t q_row0, hipStream_t s) {
     constexpr int SMEM = 2 * A64_NSTAGE * A64_TILE;
     static bool attr_set = false;
     if (!attr_set) {
@@ -678,13 +678,15 @@ void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ld
     const int nqt = (int)((N + 255) / 256);
     const int hpx = (Hq % 8 == 0) ? Hq / 8 : 0;
     const float sc_log2e = (float)(1.4426950408889634 / sqrt(128.0));
-    hipLaunchKernelGGL(attn_fwd64_kernel, dim3((unsigned)(nqt * Hq)), dim3(256), SMEM, s, q, k, vt, ldv, o, (int)N, Hq,
+    // workgroups enumerate query tiles from the last one down: fewer of them = only the last tiles
+    const int nsel = nqt - (int)((q_row0 > 0 && q_row0 < N) ? q_row0 / 256 : 0);
+    hipLaunchKernelGGL(attn_fwd64_kernel, dim3((unsigned)(nsel * Hq)), dim3(256), SMEM, s, q, k, vt, ldv, o, (int)N, Hq,
                        Hkv, sc_log2e, nqt, hpx);
 }
 
 template <int HD, int QT, int NW>
 void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
-              int Hkv, hipStream_t s) {
+              int Hkv, int64_t q_row0, hipStream_t s) {
     constexpr int BMQ = NW * QT * 32;
     constexpr int SMEM = 2 * 2 * BNK * HD * 2;
     static bool attr_set = false;
@@ -696,7 +698,9 @@ void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, b
     const int nqt = (int)((N + BMQ - 1) / BMQ);
     const int hpx = (Hq % 8 == 0) ? Hq / 8 : 0;
     const float sc_log2e = (float)(1.4426950408889634 / sqrt((double)HD));
-    hipLaunchKernelGGL((attn_fwd_kernel<HD, QT, NW>), dim3((unsigned)(nqt * Hq)), dim3(NW * 64), SMEM, s, q, k, vt,
+    // workgroups enumerate query tiles from the last one down: fewer of them = only the last tiles
+    const int nsel = nqt - (int)((q_row0 > 0 && q_row0 < N) ? q_row0 / BMQ : 0);
+    hipLaunchKernelGGL((attn_fwd_kernel<HD, QT, NW>), dim3((unsigned)(nsel * Hq)), dim3(NW * 64), SMEM, s, q, k, vt,
                        ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, hpx);
 }
 
@@ -707,10 +711,10 @@ bool attention_mfma_supported(int Hq, int Hkv, int hd) {
 }
 
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N,
-                           int Hq, int Hkv, int hd, hipStream_t s) {
+                           int Hq, int Hkv, int hd, int64_t q_row0, hipStream_t s) {
     if (N <= 0) return;
-    if (hd == 128) launch_fwd64(q, k, vt, ldv, o, N, Hq, Hkv, s);
-    else if (hd == 64) launch_t<64, 1, 8>(q, k, vt, ldv, o, N, Hq, Hkv, s);
+    if (hd == 128) launch_fwd64(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, s);
+    else if (hd == 64) launch_t<64, 1, 8>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, s);
 }
 
 }  // namespace po

@@ -260,12 +260,12 @@ void launch_silu_mul(int dtype, const void* GU, void* H, int64_t M, int F, hipSt
 template <typename T, int HD>
 __global__ void __launch_bounds__(64) attention_basic_kernel(const T* q, const T* __restrict__ k,
                                                              const T* __restrict__ v, T* o, int64_t N, int Hq,
-                                                             int Hkv) {
+                                                             int Hkv, int64_t blk0) {
     __shared__ float Ks[32][HD];
     __shared__ float Vs[32][HD];
     const int h = blockIdx.y;
     const int c = h / (Hq / Hkv);
-    const int64_t r0 = (int64_t)blockIdx.x * 64;
+    const int64_t r0 = ((int64_t)blockIdx.x + blk0) * 64;
     const int64_t t = r0 + threadIdx.x;
     const bool live = t < N;
     float qv[HD], ov[HD];
@@ -312,12 +312,13 @@ __global__ void __launch_bounds__(64) attention_basic_kernel(const T* q, const T
 }
 
 void launch_attention_basic(int dtype, const void* q, const void* k, const void* v, void* o, int64_t N, int Hq,
-                            int Hkv, int hd, hipStream_t s) {
+                            int Hkv, int hd, int64_t q_row0, hipStream_t s) {
     if (N <= 0) return;
-    const dim3 grid((unsigned)((N + 63) / 64), (unsigned)Hq);
+    const int64_t blk0 = (q_row0 > 0 && q_row0 < N) ? q_row0 / 64 : 0;
+    const dim3 grid((unsigned)((N + 63) / 64 - blk0), (unsigned)Hq);
 #define PO_ATT(T, HDV)                                                                                       \
     hipLaunchKernelGGL((attention_basic_kernel<T, HDV>), grid, dim3(64), 0, s, (const T*)q, (const T*)k,    \
-                       (const T*)v, (T*)o, N, Hq, Hkv)
+                       (const T*)v, (T*)o, N, Hq, Hkv, blk0)
     if (dtype == 0) {
         if (hd == 64) PO_ATT(float, 64);
         else if (hd == 128) PO_ATT(float, 128);

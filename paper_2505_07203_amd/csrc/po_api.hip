@@ -139,6 +139,7 @@ struct po_ctx {
     std::vector<uint32_t> loaded;     // per layer bitmask of tensor kinds; index n_layers = globals
     hipEvent_t ev_start, ev_stop;
     bool phase_timing;
+    bool lazy_last_layer;             // last layer: queries, attention rows and MLP only where the last token needs them
     std::vector<hipEvent_t> ev_pool;  // pairs
     std::vector<int> ev_kind;         // per pair: po_kernel_class
     size_t ev_used;
@@ -242,18 +243,24 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
             launch_rope(dt, Q, qd, rc, rs, len, m.n_q_heads, hd, s);
             launch_rope(dt, K, kvd, rc, rs, len, m.n_kv_heads, hd, s);
         }
+        // Nothing reads the last layer's output except the last position (one output token, Section 1):
+        // there the keys and values of every position are still needed, but attention, O-projection and
+        // MLP only for the row block / the row that holds position len - 1.  Row results do not depend on
+        // which other rows are computed, so the logits are bit-identical with and without this.
+        const bool last_only = c->lazy_last_layer && l == m.n_layers - 1;
         // ---- attention over the whole sequence in one call; O overwrites Q
         {
             PhaseTimer pt(c, PO_K_ATTENTION);
+            const int64_t q_row0 = last_only ? len - 1 : 0;
             if (dt == PO_BF16) {
                 launch_attention_mfma((const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)(ws + L.Vt), L.ldv,
-                                      (bf16_t*)Q, len, m.n_q_heads, m.n_kv_heads, hd, s);
+                                      (bf16_t*)Q, len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
             } else {
-                launch_attention_basic(dt, Q, K, V, Q, len, m.n_q_heads, m.n_kv_heads, hd, s);
+                launch_attention_basic(dt, Q, K, V, Q, len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
             }
         }
         // ---- position-wise part after attention, chunk by chunk, residual stream in place
-        for (int64_t c0 = 0; c0 < len; c0 += C) {
+        for (int64_t c0 = last_only ? len - 1 : 0; c0 < len; c0 += C) {
             const int64_t rows = (len - c0 < C) ? len - c0 : C;
             unsigned char* Xc = X + (size_t)c0 * d * esz;
             const unsigned char* Oc = Q + (size_t)c0 * qd * esz;
@@ -390,6 +397,7 @@ po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t m
     c->stream = (hipStream_t)hip_stream;
     c->loaded.assign(cfg->n_layers + 1, 0u);
     c->phase_timing = false;
+    c->lazy_last_layer = true;
     c->ev_used = 0;
     memset(&c->stats, 0, sizeof(c->stats));
     c->stats.weights_bytes = c->lay.weights_bytes;
@@ -551,6 +559,12 @@ po_status po_profile(po_ctx* c, int64_t len, double* elapsed_ms, size_t* touched
     return st;
 }
 
+po_status po_set_lazy_last_layer(po_ctx* c, int32_t on) {
+    if (!c) return PO_ERR_INVALID_ARG;
+    c->lazy_last_layer = on != 0;
+    return PO_OK;
+}
+
 po_status po_set_phase_timing(po_ctx* c, int32_t on) {
     if (!c) return PO_ERR_INVALID_ARG;
     c->phase_timing = on != 0;
@@ -650,10 +664,10 @@ po_status po_op_attention(int32_t dtype, const void* q, const void* k, const voi
         const int64_t ldv = round_up64(N, 64);
         launch_v_transpose((const bf16_t*)v, (bf16_t*)scratch, N, Hkv * hd, ldv, (hipStream_t)stream);
         launch_attention_mfma((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)scratch, ldv, (bf16_t*)o, N, Hq, Hkv,
-                              hd, (hipStream_t)stream);
+                              hd, 0, (hipStream_t)stream);
     } else {
         if (hd != 32 && hd != 64 && hd != 128) return PO_ERR_BAD_CONFIG;
-        launch_attention_basic(dtype, q, k, v, o, N, Hq, Hkv, hd, (hipStream_t)stream);
+        launch_attention_basic(dtype, q, k, v, o, N, Hq, Hkv, hd, 0, (hipStream_t)stream);
     }
     PO_HIP(hipGetLastError());
     return PO_OK;

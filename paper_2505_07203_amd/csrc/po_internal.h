@@ -39,8 +39,9 @@ void launch_gemm_basic(int dtype, const void* A, int64_t lda, const void* W, int
 // H[M,F] = silu(GU[:, :F]) * GU[:, F:]   (GU row stride 2F)
 void launch_silu_mul(int dtype, const void* GU, void* H, int64_t M, int F, hipStream_t s);
 // fp32-path attention (one thread per query row), o may alias q
+// (q_row0: only the query-row blocks from the one that holds row q_row0 on are computed; 0 = all rows)
 void launch_attention_basic(int dtype, const void* q, const void* k, const void* v, void* o, int64_t N,
-                            int Hq, int Hkv, int hd, hipStream_t s);
+                            int Hq, int Hkv, int hd, int64_t q_row0, hipStream_t s);
 // logits[V] = x[d] . W[V,d]^T
 void launch_lm_head(int dtype, const void* x, const void* W, float* logits, int V, int d, hipStream_t s);
 // lp[i] = logits[cand[i]] - logsumexp_j logits[cand[j]]
@@ -76,7 +77,7 @@ void launch_high_water(const void* ws, size_t bytes, uint32_t pattern, unsigned 
 void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int64_t ldv, hipStream_t s);
 // causal GQA flash attention; q [N,Hq,hd], k [N,Hkv,hd], vt [Hkv*hd][ldv]; o may alias q
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
-                           int64_t N, int Hq, int Hkv, int hd, hipStream_t s);
+                           int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, hipStream_t s);
 bool gemm_mfma_supported(int N, int K);
 bool attention_mfma_supported(int Hq, int Hkv, int hd);
 

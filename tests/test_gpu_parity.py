@@ -316,3 +316,24 @@ def test_profile_run_measures_the_static_footprint():
         assert np.array_equal(z0, z1) and np.array_equal(lp0, lp1)
     finally:
         ctx.po_destroy()
+
+
+@pytest.mark.parametrize("cfg,n", [(I.TINY, 300), (I.TINY.replace(dtype=I.BF16, ffn_dim=704), 777),
+                                   (I.LLAMA8B.replace(n_layers=2, vocab_size=4096), 1000)])
+def test_last_layer_shortcut_is_bitwise(cfg, n):
+    """The last layer computed only where the single output token needs it: same bits."""
+    ctx = make_ctx(cfg, 17, n, 256)
+    try:
+        tokens = I.make_tokens(cfg, 23, n)
+        cand = I.label_ids(cfg)
+        z_on, lp_on = ctx.po_prefill(tokens, cand)
+        ctx.po_set_lazy_last_layer(False)
+        z_off, lp_off = ctx.po_prefill(tokens, cand)
+        assert np.array_equal(z_on, z_off) and np.array_equal(lp_on, lp_off)
+        ctx.po_set_lazy_last_layer(True)
+        z_1, _ = ctx.po_prefill(tokens[:1], cand)       # a single token: the last row is row 0
+        ctx.po_set_lazy_last_layer(False)
+        z_1off, _ = ctx.po_prefill(tokens[:1], cand)
+        assert np.array_equal(z_1, z_1off)
+    finally:
+        ctx.po_destroy()
