@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one elementwise kernel that reads 1 GiB and writes 1 GiB, so that a "
                          "counter run of this command holds a dispatch of known HBM traffic")
+    ap.add_argument("--reuse-prefix", type=int, default=0,
+                    help="also time the first request again with the K/V of its first P tokens in the prefix "
+                         "cache (reported under prefix_reuse; not part of value)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (requests are independent; more GPUs run more "
@@ -206,6 +209,20 @@ def main():
         order = sorted(classes, key=lambda k: -k_ms[k])
         out["roofline"] = roof(order[0])
         out["roofline_other_kernels"] = [roof(k) for k in order[1:]]
+    if args.reuse_prefix > 0:
+        # not part of `value`: the same request again with the K/V of its first P tokens cached
+        p_len = min(args.reuse_prefix, lens[0] - 1)
+        cache_bytes = ctx.po_attach_kv_cache(p_len)
+        ctx.po_prefill_prefix(reqs[0], p_len, cand, want_logits=False)          # stores the prefix
+        ctx.po_prefill_prefix(reqs[0], 0, cand, want_logits=False)              # warm-up of the reuse path
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            _, _, reused = ctx.po_prefill_prefix(reqs[0], 0, cand, want_logits=False)
+        torch.cuda.synchronize()
+        out["prefix_reuse"] = {"request_tokens": lens[0], "reused_prefix_tokens": int(reused),
+                               "ms_per_request": 1e3 * (time.perf_counter() - t0) / args.steps,
+                               "kv_cache_bytes": int(cache_bytes)}
     ctx.po_destroy()
     del ctx
     torch.cuda.empty_cache()

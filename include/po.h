@@ -160,6 +160,29 @@ po_status po_prefill_batch(po_ctx* ctx, const int32_t* tokens_concat, const int6
  * the arena (the rotary table, the only content that outlives a request, is rebuilt). */
 po_status po_profile(po_ctx* ctx, int64_t len, double* elapsed_ms, size_t* touched_bytes);
 
+/* Prefix K/V cache (Section 5.1, suffix KV cache discarding: the K/V of a request's prefix
+ * tokens is kept on the GPU for later requests that share the prefix, the K/V of its suffix
+ * is discarded with each layer as before).  The cache is caller-provided device memory
+ * (256-byte aligned) of po_kv_cache_bytes(cfg, prefix_capacity) bytes: per layer the K rows
+ * and the V rows (stored transposed for bf16) of up to prefix_capacity positions, i.e.
+ * 2 * n_layers * n_kv_heads * head_dim elements per position.  dev_cache = NULL detaches. */
+po_status po_kv_cache_bytes(const po_model_config* cfg, int64_t prefix_capacity, size_t* bytes);
+po_status po_attach_kv_cache(po_ctx* ctx, void* dev_cache, size_t bytes, int64_t prefix_capacity);
+
+/* po_prefill with the prefix cache.  The longest common prefix of tokens[] with the tokens
+ * whose K/V the cache holds (at most len - 1 positions) is NOT recomputed: embedding,
+ * projections and MLP run on the remaining positions only, and attention reads the cached
+ * K/V of the prefix next to the fresh K/V of the rest (rectangular block for the prefix keys,
+ * causal block for the rest).  *reused_prefix_len (may be NULL) reports that length.
+ * keep_prefix > 0: afterwards the cache holds the K/V of tokens[0 .. keep_prefix), replacing
+ * what it held (keep_prefix <= len and <= prefix_capacity, else PO_ERR_TOO_LONG);
+ * keep_prefix = 0 leaves the cache as it is.  The outputs are bit-identical to po_prefill
+ * on the same tokens (a row's result does not depend on which other rows are computed).
+ * PO_ERR_INVALID_ARG without an attached cache. */
+po_status po_prefill_prefix(po_ctx* ctx, const int32_t* tokens, int64_t len, int64_t keep_prefix,
+                            const int32_t* cand_ids, int32_t n_cand,
+                            float* out_logits, float* out_cand_logprobs, int64_t* reused_prefix_len);
+
 /* Last-layer shortcut, on by default.  A prefill-only request produces one token (Section 1),
  * so nothing reads the last layer's output except at the last position: with the shortcut
  * the last layer still forms K and V for every position, but runs attention only for the

@@ -34,6 +34,7 @@ EXPORTS = [
     "po_last_device_error", "po_op_rmsnorm", "po_op_linear", "po_op_gate_up_silu",
     "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head", "po_op_rope_table",
     "po_op_pack_qkv", "po_op_qkv_rope", "po_max_input_len", "po_profile", "po_set_lazy_last_layer",
+    "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix",
 ]
 
 
@@ -85,6 +86,9 @@ def lib() -> C.CDLL:
     L.po_prefill_batch.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
     L.po_set_phase_timing.argtypes = [vp, i32]
     L.po_set_lazy_last_layer.argtypes = [vp, i32]
+    L.po_kv_cache_bytes.argtypes = [C.POINTER(ModelConfigC), i64, C.POINTER(sz)]
+    L.po_attach_kv_cache.argtypes = [vp, vp, sz, i64]
+    L.po_prefill_prefix.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, C.POINTER(i64)]
     L.po_get_stats.argtypes = [vp, C.POINTER(StatsC)]
     L.po_destroy.argtypes = [vp]
     L.po_destroy.restype = None
@@ -205,6 +209,28 @@ class Context:
         ms, touched = C.c_double(0), C.c_size_t(0)
         check(lib().po_profile(self._h, length, C.byref(ms), C.byref(touched)))
         return ms.value, touched.value
+
+    def po_attach_kv_cache(self, prefix_capacity: int) -> int:
+        """Allocates (torch) and attaches a prefix K/V cache; returns its size in bytes."""
+        n = C.c_size_t(0)
+        cc = config_c(self.cfg)
+        check(lib().po_kv_cache_bytes(C.byref(cc), prefix_capacity, C.byref(n)))
+        self._kvc = self._torch.empty(n.value, dtype=self._torch.uint8, device=self.device)
+        check(lib().po_attach_kv_cache(self._h, self._kvc.data_ptr(), n.value, prefix_capacity))
+        return n.value
+
+    def po_prefill_prefix(self, tokens: np.ndarray, keep_prefix: int, cand: Optional[Sequence[int]] = None,
+                          want_logits: bool = True):
+        """-> (logits or None, candidate log-probs or None, reused prefix length)"""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        n_cand = 0 if cand is None else len(cand)
+        cand_a = None if cand is None else np.ascontiguousarray(cand, dtype=np.int32)
+        logits = np.empty(self.cfg.vocab_size, dtype=np.float32) if want_logits else None
+        lp = np.empty(n_cand, dtype=np.float32) if n_cand else None
+        reused = C.c_int64(0)
+        check(lib().po_prefill_prefix(self._h, _host_ptr(tok), tok.shape[0], keep_prefix, _host_ptr(cand_a), n_cand,
+                                      _host_ptr(logits), _host_ptr(lp), C.byref(reused)))
+        return logits, lp, reused.value
 
     def po_set_lazy_last_layer(self, on: bool) -> None:
         check(lib().po_set_lazy_last_layer(self._h, 1 if on else 0))

@@ -8,6 +8,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -126,6 +127,15 @@ po_status make_layout(const po_model_config* c, int64_t max_len, int32_t mlp_chu
     return PO_OK;
 }
 
+void kv_cache_geometry(const po_model_config* c, int64_t cap, int64_t* ldvc, size_t* v_off, size_t* layer_bytes) {
+    const size_t esz = c->dtype == PO_F32 ? 4 : 2;
+    const size_t kvd = (size_t)c->n_kv_heads * c->head_dim;
+    *ldvc = round_up64(cap, 64);
+    *v_off = align_up((size_t)cap * kvd * esz);
+    const size_t v_bytes = c->dtype == PO_BF16 ? kvd * (size_t)*ldvc * esz : (size_t)cap * kvd * esz;
+    *layer_bytes = *v_off + align_up(v_bytes);
+}
+
 }  // namespace
 
 struct po_ctx {
@@ -140,6 +150,12 @@ struct po_ctx {
     hipEvent_t ev_start, ev_stop;
     bool phase_timing;
     bool lazy_last_layer;             // last layer: queries, attention rows and MLP only where the last token needs them
+    // prefix K/V cache (caller-provided device memory): per layer K [cap, kvd], then V^T [kvd, ldvc]
+    // (bf16) or V [cap, kvd] (fp32); kv_tokens are the token ids whose K/V it currently holds
+    unsigned char* kvc;
+    int64_t kv_cap, kv_ldv;
+    size_t kv_layer_bytes, kv_v_off;
+    std::vector<int32_t> kv_tokens;
     std::vector<hipEvent_t> ev_pool;  // pairs
     std::vector<int> ev_kind;         // per pair: po_kernel_class
     size_t ev_used;
@@ -181,8 +197,11 @@ struct PhaseTimer {
 };
 
 // one request on the device; tokens already validated
+// p_reuse: positions [0, p_reuse) are not computed; their K/V of every layer come from the prefix cache
+// (0 = compute everything).  p_store: afterwards the cache holds the K/V of positions [0, p_store)
+// (positions [p_reuse, p_store) are copied out of this run; 0 = the cache is left alone).
 po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32_t* cand, int32_t n_cand,
-                      float* out_logits, float* out_lp) {
+                      float* out_logits, float* out_lp, int64_t p_reuse = 0, int64_t p_store = 0) {
     const po_model_config& m = c->cfg;
     const Layout& L = c->lay;
     const int dt = m.dtype;
@@ -207,7 +226,7 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
     PO_HIP(hipMemcpyAsync(d_tok, tokens, (size_t)len * 4, hipMemcpyHostToDevice, s));
     if (n_cand > 0) PO_HIP(hipMemcpyAsync(ws + L.cand, cand, (size_t)n_cand * 4, hipMemcpyHostToDevice, s));
     PO_HIP(hipEventRecord(c->ev_start, s));
-    launch_embed(dt, d_tok, c->w + L.embed, X, len, d, s);
+    launch_embed(dt, d_tok + p_reuse, c->w + L.embed, X + (size_t)p_reuse * d * esz, len - p_reuse, d, s);
     // the last key tile of the attention reads V^T up to the next multiple of 64 positions
     if (dt == PO_BF16) launch_vt_pad_zero((bf16_t*)(ws + L.Vt), kvd, L.ldv, len, s);
 
@@ -221,7 +240,17 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
         // tiles that fills whole rounds of the 256 CUs (e.g. 32 x 24 tiles = 3 rounds).
         const int64_t Cq = ((int64_t)C * F >= 2 * (int64_t)C * d) ? 2 * (int64_t)C : C;
         unsigned char* Xq = (Cq > C) ? H : Xn;
-        for (int64_t c0 = 0; c0 < len; c0 += Cq) {
+        unsigned char* kc_l = c->kvc ? c->kvc + (size_t)l * c->kv_layer_bytes : nullptr;
+        if (p_reuse > 0) {
+            // cached prefix of this layer -> rows [0, p_reuse) of the one-layer K / V buffers
+            PO_HIP(hipMemcpyAsync(K, kc_l, (size_t)p_reuse * kvd * esz, hipMemcpyDeviceToDevice, s));
+            if (dt == PO_BF16)
+                PO_HIP(hipMemcpy2DAsync(ws + L.Vt, (size_t)L.ldv * esz, kc_l + c->kv_v_off, (size_t)c->kv_ldv * esz,
+                                        (size_t)p_reuse * esz, kvd, hipMemcpyDeviceToDevice, s));
+            else
+                PO_HIP(hipMemcpyAsync(V, kc_l + c->kv_v_off, (size_t)p_reuse * kvd * esz, hipMemcpyDeviceToDevice, s));
+        }
+        for (int64_t c0 = p_reuse; c0 < len; c0 += Cq) {
             const int64_t rows = (len - c0 < Cq) ? len - c0 : Cq;
             unsigned char* Xn = Xq;     // (shadows the MLP-phase buffer inside this loop)
             launch_rmsnorm(dt, X + (size_t)c0 * d * esz, c->w + o.attn_norm, Xn, rows, d, m.rms_eps, s);
@@ -240,8 +269,21 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
             }
         }
         if (dt == PO_F32) {
-            launch_rope(dt, Q, qd, rc, rs, len, m.n_q_heads, hd, s);
-            launch_rope(dt, K, kvd, rc, rs, len, m.n_kv_heads, hd, s);
+            // (rows below p_reuse came rotated out of the prefix cache)
+            const size_t t0 = (size_t)p_reuse * (hd / 2);
+            launch_rope(dt, Q + (size_t)p_reuse * qd * esz, qd, rc + t0, rs + t0, len - p_reuse, m.n_q_heads, hd, s);
+            launch_rope(dt, K + (size_t)p_reuse * kvd * esz, kvd, rc + t0, rs + t0, len - p_reuse, m.n_kv_heads, hd, s);
+        }
+        if (p_store > p_reuse) {
+            // Section 5.1: keep the K/V of the prefix, discard the suffix's with the layer
+            const size_t r0 = (size_t)p_reuse, nr = (size_t)(p_store - p_reuse);
+            PO_HIP(hipMemcpyAsync(kc_l + r0 * kvd * esz, K + r0 * kvd * esz, nr * kvd * esz, hipMemcpyDeviceToDevice, s));
+            if (dt == PO_BF16)
+                PO_HIP(hipMemcpy2DAsync(kc_l + c->kv_v_off + r0 * esz, (size_t)c->kv_ldv * esz, ws + L.Vt + r0 * esz,
+                                        (size_t)L.ldv * esz, nr * esz, kvd, hipMemcpyDeviceToDevice, s));
+            else
+                PO_HIP(hipMemcpyAsync(kc_l + c->kv_v_off + r0 * kvd * esz, V + r0 * kvd * esz, nr * kvd * esz,
+                                      hipMemcpyDeviceToDevice, s));
         }
         // Nothing reads the last layer's output except the last position (one output token, Section 1):
         // there the keys and values of every position are still needed, but attention, O-projection and
@@ -251,7 +293,7 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
         // ---- attention over the whole sequence in one call; O overwrites Q
         {
             PhaseTimer pt(c, PO_K_ATTENTION);
-            const int64_t q_row0 = last_only ? len - 1 : 0;
+            const int64_t q_row0 = last_only ? len - 1 : p_reuse;
             if (dt == PO_BF16) {
                 launch_attention_mfma((const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)(ws + L.Vt), L.ldv,
                                       (bf16_t*)Q, len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
@@ -260,7 +302,7 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
             }
         }
         // ---- position-wise part after attention, chunk by chunk, residual stream in place
-        for (int64_t c0 = last_only ? len - 1 : 0; c0 < len; c0 += C) {
+        for (int64_t c0 = last_only ? len - 1 : p_reuse; c0 < len; c0 += C) {
             const int64_t rows = (len - c0 < C) ? len - c0 : C;
             unsigned char* Xc = X + (size_t)c0 * d * esz;
             const unsigned char* Oc = Q + (size_t)c0 * qd * esz;
@@ -398,6 +440,9 @@ po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t m
     c->loaded.assign(cfg->n_layers + 1, 0u);
     c->phase_timing = false;
     c->lazy_last_layer = true;
+    c->kvc = nullptr;
+    c->kv_cap = c->kv_ldv = 0;
+    c->kv_layer_bytes = c->kv_v_off = 0;
     c->ev_used = 0;
     memset(&c->stats, 0, sizeof(c->stats));
     c->stats.weights_bytes = c->lay.weights_bytes;
@@ -557,6 +602,62 @@ po_status po_profile(po_ctx* c, int64_t len, double* elapsed_ms, size_t* touched
     }
     (void)hipFree(d_mark);
     return st;
+}
+
+po_status po_kv_cache_bytes(const po_model_config* cfg, int64_t prefix_capacity, size_t* bytes) {
+    if (!cfg || !bytes) return PO_ERR_INVALID_ARG;
+    po_status st = validate_config(cfg);
+    if (st != PO_OK) return st;
+    if (prefix_capacity <= 0) return PO_ERR_INVALID_ARG;
+    int64_t ldvc;
+    size_t v_off, layer_bytes;
+    kv_cache_geometry(cfg, prefix_capacity, &ldvc, &v_off, &layer_bytes);
+    *bytes = layer_bytes * (size_t)cfg->n_layers;
+    return PO_OK;
+}
+
+po_status po_attach_kv_cache(po_ctx* c, void* dev_cache, size_t bytes, int64_t prefix_capacity) {
+    if (!c) return PO_ERR_INVALID_ARG;
+    if (!dev_cache) {               // detach
+        c->kvc = nullptr;
+        c->kv_cap = 0;
+        c->kv_tokens.clear();
+        return PO_OK;
+    }
+    if (prefix_capacity <= 0 || ((uintptr_t)dev_cache % ALIGN)) return PO_ERR_INVALID_ARG;
+    if (prefix_capacity > c->max_len) return PO_ERR_TOO_LONG;
+    size_t need = 0;
+    po_status st = po_kv_cache_bytes(&c->cfg, prefix_capacity, &need);
+    if (st != PO_OK) return st;
+    if (bytes < need) return PO_ERR_WORKSPACE_TOO_SMALL;
+    c->kvc = (unsigned char*)dev_cache;
+    c->kv_cap = prefix_capacity;
+    kv_cache_geometry(&c->cfg, prefix_capacity, &c->kv_ldv, &c->kv_v_off, &c->kv_layer_bytes);
+    c->kv_tokens.clear();
+    return PO_OK;
+}
+
+po_status po_prefill_prefix(po_ctx* c, const int32_t* tokens, int64_t len, int64_t keep_prefix,
+                            const int32_t* cand_ids, int32_t n_cand, float* out_logits, float* out_cand_logprobs,
+                            int64_t* reused_prefix_len) {
+    if (!c || keep_prefix < 0) return PO_ERR_INVALID_ARG;
+    po_status st = validate_request(c, tokens, len, cand_ids, n_cand);
+    if (st != PO_OK) return st;
+    if (!c->kvc) return PO_ERR_INVALID_ARG;
+    if (keep_prefix > len || keep_prefix > c->kv_cap) return PO_ERR_TOO_LONG;
+    if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
+    // longest common prefix with what the cache holds; at least one position is always computed
+    int64_t m = 0;
+    const int64_t lim = std::min<int64_t>((int64_t)c->kv_tokens.size(), len - 1);
+    while (m < lim && c->kv_tokens[(size_t)m] == tokens[m]) ++m;
+    st = run_prefill(c, tokens, len, cand_ids, n_cand, out_logits, out_cand_logprobs, m, keep_prefix);
+    if (st != PO_OK) {              // the cache may be half written: forget it
+        c->kv_tokens.clear();
+        return st;
+    }
+    if (keep_prefix > 0) c->kv_tokens.assign(tokens, tokens + keep_prefix);
+    if (reused_prefix_len) *reused_prefix_len = m;
+    return PO_OK;
 }
 
 po_status po_set_lazy_last_layer(po_ctx* c, int32_t on) {

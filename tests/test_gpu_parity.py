@@ -337,3 +337,37 @@ def test_last_layer_shortcut_is_bitwise(cfg, n):
         assert np.array_equal(z_1, z_1off)
     finally:
         ctx.po_destroy()
+
+
+@pytest.mark.parametrize("cfg,n,keep", [(I.TINY, 700, 300), (I.TINY.replace(dtype=I.BF16, ffn_dim=704), 900, 512),
+                                        (I.LLAMA8B.replace(n_layers=2, vocab_size=4096), 1500, 1000)])
+def test_prefix_cache_reuse_is_bitwise(cfg, n, keep):
+    """Section 5.1: a request that shares a cached prefix computes only its suffix, and gets the same bits."""
+    ctx = make_ctx(cfg, 19, n, 256)
+    try:
+        cand = I.label_ids(cfg)
+        a = I.make_tokens(cfg, 41, n)
+        b = a.copy()
+        b[keep + 7:] = I.make_tokens(cfg, 42, n)[keep + 7:]        # shares keep + 7 tokens with a
+        c = a.copy()
+        c[keep // 2] = (c[keep // 2] + 1) % cfg.vocab_size         # diverges in the middle of the prefix
+        ref = {k: ctx.po_prefill(t, cand) for k, t in (("a", a), ("b", b), ("c", c), ("short", a[:keep // 3]))}
+        with pytest.raises(B.PoError):
+            ctx.po_prefill_prefix(a, keep, cand)                   # no cache attached
+        ctx.po_attach_kv_cache(keep)
+        z, lp, r = ctx.po_prefill_prefix(a, keep, cand)            # cold: nothing to reuse, stores the prefix
+        assert r == 0 and np.array_equal(z, ref["a"][0]) and np.array_equal(lp, ref["a"][1])
+        z, lp, r = ctx.po_prefill_prefix(b, 0, cand)               # reuses the stored prefix, keeps the cache
+        assert r == keep and np.array_equal(z, ref["b"][0]) and np.array_equal(lp, ref["b"][1])
+        z, lp, r = ctx.po_prefill_prefix(a, 0, cand)               # whole stored prefix again
+        assert r == keep and np.array_equal(z, ref["a"][0])
+        z, lp, r = ctx.po_prefill_prefix(c, keep, cand)            # partial hit, then replaces the prefix
+        assert r == keep // 2 and np.array_equal(z, ref["c"][0])
+        z, lp, r = ctx.po_prefill_prefix(c, 0, cand)
+        assert r == keep and np.array_equal(z, ref["c"][0])
+        z, lp, r = ctx.po_prefill_prefix(a[:keep // 3], 0, cand)   # request shorter than the prefix: one row is computed
+        assert r == min(keep // 2, keep // 3 - 1) and np.array_equal(z, ref["short"][0])
+        with pytest.raises(B.PoError):
+            ctx.po_prefill_prefix(a, keep + 1, cand)               # beyond the capacity
+    finally:
+        ctx.po_destroy()
