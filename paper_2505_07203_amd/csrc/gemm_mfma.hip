@@ -201,18 +201,22 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
 
     // ---- global -> LDS map.  Load instruction i (0..3) of wavefront w fills rows
     // (w*4 + i)*16 .. +15 of an operand slice: lane l -> row + l/4, physical segment l & 3,
-    // which holds logical segment (l & 3) ^ ((row >> 2) & 3).  Addresses are a wavefront-uniform
-    // 64-bit base (tile origin + slice) plus a 32-bit per-lane byte offset that never changes,
-    // so issuing a load costs no vector arithmetic.
-    const unsigned char* sA = (const unsigned char*)(p.A + (int64_t)m0 * p.lda);
-    const unsigned char* sW = (const unsigned char*)(p.W + (int64_t)n0 * p.ldw);
+    // which holds logical segment (l & 3) ^ ((row >> 2) & 3).  Each operand is addressed through a
+    // buffer resource that starts at the tile's first row and ends with the matrix: the per-lane
+    // byte offset never changes, the slice offset is one scalar, and rows of a ragged last tile
+    // beyond the matrix read as zero instead of needing a clamp (they are never stored).
+    const uint64_t a_bytes = (uint64_t)(p.M - m0) * (uint64_t)p.lda * 2, w_bytes = (uint64_t)(p.N - n0) * (uint64_t)p.ldw * 2;
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.A + (int64_t)m0 * p.lda), 0, (int)(uint32_t)(a_bytes > 0xffffffffull ? 0xffffffffull : a_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.W + (int64_t)n0 * p.ldw), 0, (int)(uint32_t)(w_bytes > 0xffffffffull ? 0xffffffffull : w_bytes), 0x00020000);
     uint32_t voa[4], vow[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = (wave * 4 + i) * 16 + (lane >> 2);
         const int lseg = (lane & 3) ^ ((row >> 2) & 3);
-        voa[i] = (uint32_t)min(row, p.M - 1 - m0) * (uint32_t)(p.lda * 2) + lseg * 16;
-        vow[i] = (uint32_t)min(row, p.N - 1 - n0) * (uint32_t)(p.ldw * 2) + lseg * 16;
+        voa[i] = (uint32_t)row * (uint32_t)(p.lda * 2) + lseg * 16;
+        vow[i] = (uint32_t)row * (uint32_t)(p.ldw * 2) + lseg * 16;
     }
     const int KT = p.K / BK;
     // one 16-byte-per-lane load of operand slice kt_: j_ = 0..3 activations, 4..7 weights
@@ -221,11 +225,8 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
         const int t_ = min((kt_), KT - 1);                                                                    \
         unsigned char* sa_ = smem + ((kt_) & (NSTAGE - 1)) * STAGE_BYTES + wave * 4096 + ((j_) & 3) * 1024 +  \
                              ((j_) >> 2) * OPER_BYTES;                                                        \
-        const unsigned char* b_ = ((j_) >> 2 ? sW : sA) + t_ * (BK * 2);                                      \
-        asm volatile("" : "+s"(b_));  /* slice base stays scalar: address = SGPR pair + 32-bit lane offset */ \
-        const unsigned char* g_ = b_ + ((j_) >> 2 ? vow[(j_) & 3] : voa[(j_) & 3]);                           \
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g_,                  \
-                                         (__attribute__((address_space(3))) void*)sa_, 16, 0, 0);             \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds((j_) >> 2 ? rw : ra, (__attribute__((address_space(3))) void*)sa_, 16, \
+                                                 (j_) >> 2 ? vow[(j_) & 3] : voa[(j_) & 3], t_ * (BK * 2), 0, 0); \
     }
 #define PO_ISSUE(kt_)                                                                                         \
     { _Pragma("unroll") for (int j = 0; j < 8; ++j) PO_DMA(kt_, j) }
