@@ -183,6 +183,29 @@ po_status po_prefill_prefix(po_ctx* ctx, const int32_t* tokens, int64_t len, int
                             const int32_t* cand_ids, int32_t n_cand,
                             float* out_logits, float* out_cand_logprobs, int64_t* reused_prefix_len);
 
+/* Request scheduling on the host (Section 6.3, Algorithm 1: shortest-remaining-job-first with
+ * continuous JCT calibration).  The scheduler keeps the waiting requests (copies of their
+ * tokens); every pick recomputes, for each of them, n_cached = the length of its common
+ * prefix with the tokens the prefix cache holds at that moment (at most len - 1) and
+ * score = jct(n_input, n_cached) - lambda * (now - arrival_time), and returns the request
+ * with the lowest score (the earliest pushed on ties), removing it from the queue.
+ * jct is the paper's default proxy n_input - n_cached, or, once set or fitted, the linear
+ * model c0 + c_input * n_input + c_cached * n_cached (the paper fits it by linear regression
+ * on profiled (n_input, n_cached) pairs; coef[3] receives c0, c_input, c_cached, may be NULL;
+ * at least 3 non-collinear samples).  lambda (>= 0; the paper uses 500 with JCT in tokens
+ * and time in seconds) trades average for worst-case latency.  po_sched_pick on an empty
+ * queue returns PO_OK with *id = -1.  No GPU is involved. */
+typedef struct po_sched po_sched;
+po_status po_sched_create(double lambda, po_sched** out);
+void po_sched_destroy(po_sched* s);
+po_status po_sched_set_jct_model(po_sched* s, double c0, double c_input, double c_cached);
+po_status po_sched_fit_jct_model(po_sched* s, const int64_t* n_input, const int64_t* n_cached,
+                                 const double* jct, int32_t n, double coef[3]);
+po_status po_sched_push(po_sched* s, int64_t id, const int32_t* tokens, int64_t len, double arrival_time);
+int64_t po_sched_size(const po_sched* s);
+po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cached_tokens, double now,
+                        int64_t* id, int64_t* n_cached_hit);
+
 /* Last-layer shortcut, on by default.  A prefill-only request produces one token (Section 1),
  * so nothing reads the last layer's output except at the last position: with the shortcut
  * the last layer still forms K and V for every position, but runs attention only for the

@@ -35,6 +35,8 @@ EXPORTS = [
     "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head", "po_op_rope_table",
     "po_op_pack_qkv", "po_op_qkv_rope", "po_max_input_len", "po_profile", "po_set_lazy_last_layer",
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix",
+    "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
+    "po_sched_size", "po_sched_pick",
 ]
 
 
@@ -106,8 +108,18 @@ def lib() -> C.CDLL:
     L.po_op_rope_table.argtypes = [vp, vp, i64, i32, f32, vp]
     L.po_op_pack_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
     L.po_op_qkv_rope.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i32, i32, i32, i32, vp]
+    f64 = C.c_double
+    L.po_sched_create.argtypes = [f64, C.POINTER(vp)]
+    L.po_sched_destroy.argtypes = [vp]
+    L.po_sched_destroy.restype = None
+    L.po_sched_set_jct_model.argtypes = [vp, f64, f64, f64]
+    L.po_sched_fit_jct_model.argtypes = [vp, vp, vp, vp, i32, C.POINTER(f64 * 3)]
+    L.po_sched_push.argtypes = [vp, i64, vp, i64, f64]
+    L.po_sched_size.argtypes = [vp]
+    L.po_sched_size.restype = i64
+    L.po_sched_pick.argtypes = [vp, vp, i64, f64, C.POINTER(i64), C.POINTER(i64)]
     for name in EXPORTS:
-        if name not in ("po_destroy", "po_strerror", "po_last_device_error"):
+        if name not in ("po_destroy", "po_strerror", "po_last_device_error", "po_sched_destroy", "po_sched_size"):
             getattr(L, name).restype = i32
     _lib = L
     return L
@@ -380,3 +392,50 @@ def po_op_qkv_rope(a, wqkv, bqkv, cos, sin, n_q_heads: int, n_kv_heads: int, hea
                                q.data_ptr(), k.data_ptr(), vt.data_ptr(), vt.shape[1], cos.data_ptr(),
                                sin.data_ptr(), pos0, M, n_q_heads, n_kv_heads, head_dim, K, _stream()))
     return q, k, vt
+
+
+# ---- host-side scheduler ------------------------------------------------------------------------
+
+class Scheduler:
+    """A po_sched: SRJF with continuous JCT calibration (same names as the C ABI)."""
+
+    def __init__(self, lam: float):
+        h = C.c_void_p()
+        check(lib().po_sched_create(lam, C.byref(h)))
+        self._h = h
+
+    def po_sched_set_jct_model(self, c0: float, c_input: float, c_cached: float) -> None:
+        check(lib().po_sched_set_jct_model(self._h, c0, c_input, c_cached))
+
+    def po_sched_fit_jct_model(self, n_input, n_cached, jct):
+        a = np.ascontiguousarray(n_input, dtype=np.int64)
+        b = np.ascontiguousarray(n_cached, dtype=np.int64)
+        z = np.ascontiguousarray(jct, dtype=np.float64)
+        coef = (C.c_double * 3)()
+        check(lib().po_sched_fit_jct_model(self._h, _host_ptr(a), _host_ptr(b), _host_ptr(z), len(a), C.byref(coef)))
+        return tuple(coef)
+
+    def po_sched_push(self, rid: int, tokens, arrival_time: float) -> None:
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        check(lib().po_sched_push(self._h, rid, _host_ptr(t), t.shape[0], arrival_time))
+
+    def po_sched_size(self) -> int:
+        return int(lib().po_sched_size(self._h))
+
+    def po_sched_pick(self, cached_tokens, now: float):
+        """-> (id or -1, tokens of that request that hit the prefix cache)"""
+        c = np.ascontiguousarray(cached_tokens, dtype=np.int32)
+        rid, hit = C.c_int64(-1), C.c_int64(0)
+        check(lib().po_sched_pick(self._h, _host_ptr(c) if c.size else None, c.shape[0], now, C.byref(rid), C.byref(hit)))
+        return rid.value, hit.value
+
+    def po_sched_destroy(self) -> None:
+        if getattr(self, "_h", None):
+            lib().po_sched_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.po_sched_destroy()
+        except Exception:
+            pass

@@ -1,0 +1,124 @@
+// Host-side request scheduler: shortest-remaining-job-first with continuous JCT calibration
+// (Section 6.3, Algorithm 1).  Every pick re-evaluates the job completion time of every waiting
+// request against what the prefix cache holds NOW, so that requests that can hit the prefix a
+// just-finished request left behind are taken before the cache moves on; the queuing time, scaled
+// by lambda, is subtracted against starvation.  No device code: plain C++ behind the C ABI.
+#include "../../include/po.h"
+
+#include <stdint.h>
+
+#include <cmath>
+#include <limits>
+#include <new>
+#include <vector>
+
+struct po_sched {
+    double lambda;
+    bool linear;              // false: the paper's default proxy n_input - n_cached
+    double c0, c_input, c_cached;
+    struct Req {
+        int64_t id;
+        double arrival;
+        std::vector<int32_t> tokens;
+    };
+    std::vector<Req> queue;   // push order
+};
+
+namespace {
+
+int64_t hit_len(const std::vector<int32_t>& t, const int32_t* cached, int64_t n_cached_tokens) {
+    // common prefix with the cache; one position of a request is always computed
+    const int64_t lim = std::min<int64_t>((int64_t)t.size() - 1, n_cached_tokens);
+    int64_t m = 0;
+    while (m < lim && t[(size_t)m] == cached[m]) ++m;
+    return m;
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+po_status po_sched_create(double lambda, po_sched** out) {
+    if (!out || !(lambda >= 0.0)) return PO_ERR_INVALID_ARG;
+    po_sched* s = new (std::nothrow) po_sched();
+    if (!s) return PO_ERR_OOM;
+    s->lambda = lambda;
+    s->linear = false;
+    s->c0 = s->c_input = s->c_cached = 0.0;
+    *out = s;
+    return PO_OK;
+}
+
+void po_sched_destroy(po_sched* s) { delete s; }
+
+po_status po_sched_set_jct_model(po_sched* s, double c0, double c_input, double c_cached) {
+    if (!s || !std::isfinite(c0) || !std::isfinite(c_input) || !std::isfinite(c_cached)) return PO_ERR_INVALID_ARG;
+    s->linear = true;
+    s->c0 = c0;
+    s->c_input = c_input;
+    s->c_cached = c_cached;
+    return PO_OK;
+}
+
+po_status po_sched_fit_jct_model(po_sched* s, const int64_t* n_input, const int64_t* n_cached, const double* jct,
+                                 int32_t n, double coef[3]) {
+    if (!s || !n_input || !n_cached || !jct || n < 3) return PO_ERR_INVALID_ARG;
+    // normal equations of jct ~ c0 + c_input * n_input + c_cached * n_cached, centred for conditioning
+    double mx = 0, my = 0, mz = 0;
+    for (int32_t i = 0; i < n; ++i) { mx += (double)n_input[i]; my += (double)n_cached[i]; mz += jct[i]; }
+    mx /= n; my /= n; mz /= n;
+    double sxx = 0, sxy = 0, syy = 0, sxz = 0, syz = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        const double x = (double)n_input[i] - mx, y = (double)n_cached[i] - my, z = jct[i] - mz;
+        sxx += x * x; sxy += x * y; syy += y * y; sxz += x * z; syz += y * z;
+    }
+    const double det = sxx * syy - sxy * sxy;
+    if (!(std::fabs(det) > 1e-12 * (sxx * syy + 1e-300))) return PO_ERR_INVALID_ARG;    // collinear samples
+    const double a = (sxz * syy - syz * sxy) / det, b = (syz * sxx - sxz * sxy) / det;
+    s->linear = true;
+    s->c_input = a;
+    s->c_cached = b;
+    s->c0 = mz - a * mx - b * my;
+    if (coef) { coef[0] = s->c0; coef[1] = a; coef[2] = b; }
+    return PO_OK;
+}
+
+po_status po_sched_push(po_sched* s, int64_t id, const int32_t* tokens, int64_t len, double arrival_time) {
+    if (!s || !tokens || len <= 0 || !std::isfinite(arrival_time)) return PO_ERR_INVALID_ARG;
+    po_sched::Req r;
+    r.id = id;
+    r.arrival = arrival_time;
+    r.tokens.assign(tokens, tokens + len);
+    s->queue.push_back(std::move(r));
+    return PO_OK;
+}
+
+int64_t po_sched_size(const po_sched* s) { return s ? (int64_t)s->queue.size() : 0; }
+
+po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cached_tokens, double now, int64_t* id,
+                        int64_t* n_cached_hit) {
+    if (!s || !id || n_cached_tokens < 0 || (n_cached_tokens > 0 && !cached_tokens)) return PO_ERR_INVALID_ARG;
+    *id = -1;
+    if (n_cached_hit) *n_cached_hit = 0;
+    size_t best = 0;
+    int64_t best_hit = 0;
+    double best_score = std::numeric_limits<double>::infinity();
+    bool found = false;
+    for (size_t i = 0; i < s->queue.size(); ++i) {
+        const po_sched::Req& r = s->queue[i];
+        const int64_t hit = hit_len(r.tokens, cached_tokens, n_cached_tokens);
+        const double n_in = (double)r.tokens.size();
+        const double jct = s->linear ? s->c0 + s->c_input * n_in + s->c_cached * (double)hit : n_in - (double)hit;
+        const double score = jct - s->lambda * (now - r.arrival);
+        if (!found || score < best_score) { best = i; best_score = score; best_hit = hit; found = true; }
+    }
+    if (!found) return PO_OK;
+    *id = s->queue[best].id;
+    if (n_cached_hit) *n_cached_hit = best_hit;
+    s->queue.erase(s->queue.begin() + (std::ptrdiff_t)best);
+    return PO_OK;
+}
+
+#pragma GCC visibility pop
+}

@@ -371,3 +371,43 @@ def test_prefix_cache_reuse_is_bitwise(cfg, n, keep):
             ctx.po_prefill_prefix(a, keep + 1, cand)               # beyond the capacity
     finally:
         ctx.po_destroy()
+
+
+def test_scheduler_with_prefix_cache_end_to_end():
+    """Sections 5.1 + 6.3 together on the paper's example shape: four requests, two shared prefixes, a
+    cache that holds the last request; the calibrated order reuses twice, arrival order once."""
+    cfg = I.TINY
+    rng = np.random.default_rng(3)
+    p1, p2 = rng.integers(0, cfg.vocab_size, 300), rng.integers(0, cfg.vocab_size, 300)
+    tail = lambda n: rng.integers(0, cfg.vocab_size, n)
+    reqs = [np.concatenate([p1, tail(40)]), np.concatenate([p2, tail(350)]),
+            np.concatenate([p2, tail(200)]), np.concatenate([p1, tail(450)])]     # A, B, C, D: A < C < B < D
+    cand = I.label_ids(cfg)
+    ctx = make_ctx(cfg, 29, 800, 256)
+    try:
+        ref = [ctx.po_prefill(t, cand)[0] for t in reqs]
+        ctx.po_attach_kv_cache(800)
+
+        def run(order_fn):
+            ctx.po_attach_kv_cache(800)              # fresh, empty cache
+            cached, hits, order = np.zeros(0, np.int32), 0, []
+            sch = B.Scheduler(0.0)
+            for rid, t in enumerate(reqs):
+                sch.po_sched_push(rid, t, 0.0)
+            left = list(range(len(reqs)))
+            while left:
+                rid = order_fn(sch, cached, left)
+                left.remove(rid)
+                z, _, reused = ctx.po_prefill_prefix(reqs[rid], len(reqs[rid]), cand)
+                assert np.array_equal(z, ref[rid])
+                hits += reused > 0
+                cached = reqs[rid]
+                order.append(rid)
+            return order, hits
+
+        order, hits = run(lambda sch, cached, left: sch.po_sched_pick(cached, 0.0)[0])
+        assert (order, hits) == ([0, 3, 2, 1], 2)
+        order, hits = run(lambda sch, cached, left: left[0])
+        assert (order, hits) == ([0, 1, 2, 3], 1)
+    finally:
+        ctx.po_destroy()
