@@ -45,6 +45,7 @@ constexpr int NSTAGE = 4;
 constexpr int OPER_BYTES = BM * BK * 2;            // 16 KiB per operand per stage
 constexpr int STAGE_BYTES = 2 * OPER_BYTES;        // A + W
 constexpr int SMEM_BYTES = NSTAGE * STAGE_BYTES;   // 128 KiB
+constexpr int W_REGION = NSTAGE * OPER_BYTES;      // LDS offset of the weight slices
 constexpr int GROUP_M = 4;
 
 struct GemmParams {
@@ -220,16 +221,15 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     }
     const int KT = p.K / BK;
     // one 16-byte-per-lane load of operand slice kt_: j_ = 0..3 activations, 4..7 weights
-#define PO_DMA(kt_, j_)                                                                                       \
+#define PO_DMA(kt_, stg_, j_)                                                                                 \
     {                                                                                                         \
         const int t_ = min((kt_), KT - 1);                                                                    \
-        unsigned char* sa_ = smem + ((kt_) & (NSTAGE - 1)) * STAGE_BYTES + wave * 4096 + ((j_) & 3) * 1024 +  \
-                             ((j_) >> 2) * OPER_BYTES;                                                        \
+        unsigned char* sa_ = smem + ((j_) >> 2) * W_REGION + (stg_) * OPER_BYTES + wave * 4096 + ((j_) & 3) * 1024; \
         __builtin_amdgcn_raw_ptr_buffer_load_lds((j_) >> 2 ? rw : ra, (__attribute__((address_space(3))) void*)sa_, 16, \
                                                  (j_) >> 2 ? vow[(j_) & 3] : voa[(j_) & 3], t_ * (BK * 2), 0, 0); \
     }
 #define PO_ISSUE(kt_)                                                                                         \
-    { _Pragma("unroll") for (int j = 0; j < 8; ++j) PO_DMA(kt_, j) }
+    { _Pragma("unroll") for (int j = 0; j < 8; ++j) PO_DMA(kt_, (kt_) & (NSTAGE - 1), j) }
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -244,8 +244,15 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     int f_off[2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) f_off[kk] = l31 * 64 + (((kk * 2 + lhi) ^ fsw) << 4);
-    const int a_base = wm * 128 * 64;
-    const int w_base = OPER_BYTES + wn * 128 * 64;
+    // LDS: the activation slices of the four stages in the first 64 KiB, the weight slices in the second.
+    // With the stage number a literal (main loop unrolled over the four stages) a fragment address is one of
+    // these four lane registers plus an immediate below 64 KiB.
+    int a_addr[2], w_addr[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        a_addr[kk] = wm * 128 * 64 + f_off[kk];
+        w_addr[kk] = W_REGION + wn * 128 * 64 + f_off[kk];
+    }
 
     // Software pipeline inside the wavefront.  There is only one wavefront per SIMD, so every
     // cycle it spends issuing something other than an MFMA while the matrix pipe is empty is
@@ -263,8 +270,8 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     bf16x8 af0[4], wf0[4], af1[4], wf1[4];
 #define PO_FRAG1(AF, WF, st_, kk_, j_)                                                              \
     {                                                                                               \
-        if ((j_) < 4) AF[(j_) & 3] = *(const bf16x8*)((st_) + a_base + ((j_) & 3) * 2048 + f_off[kk_]); \
-        else          WF[(j_) & 3] = *(const bf16x8*)((st_) + w_base + ((j_) & 3) * 2048 + f_off[kk_]); \
+        if ((j_) < 4) AF[(j_) & 3] = *(const bf16x8*)(smem + a_addr[kk_] + (st_) * OPER_BYTES + ((j_) & 3) * 2048); \
+        else          WF[(j_) & 3] = *(const bf16x8*)(smem + w_addr[kk_] + (st_) * OPER_BYTES + ((j_) & 3) * 2048); \
     }
 #define PO_MFMA1(AF, WF, t_)                                                                        \
     acc[(t_) >> 2][(t_) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[(t_) & 3], AF[(t_) >> 2], acc[(t_) >> 2][(t_) & 3], 0, 0, 0);
@@ -276,39 +283,46 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     PO_ISSUE(1);
     PO_ISSUE(2);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) PO_DMA(3, j);
+    for (int j = 0; j < 4; ++j) PO_DMA(3, 3, j);
     asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");     // slice 0 has landed
 #pragma unroll
-    for (int j = 0; j < 8; ++j) PO_FRAG1(af0, wf0, smem, 0, j);
-    for (int kt = 0; kt < KT; ++kt) {
-        const unsigned char* st = smem + (kt & (NSTAGE - 1)) * STAGE_BYTES;
-        const unsigned char* stn = smem + ((kt + 1) & (NSTAGE - 1)) * STAGE_BYTES;
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            PO_MFMA1(af0, wf0, t);
-            __builtin_amdgcn_sched_barrier(0);
-            if (PO_READ_SLOT(t) >= 0) {
-                PO_FRAG1(af1, wf1, st, 1, PO_READ_SLOT(t));
-                __builtin_amdgcn_sched_barrier(0);
-            } else if ((t & 3) == 2) {
-                PO_DMA(kt + 3, 4 + (t >> 2));
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        PO_HANDOVER();
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            PO_MFMA1(af1, wf1, t);
-            __builtin_amdgcn_sched_barrier(0);
-            if (PO_READ_SLOT(t) >= 0) {
-                PO_FRAG1(af0, wf0, stn, 0, PO_READ_SLOT(t));
-                __builtin_amdgcn_sched_barrier(0);
-            } else if ((t & 3) == 2) {
-                PO_DMA(kt + 4, t >> 2);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
+    for (int j = 0; j < 8; ++j) PO_FRAG1(af0, wf0, 0, 0, j);
+    // one slice; s_ = kt & 3 is its stage
+#define PO_SLICE(kt_, s_)                                                                           \
+    {                                                                                               \
+        _Pragma("unroll") for (int t = 0; t < 16; ++t) {                                            \
+            PO_MFMA1(af0, wf0, t);                                                                  \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+            if (PO_READ_SLOT(t) >= 0) {                                                             \
+                PO_FRAG1(af1, wf1, (s_), 1, PO_READ_SLOT(t));                                       \
+                __builtin_amdgcn_sched_barrier(0);                                                  \
+            } else if ((t & 3) == 2) {                                                              \
+                PO_DMA((kt_) + 3, ((s_) + 3) & 3, 4 + (t >> 2));                                    \
+                __builtin_amdgcn_sched_barrier(0);                                                  \
+            }                                                                                       \
+        }                                                                                           \
+        PO_HANDOVER();                                                                              \
+        _Pragma("unroll") for (int t = 0; t < 16; ++t) {                                            \
+            PO_MFMA1(af1, wf1, t);                                                                  \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+            if (PO_READ_SLOT(t) >= 0) {                                                             \
+                PO_FRAG1(af0, wf0, ((s_) + 1) & 3, 0, PO_READ_SLOT(t));                             \
+                __builtin_amdgcn_sched_barrier(0);                                                  \
+            } else if ((t & 3) == 2) {                                                              \
+                PO_DMA((kt_) + 4, (s_), t >> 2);                                                    \
+                __builtin_amdgcn_sched_barrier(0);                                                  \
+            }                                                                                       \
+        }                                                                                           \
     }
+    int kt = 0;
+    for (; kt + 4 <= KT; kt += 4) {
+        PO_SLICE(kt, 0);
+        PO_SLICE(kt + 1, 1);
+        PO_SLICE(kt + 2, 2);
+        PO_SLICE(kt + 3, 3);
+    }
+    for (; kt < KT; ++kt) PO_SLICE(kt, kt & 3);
+#undef PO_SLICE
 #undef PO_READ_SLOT
 #undef PO_ISSUE
 #undef PO_DMA
