@@ -104,6 +104,9 @@ def main():
     ap.add_argument("--reuse-prefix", type=int, default=0,
                     help="also time the first request again with the K/V of its first P tokens in the prefix "
                          "cache (reported under prefix_reuse; not part of value)")
+    ap.add_argument("--packed", type=int, default=0,
+                    help="variant: run the workload's requests through po_prefill_packed with buffers of this many "
+                         "rows (consecutive short requests share the launches of the position-wise layers)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (requests are independent; more GPUs run more "
@@ -126,7 +129,7 @@ def main():
     reqs = [I.make_tokens(cfg, w["tseed"], n, request=i) for i, n in enumerate(lens)]
 
     t0 = time.perf_counter()
-    ctx = B.Context(cfg, max(lens), w["chunk"])
+    ctx = B.Context(cfg, max(max(lens), args.packed), w["chunk"])
     ctx.load_synthetic(w["wseed"], threads=16)
     load_s = time.perf_counter() - t0
     ctx.po_set_phase_timing(not args.no_phase_timing)
@@ -136,8 +139,11 @@ def main():
     def step():
         ms = dict.fromkeys(classes, 0.0)
         n = dict.fromkeys(classes, 0)
-        for t in reqs:
-            ctx.po_prefill(t, cand, want_logits=len(reqs) == 1)
+        for t in ([None] if args.packed else reqs):
+            if args.packed:
+                ctx.po_prefill_packed(reqs, cand)
+            else:
+                ctx.po_prefill(t, cand, want_logits=len(reqs) == 1)
             st = ctx.po_get_stats()
             for k in classes:
                 ms[k] += st["kernel_ms"][k]
@@ -195,7 +201,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == I.BF16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": cfg.n_layers, "d_model": cfg.d_model,
-                   "requests": len(lens), "tokens": tokens, "mlp_chunk": chunk,
+                   "requests": len(lens), "tokens": tokens, "mlp_chunk": chunk, "packed_rows": args.packed,
                    "weights": "random-init N(0,0.02), seeded"},
         "end_to_end": {"algorithmic_tflop": (lin_f + att_f) / 1e12,
                        "achieved_tflops": (lin_f + att_f) / 1e12 / (ms_per_step / 1e3),

@@ -148,6 +148,19 @@ po_status po_prefill_batch(po_ctx* ctx, const int32_t* tokens_concat, const int6
                            int32_t n_req, const int32_t* cand_ids, int32_t n_cand,
                            float* out_logits, float* out_cand_logprobs);
 
+/* The same n_req requests with their tokens packed into one buffer for the position-wise
+ * layers.  A variant beside the paper's design: Section 6.1 runs requests one at a time
+ * because a long prefill already saturates the GPU; short requests do not fill whole
+ * rounds of GEMM tiles, so here consecutive requests are laid one after the other (each
+ * starting on a multiple of 64 rows, as many as max_input_len rows hold), norms and linear
+ * layers run over all their rows at once, attention runs per request, every request
+ * restarts at position 0, and each request's last row goes through the final norm and LM
+ * head.  Same arguments, outputs and validation as po_prefill_batch, and bit-identical
+ * results: no kernel's result for a row depends on which other rows share its launch. */
+po_status po_prefill_packed(po_ctx* ctx, const int32_t* tokens_concat, const int64_t* lens,
+                            int32_t n_req, const int32_t* cand_ids, int32_t n_cand,
+                            float* out_logits, float* out_cand_logprobs);
+
 /* Profile run (Section 3: at start-up the engine forwards a fake request of the declared
  * maximum input length and sizes what is left of the GPU from it).  Fills the activation
  * arena with a byte pattern, runs one request of `len` copies of token 0 (len <= the

@@ -34,7 +34,7 @@ EXPORTS = [
     "po_last_device_error", "po_op_rmsnorm", "po_op_linear", "po_op_gate_up_silu",
     "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head", "po_op_rope_table",
     "po_op_pack_qkv", "po_op_qkv_rope", "po_max_input_len", "po_profile", "po_set_lazy_last_layer",
-    "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix",
+    "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick",
 ]
@@ -86,6 +86,7 @@ def lib() -> C.CDLL:
     L.po_is_loaded.argtypes = [vp]
     L.po_prefill.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.po_prefill_batch.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
+    L.po_prefill_packed.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
     L.po_set_phase_timing.argtypes = [vp, i32]
     L.po_set_lazy_last_layer.argtypes = [vp, i32]
     L.po_kv_cache_bytes.argtypes = [C.POINTER(ModelConfigC), i64, C.POINTER(sz)]
@@ -204,7 +205,7 @@ class Context:
         return logits, lp
 
     def po_prefill_batch(self, token_lists: Sequence[np.ndarray], cand: Optional[Sequence[int]] = None,
-                         want_logits: bool = False):
+                         want_logits: bool = False, packed: bool = False):
         lens = np.array([len(t) for t in token_lists], dtype=np.int64)
         tok = np.ascontiguousarray(np.concatenate([np.asarray(t, dtype=np.int32) for t in token_lists]))
         n_req = len(token_lists)
@@ -212,9 +213,14 @@ class Context:
         cand_a = None if cand is None else np.ascontiguousarray(cand, dtype=np.int32)
         logits = np.empty((n_req, self.cfg.vocab_size), dtype=np.float32) if want_logits else None
         lp = np.empty((n_req, n_cand), dtype=np.float32) if n_cand else None
-        check(lib().po_prefill_batch(self._h, _host_ptr(tok), _host_ptr(lens), n_req, _host_ptr(cand_a),
-                                     n_cand, _host_ptr(logits), _host_ptr(lp)))
+        entry = lib().po_prefill_packed if packed else lib().po_prefill_batch
+        check(entry(self._h, _host_ptr(tok), _host_ptr(lens), n_req, _host_ptr(cand_a), n_cand, _host_ptr(logits),
+                    _host_ptr(lp)))
         return logits, lp
+
+    def po_prefill_packed(self, token_lists: Sequence[np.ndarray], cand: Optional[Sequence[int]] = None,
+                          want_logits: bool = False):
+        return self.po_prefill_batch(token_lists, cand, want_logits, packed=True)
 
     def po_profile(self, length: int):
         """-> (device ms of a fake request of `length` tokens, measured high-water mark of the arena)"""

@@ -60,7 +60,9 @@ struct GemmParams {
     const float* rope_sin;
     int64_t ld, ldv;
     int64_t lda, ldw, ldr;
-    int64_t pos0;        // EPI_QKV_ROPE: sequence position of GEMM row 0
+    int64_t pos0;        // EPI_QKV_ROPE: buffer row (= V^T column) of GEMM row 0, and its sequence position
+    const int32_t* row_pos;  // EPI_QKV_ROPE: sequence position of every buffer row when several requests are
+                             // packed into one buffer (indexed by buffer row); null = position == buffer row
     int M, N, K;
     int mt, nt;          // tile counts
     int qd, kvd, hd;     // EPI_QKV_ROPE: segment widths and head size
@@ -79,8 +81,8 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
 // the patch's two 32-column sub-tiles; the lane holds features 8*(r/4) + 4*lhi + (r%4) of
 // each.  cb = first GEMM column of the patch (a multiple of 64).
 template <int EPI>
-__device__ __forceinline__ void epilogue_patch(const GemmParams& p, int row, int cb, int lhi, const f32x16& c0,
-                                               const f32x16& c1) {
+__device__ __forceinline__ void epilogue_patch(const GemmParams& p, int row, int64_t pos, int cb, int lhi,
+                                               const f32x16& c0, const f32x16& c1) {
     if (EPI == EPI_SILU_MUL) {
         // sub-tile 0 = gate, sub-tile 1 = up of the same 32 features (weight rows interleaved)
         bf16_t* drow = p.dst + (int64_t)row * p.ld + cb / 2 + 4 * lhi;
@@ -100,8 +102,8 @@ __device__ __forceinline__ void epilogue_patch(const GemmParams& p, int row, int
             const int patch = (c - head * p.hd) >> 6;
             const int i0 = patch * 32 + 4 * lhi;             // rotary index of register quad 0
             bf16_t* drow = (is_q ? p.dst + (int64_t)row * p.qd : p.dst_k + (int64_t)row * p.kvd) + head * p.hd + i0;
-            const float* ct = p.rope_cos + (p.pos0 + row) * half + i0;
-            const float* st = p.rope_sin + (p.pos0 + row) * half + i0;
+            const float* ct = p.rope_cos + pos * half + i0;
+            const float* st = p.rope_sin + pos * half + i0;
             const bf16_t* bp = p.bias ? p.bias + cb + 4 * lhi : nullptr;
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
@@ -335,11 +337,13 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     for (int mi = 0; mi < 4; ++mi) {
         const int row = m0 + wm * 128 + mi * 32 + l31;
         if (row >= p.M) continue;
+        int64_t pos = 0;      // rotary position of this token row
+        if (EPI == EPI_QKV_ROPE) pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
             const int cb = n0 + wn * 128 + pt * 64;
             if (cb >= p.N) continue;
-            epilogue_patch<EPI>(p, row, cb, lhi, acc[mi][2 * pt], acc[mi][2 * pt + 1]);
+            epilogue_patch<EPI>(p, row, pos, cb, lhi, acc[mi][2 * pt], acc[mi][2 * pt + 1]);
         }
     }
 }
@@ -388,12 +392,12 @@ void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, in
 
 void launch_gemm_qkv_rope(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
                           bf16_t* Q, bf16_t* Kd, bf16_t* Vt, int64_t ldv, const float* rope_cos,
-                          const float* rope_sin, int64_t pos0, int64_t M, int qd, int kvd, int hd, int K,
-                          hipStream_t s) {
+                          const float* rope_sin, int64_t pos0, const int32_t* row_pos, int64_t M, int qd, int kvd,
+                          int hd, int K, hipStream_t s) {
     if (M <= 0) return;
     GemmParams p = base_params(A, lda, Wqkv, ldw, M, qd + 2 * kvd, K);
     p.bias = bias; p.dst = Q; p.dst_k = Kd; p.dst_vt = Vt; p.ldv = ldv;
-    p.rope_cos = rope_cos; p.rope_sin = rope_sin; p.pos0 = pos0;
+    p.rope_cos = rope_cos; p.rope_sin = rope_sin; p.pos0 = pos0; p.row_pos = row_pos;
     p.qd = qd; p.kvd = kvd; p.hd = hd;
     launch_t<EPI_QKV_ROPE>(p, s);
 }

@@ -196,12 +196,24 @@ struct PhaseTimer {
     }
 };
 
-// one request on the device; tokens already validated
-// p_reuse: positions [0, p_reuse) are not computed; their K/V of every layer come from the prefix cache
-// (0 = compute everything).  p_store: afterwards the cache holds the K/V of positions [0, p_store)
-// (positions [p_reuse, p_store) are copied out of this run; 0 = the cache is left alone).
-po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32_t* cand, int32_t n_cand,
-                      float* out_logits, float* out_lp, int64_t p_reuse = 0, int64_t p_store = 0) {
+// One request inside the token buffer of a run: rows [start, start + len) of X / Q / K / V^T.
+struct Seg {
+    int64_t start, len;
+};
+constexpr int64_t SEG_ALIGN = 64;   // packed requests start on a key-tile boundary (16-byte aligned V^T columns)
+
+// One pass of the whole path over a token buffer that holds one request (segs = {{0, len}}) or several
+// requests packed one after the other; tokens already validated.  `tokens` holds `total` ids (packed:
+// gaps between requests filled with id 0; those rows are computed and never read).  The position-wise
+// operators run over all rows at once, attention runs per request, and each request's last row gets the
+// final norm, the LM head and the candidate log-probs; out_logits / out_lp receive one row per request.
+// Row results of the position-wise kernels do not depend on the other rows in a launch, so every request's
+// output is bit-identical to running it alone.
+// p_reuse / p_store (single request only): positions [0, p_reuse) are not computed, their K/V of every
+// layer come from the prefix cache; afterwards the cache holds the K/V of positions [0, p_store).
+po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::vector<Seg>& segs,
+                   const int32_t* cand, int32_t n_cand, float* out_logits, float* out_lp, int64_t p_reuse = 0,
+                   int64_t p_store = 0) {
     const po_model_config& m = c->cfg;
     const Layout& L = c->lay;
     const int dt = m.dtype;
@@ -221,14 +233,27 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
     const float* rs = (const float*)(ws + L.rope_sin);
     float* d_logits = (float*)(ws + L.logits);
     const int C = L.chunk;
+    const bool packed = segs.size() > 1;
+    const int64_t n_seg = (int64_t)segs.size();
 
     c->ev_used = 0;
-    PO_HIP(hipMemcpyAsync(d_tok, tokens, (size_t)len * 4, hipMemcpyHostToDevice, s));
+    PO_HIP(hipMemcpyAsync(d_tok, tokens, (size_t)total * 4, hipMemcpyHostToDevice, s));
     if (n_cand > 0) PO_HIP(hipMemcpyAsync(ws + L.cand, cand, (size_t)n_cand * 4, hipMemcpyHostToDevice, s));
     PO_HIP(hipEventRecord(c->ev_start, s));
-    launch_embed(dt, d_tok + p_reuse, c->w + L.embed, X + (size_t)p_reuse * d * esz, len - p_reuse, d, s);
+    launch_embed(dt, d_tok + p_reuse, c->w + L.embed, X + (size_t)p_reuse * d * esz, total - p_reuse, d, s);
+    // Packed: the sequence position of every buffer row, for the rotary embedding in the QKV epilogue.  The
+    // token ids are dead once the embedding has been gathered, so the positions take over their buffer.
+    std::vector<int32_t> row_pos;
+    const int32_t* d_row_pos = nullptr;
+    if (packed) {
+        row_pos.assign((size_t)total, 0);
+        for (const Seg& g : segs)
+            for (int64_t i = 0; i < g.len; ++i) row_pos[(size_t)(g.start + i)] = (int32_t)i;
+        PO_HIP(hipMemcpyAsync(d_tok, row_pos.data(), (size_t)total * 4, hipMemcpyHostToDevice, s));
+        d_row_pos = d_tok;
+    }
     // the last key tile of the attention reads V^T up to the next multiple of 64 positions
-    if (dt == PO_BF16) launch_vt_pad_zero((bf16_t*)(ws + L.Vt), kvd, L.ldv, len, s);
+    if (dt == PO_BF16) launch_vt_pad_zero((bf16_t*)(ws + L.Vt), kvd, L.ldv, total, s);
 
     for (int l = 0; l < m.n_layers; ++l) {
         const LayerOff& o = L.layers[l];
@@ -250,8 +275,8 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
             else
                 PO_HIP(hipMemcpyAsync(V, kc_l + c->kv_v_off, (size_t)p_reuse * kvd * esz, hipMemcpyDeviceToDevice, s));
         }
-        for (int64_t c0 = p_reuse; c0 < len; c0 += Cq) {
-            const int64_t rows = (len - c0 < Cq) ? len - c0 : Cq;
+        for (int64_t c0 = p_reuse; c0 < total; c0 += Cq) {
+            const int64_t rows = (total - c0 < Cq) ? total - c0 : Cq;
             unsigned char* Xn = Xq;     // (shadows the MLP-phase buffer inside this loop)
             launch_rmsnorm(dt, X + (size_t)c0 * d * esz, c->w + o.attn_norm, Xn, rows, d, m.rms_eps, s);
             PhaseTimer pt(c, PO_K_QKV);
@@ -259,7 +284,7 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
                 // one GEMM: RoPE applied to Q and K in the epilogue, V written as V^T
                 launch_gemm_qkv_rope((const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, (const bf16_t*)bqkv,
                                      (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
-                                     (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, rows, qd, kvd, hd, d, s);
+                                     (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, s);
             } else {
                 launch_gemm_basic(dt, Xn, d, wqkv, d, Q + (size_t)c0 * qd * esz, qd, bqkv, nullptr, 0, rows, qd, d, s);
                 launch_gemm_basic(dt, Xn, d, wqkv + (size_t)qd * d * esz, d, K + (size_t)c0 * kvd * esz, kvd,
@@ -269,10 +294,13 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
             }
         }
         if (dt == PO_F32) {
-            // (rows below p_reuse came rotated out of the prefix cache)
-            const size_t t0 = (size_t)p_reuse * (hd / 2);
-            launch_rope(dt, Q + (size_t)p_reuse * qd * esz, qd, rc + t0, rs + t0, len - p_reuse, m.n_q_heads, hd, s);
-            launch_rope(dt, K + (size_t)p_reuse * kvd * esz, kvd, rc + t0, rs + t0, len - p_reuse, m.n_kv_heads, hd, s);
+            // every request restarts at position 0 (rows below p_reuse came rotated out of the prefix cache)
+            for (const Seg& g : segs) {
+                const int64_t r0 = g.start + p_reuse, nr = g.len - p_reuse;
+                const size_t t0 = (size_t)p_reuse * (hd / 2);
+                launch_rope(dt, Q + (size_t)r0 * qd * esz, qd, rc + t0, rs + t0, nr, m.n_q_heads, hd, s);
+                launch_rope(dt, K + (size_t)r0 * kvd * esz, kvd, rc + t0, rs + t0, nr, m.n_kv_heads, hd, s);
+            }
         }
         if (p_store > p_reuse) {
             // Section 5.1: keep the K/V of the prefix, discard the suffix's with the layer
@@ -287,23 +315,45 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
         }
         // Nothing reads the last layer's output except the last position (one output token, Section 1):
         // there the keys and values of every position are still needed, but attention, O-projection and
-        // MLP only for the row block / the row that holds position len - 1.  Row results do not depend on
-        // which other rows are computed, so the logits are bit-identical with and without this.
+        // MLP only for the row block / the row that holds a request's last position.  Row results do not
+        // depend on which other rows are computed, so the logits are bit-identical with and without this.
         const bool last_only = c->lazy_last_layer && l == m.n_layers - 1;
-        // ---- attention over the whole sequence in one call; O overwrites Q
-        {
+        // ---- attention over each request's whole sequence in one call; O overwrites Q
+        for (const Seg& g : segs) {
             PhaseTimer pt(c, PO_K_ATTENTION);
-            const int64_t q_row0 = last_only ? len - 1 : p_reuse;
+            const int64_t q_row0 = last_only ? g.len - 1 : p_reuse;
+            unsigned char* Qg = Q + (size_t)g.start * qd * esz;
             if (dt == PO_BF16) {
-                launch_attention_mfma((const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)(ws + L.Vt), L.ldv,
-                                      (bf16_t*)Q, len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
+                launch_attention_mfma((const bf16_t*)Qg, (const bf16_t*)(K + (size_t)g.start * kvd * esz),
+                                      (const bf16_t*)(ws + L.Vt) + g.start, L.ldv, (bf16_t*)Qg, g.len, m.n_q_heads,
+                                      m.n_kv_heads, hd, q_row0, s);
             } else {
-                launch_attention_basic(dt, Q, K, V, Q, len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
+                launch_attention_basic(dt, Qg, K + (size_t)g.start * kvd * esz, V + (size_t)g.start * kvd * esz, Qg,
+                                       g.len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
             }
         }
         // ---- position-wise part after attention, chunk by chunk, residual stream in place
-        for (int64_t c0 = last_only ? len - 1 : p_reuse; c0 < len; c0 += C) {
-            const int64_t rows = (len - c0 < C) ? len - c0 : C;
+        int64_t pw0 = p_reuse, pw1 = total;
+        if (last_only) {
+            if (!packed) {
+                pw0 = total - 1;
+            } else {
+                // the requests' last rows, gathered into rows 0 .. n_seg-1 (whose own contents nothing reads
+                // any more; request j's last row is at or beyond row j, so ascending order overwrites no source)
+                for (int64_t j = 0; j < n_seg; ++j) {
+                    const int64_t r = segs[j].start + segs[j].len - 1;
+                    if (r == j) continue;
+                    PO_HIP(hipMemcpyAsync(X + (size_t)j * d * esz, X + (size_t)r * d * esz, (size_t)d * esz,
+                                          hipMemcpyDeviceToDevice, s));
+                    PO_HIP(hipMemcpyAsync(Q + (size_t)j * qd * esz, Q + (size_t)r * qd * esz, (size_t)qd * esz,
+                                          hipMemcpyDeviceToDevice, s));
+                }
+                pw0 = 0;
+                pw1 = n_seg;
+            }
+        }
+        for (int64_t c0 = pw0; c0 < pw1; c0 += C) {
+            const int64_t rows = (pw1 - c0 < C) ? pw1 - c0 : C;
             unsigned char* Xc = X + (size_t)c0 * d * esz;
             const unsigned char* Oc = Q + (size_t)c0 * qd * esz;
             if (dt == PO_BF16) {
@@ -338,22 +388,30 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
             }
         }
     }
-    // ---- last position only: final norm, LM head, candidate log-probs
-    launch_rmsnorm(dt, X + (size_t)(len - 1) * d * esz, c->w + L.final_norm, ws + L.xn_last, 1, d, m.rms_eps, s);
-    launch_lm_head(dt, ws + L.xn_last, c->w + L.lm_head, d_logits, m.vocab_size, d, s);
-    if (n_cand > 0)
-        launch_cand_logprobs(d_logits, (const int32_t*)(ws + L.cand), n_cand, (float*)(ws + L.cand_lp), s);
-    PO_HIP(hipEventRecord(c->ev_stop, s));
-    PO_HIP(hipGetLastError());
-    if (out_logits)
-        PO_HIP(hipMemcpyAsync(out_logits, d_logits, (size_t)m.vocab_size * 4, hipMemcpyDeviceToHost, s));
-    if (out_lp && n_cand > 0)
-        PO_HIP(hipMemcpyAsync(out_lp, ws + L.cand_lp, (size_t)n_cand * 4, hipMemcpyDeviceToHost, s));
+    // ---- each request's last position only: final norm, LM head, candidate log-probs
+    const bool gathered = packed && c->lazy_last_layer && m.n_layers > 0;
+    for (int64_t j = 0; j < n_seg; ++j) {
+        const int64_t r = gathered ? j : segs[j].start + segs[j].len - 1;
+        launch_rmsnorm(dt, X + (size_t)r * d * esz, c->w + L.final_norm, ws + L.xn_last, 1, d, m.rms_eps, s);
+        launch_lm_head(dt, ws + L.xn_last, c->w + L.lm_head, d_logits, m.vocab_size, d, s);
+        if (n_cand > 0)
+            launch_cand_logprobs(d_logits, (const int32_t*)(ws + L.cand), n_cand, (float*)(ws + L.cand_lp), s);
+        if (j == n_seg - 1) {
+            PO_HIP(hipEventRecord(c->ev_stop, s));
+            PO_HIP(hipGetLastError());
+        }
+        // (stream-ordered: the copies finish before the next request's LM head overwrites the buffers)
+        if (out_logits)
+            PO_HIP(hipMemcpyAsync(out_logits + (size_t)j * m.vocab_size, d_logits, (size_t)m.vocab_size * 4,
+                                  hipMemcpyDeviceToHost, s));
+        if (out_lp && n_cand > 0)
+            PO_HIP(hipMemcpyAsync(out_lp + (size_t)j * n_cand, ws + L.cand_lp, (size_t)n_cand * 4, hipMemcpyDeviceToHost, s));
+    }
     PO_HIP(hipStreamSynchronize(s));
     float ms = 0.f;
     PO_HIP(hipEventElapsedTime(&ms, c->ev_start, c->ev_stop));
     c->stats.last_prefill_ms = ms;
-    c->stats.last_len = len;
+    c->stats.last_len = total;
     for (int kc = 0; kc < PO_K_COUNT; ++kc) { c->stats.kernel_ms[kc] = 0; c->stats.kernel_launches[kc] = 0; }
     for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
         float t = 0.f;
@@ -363,6 +421,12 @@ po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32
         }
     }
     return PO_OK;
+}
+
+// one request on the device
+po_status run_prefill(po_ctx* c, const int32_t* tokens, int64_t len, const int32_t* cand, int32_t n_cand,
+                      float* out_logits, float* out_lp, int64_t p_reuse = 0, int64_t p_store = 0) {
+    return run_rows(c, tokens, len, std::vector<Seg>{{0, len}}, cand, n_cand, out_logits, out_lp, p_reuse, p_store);
 }
 
 po_status validate_request(const po_ctx* c, const int32_t* tokens, int64_t len, const int32_t* cand, int32_t n_cand) {
@@ -564,6 +628,56 @@ po_status po_prefill_batch(po_ctx* c, const int32_t* tokens_concat, const int64_
         total_ms += c->stats.last_prefill_ms;
         for (int kc = 0; kc < PO_K_COUNT; ++kc) { k_ms[kc] += c->stats.kernel_ms[kc]; k_n[kc] += c->stats.kernel_launches[kc]; }
         off += lens[r];
+    }
+    c->stats.last_prefill_ms = total_ms;
+    for (int kc = 0; kc < PO_K_COUNT; ++kc) { c->stats.kernel_ms[kc] = k_ms[kc]; c->stats.kernel_launches[kc] = k_n[kc]; }
+    c->stats.last_len = off;
+    return PO_OK;
+}
+
+po_status po_prefill_packed(po_ctx* c, const int32_t* tokens_concat, const int64_t* lens, int32_t n_req,
+                            const int32_t* cand_ids, int32_t n_cand, float* out_logits, float* out_cand_logprobs) {
+    if (!c || !tokens_concat || !lens || n_req <= 0) return PO_ERR_INVALID_ARG;
+    int64_t off = 0;
+    for (int32_t r = 0; r < n_req; ++r) {
+        if (lens[r] <= 0) return PO_ERR_INVALID_ARG;
+        po_status st = validate_request(c, tokens_concat + off, lens[r], cand_ids, n_cand);
+        if (st != PO_OK) return st;
+        off += lens[r];
+    }
+    if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
+    double total_ms = 0, k_ms[PO_K_COUNT] = {0, 0, 0, 0};
+    int64_t k_n[PO_K_COUNT] = {0, 0, 0, 0};
+    std::vector<Seg> segs;
+    std::vector<int32_t> buf;
+    off = 0;
+    int32_t r = 0;
+    while (r < n_req) {
+        // the next group: consecutive requests, each starting on a multiple of SEG_ALIGN rows, as many as
+        // the buffers (sized for max_input_len rows) hold
+        segs.clear();
+        const int32_t r_first = r;
+        int64_t end = 0;
+        while (r < n_req) {
+            const int64_t start = (end + SEG_ALIGN - 1) / SEG_ALIGN * SEG_ALIGN;
+            if (!segs.empty() && start + lens[r] > c->max_len) break;
+            segs.push_back(Seg{start, lens[r]});
+            end = start + lens[r];
+            ++r;
+        }
+        buf.assign((size_t)end, 0);
+        int64_t src = off;
+        for (const Seg& g : segs) {
+            memcpy(buf.data() + g.start, tokens_concat + src, (size_t)g.len * 4);
+            src += g.len;
+        }
+        po_status st = run_rows(c, buf.data(), end, segs, cand_ids, n_cand,
+                                out_logits ? out_logits + (size_t)r_first * c->cfg.vocab_size : nullptr,
+                                out_cand_logprobs ? out_cand_logprobs + (size_t)r_first * n_cand : nullptr);
+        if (st != PO_OK) return st;
+        total_ms += c->stats.last_prefill_ms;
+        for (int kc = 0; kc < PO_K_COUNT; ++kc) { k_ms[kc] += c->stats.kernel_ms[kc]; k_n[kc] += c->stats.kernel_launches[kc]; }
+        off = src;
     }
     c->stats.last_prefill_ms = total_ms;
     for (int kc = 0; kc < PO_K_COUNT; ++kc) { c->stats.kernel_ms[kc] = k_ms[kc]; c->stats.kernel_launches[kc] = k_n[kc]; }
@@ -829,7 +943,7 @@ po_status po_op_qkv_rope(const void* a, const void* wqkv, const void* bqkv, void
     if ((hd != 64 && hd != 128) || !gemm_mfma_supported((Hq + 2 * Hkv) * hd, K)) return PO_ERR_BAD_CONFIG;
     if (ldv < pos0 + M || ldv % 8) return PO_ERR_INVALID_ARG;
     launch_gemm_qkv_rope((const bf16_t*)a, K, (const bf16_t*)wqkv, K, (const bf16_t*)bqkv, (bf16_t*)q, (bf16_t*)k,
-                         (bf16_t*)vt, ldv, cos_t, sin_t, pos0, M, Hq * hd, Hkv * hd, hd, K, (hipStream_t)stream);
+                         (bf16_t*)vt, ldv, cos_t, sin_t, pos0, nullptr, M, Hq * hd, Hkv * hd, hd, K, (hipStream_t)stream);
     PO_HIP(hipGetLastError());
     return PO_OK;
 }

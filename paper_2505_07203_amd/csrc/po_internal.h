@@ -61,11 +61,13 @@ void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, in
 // Fused QKV projection: [Q|K|V] = A Wqkv^T (+bias), rotary embedding applied to Q and K in
 // the fp32 epilogue, V written transposed.  Wqkv (and bias) rows must be in the packed order
 // of launch_pack_rope_rows.  Q, K point at the first row of this call (row stride qd / kvd);
-// Vt is the base of V^T [kvd][ldv] and the call writes columns pos0 .. pos0+M-1.
+// Vt is the base of V^T [kvd][ldv] and the call writes columns pos0 .. pos0+M-1.  GEMM row r is
+// rotated for sequence position row_pos[pos0 + r] (device array over buffer rows: several requests
+// packed into one buffer), or pos0 + r when row_pos is null.
 void launch_gemm_qkv_rope(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
                           bf16_t* Q, bf16_t* K, bf16_t* Vt, int64_t ldv, const float* rope_cos,
-                          const float* rope_sin, int64_t pos0, int64_t M, int qd, int kvd, int hd, int Kdim,
-                          hipStream_t s);
+                          const float* rope_sin, int64_t pos0, const int32_t* row_pos, int64_t M, int qd, int kvd,
+                          int hd, int Kdim, hipStream_t s);
 // In place: within every head of `hd` rows (hd == 128 only; hd == 64 is already in order)
 // swap row blocks [32,64) and [64,96), so that rotary partners i and i + hd/2 sit 32 rows
 // apart inside one 64-row group.  row_elems = elements per row (1 for a bias vector).

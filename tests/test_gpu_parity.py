@@ -411,3 +411,54 @@ def test_scheduler_with_prefix_cache_end_to_end():
         assert (order, hits) == ([0, 1, 2, 3], 1)
     finally:
         ctx.po_destroy()
+
+
+# ------------------------------------------------------------------ packed short requests
+
+@pytest.mark.parametrize("cfg,lens,max_len,chunk", [
+    (I.TINY, (300, 1, 65, 512, 7, 64, 63, 129), 1024, 128),
+    (I.TINY.replace(dtype=I.BF16, ffn_dim=704), (300, 1, 65, 777, 7, 64, 63, 257, 1000), 2048, 256),
+    (I.ModelConfig(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=1, head_dim=128, ffn_dim=704, vocab_size=1024,
+                   rms_eps=1e-5, rope_theta=10000.0, dtype=I.BF16, qkv_bias=1), (130, 513, 1, 256, 90), 1024, 512),
+    (I.LLAMA8B.replace(n_layers=2, vocab_size=4096), (256, 1000, 4097, 64, 1, 2500), 8192, 4096)])
+def test_packed_requests_equal_sequential_bitwise(cfg, lens, max_len, chunk):
+    """Several requests packed into one buffer for the position-wise layers give, request by request, the
+    bits of running each alone (with and without the last-layer shortcut), and match the oracle."""
+    ctx = make_ctx(cfg, 31, max_len, chunk)
+    try:
+        cand = I.label_ids(cfg)
+        reqs = [I.make_tokens(cfg, 41, n, request=i) for i, n in enumerate(lens)]
+        zb, lpb = ctx.po_prefill_batch(reqs, cand, want_logits=True)
+        zp, lpp = ctx.po_prefill_packed(reqs, cand, want_logits=True)
+        assert np.array_equal(zp, zb) and np.array_equal(lpp, lpb)
+        ctx.po_set_lazy_last_layer(False)
+        zq, lpq = ctx.po_prefill_packed(reqs, cand, want_logits=True)
+        assert np.array_equal(zq, zb) and np.array_equal(lpq, lpb)
+        ctx.po_set_lazy_last_layer(True)
+        # a single request afterwards is unaffected by what the packed run left in the buffers
+        z0, _ = ctx.po_prefill(reqs[0], cand)
+        assert np.array_equal(z0, zb[0])
+        # the oracle, directly, for the two shortest requests of more than one token
+        for i in sorted((i for i in range(len(lens)) if lens[i] > 1), key=lambda i: lens[i])[:2]:
+            z_ref, _ = H.oracle_prefill(cfg, 31, reqs[i])
+            if cfg.dtype == I.F32:
+                assert np.max(np.abs(zp[i] - z_ref)) <= 1e-4
+            else:
+                assert H.normalised_max_rel(zp[i].astype(np.float64), z_ref) <= 2e-2
+    finally:
+        ctx.po_destroy()
+
+
+def test_packed_rejects_bad_input_before_any_launch():
+    cfg = I.TINY
+    ctx = make_ctx(cfg, 31, 256, 128)
+    try:
+        good = I.make_tokens(cfg, 41, 100)
+        bad = good.copy()
+        bad[50] = cfg.vocab_size
+        with pytest.raises(B.PoError):
+            ctx.po_prefill_packed([good, bad], I.label_ids(cfg))
+        with pytest.raises(B.PoError):
+            ctx.po_prefill_packed([good, I.make_tokens(cfg, 41, 257)], I.label_ids(cfg))     # longer than max_input_len
+    finally:
+        ctx.po_destroy()
