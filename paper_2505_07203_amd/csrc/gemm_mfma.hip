@@ -39,13 +39,11 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 32;
+constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
-constexpr int NSTAGE = 4;
-constexpr int OPER_BYTES = BM * BK * 2;            // 16 KiB per operand per stage
-constexpr int STAGE_BYTES = 2 * OPER_BYTES;        // A + W
-constexpr int SMEM_BYTES = NSTAGE * STAGE_BYTES;   // 128 KiB
-constexpr int W_REGION = NSTAGE * OPER_BYTES;      // LDS offset of the weight slices
+constexpr int UNIT_BYTES = BM * BK * 2;            // one operand's slice: 256 rows x 128 bytes = 32 KiB
+constexpr int NUNIT = 5;                           // ring of five units: the whole 160 KiB of LDS
+constexpr int SMEM_BYTES = NUNIT * UNIT_BYTES;
 constexpr int GROUP_M = 4;
 
 struct GemmParams {
@@ -171,12 +169,12 @@ __device__ __forceinline__ void epilogue_patch(const GemmParams& p, int row, int
     }
 }
 
-// Stage hand-over: wait until this wavefront's global->LDS loads of the NEXT slice have
-// landed (all but the 16 youngest, i.e. the two slices after it, may stay in flight) and its
-// own LDS reads have returned, then meet the other wavefronts.  A plain __syncthreads() would
-// also wait for every load in flight and so cancel the prefetch distance; the "memory"
-// clobber keeps the compiler from moving LDS accesses across the barrier.
-#define PO_HANDOVER() asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory")
+// Stage hand-over: wait until this wavefront's global->LDS loads of the NEXT slice have landed (all
+// but the 8 youngest, the activation unit after it, may stay in flight) and its own LDS reads have
+// returned, then meet the other wavefronts.  A plain __syncthreads() would also wait for every load
+// in flight and so cancel the prefetch distance; the "memory" clobber keeps the compiler from moving
+// LDS accesses across the barrier.
+#define PO_HANDOVER() asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
 template <int EPI>
 __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmParams p) {
@@ -202,36 +200,36 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     const int l31 = lane & 31, lhi = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // ---- global -> LDS map.  Load instruction i (0..3) of wavefront w fills rows
-    // (w*4 + i)*16 .. +15 of an operand slice: lane l -> row + l/4, physical segment l & 3,
-    // which holds logical segment (l & 3) ^ ((row >> 2) & 3).  Each operand is addressed through a
-    // buffer resource that starts at the tile's first row and ends with the matrix: the per-lane
-    // byte offset never changes, the slice offset is one scalar, and rows of a ragged last tile
-    // beyond the matrix read as zero instead of needing a clamp (they are never stored).
+    // ---- global -> LDS map.  A unit (one operand's 256 rows x 64 k) is 32 one-KiB loads; wavefront w issues
+    // loads w*8 .. w*8+7, load q fills rows q*8 .. q*8+7: lane l -> row q*8 + l/8, physical segment l & 7,
+    // which holds logical segment (l & 7) ^ ((row >> 1) & 7).  Eight lanes fetch one whole 128-byte line.
+    // Each operand is addressed through a buffer resource that starts at the tile's first row and ends with
+    // the matrix: the per-lane byte offset never changes, the slice offset is one scalar, and rows of a
+    // ragged last tile beyond the matrix read as zero instead of needing a clamp (they are never stored).
     const uint64_t a_bytes = (uint64_t)(p.M - m0) * (uint64_t)p.lda * 2, w_bytes = (uint64_t)(p.N - n0) * (uint64_t)p.ldw * 2;
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(p.A + (int64_t)m0 * p.lda), 0, (int)(uint32_t)(a_bytes > 0xffffffffull ? 0xffffffffull : a_bytes), 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(p.W + (int64_t)n0 * p.ldw), 0, (int)(uint32_t)(w_bytes > 0xffffffffull ? 0xffffffffull : w_bytes), 0x00020000);
-    uint32_t voa[4], vow[4];
+    // (the whole row term sits in the per-lane offset: the scalar offset is exempt from the range check)
+    uint32_t voa[8], vow[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (wave * 4 + i) * 16 + (lane >> 2);
-        const int lseg = (lane & 3) ^ ((row >> 2) & 3);
+    for (int i = 0; i < 8; ++i) {
+        const int row = wave * 64 + i * 8 + (lane >> 3);
+        const int lseg = (lane & 7) ^ ((row >> 1) & 7);
         voa[i] = (uint32_t)row * (uint32_t)(p.lda * 2) + lseg * 16;
         vow[i] = (uint32_t)row * (uint32_t)(p.ldw * 2) + lseg * 16;
     }
     const int KT = p.K / BK;
-    // one 16-byte-per-lane load of operand slice kt_: j_ = 0..3 activations, 4..7 weights
-#define PO_DMA(kt_, stg_, j_)                                                                                 \
+    // load i_ (0..7) of this wavefront's share of unit u_ (even: activations of slice u_/2, odd: weights)
+    // into ring position pos_
+#define PO_DMA(u_, pos_, i_)                                                                                  \
     {                                                                                                         \
-        const int t_ = min((kt_), KT - 1);                                                                    \
-        unsigned char* sa_ = smem + ((j_) >> 2) * W_REGION + (stg_) * OPER_BYTES + wave * 4096 + ((j_) & 3) * 1024; \
-        __builtin_amdgcn_raw_ptr_buffer_load_lds((j_) >> 2 ? rw : ra, (__attribute__((address_space(3))) void*)sa_, 16, \
-                                                 (j_) >> 2 ? vow[(j_) & 3] : voa[(j_) & 3], t_ * (BK * 2), 0, 0); \
+        const int t_ = min((u_) >> 1, KT - 1);                                                                \
+        unsigned char* sa_ = smem + (pos_) * UNIT_BYTES + wave * 8192 + (i_) * 1024;                          \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds((u_) & 1 ? rw : ra, (__attribute__((address_space(3))) void*)sa_, 16, \
+                                                 (u_) & 1 ? vow[(i_)] : voa[(i_)], t_ * (BK * 2), 0, 0);      \
     }
-#define PO_ISSUE(kt_)                                                                                         \
-    { _Pragma("unroll") for (int j = 0; j < 8; ++j) PO_DMA(kt_, (kt_) & (NSTAGE - 1), j) }
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -241,39 +239,35 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    // fragment read offsets: row l31 of a 32-row tile, logical segment kk*2 + lhi
-    const int fsw = (l31 >> 2) & 3;
-    int f_off[2];
+    // fragment read offsets: row l31 of a 32-row tile, logical segment kk*2 + lhi of its 128 bytes; one lane
+    // register per k-step, operand and 64 KiB of LDS, the rest of an address is an immediate below 64 KiB
+    int a_off[3][4], w_off[3][4];
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) f_off[kk] = l31 * 64 + (((kk * 2 + lhi) ^ fsw) << 4);
-    // LDS: the activation slices of the four stages in the first 64 KiB, the weight slices in the second.
-    // With the stage number a literal (main loop unrolled over the four stages) a fragment address is one of
-    // these four lane registers plus an immediate below 64 KiB.
-    int a_addr[2], w_addr[2];
+    for (int kk = 0; kk < 4; ++kk) {
+        const int fo = l31 * 128 + (((kk * 2 + lhi) ^ ((l31 >> 1) & 7)) << 4);
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-        a_addr[kk] = wm * 128 * 64 + f_off[kk];
-        w_addr[kk] = W_REGION + wn * 128 * 64 + f_off[kk];
+        for (int hb = 0; hb < 3; ++hb) {
+            a_off[hb][kk] = hb * 65536 + wm * 16384 + fo;
+            w_off[hb][kk] = hb * 65536 + wn * 16384 + fo;
+        }
     }
 
     // Software pipeline inside the wavefront.  There is only one wavefront per SIMD, so every
     // cycle it spends issuing something other than an MFMA while the matrix pipe is empty is
     // lost, and the four wavefronts run in lockstep, so whatever they issue together queues
     // up in the CU's single address unit.  Memory instructions are therefore issued ONE AT A
-    // TIME between MFMAs (a 32x32x16 MFMA keeps the pipe busy for 32 cycles) and the eight
-    // global->LDS loads of a slice are spread over two 16-MFMA blocks, one per four MFMAs:
-    //   block A(kt): 16 MFMA (kt, k-step 0); 8 fragment reads of (kt, k-step 1);
-    //                loads 4..7 (weights) of slice kt+3
-    //   hand-over barrier: slice kt+1 has landed, nobody reads slice kt's stage any more
-    //   block B(kt): 16 MFMA (kt, k-step 1); 8 fragment reads of (kt+1, k-step 0);
-    //                loads 0..3 (activations) of slice kt+4, into the stage slice kt occupied
-    // At the hand-over the loads issued after those of slice kt+1 are exactly the 16 of
-    // slices kt+2 and kt+3.
+    // TIME between MFMAs (a 32x32x16 MFMA keeps the pipe busy for 32 cycles).  A slice is four blocks
+    // of 16 MFMA, one per k-step; block kk also reads the 8 fragments of the next k-step and issues loads:
+    //   block 0..2 of slice s: the 8 loads of activation unit s+2, 3 + 3 + 2
+    //   hand-over barrier:     slice s+1 has landed; nobody reads slice s's units any more
+    //   block 3 of slice s:    fragments of (s+1, k-step 0); the 8 loads of weight unit s+2, into the
+    //                          position slice s's activations occupied (unit u lives at u mod 5)
+    // At the hand-over the loads issued after those of slice s+1 are the 8 of activation unit s+2.
     bf16x8 af0[4], wf0[4], af1[4], wf1[4];
-#define PO_FRAG1(AF, WF, st_, kk_, j_)                                                              \
+#define PO_FRAG1(AF, WF, pa_, pw_, kk_, j_)                                                          \
     {                                                                                               \
-        if ((j_) < 4) AF[(j_) & 3] = *(const bf16x8*)(smem + a_addr[kk_] + (st_) * OPER_BYTES + ((j_) & 3) * 2048); \
-        else          WF[(j_) & 3] = *(const bf16x8*)(smem + w_addr[kk_] + (st_) * OPER_BYTES + ((j_) & 3) * 2048); \
+        if ((j_) < 4) AF[(j_) & 3] = *(const bf16x8*)(smem + a_off[(pa_) >> 1][kk_] + ((pa_) & 1) * UNIT_BYTES + ((j_) & 3) * 4096); \
+        else          WF[(j_) & 3] = *(const bf16x8*)(smem + w_off[(pw_) >> 1][kk_] + ((pw_) & 1) * UNIT_BYTES + ((j_) & 3) * 4096); \
     }
 #define PO_MFMA1(AF, WF, t_)                                                                        \
     acc[(t_) >> 2][(t_) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[(t_) & 3], AF[(t_) >> 2], acc[(t_) >> 2][(t_) & 3], 0, 0, 0);
@@ -281,69 +275,200 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     // MFMA t needs AF[t >> 2] and WF[t & 3])
 #define PO_READ_SLOT(t_) ((t_) == 0 ? 0 : (t_) == 1 ? 4 : (t_) == 3 ? 5 : (t_) == 4 ? 6 : (t_) == 5 ? 7 : \
                           (t_) == 7 ? 1 : (t_) == 8 ? 2 : (t_) == 9 ? 3 : -1)
-    PO_ISSUE(0);
-    PO_ISSUE(1);
-    PO_ISSUE(2);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) PO_DMA(3, 3, j);
-    asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");     // slice 0 has landed
-#pragma unroll
-    for (int j = 0; j < 8; ++j) PO_FRAG1(af0, wf0, 0, 0, j);
-    // one slice; s_ = kt & 3 is its stage
-#define PO_SLICE(kt_, s_)                                                                           \
+    // load slots of blocks 0..2 (3, 3, 2 loads) and of block 3 (all eight free slots)
+#define PO_LOAD_SLOT_A(t_) ((t_) == 2 ? 0 : (t_) == 6 ? 1 : (t_) == 10 ? 2 : -1)
+#define PO_LOAD_SLOT_W(t_) ((t_) == 2 ? 0 : (t_) == 6 ? 1 : (t_) >= 10 ? (t_) - 8 : -1)
+    // one block: MFMAs on (AFc, WFc); reads k-step kkn_ of the slice at positions (pa_, pw_) into (AFn, WFn);
+    // loads of unit u_ into position up_: numbers base_ + slot, nl_ of them (block 3: nl_ = 8, W slots)
+#define PO_BLOCK(AFc, WFc, AFn, WFn, pa_, pw_, kkn_, u_, up_, base_, nl_)                             \
+    _Pragma("unroll") for (int t = 0; t < 16; ++t) {                                                \
+        PO_MFMA1(AFc, WFc, t);                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        if (PO_READ_SLOT(t) >= 0) {                                                                 \
+            PO_FRAG1(AFn, WFn, pa_, pw_, kkn_, PO_READ_SLOT(t));                                    \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+        } else if (((nl_) == 8 ? PO_LOAD_SLOT_W(t) : PO_LOAD_SLOT_A(t)) >= 0 &&                     \
+                   ((nl_) == 8 ? PO_LOAD_SLOT_W(t) : PO_LOAD_SLOT_A(t)) < (nl_)) {                  \
+            PO_DMA(u_, up_, (base_) + ((nl_) == 8 ? PO_LOAD_SLOT_W(t) : PO_LOAD_SLOT_A(t)));        \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+        }                                                                                           \
+    }
+    // slice s_ whose number is j_ modulo 5 (a literal): its units sit at positions 2j mod 5 and 2j+1 mod 5
+#define PO_SLICE(s_, j_)                                                                            \
     {                                                                                               \
-        _Pragma("unroll") for (int t = 0; t < 16; ++t) {                                            \
-            PO_MFMA1(af0, wf0, t);                                                                  \
-            __builtin_amdgcn_sched_barrier(0);                                                      \
-            if (PO_READ_SLOT(t) >= 0) {                                                             \
-                PO_FRAG1(af1, wf1, (s_), 1, PO_READ_SLOT(t));                                       \
-                __builtin_amdgcn_sched_barrier(0);                                                  \
-            } else if ((t & 3) == 2) {                                                              \
-                PO_DMA((kt_) + 3, ((s_) + 3) & 3, 4 + (t >> 2));                                    \
-                __builtin_amdgcn_sched_barrier(0);                                                  \
-            }                                                                                       \
-        }                                                                                           \
+        PO_BLOCK(af0, wf0, af1, wf1, (2 * (j_)) % 5, (2 * (j_) + 1) % 5, 1, 2 * (s_) + 4, (2 * (j_) + 4) % 5, 0, 3); \
+        PO_BLOCK(af1, wf1, af0, wf0, (2 * (j_)) % 5, (2 * (j_) + 1) % 5, 2, 2 * (s_) + 4, (2 * (j_) + 4) % 5, 3, 3); \
+        PO_BLOCK(af0, wf0, af1, wf1, (2 * (j_)) % 5, (2 * (j_) + 1) % 5, 3, 2 * (s_) + 4, (2 * (j_) + 4) % 5, 6, 2); \
         PO_HANDOVER();                                                                              \
-        _Pragma("unroll") for (int t = 0; t < 16; ++t) {                                            \
-            PO_MFMA1(af1, wf1, t);                                                                  \
-            __builtin_amdgcn_sched_barrier(0);                                                      \
-            if (PO_READ_SLOT(t) >= 0) {                                                             \
-                PO_FRAG1(af0, wf0, ((s_) + 1) & 3, 0, PO_READ_SLOT(t));                             \
-                __builtin_amdgcn_sched_barrier(0);                                                  \
-            } else if ((t & 3) == 2) {                                                              \
-                PO_DMA((kt_) + 4, (s_), t >> 2);                                                    \
-                __builtin_amdgcn_sched_barrier(0);                                                  \
-            }                                                                                       \
-        }                                                                                           \
+        PO_BLOCK(af1, wf1, af0, wf0, (2 * (j_) + 2) % 5, (2 * (j_) + 3) % 5, 0, 2 * (s_) + 5, (2 * (j_)) % 5, 0, 8); \
     }
-    int kt = 0;
-    for (; kt + 4 <= KT; kt += 4) {
-        PO_SLICE(kt, 0);
-        PO_SLICE(kt + 1, 1);
-        PO_SLICE(kt + 2, 2);
-        PO_SLICE(kt + 3, 3);
+    // in flight when the first slice is awaited: units 0..3 (slices 0 and 1)
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) PO_DMA(u, u, i);
+    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");     // slice 0 has landed
+#pragma unroll
+    for (int j = 0; j < 8; ++j) PO_FRAG1(af0, wf0, 0, 1, 0, j);
+    int s = 0;
+    for (; s + 5 <= KT; s += 5) {
+        PO_SLICE(s, 0);
+        PO_SLICE(s + 1, 1);
+        PO_SLICE(s + 2, 2);
+        PO_SLICE(s + 3, 3);
+        PO_SLICE(s + 4, 4);
     }
-    for (; kt < KT; ++kt) PO_SLICE(kt, kt & 3);
+    if (s < KT) { PO_SLICE(s, 0); ++s; }
+    if (s < KT) { PO_SLICE(s, 1); ++s; }
+    if (s < KT) { PO_SLICE(s, 2); ++s; }
+    if (s < KT) { PO_SLICE(s, 3); ++s; }
 #undef PO_SLICE
+#undef PO_BLOCK
+#undef PO_LOAD_SLOT_A
+#undef PO_LOAD_SLOT_W
 #undef PO_READ_SLOT
-#undef PO_ISSUE
 #undef PO_DMA
 #undef PO_FRAG1
 #undef PO_MFMA1
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the clamped tail loads
+    // the clamped tail loads have landed and every wavefront has finished reading the ring
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-    // ---- epilogue: lane = token row, 64-column patches
+    // ---- epilogue.  In an accumulator tile a lane holds one token row and runs of four consecutive
+    // features, so storing from there puts 8 bytes per lane into 32 different rows: partial cache lines,
+    // which the memory side handles several times slower than whole ones.  The position-wise epilogues
+    // therefore pass their results through LDS (the ring is free now; every wavefront uses 8 KiB of its
+    // own, so no further workgroup barrier is needed) one 32-row tile row at a time and store 16 bytes per
+    // lane, a wavefront covering whole row segments.  16-byte groups of a staged row are XOR-swizzled with
+    // the row number so that both the writes (lane = row) and the reads (lanes along a row) are free of
+    // bank conflicts.  The arithmetic (fp32 bias / residual add / SiLU-multiply, one round-to-nearest-even
+    // conversion) is the per-lane one.  QKV keeps the per-lane path (rotary pairs, V^T).
+    const int e31 = l31, ehi = lhi, elane = lane;
+    unsigned char* stg = smem + wave * 8192;
+    const int row_base = m0 + wm * 128, col_base = n0 + wn * 128;
+    if (EPI == EPI_QKV_ROPE) {
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-        const int row = m0 + wm * 128 + mi * 32 + l31;
-        if (row >= p.M) continue;
-        int64_t pos = 0;      // rotary position of this token row
-        if (EPI == EPI_QKV_ROPE) pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
+        for (int mi = 0; mi < 4; ++mi) {
+            const int row = row_base + mi * 32 + e31;
+            if (row >= p.M) continue;
+            const int64_t pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
 #pragma unroll
-        for (int pt = 0; pt < 2; ++pt) {
-            const int cb = n0 + wn * 128 + pt * 64;
-            if (cb >= p.N) continue;
-            epilogue_patch<EPI>(p, row, pos, cb, lhi, acc[mi][2 * pt], acc[mi][2 * pt + 1]);
+            for (int pt = 0; pt < 2; ++pt) {
+                const int cb = col_base + pt * 64;
+                if (cb >= p.N) continue;
+                epilogue_patch<EPI>(p, row, pos, cb, ehi, acc[mi][2 * pt], acc[mi][2 * pt + 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else if (EPI == EPI_RESIDUAL) {
+        // 32 rows x 64 features at a time as fp32 (256-byte rows, 16 groups), then 8 consecutive features
+        // per elane: + residual (read 16 bytes per elane; it may alias the destination), convert, store
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+#pragma unroll
+                for (int n2 = 0; n2 < 2; ++n2)
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        const f32x16& cc = acc[mi][2 * hf + n2];
+                        float4 v = {cc[4 * g4], cc[4 * g4 + 1], cc[4 * g4 + 2], cc[4 * g4 + 3]};
+                        const int grp = n2 * 8 + 2 * g4 + ehi;             // 4 features = one 16-byte group
+                        *(float4*)(stg + e31 * 256 + ((grp ^ (e31 & 15)) << 4)) = v;
+                    }
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                const int col = col_base + hf * 64 + (elane & 7) * 8;
+                uint4 rr[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int row = row_base + mi * 32 + i * 8 + (elane >> 3);
+                    rr[i] = make_uint4(0, 0, 0, 0);
+                    if (row < p.M && col < p.N) rr[i] = *(const uint4*)(p.R + (int64_t)row * p.ldr + col);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int rl = i * 8 + (elane >> 3);
+                    const int row = row_base + mi * 32 + rl;
+                    const int g0 = (elane & 7) * 2;
+                    const float4 x0 = *(const float4*)(stg + rl * 256 + ((g0 ^ (rl & 15)) << 4));
+                    const float4 x1 = *(const float4*)(stg + rl * 256 + (((g0 + 1) ^ (rl & 15)) << 4));
+                    uint4 o;
+                    o.x = (uint32_t)f2bf(x0.x + __uint_as_float(rr[i].x << 16)) | ((uint32_t)f2bf(x0.y + __uint_as_float(rr[i].x & 0xffff0000u)) << 16);
+                    o.y = (uint32_t)f2bf(x0.z + __uint_as_float(rr[i].y << 16)) | ((uint32_t)f2bf(x0.w + __uint_as_float(rr[i].y & 0xffff0000u)) << 16);
+                    o.z = (uint32_t)f2bf(x1.x + __uint_as_float(rr[i].z << 16)) | ((uint32_t)f2bf(x1.y + __uint_as_float(rr[i].z & 0xffff0000u)) << 16);
+                    o.w = (uint32_t)f2bf(x1.z + __uint_as_float(rr[i].w << 16)) | ((uint32_t)f2bf(x1.w + __uint_as_float(rr[i].w & 0xffff0000u)) << 16);
+                    if (row < p.M && col < p.N) *(uint4*)(p.dst + (int64_t)row * p.ld + col) = o;
+                }
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    } else if (EPI == EPI_STORE) {
+        // 32 rows x 128 features at a time as bf16 (256-byte rows, 16 groups)
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const f32x16& cc = acc[mi][ni];
+                    const int c = ni * 32 + 8 * g4 + 4 * ehi;
+                    float v[4] = {cc[4 * g4], cc[4 * g4 + 1], cc[4 * g4 + 2], cc[4 * g4 + 3]};
+                    if (p.bias && col_base + c < p.N) {
+                        const uint2 bw = *(const uint2*)(p.bias + col_base + c);
+                        v[0] += __uint_as_float(bw.x << 16); v[1] += __uint_as_float(bw.x & 0xffff0000u);
+                        v[2] += __uint_as_float(bw.y << 16); v[3] += __uint_as_float(bw.y & 0xffff0000u);
+                    }
+                    const int grp = ni * 4 + g4;                           // 8 features = one 16-byte group
+                    *(uint2*)(stg + e31 * 256 + ((grp ^ (e31 & 15)) << 4) + ehi * 8) = pack4(v[0], v[1], v[2], v[3]);
+                }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            const int col = col_base + (elane & 15) * 8;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int rl = i * 4 + (elane >> 4);
+                const int row = row_base + mi * 32 + rl;
+                const uint4 o = *(const uint4*)(stg + rl * 256 + (((elane & 15) ^ (rl & 15)) << 4));
+                if (row < p.M && col < p.N) *(uint4*)(p.dst + (int64_t)row * p.ld + col) = o;
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+        // SiLU-multiply: a 64-column patch (32 gate, 32 up) gives 32 features; 32 rows x 64 features at a
+        // time as bf16 (128-byte rows, 8 groups, two rows per 256 bytes of banks: swizzle with row / 2);
+        // a wavefront then stores 8 rows x 128 bytes per instruction
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const f32x16& c0 = acc[mi][2 * pt];
+                    const f32x16& c1 = acc[mi][2 * pt + 1];
+                    const int grp = pt * 4 + g4;
+                    *(uint2*)(stg + e31 * 128 + ((grp ^ ((e31 >> 1) & 7)) << 4) + ehi * 8) =
+                        pack4(silu_f(c0[4 * g4]) * c1[4 * g4], silu_f(c0[4 * g4 + 1]) * c1[4 * g4 + 1],
+                              silu_f(c0[4 * g4 + 2]) * c1[4 * g4 + 2], silu_f(c0[4 * g4 + 3]) * c1[4 * g4 + 3]);
+                }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            const int col = col_base / 2 + (elane & 7) * 8;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int rl = i * 8 + (elane >> 3);
+                const int row = row_base + mi * 32 + rl;
+                const uint4 o = *(const uint4*)(stg + rl * 128 + (((elane & 7) ^ ((rl >> 1) & 7)) << 4));
+                if (row < p.M && col < p.N / 2) *(uint4*)(p.dst + (int64_t)row * p.ld + col) = o;
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
