@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 # Memory traffic per launch in bytes, from two counter runs of this command at the default
 # workload (FETCH_SIZE x 2.0 and WRITE_SIZE x 1.0 KiB per dispatch, the factors a 1 GiB
 # elementwise kernel calibrates; summary under profiles/).  Other workloads report null.
-MEASURED_TRAFFIC = {"llama8b_32k": {"attention": 1.674e9, "gate_up": 1.528e9, "residual": 0.520e9, "qkv": 0.780e9}}
+MEASURED_TRAFFIC = {"llama8b_32k": {"attention": 1.628e9, "gate_up": 1.523e9, "residual": 0.519e9, "qkv": 0.814e9}}
 
 
 def flop_model(cfg, lens, lazy_last_layer=True):

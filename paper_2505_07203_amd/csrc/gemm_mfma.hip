@@ -3,28 +3,34 @@
 //   C[M, N] = A[M, K] * W[N, K]^T        A: activations (token-major), W: weights in the
 //                                        checkpoint layout [out, in]; both K-contiguous.
 //
-// Design (what bounds it: the matrix pipe, then LDS read bandwidth):
+// Design (what bounds it: the matrix pipe, and the board's power limit, which sets the clock: every byte
+// moved costs clock):
 //  * Block tile 256 x 256, 256 threads = 4 wavefronts (one per SIMD) arranged 2 x 2; each
 //    wavefront owns a 128 x 128 patch = 4 x 4 MFMA 32x32x16 tiles (256 fp32 accumulators per
 //    lane).  The large per-wavefront patch is what keeps LDS traffic down: 8 fragment reads
 //    feed 16 MFMAs per k-step (0.5 KiB of LDS reads per MFMA).
-//  * K is consumed in slices of 32.  Operand slices go straight from global memory into
-//    LDS (global_load_lds, 16 bytes per lane, no staging registers) through a ring of four
-//    32 KiB stages: the loads of slice k+4 are issued while slice k is multiplied, which
-//    covers HBM latency; one workgroup barrier per slice hands a stage over.
-//  * LDS layout: 64-byte rows (32 bf16), the four 16-byte segments of a row XOR-swizzled
-//    with (row >> 2) & 3, so that the MFMA fragment reads (16 lanes = 16 consecutive rows,
-//    same logical segment) touch 16 distinct 16-byte bank groups.  The DMA writes a
-//    wavefront's 64 x 16 bytes contiguously, so the swizzle is applied on the global side:
-//    lane l of a load fetches logical segment (l & 3) ^ swizzle(row).
+//  * K is consumed in slices of 64, so that a row of an operand slice is one whole 128-byte cache
+//    line: eight lanes of a load fetch one line.  (With 64-byte rows every line was requested twice,
+//    in two successive slices, and the L2 serves half lines at the cost of whole ones: 9-12 % slower.)
+//    Operand slices go straight from global memory into LDS (buffer_load ... lds, 16 bytes per lane,
+//    no staging registers).  One operand's slice is a 32 KiB unit; LDS (160 KiB) is a ring of five
+//    units filled in the order A0 W0 A1 W1 ...: two units are being multiplied while up to three are
+//    in flight, which covers HBM latency; one workgroup barrier per slice (64 MFMAs per wavefront)
+//    hands units over.
+//  * LDS layout: 128-byte rows (64 bf16), the eight 16-byte segments of a row XOR-swizzled with
+//    (row >> 1) & 7, so that the MFMA fragment reads (16 lanes = 16 consecutive rows, same logical
+//    segment; two rows share the 256 bytes the banks span) touch 16 distinct 16-byte bank groups.
+//    The DMA writes a wavefront's 64 x 16 bytes contiguously, so the swizzle is applied on the global
+//    side: lane l of a load fetches logical segment (l & 7) ^ swizzle(row).
 //  * Workgroups are dispatched round-robin over the 8 XCDs (each with a private L2), so the
 //    block id is first split into (XCD, local index) and every XCD walks a contiguous range
 //    of output tiles in groups of 4 M-tiles x consecutive N-tiles: the 32 tiles resident on
 //    one XCD share 4 activation panels and 8 weight panels through that XCD's L2.
 //  * The MFMA is issued as (W fragment) x (A fragment)^T: in an accumulator tile a lane
 //    holds ONE token row and four consecutive output features per register quad, so the
-//    epilogues (bias, residual add in fp32, SiLU-multiply of gate/up pairs, rotary embedding
-//    of Q/K pairs, transposed store of V) work on whole lanes and move 8 bytes at a time.
+//    epilogue arithmetic (bias, residual add in fp32, SiLU-multiply of gate/up pairs, rotary embedding
+//    of Q/K pairs) works on whole lanes; the position-wise results then pass through LDS so that
+//    they leave as whole cache lines (see the epilogue).
 //
 // A row's K reduction order is fixed by the kernel and independent of how M is tiled or
 // chunked, which is what makes the chunk-by-chunk evaluation of Section 4.2 bit-exact.
@@ -211,7 +217,6 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
         (void*)(p.A + (int64_t)m0 * p.lda), 0, (int)(uint32_t)(a_bytes > 0xffffffffull ? 0xffffffffull : a_bytes), 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(p.W + (int64_t)n0 * p.ldw), 0, (int)(uint32_t)(w_bytes > 0xffffffffull ? 0xffffffffull : w_bytes), 0x00020000);
-    // (the whole row term sits in the per-lane offset: the scalar offset is exempt from the range check)
     uint32_t voa[8], vow[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
