@@ -196,6 +196,37 @@ struct PhaseTimer {
     }
 };
 
+// Rows per launch of a chunk loop.  The MFMA GEMM works in 256 x 256 tiles, one per CU at a time, so a
+// launch costs ceil(tiles / 256) rounds of its K-loop: among the multiples of 256 rows up to max_rows this
+// picks the one with the least such cost per row, summed over the GEMMs of the loop (ties: the larger).
+// Results do not depend on the choice (row results are independent of the other rows of a launch); only
+// the buffers' capacity (max_rows) binds it.
+struct GemmCols {
+    int64_t n_cols, k;
+};
+int64_t pick_chunk_rows(int64_t max_rows, std::initializer_list<GemmCols> gemms) {
+    if (max_rows < 512) return max_rows;
+    int64_t best = max_rows;
+    double best_cost = -1;
+    for (int64_t m = max_rows / 256; m >= 1; --m) {
+        double cost = 0;
+        for (const GemmCols& g : gemms) {
+            const int64_t tiles = m * ((g.n_cols + 255) / 256);
+            cost += (double)((tiles + 255) / 256) * (double)g.k;
+        }
+        cost /= (double)m;
+        if (best_cost < 0 || cost < best_cost * (1 - 1e-9)) { best_cost = cost; best = m * 256; }
+    }
+    // (a capacity that is not a multiple of 256 is kept when no multiple below it does better per row)
+    if (max_rows % 256) {
+        double cost = 0;
+        const int64_t mt = (max_rows + 255) / 256;
+        for (const GemmCols& g : gemms) cost += (double)((mt * ((g.n_cols + 255) / 256) + 255) / 256) * (double)g.k;
+        if (cost / ((double)max_rows / 256.0) <= best_cost) best = max_rows;
+    }
+    return best;
+}
+
 // One request inside the token buffer of a run: rows [start, start + len) of X / Q / K / V^T.
 struct Seg {
     int64_t start, len;
@@ -232,7 +263,10 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
     const float* rc = (const float*)(ws + L.rope_cos);
     const float* rs = (const float*)(ws + L.rope_sin);
     float* d_logits = (float*)(ws + L.logits);
-    const int C = L.chunk;
+    // rows per launch of the position-wise loops: the chunk buffers' capacity, or less where that wastes
+    // fewer CU rounds (bf16 path; e.g. d = 5120 gives 20 column tiles: 12 row tiles fill 240 CUs in one
+    // round where 16 would take two)
+    const int C = dt == PO_BF16 ? (int)pick_chunk_rows(L.chunk, {{d, qd}, {2 * (int64_t)F, d}, {d, F}}) : L.chunk;
     const bool packed = segs.size() > 1;
     const int64_t n_seg = (int64_t)segs.size();
 
@@ -263,8 +297,11 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
         // Its only intermediate is the normalised chunk, so it borrows the (larger, idle) MLP
         // chunk buffer and runs on up to twice as many tokens per launch: with 256-token
         // tiles that fills whole rounds of the 256 CUs (e.g. 32 x 24 tiles = 3 rounds).
-        const int64_t Cq = ((int64_t)C * F >= 2 * (int64_t)C * d) ? 2 * (int64_t)C : C;
-        unsigned char* Xq = (Cq > C) ? H : Xn;
+        const int64_t cap_q = (int64_t)L.chunk * F / d;          // rows of d values the MLP chunk buffer holds
+        int64_t Cq = L.chunk;
+        if (dt == PO_BF16 && cap_q > L.chunk) Cq = pick_chunk_rows(cap_q, {{qd + 2 * (int64_t)kvd, d}});
+        else if (cap_q >= 2 * (int64_t)L.chunk) Cq = 2 * (int64_t)L.chunk;
+        unsigned char* Xq = (Cq > L.chunk) ? H : Xn;
         unsigned char* kc_l = c->kvc ? c->kvc + (size_t)l * c->kv_layer_bytes : nullptr;
         if (p_reuse > 0) {
             // cached prefix of this layer -> rows [0, p_reuse) of the one-layer K / V buffers
