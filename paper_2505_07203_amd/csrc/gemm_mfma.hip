@@ -366,7 +366,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
         }
     } else if (EPI == EPI_RESIDUAL) {
         // 32 rows x 64 features at a time as fp32 (256-byte rows, 16 groups), then 8 consecutive features
-        // per elane: + residual (read 16 bytes per elane; it may alias the destination), convert, store
+        // per lane: + residual (read 16 bytes per lane; it may alias the destination), convert, store
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
