@@ -129,22 +129,28 @@ def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray,
     return out
 
 
-def swiglu_mlp(m: np.ndarray, wg: np.ndarray, wu: np.ndarray, wd: np.ndarray, store=None) -> np.ndarray:
+def _matmul_t(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    return x @ w.T
+
+
+def swiglu_mlp(m: np.ndarray, wg: np.ndarray, wu: np.ndarray, wd: np.ndarray, store=None, linear=None) -> np.ndarray:
     """( silu(m Wg^T) * (m Wu^T) ) Wd^T with silu(z) = z / (1 + exp(-z)).
-    `store` (optional) is applied to the gated intermediate before the down projection."""
+    `store` (optional) is applied to the gated intermediate before the down projection;
+    `linear` (optional) replaces y = x W^T (see decoder_layer)."""
     st = store or _keep
-    gate = m @ wg.T
-    up = m @ wu.T
+    lin = linear or _matmul_t
+    gate = lin(m, wg)
+    up = lin(m, wu)
     h = st(gate / (1.0 + np.exp(-gate)) * up)
-    return h @ wd.T
+    return lin(h, wd)
 
 
-def _qkv(a, W, cfg, positions, st=_keep):
+def _qkv(a, W, cfg, positions, st=_keep, lin=_matmul_t):
     N = a.shape[0]
     hd = cfg.head_dim
-    q = a @ W["wq"].T
-    k = a @ W["wk"].T
-    v = a @ W["wv"].T
+    q = lin(a, W["wq"])
+    k = lin(a, W["wk"])
+    v = lin(a, W["wv"])
     if cfg.qkv_bias:
         q = q + W["bq"]
         k = k + W["bk"]
@@ -156,36 +162,39 @@ def _qkv(a, W, cfg, positions, st=_keep):
 
 
 def decoder_layer(x: np.ndarray, W: dict, cfg, mlp_chunk: int | None = None,
-                  last_row_only: bool = False, store=None) -> np.ndarray:
+                  last_row_only: bool = False, store=None, linear=None) -> np.ndarray:
     """One pre-norm decoder block on the residual stream x [N, d].
 
     last_row_only: K and V are formed for every position but the query, attention
     output, O-projection and MLP only for position N-1 (enough when no later layer
     reads the other rows); returns [1, d].
-    store: see the module header (None = nothing is rounded)."""
+    store: see the module header (None = nothing is rounded).
+    linear: optional function (x [M, K], W [N, K]) -> [M, N] used for the block's seven linear
+    layers in place of x W^T (the FP8-dynamic variant passes fp8_oracle.dynamic_linear)."""
     st = store or _keep
+    lin = linear or _matmul_t
     N = x.shape[0]
     pos = np.arange(N)
     a = st(rmsnorm(x, W["attn_norm"], cfg.rms_eps))
-    q, k, v = _qkv(a, W, cfg, pos, st)
+    q, k, v = _qkv(a, W, cfg, pos, st, lin)
     rows = np.array([N - 1]) if last_row_only else None
     o = st(causal_gqa_attention(q, k, v, rows))
     xr = x[N - 1:N] if last_row_only else x
-    xr = st(xr + o.reshape(o.shape[0], -1) @ W["wo"].T)
+    xr = st(xr + lin(o.reshape(o.shape[0], -1), W["wo"]))
     m = st(rmsnorm(xr, W["mlp_norm"], cfg.rms_eps))
     if mlp_chunk is None:
-        y = swiglu_mlp(m, W["wg"], W["wu"], W["wd"], store)
+        y = swiglu_mlp(m, W["wg"], W["wu"], W["wd"], store, linear)
     else:
         # Section 4.2/4.3: the position-wise part evaluated chunk by chunk over tokens,
         # each chunk written into its slice of a preallocated output.
         y = np.empty_like(xr)
         for s0 in range(0, xr.shape[0], mlp_chunk):
-            y[s0:s0 + mlp_chunk] = swiglu_mlp(m[s0:s0 + mlp_chunk], W["wg"], W["wu"], W["wd"], store)
+            y[s0:s0 + mlp_chunk] = swiglu_mlp(m[s0:s0 + mlp_chunk], W["wg"], W["wu"], W["wd"], store, linear)
     return st(xr + y)
 
 
 def forward_hidden(tokens: np.ndarray, embed: np.ndarray, layers, cfg,
-                   mlp_chunk: int | None = None, lazy_last_layer: bool = False, store=None) -> np.ndarray:
+                   mlp_chunk: int | None = None, lazy_last_layer: bool = False, store=None, linear=None) -> np.ndarray:
     """Residual stream after all layers.  `layers` is an iterable yielding one dict of
     float64 arrays per layer (so a large model can be streamed).  Returns [N, d], or
     [1, d] (the last position) when lazy_last_layer is set."""
@@ -194,7 +203,7 @@ def forward_hidden(tokens: np.ndarray, embed: np.ndarray, layers, cfg,
     L = cfg.n_layers
     for l, W in enumerate(layers):
         lazy = lazy_last_layer and (l == L - 1)
-        x = decoder_layer(x, W, cfg, mlp_chunk, last_row_only=lazy, store=store)
+        x = decoder_layer(x, W, cfg, mlp_chunk, last_row_only=lazy, store=store, linear=linear)
     return x
 
 
@@ -224,9 +233,10 @@ def full_vocab_logprobs(z: np.ndarray, ids: np.ndarray) -> np.ndarray:
 
 def prefill(tokens: np.ndarray, embed, layers, final_norm, lm_head, cfg,
             cand: np.ndarray | None = None, mlp_chunk: int | None = None,
-            lazy_last_layer: bool = False, store=None):
-    """Whole path: tokens -> (last-token logits [V], candidate log-probs or None)."""
-    x = forward_hidden(tokens, embed, layers, cfg, mlp_chunk, lazy_last_layer, store)
+            lazy_last_layer: bool = False, store=None, linear=None):
+    """Whole path: tokens -> (last-token logits [V], candidate log-probs or None).
+    `linear` replaces the decoder blocks' linear layers (never the LM head)."""
+    x = forward_hidden(tokens, embed, layers, cfg, mlp_chunk, lazy_last_layer, store, linear)
     z = last_token_logits(x[-1], final_norm, lm_head, cfg.rms_eps, store)
     lp = None if cand is None else candidate_logprobs(z, cand)
     return z, lp

@@ -503,8 +503,7 @@ GemmParams base_params(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ld
 
 }  // namespace
 
-// K must be a multiple of 64 (two 32-wide slices keep the 16-byte segments whole), N of 64
-// (the epilogues work on 64-column patches).
+// K must be a multiple of 64 (whole slices), N of 64 (the epilogues work on 64-column patches).
 bool gemm_mfma_supported(int N, int K) { return K > 0 && K % 64 == 0 && N > 0 && N % 64 == 0; }
 
 void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* C, int64_t ldc,
