@@ -304,6 +304,39 @@ po_status po_op_qkv_rope(const void* dev_a, const void* dev_wqkv, const void* de
                          int64_t M, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t K,
                          void* hip_stream);
 
+/* ---- FP8-dynamic variant of the decoder's linear layers (Section 7.1 names FP8-dynamic
+ * checkpoints; the scheme is the public convention: OCP E4M3 codes, one float32 scale per
+ * output channel of a weight and per token of an activation).  A bf16 row x with
+ * amax = max|x_k| becomes codes e4m3(x_k * (448 / amax)), round to nearest even, and the
+ * scale amax / 448 (amax == 0: codes 0, scale 1); single float32 operations throughout, so
+ * codes and scales are reproducible bit for bit. */
+
+/* codes [M, K] (one byte each) and scales [M] of the bf16 rows x [M, K].  K % 8 == 0,
+ * K <= 28672.  dev_codes may be dev_x itself (a row's codes then occupy the first half of
+ * the row). */
+po_status po_op_quantize_rows(const void* dev_x, void* dev_codes, float* dev_scales, int64_t M, int32_t K,
+                              void* hip_stream);
+
+/* The same of bf16(rmsnorm(x; g)), the normalised row formed exactly as po_op_rmsnorm
+ * forms it (d % 8 == 0, d <= 8192). */
+po_status po_op_rmsnorm_quantize(const void* dev_x, const void* dev_g, void* dev_codes, float* dev_scales,
+                                 int64_t rows, int32_t d, float eps, void* hip_stream);
+
+/* C = (Qa Qw^T) * sa[row] * sw[col], products accumulated in fp32, result bf16.
+ * epilogue 0: C [M, N]; 1: C = ... + residual [M, N] (added in fp32, may alias C);
+ * 2: Qw rows in the interleaved gate/up order of po_op_pack_gate_up (and dev_w_scales in the
+ * same order), C [M, N/2] = silu(gate) * up.  K % 128 == 0, N % 64 == 0. */
+po_status po_op_linear_fp8(int32_t epilogue, const void* dev_a_codes, const float* dev_a_scales,
+                           const void* dev_w_codes, const float* dev_w_scales, void* dev_c,
+                           const void* dev_residual, int64_t M, int32_t N, int32_t K, void* hip_stream);
+
+/* po_op_qkv_rope with FP8 operands: dev_w_codes / dev_w_scales hold the packed QKV weight rows
+ * (the order po_op_pack_qkv produces), dev_bqkv (bf16, packed order) may be NULL. */
+po_status po_op_qkv_rope_fp8(const void* dev_a_codes, const float* dev_a_scales, const void* dev_w_codes,
+                             const float* dev_w_scales, const void* dev_bqkv, void* dev_q, void* dev_k, void* dev_vt,
+                             int64_t ldv, const float* dev_cos, const float* dev_sin, int64_t pos0, int64_t M,
+                             int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t K, void* hip_stream);
+
 /* Last-position LM head: logits[V] = x[d] . W[V, d]^T  (fp32 output). */
 po_status po_op_lm_head(int32_t dtype, const void* dev_x, const void* dev_w, float* dev_logits,
                         int32_t V, int32_t d, void* hip_stream);

@@ -35,6 +35,7 @@ EXPORTS = [
     "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head", "po_op_rope_table",
     "po_op_pack_qkv", "po_op_qkv_rope", "po_max_input_len", "po_profile", "po_set_lazy_last_layer",
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
+    "po_op_quantize_rows", "po_op_rmsnorm_quantize", "po_op_linear_fp8", "po_op_qkv_rope_fp8",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick",
 ]
@@ -109,6 +110,10 @@ def lib() -> C.CDLL:
     L.po_op_rope_table.argtypes = [vp, vp, i64, i32, f32, vp]
     L.po_op_pack_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
     L.po_op_qkv_rope.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i32, i32, i32, i32, vp]
+    L.po_op_quantize_rows.argtypes = [vp, vp, vp, i64, i32, vp]
+    L.po_op_rmsnorm_quantize.argtypes = [vp, vp, vp, vp, i64, i32, f32, vp]
+    L.po_op_linear_fp8.argtypes = [i32, vp, vp, vp, vp, vp, vp, i64, i32, i32, vp]
+    L.po_op_qkv_rope_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i32, i32, i32, i32, vp]
     f64 = C.c_double
     L.po_sched_create.argtypes = [f64, C.POINTER(vp)]
     L.po_sched_destroy.argtypes = [vp]
@@ -315,6 +320,58 @@ def po_op_linear(a, w, residual=None, out=None):
     check(lib().po_op_linear(_dt(a), a.data_ptr(), w.data_ptr(), c.data_ptr(),
                              None if residual is None else residual.data_ptr(), M, N, K, _stream()))
     return c
+
+
+def po_op_quantize_rows(x, in_place=False):
+    """bf16 [M, K] -> (uint8 codes [M, K], float32 scales [M]); in_place: the codes overwrite x's memory
+    (returned as a uint8 view [M, 2K] whose first K columns are the codes)"""
+    import torch
+    M, K = x.shape
+    scales = torch.empty(M, dtype=torch.float32, device=x.device)
+    if in_place:
+        codes = x.view(torch.uint8)
+        check(lib().po_op_quantize_rows(x.data_ptr(), x.data_ptr(), scales.data_ptr(), M, K, _stream()))
+        # (the library writes each row's codes at the row's own start: pitch 2K bytes)
+        return codes, scales
+    codes = torch.empty((M, K), dtype=torch.uint8, device=x.device)
+    check(lib().po_op_quantize_rows(x.data_ptr(), codes.data_ptr(), scales.data_ptr(), M, K, _stream()))
+    return codes, scales
+
+
+def po_op_rmsnorm_quantize(x, g, eps):
+    import torch
+    M, d = x.shape
+    codes = torch.empty((M, d), dtype=torch.uint8, device=x.device)
+    scales = torch.empty(M, dtype=torch.float32, device=x.device)
+    check(lib().po_op_rmsnorm_quantize(x.data_ptr(), g.data_ptr(), codes.data_ptr(), scales.data_ptr(), M, d, eps,
+                                       _stream()))
+    return codes, scales
+
+
+def po_op_linear_fp8(a_codes, a_scales, w_codes, w_scales, residual=None, out=None, silu_mul=False):
+    import torch
+    M, K = a_codes.shape
+    N = w_codes.shape[0]
+    epi = 2 if silu_mul else (1 if residual is not None else 0)
+    c = out if out is not None else torch.empty((M, N // 2 if silu_mul else N), dtype=torch.bfloat16, device=a_codes.device)
+    check(lib().po_op_linear_fp8(epi, a_codes.data_ptr(), a_scales.data_ptr(), w_codes.data_ptr(), w_scales.data_ptr(),
+                                 c.data_ptr(), None if residual is None else residual.data_ptr(), M, N, K, _stream()))
+    return c
+
+
+def po_op_qkv_rope_fp8(a_codes, a_scales, w_codes, w_scales, bqkv, cos, sin, n_q_heads, n_kv_heads, head_dim, pos0=0):
+    import torch
+    M, K = a_codes.shape
+    qd, kvd = n_q_heads * head_dim, n_kv_heads * head_dim
+    ldv = (pos0 + M + 63) // 64 * 64
+    q = torch.empty((M, qd), dtype=torch.bfloat16, device=a_codes.device)
+    k = torch.empty((M, kvd), dtype=torch.bfloat16, device=a_codes.device)
+    vt = torch.zeros((kvd, ldv), dtype=torch.bfloat16, device=a_codes.device)
+    check(lib().po_op_qkv_rope_fp8(a_codes.data_ptr(), a_scales.data_ptr(), w_codes.data_ptr(), w_scales.data_ptr(),
+                                   None if bqkv is None else bqkv.data_ptr(), q.data_ptr(), k.data_ptr(), vt.data_ptr(),
+                                   ldv, cos.data_ptr(), sin.data_ptr(), pos0, M, n_q_heads, n_kv_heads, head_dim, K,
+                                   _stream()))
+    return q, k, vt
 
 
 def po_op_pack_gate_up(wg, wu):

@@ -34,146 +34,22 @@
 //
 // A row's K reduction order is fixed by the kernel and independent of how M is tiled or
 // chunked, which is what makes the chunk-by-chunk evaluation of Section 4.2 bit-exact.
-#include "po_internal.h"
+#include "gemm_common.h"
 
 #include <string.h>
 
 namespace po {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int NTHREADS = 256;
+using namespace gemm;
+
+constexpr int BK = 64;
 constexpr int UNIT_BYTES = BM * BK * 2;            // one operand's slice: 256 rows x 128 bytes = 32 KiB
 constexpr int NUNIT = 5;                           // ring of five units: the whole 160 KiB of LDS
 constexpr int SMEM_BYTES = NUNIT * UNIT_BYTES;
-constexpr int GROUP_M = 4;
-
-struct GemmParams {
-    const bf16_t* A;
-    const bf16_t* W;
-    const bf16_t* bias;
-    const bf16_t* R;
-    bf16_t* dst;         // EPI_STORE / EPI_RESIDUAL / EPI_SILU_MUL destination; EPI_QKV_ROPE: Q
-    bf16_t* dst_k;       // EPI_QKV_ROPE: K [*, kvd]
-    bf16_t* dst_vt;      // EPI_QKV_ROPE: V^T [kvd][ldv]
-    const float* rope_cos;   // [positions, hd/2]
-    const float* rope_sin;
-    int64_t ld, ldv;
-    int64_t lda, ldw, ldr;
-    int64_t pos0;        // EPI_QKV_ROPE: buffer row (= V^T column) of GEMM row 0, and its sequence position
-    const int32_t* row_pos;  // EPI_QKV_ROPE: sequence position of every buffer row when several requests are
-                             // packed into one buffer (indexed by buffer row); null = position == buffer row
-    int M, N, K;
-    int mt, nt;          // tile counts
-    int qd, kvd, hd;     // EPI_QKV_ROPE: segment widths and head size
-};
-
-__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
-
-__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
-    uint2 w;
-    w.x = (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
-    w.y = (uint32_t)f2bf(c) | ((uint32_t)f2bf(d) << 16);
-    return w;
-}
-
-// Epilogue of one 64-column patch of one token row.  c0 / c1 are the accumulator tiles of
-// the patch's two 32-column sub-tiles; the lane holds features 8*(r/4) + 4*lhi + (r%4) of
-// each.  cb = first GEMM column of the patch (a multiple of 64).
-template <int EPI>
-__device__ __forceinline__ void epilogue_patch(const GemmParams& p, int row, int64_t pos, int cb, int lhi,
-                                               const f32x16& c0, const f32x16& c1) {
-    if (EPI == EPI_SILU_MUL) {
-        // sub-tile 0 = gate, sub-tile 1 = up of the same 32 features (weight rows interleaved)
-        bf16_t* drow = p.dst + (int64_t)row * p.ld + cb / 2 + 4 * lhi;
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4)
-            *(uint2*)(drow + 8 * g4) =
-                pack4(silu_f(c0[4 * g4]) * c1[4 * g4], silu_f(c0[4 * g4 + 1]) * c1[4 * g4 + 1],
-                      silu_f(c0[4 * g4 + 2]) * c1[4 * g4 + 2], silu_f(c0[4 * g4 + 3]) * c1[4 * g4 + 3]);
-    } else if (EPI == EPI_QKV_ROPE) {
-        const int half = p.hd >> 1;
-        if (cb < p.qd + p.kvd) {
-            // Q or K patch: sub-tile 0 holds rotary index i, sub-tile 1 holds i + hd/2 (the
-            // weight rows were packed that way), so a pair sits in one lane, same register.
-            const bool is_q = cb < p.qd;
-            const int c = is_q ? cb : cb - p.qd;
-            const int head = c / p.hd;
-            const int patch = (c - head * p.hd) >> 6;
-            const int i0 = patch * 32 + 4 * lhi;             // rotary index of register quad 0
-            bf16_t* drow = (is_q ? p.dst + (int64_t)row * p.qd : p.dst_k + (int64_t)row * p.kvd) + head * p.hd + i0;
-            const float* ct = p.rope_cos + pos * half + i0;
-            const float* st = p.rope_sin + pos * half + i0;
-            const bf16_t* bp = p.bias ? p.bias + cb + 4 * lhi : nullptr;
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const float4 cs = *(const float4*)(ct + 8 * g4);
-                const float4 sn = *(const float4*)(st + 8 * g4);
-                const float cv[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
-                float lo[4], hi[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float a = c0[4 * g4 + e], b = c1[4 * g4 + e];
-                    if (bp) { a += bf2f(bp[8 * g4 + e]); b += bf2f(bp[32 + 8 * g4 + e]); }
-                    lo[e] = a * cv[e] - b * sv[e];
-                    hi[e] = b * cv[e] + a * sv[e];
-                }
-                *(uint2*)(drow + 8 * g4) = pack4(lo[0], lo[1], lo[2], lo[3]);
-                *(uint2*)(drow + half + 8 * g4) = pack4(hi[0], hi[1], hi[2], hi[3]);
-            }
-        } else {
-            // V patch: stored transposed, V^T[feature][position]; consecutive lanes are
-            // consecutive positions.
-            const int f0 = cb - p.qd - p.kvd + 4 * lhi;
-            bf16_t* dcol = p.dst_vt + p.pos0 + row;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int f = f0 + 8 * (r >> 2) + (r & 3);
-                float v0 = c0[r], v1 = c1[r];
-                if (p.bias) { v0 += bf2f(p.bias[p.qd + p.kvd + f]); v1 += bf2f(p.bias[p.qd + p.kvd + f + 32]); }
-                dcol[(int64_t)f * p.ldv] = f2bf(v0);
-                dcol[(int64_t)(f + 32) * p.ldv] = f2bf(v1);
-            }
-        }
-    } else {
-        // (N is a multiple of 64, so a patch is either wholly inside or wholly outside)
-        // The residual may alias the destination (in-place update of the residual stream):
-        // all eight 8-byte pieces of this lane are read before the first one is written,
-        // so the loads are issued back to back instead of one per store.
-        uint2 rw[2][4];
-        if (EPI == EPI_RESIDUAL) {
-            const bf16_t* rrow = p.R + (int64_t)row * p.ldr + cb + 4 * lhi;
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) rw[ni][g4] = *(const uint2*)(rrow + ni * 32 + 8 * g4);
-        }
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            const f32x16& cc = ni ? c1 : c0;
-            const int col = cb + ni * 32 + 4 * lhi;
-            bf16_t* drow = p.dst + (int64_t)row * p.ld + col;
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                float v[4] = {cc[4 * g4], cc[4 * g4 + 1], cc[4 * g4 + 2], cc[4 * g4 + 3]};
-                if (EPI == EPI_STORE && p.bias) {
-                    const uint2 bw = *(const uint2*)(p.bias + col + 8 * g4);
-                    v[0] += __uint_as_float(bw.x << 16); v[1] += __uint_as_float(bw.x & 0xffff0000u);
-                    v[2] += __uint_as_float(bw.y << 16); v[3] += __uint_as_float(bw.y & 0xffff0000u);
-                }
-                if (EPI == EPI_RESIDUAL) {
-                    v[0] += __uint_as_float(rw[ni][g4].x << 16); v[1] += __uint_as_float(rw[ni][g4].x & 0xffff0000u);
-                    v[2] += __uint_as_float(rw[ni][g4].y << 16); v[3] += __uint_as_float(rw[ni][g4].y & 0xffff0000u);
-                }
-                *(uint2*)(drow + 8 * g4) = pack4(v[0], v[1], v[2], v[3]);
-            }
-        }
-    }
-}
 
 // Stage hand-over: wait until this wavefront's global->LDS loads of the NEXT slice have landed (all
 // but the 8 youngest, the activation unit after it, may stay in flight) and its own LDS reads have
@@ -338,144 +214,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     // the clamped tail loads have landed and every wavefront has finished reading the ring
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-    // ---- epilogue.  In an accumulator tile a lane holds one token row and runs of four consecutive
-    // features, so storing from there puts 8 bytes per lane into 32 different rows: partial cache lines,
-    // which the memory side handles several times slower than whole ones.  The position-wise epilogues
-    // therefore pass their results through LDS (the ring is free now; every wavefront uses 8 KiB of its
-    // own, so no further workgroup barrier is needed) one 32-row tile row at a time and store 16 bytes per
-    // lane, a wavefront covering whole row segments.  16-byte groups of a staged row are XOR-swizzled with
-    // the row number so that both the writes (lane = row) and the reads (lanes along a row) are free of
-    // bank conflicts.  The arithmetic (fp32 bias / residual add / SiLU-multiply, one round-to-nearest-even
-    // conversion) is the per-lane one.  QKV keeps the per-lane path (rotary pairs, V^T).
-    const int e31 = l31, ehi = lhi, elane = lane;
-    unsigned char* stg = smem + wave * 8192;
-    const int row_base = m0 + wm * 128, col_base = n0 + wn * 128;
-    if (EPI == EPI_QKV_ROPE) {
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-            const int row = row_base + mi * 32 + e31;
-            if (row >= p.M) continue;
-            const int64_t pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt) {
-                const int cb = col_base + pt * 64;
-                if (cb >= p.N) continue;
-                epilogue_patch<EPI>(p, row, pos, cb, ehi, acc[mi][2 * pt], acc[mi][2 * pt + 1]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    } else if (EPI == EPI_RESIDUAL) {
-        // 32 rows x 64 features at a time as fp32 (256-byte rows, 16 groups), then 8 consecutive features
-        // per lane: + residual (read 16 bytes per lane; it may alias the destination), convert, store
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-#pragma unroll
-                for (int n2 = 0; n2 < 2; ++n2)
-#pragma unroll
-                    for (int g4 = 0; g4 < 4; ++g4) {
-                        const f32x16& cc = acc[mi][2 * hf + n2];
-                        float4 v = {cc[4 * g4], cc[4 * g4 + 1], cc[4 * g4 + 2], cc[4 * g4 + 3]};
-                        const int grp = n2 * 8 + 2 * g4 + ehi;             // 4 features = one 16-byte group
-                        *(float4*)(stg + e31 * 256 + ((grp ^ (e31 & 15)) << 4)) = v;
-                    }
-                asm volatile("" ::: "memory");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-                const int col = col_base + hf * 64 + (elane & 7) * 8;
-                uint4 rr[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int row = row_base + mi * 32 + i * 8 + (elane >> 3);
-                    rr[i] = make_uint4(0, 0, 0, 0);
-                    if (row < p.M && col < p.N) rr[i] = *(const uint4*)(p.R + (int64_t)row * p.ldr + col);
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int rl = i * 8 + (elane >> 3);
-                    const int row = row_base + mi * 32 + rl;
-                    const int g0 = (elane & 7) * 2;
-                    const float4 x0 = *(const float4*)(stg + rl * 256 + ((g0 ^ (rl & 15)) << 4));
-                    const float4 x1 = *(const float4*)(stg + rl * 256 + (((g0 + 1) ^ (rl & 15)) << 4));
-                    uint4 o;
-                    o.x = (uint32_t)f2bf(x0.x + __uint_as_float(rr[i].x << 16)) | ((uint32_t)f2bf(x0.y + __uint_as_float(rr[i].x & 0xffff0000u)) << 16);
-                    o.y = (uint32_t)f2bf(x0.z + __uint_as_float(rr[i].y << 16)) | ((uint32_t)f2bf(x0.w + __uint_as_float(rr[i].y & 0xffff0000u)) << 16);
-                    o.z = (uint32_t)f2bf(x1.x + __uint_as_float(rr[i].z << 16)) | ((uint32_t)f2bf(x1.y + __uint_as_float(rr[i].z & 0xffff0000u)) << 16);
-                    o.w = (uint32_t)f2bf(x1.z + __uint_as_float(rr[i].w << 16)) | ((uint32_t)f2bf(x1.w + __uint_as_float(rr[i].w & 0xffff0000u)) << 16);
-                    if (row < p.M && col < p.N) *(uint4*)(p.dst + (int64_t)row * p.ld + col) = o;
-                }
-                asm volatile("" ::: "memory");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-            }
-    } else if (EPI == EPI_STORE) {
-        // 32 rows x 128 features at a time as bf16 (256-byte rows, 16 groups)
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const f32x16& cc = acc[mi][ni];
-                    const int c = ni * 32 + 8 * g4 + 4 * ehi;
-                    float v[4] = {cc[4 * g4], cc[4 * g4 + 1], cc[4 * g4 + 2], cc[4 * g4 + 3]};
-                    if (p.bias && col_base + c < p.N) {
-                        const uint2 bw = *(const uint2*)(p.bias + col_base + c);
-                        v[0] += __uint_as_float(bw.x << 16); v[1] += __uint_as_float(bw.x & 0xffff0000u);
-                        v[2] += __uint_as_float(bw.y << 16); v[3] += __uint_as_float(bw.y & 0xffff0000u);
-                    }
-                    const int grp = ni * 4 + g4;                           // 8 features = one 16-byte group
-                    *(uint2*)(stg + e31 * 256 + ((grp ^ (e31 & 15)) << 4) + ehi * 8) = pack4(v[0], v[1], v[2], v[3]);
-                }
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            const int col = col_base + (elane & 15) * 8;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int rl = i * 4 + (elane >> 4);
-                const int row = row_base + mi * 32 + rl;
-                const uint4 o = *(const uint4*)(stg + rl * 256 + (((elane & 15) ^ (rl & 15)) << 4));
-                if (row < p.M && col < p.N) *(uint4*)(p.dst + (int64_t)row * p.ld + col) = o;
-            }
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    } else {
-        // SiLU-multiply: a 64-column patch (32 gate, 32 up) gives 32 features; 32 rows x 64 features at a
-        // time as bf16 (128-byte rows, 8 groups, two rows per 256 bytes of banks: swizzle with row / 2);
-        // a wavefront then stores 8 rows x 128 bytes per instruction
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const f32x16& c0 = acc[mi][2 * pt];
-                    const f32x16& c1 = acc[mi][2 * pt + 1];
-                    const int grp = pt * 4 + g4;
-                    *(uint2*)(stg + e31 * 128 + ((grp ^ ((e31 >> 1) & 7)) << 4) + ehi * 8) =
-                        pack4(silu_f(c0[4 * g4]) * c1[4 * g4], silu_f(c0[4 * g4 + 1]) * c1[4 * g4 + 1],
-                              silu_f(c0[4 * g4 + 2]) * c1[4 * g4 + 2], silu_f(c0[4 * g4 + 3]) * c1[4 * g4 + 3]);
-                }
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            const int col = col_base / 2 + (elane & 7) * 8;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int rl = i * 8 + (elane >> 3);
-                const int row = row_base + mi * 32 + rl;
-                const uint4 o = *(const uint4*)(stg + rl * 128 + (((elane & 7) ^ ((rl >> 1) & 7)) << 4));
-                if (row < p.M && col < p.N / 2) *(uint4*)(p.dst + (int64_t)row * p.ld + col) = o;
-            }
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
+    tile_epilogue<EPI>(p, acc, smem, m0, n0, wave, lane);
 }
 
 template <int EPI>

@@ -985,6 +985,55 @@ po_status po_op_qkv_rope(const void* a, const void* wqkv, const void* bqkv, void
     return PO_OK;
 }
 
+po_status po_op_quantize_rows(const void* x, void* codes, float* scales, int64_t M, int32_t K, void* stream) {
+    if (!x || !codes || !scales || M <= 0 || K <= 0) return PO_ERR_INVALID_ARG;
+    if (!quant_rows_supported(K)) return PO_ERR_BAD_CONFIG;
+    // in place: a row's codes start where the row starts (pitch 2K bytes); otherwise dense rows of K bytes
+    launch_quant_rows((const bf16_t*)x, K, (unsigned char*)codes, codes == x ? 2 * (int64_t)K : K, scales, M, K, 0, 0, 0,
+                      (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_rmsnorm_quantize(const void* x, const void* g, void* codes, float* scales, int64_t rows, int32_t d,
+                                 float eps, void* stream) {
+    if (!x || !g || !codes || !scales || rows <= 0 || d <= 0) return PO_ERR_INVALID_ARG;
+    if (d % 8 || d > 8192) return PO_ERR_BAD_CONFIG;
+    launch_rmsnorm_quant((const bf16_t*)x, (const bf16_t*)g, (unsigned char*)codes, scales, rows, d, eps, (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_linear_fp8(int32_t epilogue, const void* a_codes, const float* a_scales, const void* w_codes,
+                           const float* w_scales, void* cc, const void* residual, int64_t M, int32_t N, int32_t K,
+                           void* stream) {
+    if (!a_codes || !a_scales || !w_codes || !w_scales || !cc || M <= 0 || N <= 0 || K <= 0) return PO_ERR_INVALID_ARG;
+    if (epilogue != EPI_STORE && epilogue != EPI_RESIDUAL && epilogue != EPI_SILU_MUL) return PO_ERR_INVALID_ARG;
+    if (epilogue == EPI_RESIDUAL && !residual) return PO_ERR_INVALID_ARG;
+    if (!gemm_fp8_supported(N, K) || (epilogue == EPI_SILU_MUL && N % (2 * GU_INTERLEAVE_BF16))) return PO_ERR_BAD_CONFIG;
+    const int64_t ldc = epilogue == EPI_SILU_MUL ? N / 2 : N;
+    launch_gemm_fp8(epilogue, (const unsigned char*)a_codes, K, a_scales, (const unsigned char*)w_codes, K, w_scales,
+                    (bf16_t*)cc, ldc, nullptr, (const bf16_t*)residual, N, M, N, K, (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_qkv_rope_fp8(const void* a_codes, const float* a_scales, const void* w_codes, const float* w_scales,
+                             const void* bqkv, void* q, void* k, void* vt, int64_t ldv, const float* cos_t,
+                             const float* sin_t, int64_t pos0, int64_t M, int32_t Hq, int32_t Hkv, int32_t hd, int32_t K,
+                             void* stream) {
+    if (!a_codes || !a_scales || !w_codes || !w_scales || !q || !k || !vt || !cos_t || !sin_t || M <= 0 || pos0 < 0 ||
+        Hq <= 0 || Hkv <= 0 || K <= 0)
+        return PO_ERR_INVALID_ARG;
+    if ((hd != 64 && hd != 128) || !gemm_fp8_supported((Hq + 2 * Hkv) * hd, K)) return PO_ERR_BAD_CONFIG;
+    if (ldv < pos0 + M || ldv % 8) return PO_ERR_INVALID_ARG;
+    launch_gemm_fp8_qkv_rope((const unsigned char*)a_codes, K, a_scales, (const unsigned char*)w_codes, K, w_scales,
+                             (const bf16_t*)bqkv, (bf16_t*)q, (bf16_t*)k, (bf16_t*)vt, ldv, cos_t, sin_t, pos0, nullptr, M,
+                             Hq * hd, Hkv * hd, hd, K, (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
 po_status po_op_lm_head(int32_t dtype, const void* x, const void* w, float* logits, int32_t V, int32_t d,
                         void* stream) {
     if (bad_dtype(dtype) || !x || !w || !logits || V <= 0 || d <= 0 || d % 8) return PO_ERR_INVALID_ARG;

@@ -81,6 +81,26 @@ void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int6
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
                            int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, hipStream_t s);
 bool gemm_mfma_supported(int N, int K);
+
+// ---- FP8-dynamic linear layers (OCP E4M3 codes + float32 scales) -----------------------------------
+// rows of bf16 -> codes + one scale per row; source row r goes to destination row
+// (r / blk) * dst_blk_stride + r % blk + dst_off (blk <= 0: rows stay in order); q may be x itself
+bool quant_rows_supported(int K);
+void launch_quant_rows(const bf16_t* x, int64_t ldx, unsigned char* q, int64_t ldq, float* scales, int64_t rows, int K,
+                       int blk, int64_t dst_blk_stride, int64_t dst_off, hipStream_t s);
+// C = (Qa Qw^T) * sa[row] * sw[col] with the epilogues of launch_gemm_mfma / launch_gemm_qkv_rope; codes one byte
+// each, lda / ldw in bytes (K % 128 == 0)
+bool gemm_fp8_supported(int N, int K);
+void launch_gemm_fp8(int epi, const unsigned char* A, int64_t lda, const float* sa, const unsigned char* W, int64_t ldw,
+                     const float* sw, bf16_t* C, int64_t ldc, const bf16_t* bias, const bf16_t* R, int64_t ldr, int64_t M,
+                     int N, int K, hipStream_t s);
+void launch_gemm_fp8_qkv_rope(const unsigned char* A, int64_t lda, const float* sa, const unsigned char* Wqkv, int64_t ldw,
+                              const float* sw, const bf16_t* bias, bf16_t* Q, bf16_t* K, bf16_t* Vt, int64_t ldv,
+                              const float* rope_cos, const float* rope_sin, int64_t pos0, const int32_t* row_pos,
+                              int64_t M, int qd, int kvd, int hd, int Kdim, hipStream_t s);
+// q, scales = quantise(bf16(rmsnorm(x; g)))   (d % 8 == 0, d <= 8192)
+void launch_rmsnorm_quant(const bf16_t* x, const bf16_t* g, unsigned char* q, float* scales, int64_t rows, int d,
+                          float eps, hipStream_t s);
 bool attention_mfma_supported(int Hq, int Hkv, int hd);
 
 }  // namespace po

@@ -1,0 +1,139 @@
+"""FP8-dynamic variant of the decoder's linear layers: libpo against oracle/fp8_oracle.py.
+
+Codes and scales are integer / single-rounding results: compared bit for bit.  The FP8 GEMM sums
+products of 4-bit-significand codes in fp32 on the matrix cores: compared with the oracle's exact sum
+of the same codes within a tolerance stated in the test.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_07203_amd import binding as B
+from paper_2505_07203_amd import inputs as I
+from oracle import fp8_oracle as F
+from oracle import prefill_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+
+
+def bf16_dev(x32: np.ndarray):
+    bits = I.f32_to_bf16_bits(x32)
+    t = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return t, I.stored_to_f64(bits)
+
+
+def host64(t) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("M,K", [(1, 8), (3, 256), (70, 4096), (33, 14336), (5, 28672), (17, 5120)])
+def test_quantize_rows_is_bit_exact(M, K):
+    rng = np.random.default_rng(M * 100003 + K)
+    x = rng.standard_normal((M, K), dtype=np.float32) * np.exp2(rng.integers(-8, 8, (M, 1))).astype(np.float32)
+    if M > 2:
+        x[1] = 0.0                                          # an all-zero row
+        x[2, : K // 2] = 0.0
+    xd, x64 = bf16_dev(x)
+    q_ref, s_ref = F.quantize_rows(x64)
+    q, s = B.po_op_quantize_rows(xd)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+    # in place: the codes of a row land on the first half of the row
+    q2, s2 = B.po_op_quantize_rows(xd.clone(), in_place=True)
+    assert np.array_equal(q2.cpu().numpy()[:, :K], q_ref) and np.array_equal(s2.cpu().numpy(), s_ref)
+
+
+@pytest.mark.parametrize("M,d", [(5, 256), (300, 4096), (9, 5120), (2, 8192)])
+def test_rmsnorm_quantize_equals_rmsnorm_then_quantize(M, d):
+    rng = np.random.default_rng(d + M)
+    xd, _ = bf16_dev(rng.standard_normal((M, d), dtype=np.float32) * 3.0)
+    gd, _ = bf16_dev(1.0 + 0.02 * rng.standard_normal(d, dtype=np.float32))
+    y = B.po_op_rmsnorm(xd, gd, 1e-5)
+    q_ref, s_ref = F.quantize_rows(host64(y))               # the oracle's quantiser on the library's bf16 row
+    q, s = B.po_op_rmsnorm_quantize(xd, gd, 1e-5)
+    assert np.array_equal(q.cpu().numpy(), q_ref) and np.array_equal(s.cpu().numpy(), s_ref)
+
+
+def _quantised(rng, M, K, scale=1.0):
+    xd, x64 = bf16_dev(rng.standard_normal((M, K), dtype=np.float32) * scale)
+    q, s = B.po_op_quantize_rows(xd)
+    return q, s, F.e4m3_decode(q.cpu().numpy()), s.cpu().numpy().astype(np.float64), x64
+
+
+def _gemm_tol(aq, wq, sa, sw):
+    """fp32 accumulation of K exact products (each <= 448^2) in an order the hardware chooses, two scale
+    multiplications and the bf16 rounding of the result: 2^-8 of the result plus K * 2^-22 of the term sum."""
+    return (2.0 ** -8) * np.abs((aq @ wq.T) * sa[:, None] * sw[None, :]) + \
+        (aq.shape[1] * 2.0 ** -22) * (np.abs(aq) @ np.abs(wq).T) * sa[:, None] * sw[None, :] + 1e-30
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 320, 256), (1000, 4096 + 64, 512), (1, 64, 128), (257, 1024, 4096)])
+def test_linear_fp8(M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    qa, sa_d, aq, sa, a64 = _quantised(rng, M, K)
+    qw, sw_d, wq, sw, w64 = _quantised(rng, N, K, 0.02)
+    ref = (aq @ wq.T) * sa[:, None] * sw[None, :]
+    got = host64(B.po_op_linear_fp8(qa, sa_d, qw, sw_d))
+    assert np.all(np.abs(got - ref) <= _gemm_tol(aq, wq, sa, sw))
+    # the oracle's quantised linear layer on the bf16 inputs is the same thing
+    assert np.array_equal(F.dynamic_linear(a64, w64), ref)
+    # residual added in fp32, in place
+    rd, r64 = bf16_dev(rng.standard_normal((M, N), dtype=np.float32))
+    B.po_op_linear_fp8(qa, sa_d, qw, sw_d, residual=rd, out=rd)
+    assert np.all(np.abs(host64(rd) - (ref + r64)) <= _gemm_tol(aq, wq, sa, sw) + 2.0 ** -8 * np.abs(ref + r64))
+    # against the unquantised product: the format's 2^-4 per operand
+    exact = a64 @ w64.T
+    assert np.max(np.abs(got - exact)) / np.max(np.abs(exact)) < 0.08
+
+
+def test_gate_up_silu_fp8():
+    M, Fd, K = 513, 1024 + 32, 256
+    rng = np.random.default_rng(77)
+    qa, sa_d, aq, sa, _ = _quantised(rng, M, K)
+    qg, sg_d, gq, sg, _ = _quantised(rng, Fd, K, 0.05)
+    qu, su_d, uq, su, _ = _quantised(rng, Fd, K, 0.05)
+    # interleave gate and up rows (codes and scales alike) in blocks of 32, as po_op_pack_gate_up orders them
+    def pack(g, u):
+        return torch.stack((g.view(Fd // 32, 32, *g.shape[1:]), u.view(Fd // 32, 32, *u.shape[1:])), dim=1).reshape(2 * Fd, *g.shape[1:]).contiguous()
+    got = host64(B.po_op_linear_fp8(qa, sa_d, pack(qg, qu), pack(sg_d, su_d), silu_mul=True))
+    gate = (aq @ gq.T) * sa[:, None] * sg[None, :]
+    up = (aq @ uq.T) * sa[:, None] * su[None, :]
+    ref = gate / (1 + np.exp(-gate)) * up
+    assert np.max(np.abs(got - ref)) <= 2.0 ** -7 * np.max(np.abs(ref))
+
+
+@pytest.mark.parametrize("Hq,Hkv,hd,K,M,pos0,bias", [(4, 2, 128, 256, 300, 0, 0), (8, 2, 64, 128, 257, 64, 1)])
+def test_qkv_rope_fp8(Hq, Hkv, hd, K, M, pos0, bias):
+    theta = 10000.0
+    rng = np.random.default_rng(Hq * 7 + M)
+    qa, sa_d, aq, sa, _ = _quantised(rng, M, K)
+    wq_d, wq64 = bf16_dev(rng.standard_normal((Hq * hd, K), dtype=np.float32) * 0.05)
+    wk_d, wk64 = bf16_dev(rng.standard_normal((Hkv * hd, K), dtype=np.float32) * 0.05)
+    wv_d, wv64 = bf16_dev(rng.standard_normal((Hkv * hd, K), dtype=np.float32) * 0.05)
+    bq = bk = bv = None
+    b64 = [0.0, 0.0, 0.0]
+    if bias:
+        (bq, b64[0]), (bk, b64[1]), (bv, b64[2]) = (bf16_dev(rng.standard_normal(n, dtype=np.float32)) for n in (Hq * hd, Hkv * hd, Hkv * hd))
+    # the library's row order for the packed QKV weight, applied to the bf16 rows, then quantised row by row
+    wqkv, bqkv = B.po_op_pack_qkv(wq_d, wk_d, wv_d, Hq, Hkv, hd, bq, bk, bv)
+    qw, sw_d = B.po_op_quantize_rows(wqkv)
+    cos, sin = B.po_op_rope_table(pos0 + M, hd, theta)
+    q, k, vt = B.po_op_qkv_rope_fp8(qa, sa_d, qw, sw_d, bqkv, cos, sin, Hq, Hkv, hd, pos0=pos0)
+    pos = pos0 + np.arange(M)
+    x64 = aq * sa[:, None]                                   # the stored activation values
+    def lin(w64):                                            # per-output-channel quantisation of the unpacked rows
+        qq, ss = F.quantize_rows(w64)
+        return (aq @ F.e4m3_decode(qq).T) * sa[:, None] * ss.astype(np.float64)[None, :]
+    ref_q = O.rope((lin(wq64) + b64[0]).reshape(M, Hq, hd), pos, theta)
+    ref_k = O.rope((lin(wk64) + b64[1]).reshape(M, Hkv, hd), pos, theta)
+    ref_v = lin(wv64) + b64[2]
+    for name, g, r in (("q", host64(q).reshape(M, Hq, hd), ref_q), ("k", host64(k).reshape(M, Hkv, hd), ref_k),
+                       ("v", host64(vt)[:, pos0:pos0 + M].T, ref_v)):
+        e = np.max(np.abs(g - r)) / np.max(np.abs(r))
+        assert e <= 6e-3, (name, e)
