@@ -24,6 +24,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 import numpy as np
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
+PEAK_FP8_TFLOPS = 5033.2       # dense fp8 MFMA: twice the bf16 rate
 PEAK_HBM_GBS = 8000.0
 
 # Memory traffic per launch in bytes, from two counter runs of this command at the default
@@ -104,6 +105,9 @@ def main():
     ap.add_argument("--reuse-prefix", type=int, default=0,
                     help="also time the first request again with the K/V of its first P tokens in the prefix "
                          "cache (reported under prefix_reuse; not part of value)")
+    ap.add_argument("--fp8", action="store_true",
+                    help="variant: the decoder's linear layers run FP8-dynamic (E4M3 weights per output channel, "
+                         "activations per token); reported under its own metric name and dtype, never as the bf16 metric")
     ap.add_argument("--packed", type=int, default=0,
                     help="variant: run the workload's requests through po_prefill_packed with buffers of this many "
                          "rows (consecutive short requests share the launches of the position-wise layers)")
@@ -124,6 +128,8 @@ def main():
     cfg = w["cfg"]
     if args.layers:
         cfg = cfg.replace(n_layers=args.layers)
+    if args.fp8:
+        cfg = cfg.replace(dtype=I.BF16_FP8)
     lens = [int(x) for x in I.workload_lengths(args.workload)]
     cand = I.label_ids(cfg)
     reqs = [I.make_tokens(cfg, w["tseed"], n, request=i) for i, n in enumerate(lens)]
@@ -177,29 +183,31 @@ def main():
     free_b, total_b = torch.cuda.mem_get_info()
     # algorithmic flops per step of each kernel class (causal half only for attention)
     k_flop = flop_classes(cfg, lens)
+    gk = "gemm_fp8_mfma_kernel" if args.fp8 else "gemm_bf16_mfma_kernel"
     k_name = {"attention": ("attn_fwd64_kernel" if cfg.head_dim == 128 else "attn_fwd_kernel<64>") +
                            " (causal GQA flash attention, one launch per layer)",
-              "qkv": "gemm_bf16_mfma_kernel<3> (QKV projection + RoPE + transposed V)",
-              "residual": "gemm_bf16_mfma_kernel<1> (O-projection and MLP down projection + residual)",
-              "gate_up": "gemm_bf16_mfma_kernel<2> (MLP gate/up projection + SiLU-multiply)"}
+              "qkv": gk + "<3> (QKV projection + RoPE + transposed V)",
+              "residual": gk + "<1> (O-projection and MLP down projection + residual)",
+              "gate_up": gk + "<2> (MLP gate/up projection + SiLU-multiply)"}
 
     def roof(k):
         launches = k_n[k] / args.steps
         avg_ms = k_ms[k] / max(k_n[k], 1)
         ach = k_flop[k] / max(launches, 1) / 1e12 / (avg_ms / 1e3) if avg_ms > 0 else 0.0
-        return {"kernel": k_name[k], "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS,
-                "traffic": None if args.layers else MEASURED_TRAFFIC.get(args.workload, {}).get(k),
+        peak = PEAK_FP8_TFLOPS if (args.fp8 and k != "attention") else PEAK_BF16_TFLOPS
+        return {"kernel": k_name[k], "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                "frac": ach / peak,
+                "traffic": None if (args.layers or args.fp8) else MEASURED_TRAFFIC.get(args.workload, {}).get(k),
                 "launches_per_step": launches,
                 "avg_launch_ms": avg_ms, "algorithmic_flop_per_launch": k_flop[k] / max(launches, 1),
                 "share_of_step_time": (k_ms[k] / args.steps) / ms_per_step}
 
     out = {
-        "metric": "prefill tokens/s on 1 MI355X (8B-shape, 32k ctx)" if args.workload == "llama8b_32k" and not args.layers
-                  else f"prefill tokens/s on 1 MI355X ({args.workload})",
+        "metric": "prefill tokens/s on 1 MI355X (8B-shape, 32k ctx)" if args.workload == "llama8b_32k" and not args.layers and not args.fp8
+                  else f"prefill tokens/s on 1 MI355X ({args.workload}" + (", FP8-dynamic linear layers)" if args.fp8 else ")"),
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == I.BF16 else "f32", "data": "synthetic",
+        "dtype": {I.BF16: "bf16", I.F32: "f32", I.BF16_FP8: "fp8 e4m3 linear layers, bf16 elsewhere"}[cfg.dtype], "data": "synthetic",
         "config": {"workload": args.workload, "layers": cfg.n_layers, "d_model": cfg.d_model,
                    "requests": len(lens), "tokens": tokens, "mlp_chunk": chunk, "packed_rows": args.packed,
                    "weights": "random-init N(0,0.02), seeded"},

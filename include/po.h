@@ -52,7 +52,11 @@ typedef enum {
     PO_ERR_DEVICE = 8              /* a HIP call failed (message via po_last_device_error) */
 } po_status;
 
-typedef enum { PO_F32 = 0, PO_BF16 = 1 } po_dtype;
+/* PO_BF16_FP8: a bf16 model (weights are given, and activations stored, as bf16) whose decoder-block
+ * linear layers (Q/K/V, O, gate/up, down) run FP8-dynamic: weights quantised to E4M3 per output channel
+ * when they are loaded, their input activations per token when they are used (see po_op_quantize_rows);
+ * embedding, norms, rotary embedding, attention and the LM head stay bf16. */
+typedef enum { PO_F32 = 0, PO_BF16 = 1, PO_BF16_FP8 = 2 } po_dtype;
 
 /* Tensor kinds for po_load_tensor.  Per-layer kinds take layer in [0, n_layers);
  * global kinds (EMBED, FINAL_NORM, LM_HEAD) take layer = -1. */

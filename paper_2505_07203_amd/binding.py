@@ -25,7 +25,7 @@ PO_ERR_WORKSPACE_TOO_SMALL = 6
 PO_ERR_OOM = 7
 PO_ERR_DEVICE = 8
 
-PO_F32, PO_BF16 = 0, 1
+PO_F32, PO_BF16, PO_BF16_FP8 = 0, 1, 2
 KERNEL_CLASSES = ("attention", "qkv", "residual", "gate_up")   # po_kernel_class order
 
 EXPORTS = [

@@ -33,9 +33,11 @@ constexpr int MAX_CAND = 4096;
 constexpr int GU_INTERLEAVE_BF16 = 32;   // rows per gate/up block in the packed bf16 weight
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+inline bool is_bf16(int dtype) { return dtype == PO_BF16 || dtype == PO_BF16_FP8; }   // bf16 storage and kernels
 
 struct LayerOff {
     size_t attn_norm, wqkv, bqkv, wo, mlp_norm, wgu, wd;
+    size_t s_wqkv, s_wo, s_wgu, s_wd;     // PO_BF16_FP8: float32 scale per weight row (the matrices hold codes)
 };
 
 struct Layout {
@@ -45,6 +47,7 @@ struct Layout {
     size_t weights_bytes;
     // workspace arena
     size_t tokens, X, Q, K, V, Vt, Xn, H, GU, rope_cos, rope_sin, logits, xn_last, cand, cand_lp;
+    size_t sx;          // PO_BF16_FP8: float32 scale per row of the activation being multiplied
     size_t workspace_bytes;
     int64_t ldv;
     int chunk;          // effective chunk = min(mlp_chunk, max_len)
@@ -52,7 +55,7 @@ struct Layout {
 
 po_status validate_config(const po_model_config* c) {
     if (!c) return PO_ERR_INVALID_ARG;
-    if (c->dtype != PO_F32 && c->dtype != PO_BF16) return PO_ERR_INVALID_ARG;
+    if (c->dtype != PO_F32 && c->dtype != PO_BF16 && c->dtype != PO_BF16_FP8) return PO_ERR_INVALID_ARG;
     if (c->qkv_bias != 0 && c->qkv_bias != 1) return PO_ERR_INVALID_ARG;
     if (c->n_layers < 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
         c->ffn_dim <= 0 || c->vocab_size <= 0)
@@ -71,6 +74,15 @@ po_status validate_config(const po_model_config* c) {
         if (c->ffn_dim % GU_INTERLEAVE_BF16 != 0) return PO_ERR_BAD_CONFIG;
         if (!gemm_mfma_supported(2 * c->ffn_dim, c->d_model)) return PO_ERR_BAD_CONFIG;
         if (!gemm_mfma_supported(c->d_model, c->ffn_dim)) return PO_ERR_BAD_CONFIG;
+        if (c->dtype == PO_BF16_FP8) {
+            if (!gemm_fp8_supported(qd + 2 * kvd, c->d_model) || !gemm_fp8_supported(c->d_model, qd) ||
+                !gemm_fp8_supported(2 * c->ffn_dim, c->d_model) || !gemm_fp8_supported(c->d_model, c->ffn_dim))
+                return PO_ERR_BAD_CONFIG;
+            if (!quant_rows_supported(c->d_model) || !quant_rows_supported(qd) || !quant_rows_supported(c->ffn_dim))
+                return PO_ERR_BAD_CONFIG;
+            // the fused norm keeps a row in registers; the codes of an attention-output chunk borrow the norm buffer
+            if (c->d_model > 8192 || qd > 2 * c->d_model) return PO_ERR_BAD_CONFIG;
+        }
     }
     return PO_OK;
 }
@@ -81,8 +93,9 @@ po_status make_layout(const po_model_config* c, int64_t max_len, int32_t mlp_chu
     if (max_len <= 0 || mlp_chunk <= 0) return PO_ERR_INVALID_ARG;
     if (max_len > (int64_t)1 << 24) return PO_ERR_TOO_LONG;
     // the bf16 attention addresses one layer of K (and V^T) with 32-bit byte offsets
-    if (c->dtype == PO_BF16 && (max_len + 64) * c->n_kv_heads * c->head_dim * 2 >= ((int64_t)1 << 32)) return PO_ERR_TOO_LONG;
+    if (is_bf16(c->dtype) && (max_len + 64) * c->n_kv_heads * c->head_dim * 2 >= ((int64_t)1 << 32)) return PO_ERR_TOO_LONG;
     const size_t esz = c->dtype == PO_F32 ? 4 : 2;
+    const bool fp8 = c->dtype == PO_BF16_FP8;
     const size_t d = c->d_model, F = c->ffn_dim, V = c->vocab_size;
     const size_t qd = (size_t)c->n_q_heads * c->head_dim, kvd = (size_t)c->n_kv_heads * c->head_dim;
     size_t off = 0;
@@ -93,13 +106,18 @@ po_status make_layout(const po_model_config* c, int64_t max_len, int32_t mlp_chu
     L->layers.resize(c->n_layers);
     for (int l = 0; l < c->n_layers; ++l) {
         LayerOff& o = L->layers[l];
+        const size_t wsz = fp8 ? 1 : esz;         // bytes per element of a decoder linear weight
         o.attn_norm = take(d * esz);
-        o.wqkv = take((qd + 2 * kvd) * d * esz);
+        o.wqkv = take((qd + 2 * kvd) * d * wsz);
         o.bqkv = c->qkv_bias ? take((qd + 2 * kvd) * esz) : 0;
-        o.wo = take(d * qd * esz);
+        o.wo = take(d * qd * wsz);
         o.mlp_norm = take(d * esz);
-        o.wgu = take(2 * F * d * esz);
-        o.wd = take(d * F * esz);
+        o.wgu = take(2 * F * d * wsz);
+        o.wd = take(d * F * wsz);
+        o.s_wqkv = fp8 ? take((qd + 2 * kvd) * 4) : 0;
+        o.s_wo = fp8 ? take(d * 4) : 0;
+        o.s_wgu = fp8 ? take(2 * F * 4) : 0;
+        o.s_wd = fp8 ? take(d * 4) : 0;
     }
     L->weights_bytes = off;
 
@@ -113,7 +131,7 @@ po_status make_layout(const po_model_config* c, int64_t max_len, int32_t mlp_chu
     L->Q = take(N * qd * esz);
     L->K = take(N * kvd * esz);
     L->V = c->dtype == PO_F32 ? take(N * kvd * esz) : 0;   // bf16: V lives only as V^T
-    L->Vt = c->dtype == PO_BF16 ? take(kvd * (size_t)L->ldv * esz) : 0;
+    L->Vt = is_bf16(c->dtype) ? take(kvd * (size_t)L->ldv * esz) : 0;
     L->Xn = take(C * d * esz);
     L->H = take(C * F * esz);
     L->GU = c->dtype == PO_F32 ? take(C * 2 * F * esz) : 0;
@@ -123,6 +141,8 @@ po_status make_layout(const po_model_config* c, int64_t max_len, int32_t mlp_chu
     L->xn_last = take(d * esz);
     L->cand = take(MAX_CAND * 4);
     L->cand_lp = take(MAX_CAND * 4);
+    // one scale per row of a launch: at most the rows of d values the MLP chunk buffer holds
+    L->sx = fp8 ? take(std::max(C, C * F / d) * 4) : 0;
     L->workspace_bytes = off;
     return PO_OK;
 }
@@ -132,7 +152,7 @@ void kv_cache_geometry(const po_model_config* c, int64_t cap, int64_t* ldvc, siz
     const size_t kvd = (size_t)c->n_kv_heads * c->head_dim;
     *ldvc = round_up64(cap, 64);
     *v_off = align_up((size_t)cap * kvd * esz);
-    const size_t v_bytes = c->dtype == PO_BF16 ? kvd * (size_t)*ldvc * esz : (size_t)cap * kvd * esz;
+    const size_t v_bytes = is_bf16(c->dtype) ? kvd * (size_t)*ldvc * esz : (size_t)cap * kvd * esz;
     *layer_bytes = *v_off + align_up(v_bytes);
 }
 
@@ -247,12 +267,14 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                    int64_t p_store = 0) {
     const po_model_config& m = c->cfg;
     const Layout& L = c->lay;
-    const int dt = m.dtype;
+    const bool fp8 = m.dtype == PO_BF16_FP8;            // bf16 path with FP8-dynamic linear layers
+    const int dt = fp8 ? (int)PO_BF16 : m.dtype;
     const size_t esz = dt == PO_F32 ? 4 : 2;
     const int d = m.d_model, F = m.ffn_dim, hd = m.head_dim;
     const int qd = m.n_q_heads * hd, kvd = m.n_kv_heads * hd;
     hipStream_t s = c->stream;
     unsigned char* ws = c->ws;
+    float* sx = (float*)(ws + L.sx);
     int32_t* d_tok = (int32_t*)(ws + L.tokens);
     unsigned char* X = ws + L.X;
     unsigned char* Q = ws + L.Q;
@@ -315,9 +337,17 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
         for (int64_t c0 = p_reuse; c0 < total; c0 += Cq) {
             const int64_t rows = (total - c0 < Cq) ? total - c0 : Cq;
             unsigned char* Xn = Xq;     // (shadows the MLP-phase buffer inside this loop)
-            launch_rmsnorm(dt, X + (size_t)c0 * d * esz, c->w + o.attn_norm, Xn, rows, d, m.rms_eps, s);
+            if (fp8)
+                launch_rmsnorm_quant((const bf16_t*)(X + (size_t)c0 * d * esz), (const bf16_t*)(c->w + o.attn_norm), Xn, sx,
+                                     rows, d, m.rms_eps, s);
+            else
+                launch_rmsnorm(dt, X + (size_t)c0 * d * esz, c->w + o.attn_norm, Xn, rows, d, m.rms_eps, s);
             PhaseTimer pt(c, PO_K_QKV);
-            if (dt == PO_BF16) {
+            if (fp8) {
+                launch_gemm_fp8_qkv_rope(Xn, d, sx, wqkv, d, (const float*)(c->w + o.s_wqkv), (const bf16_t*)bqkv,
+                                         (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
+                                         (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, s);
+            } else if (dt == PO_BF16) {
                 // one GEMM: RoPE applied to Q and K in the epilogue, V written as V^T
                 launch_gemm_qkv_rope((const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, (const bf16_t*)bqkv,
                                      (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
@@ -393,7 +423,26 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
             const int64_t rows = (pw1 - c0 < C) ? pw1 - c0 : C;
             unsigned char* Xc = X + (size_t)c0 * d * esz;
             const unsigned char* Oc = Q + (size_t)c0 * qd * esz;
-            if (dt == PO_BF16) {
+            if (fp8) {
+                // attention output -> codes (into the norm buffer), O-projection + residual
+                launch_quant_rows((const bf16_t*)Oc, qd, Xn, qd, sx, rows, qd, 0, 0, 0, s);
+                {
+                    PhaseTimer pt(c, PO_K_RESIDUAL);
+                    launch_gemm_fp8(EPI_RESIDUAL, Xn, qd, sx, c->w + o.wo, qd, (const float*)(c->w + o.s_wo), (bf16_t*)Xc, d,
+                                    nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
+                }
+                launch_rmsnorm_quant((const bf16_t*)Xc, (const bf16_t*)(c->w + o.mlp_norm), Xn, sx, rows, d, m.rms_eps, s);
+                {
+                    PhaseTimer pt(c, PO_K_GATE_UP);
+                    launch_gemm_fp8(EPI_SILU_MUL, Xn, d, sx, c->w + o.wgu, d, (const float*)(c->w + o.s_wgu), (bf16_t*)H, F,
+                                    nullptr, nullptr, 0, rows, 2 * F, d, s);
+                }
+                // the gated intermediate -> codes in place (a row's codes take the first half of the row)
+                launch_quant_rows((const bf16_t*)H, F, H, 2 * (int64_t)F, sx, rows, F, 0, 0, 0, s);
+                PhaseTimer pt(c, PO_K_RESIDUAL);
+                launch_gemm_fp8(EPI_RESIDUAL, H, 2 * (int64_t)F, sx, c->w + o.wd, F, (const float*)(c->w + o.s_wd), (bf16_t*)Xc, d,
+                                nullptr, (const bf16_t*)Xc, d, rows, d, F, s);
+            } else if (dt == PO_BF16) {
                 {
                     PhaseTimer pt(c, PO_K_RESIDUAL);
                     launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)Oc, qd, (const bf16_t*)(c->w + o.wo), qd,
@@ -602,16 +651,61 @@ po_status po_load_tensor(po_ctx* c, int32_t kind, int32_t layer, const void* hos
         default: return PO_ERR_INVALID_ARG;
     }
     if (bytes != want * esz) return PO_ERR_INVALID_ARG;
-    if (kind == PO_T_WG || kind == PO_T_WU) {
+    const bool is_linear = kind == PO_T_WQ || kind == PO_T_WK || kind == PO_T_WV || kind == PO_T_WO || kind == PO_T_WG ||
+                           kind == PO_T_WU || kind == PO_T_WD;
+    if (m.dtype == PO_BF16_FP8 && is_linear) {
+        // FP8-dynamic: the bf16 rows go to a temporary device buffer and are quantised per output channel
+        // straight into their final (packed) row positions; the scales take the same positions
+        const size_t k_in = (kind == PO_T_WO) ? qd : (kind == PO_T_WD ? F : d);
+        const size_t rows = want / k_in;
+        size_t row0 = 0;                       // first destination row inside the matrix
+        size_t s_off = 0;
+        int blk = 0;
+        int64_t blk_stride = 0, dst_off = 0;
+        switch (kind) {
+            case PO_T_WQ: off = o->wqkv; s_off = o->s_wqkv; row0 = 0; break;
+            case PO_T_WK: off = o->wqkv; s_off = o->s_wqkv; row0 = qd; break;
+            case PO_T_WV: off = o->wqkv; s_off = o->s_wqkv; row0 = qd + kvd; break;
+            case PO_T_WO: off = o->wo; s_off = o->s_wo; break;
+            case PO_T_WD: off = o->wd; s_off = o->s_wd; break;
+            default:      // gate / up: interleaved in blocks of GU_INTERLEAVE_BF16 rows
+                off = o->wgu; s_off = o->s_wgu; blk = GU_INTERLEAVE_BF16; blk_stride = 2 * GU_INTERLEAVE_BF16;
+                dst_off = kind == PO_T_WU ? GU_INTERLEAVE_BF16 : 0;
+                break;
+        }
+        void* tmp = nullptr;
+        if (hipMalloc(&tmp, bytes) != hipSuccess) return PO_ERR_OOM;
+        hipError_t e = hipMemcpy(tmp, host, bytes, hipMemcpyHostToDevice);
+        if (e == hipSuccess) {
+            unsigned char* codes = c->w + off + row0 * k_in;
+            float* scales = (float*)(c->w + s_off) + row0;
+            launch_quant_rows((const bf16_t*)tmp, (int64_t)k_in, codes, (int64_t)k_in, scales, (int64_t)rows, (int)k_in, blk,
+                              blk_stride, dst_off, c->stream);
+            if (kind == PO_T_WQ || kind == PO_T_WK) {
+                // the rotary row order of the bf16 path, applied to the rows of codes (k_in bytes = k_in / 2
+                // two-byte units) and to their scales (4 bytes = 2 units)
+                const int heads = kind == PO_T_WQ ? m.n_q_heads : m.n_kv_heads;
+                launch_pack_rope_rows((bf16_t*)codes, heads, m.head_dim, (int64_t)(k_in / 2), c->stream);
+                launch_pack_rope_rows((bf16_t*)scales, heads, m.head_dim, 2, c->stream);
+            }
+            e = hipStreamSynchronize(c->stream);
+            if (e == hipSuccess) e = hipGetLastError();
+        }
+        (void)hipFree(tmp);
+        if (e != hipSuccess) {
+            snprintf(g_dev_err, sizeof(g_dev_err), "po_load_tensor: %s", hipGetErrorString(e));
+            return PO_ERR_DEVICE;
+        }
+    } else if (kind == PO_T_WG || kind == PO_T_WU) {
         // gate and up rows are interleaved in blocks of `il` rows so that one GEMM tile
         // holds a feature's gate and up values together (fp32 path: il = F, i.e. [Wg; Wu])
-        const size_t il = m.dtype == PO_BF16 ? GU_INTERLEAVE_BF16 : F;
+        const size_t il = is_bf16(m.dtype) ? GU_INTERLEAVE_BF16 : F;
         const size_t blk = il * d * esz;
         unsigned char* dst = c->w + off + (kind == PO_T_WU ? blk : 0);
         PO_HIP(hipMemcpy2D(dst, 2 * blk, host, blk, blk, F / il, hipMemcpyHostToDevice));
     } else {
         PO_HIP(hipMemcpy(c->w + off, host, bytes, hipMemcpyHostToDevice));
-        if (m.dtype == PO_BF16 && (kind == PO_T_WQ || kind == PO_T_WK || kind == PO_T_BQ || kind == PO_T_BK)) {
+        if (is_bf16(m.dtype) && (kind == PO_T_WQ || kind == PO_T_WK || kind == PO_T_BQ || kind == PO_T_BK)) {
             // rotary partners (i, i + head_dim/2) are brought into one 64-row group so that the
             // QKV GEMM can rotate them in its epilogue (see launch_pack_rope_rows)
             const bool is_bias = kind == PO_T_BQ || kind == PO_T_BK;

@@ -35,6 +35,7 @@ import numpy as np
 
 F32 = 0
 BF16 = 1
+BF16_FP8 = 2     # bf16 model whose decoder linear layers run FP8-dynamic (weights are still given as bf16)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -48,7 +49,7 @@ class ModelConfig:
     vocab_size: int
     rms_eps: float
     rope_theta: float
-    dtype: int = BF16          # F32 or BF16 (storage + activation dtype)
+    dtype: int = BF16          # F32, BF16 or BF16_FP8 (storage + activation dtype)
     qkv_bias: int = 0
 
     @property
@@ -173,7 +174,7 @@ def make_tensor(cfg: ModelConfig, seed: int, kind: int, layer: int = -1) -> np.n
     if kind in NORM_KINDS:
         x += np.float32(1.0)
     x = x.reshape(shape)
-    if cfg.dtype == BF16:
+    if cfg.dtype != F32:
         return f32_to_bf16_bits(x)
     return x
 

@@ -21,11 +21,11 @@ def oracle_globals(cfg, seed):
             I.stored_to_f64(g[I.KIND_LM_HEAD]))
 
 
-def oracle_prefill(cfg, wseed, tokens, cand=None, mlp_chunk=None, lazy_last_layer=False):
+def oracle_prefill(cfg, wseed, tokens, cand=None, mlp_chunk=None, lazy_last_layer=False, store=None, linear=None):
     from oracle import prefill_oracle as O
     embed, fnorm, lm = oracle_globals(cfg, wseed)
     return O.prefill(tokens, embed, oracle_layers(cfg, wseed), fnorm, lm, cfg, cand=cand,
-                     mlp_chunk=mlp_chunk, lazy_last_layer=lazy_last_layer)
+                     mlp_chunk=mlp_chunk, lazy_last_layer=lazy_last_layer, store=store, linear=linear)
 
 
 def normalised_max_rel(got, ref):

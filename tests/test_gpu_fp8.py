@@ -137,3 +137,85 @@ def test_qkv_rope_fp8(Hq, Hkv, hd, K, M, pos0, bias):
                        ("v", host64(vt)[:, pos0:pos0 + M].T, ref_v)):
         e = np.max(np.abs(g - r)) / np.max(np.abs(r))
         assert e <= 6e-3, (name, e)
+
+
+# ------------------------------------------------------------------ whole path with FP8-dynamic linear layers
+
+import helpers as H
+
+FP8_SMALL = I.ModelConfig(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn_dim=768, vocab_size=1024,
+                          rms_eps=1e-5, rope_theta=10000.0, dtype=I.BF16_FP8, qkv_bias=0)
+FP8_SMALL_128 = FP8_SMALL.replace(n_q_heads=2, n_kv_heads=1, head_dim=128, qkv_bias=1)
+FP8_WIDE = I.LLAMA8B.replace(n_layers=2, vocab_size=4096, dtype=I.BF16_FP8)
+
+
+def _oracle_fp8(cfg, wseed, tokens):
+    """The oracle's two evaluations of the FP8-dynamic model: activations stored as bf16 between operators
+    (what a bf16 model does, and what decides the codes), and nothing rounded but the FP8 operands."""
+    ocfg = cfg.replace(dtype=I.BF16)                         # same stored weights
+    z_s, _ = H.oracle_prefill(ocfg, wseed, tokens, store=O.round_bf16, linear=F.dynamic_linear)
+    z_e, _ = H.oracle_prefill(ocfg, wseed, tokens, linear=F.dynamic_linear)
+    z_b, _ = H.oracle_prefill(ocfg, wseed, tokens)           # the unquantised model
+    return z_s, z_e, z_b
+
+
+@pytest.mark.parametrize("cfg,n,chunk", [(FP8_SMALL, 300, 256), (FP8_SMALL_128, 513, 512), (FP8_WIDE, 700, 512)])
+def test_fp8_full_path_against_the_oracle(cfg, n, chunk):
+    """Tolerance: a per-token dynamic scale and a 4-bit significand turn any 2^-9 difference in an activation
+    into code flips, so two correct evaluations differ by more than the bf16 bar.  The distance between the
+    oracle's own two evaluations measures that (no GPU value enters it); the GPU path must be within twice it
+    (at least 2e-2) of both, and the quantised model must stay close to the unquantised one."""
+    tokens = I.make_tokens(cfg, 2001, n)
+    z_s, z_e, z_b = _oracle_fp8(cfg, 1001, tokens)
+    scale = np.max(np.abs(z_s))
+    self_dist = np.max(np.abs(z_s - z_e)) / scale
+    tol = max(2e-2, 2 * self_dist)
+    ctx = B.Context(cfg, 1024, chunk)
+    try:
+        ctx.load_synthetic(1001, threads=4)
+        cand = I.label_ids(cfg)
+        z, lp = ctx.po_prefill(tokens, cand)
+        z = z.astype(np.float64)
+        e_s, e_e = np.max(np.abs(z - z_s)) / scale, np.max(np.abs(z - z_e)) / scale
+        print(f"fp8 path d={cfg.d_model} N={n}: vs stored {e_s:.3e}, vs exact {e_e:.3e}, oracle stored-vs-exact {self_dist:.3e}, "
+              f"quantised-vs-unquantised {np.max(np.abs(z_s - z_b)) / scale:.3e}")
+        assert e_s <= tol and e_e <= tol
+        assert np.max(np.abs(z - z_b)) / scale < 0.25
+        assert abs(float(np.sum(np.exp(lp.astype(np.float64)))) - 1.0) < 1e-5
+        if np.sort(z_s)[-1] - np.sort(z_s)[-2] > 2 * tol * scale:
+            assert int(np.argmax(z)) == int(np.argmax(z_s))
+    finally:
+        ctx.po_destroy()
+
+
+@pytest.mark.parametrize("cfg", [FP8_SMALL, FP8_WIDE])
+def test_fp8_path_bitwise_properties(cfg):
+    """Per-token scales keep every row independent of the others in its launch: chunk size, packing and the
+    last-layer shortcut leave the bits alone in FP8 mode as well."""
+    lens = (300, 1, 65, 513, 129)
+    reqs = [I.make_tokens(cfg, 41, n, request=i) for i, n in enumerate(lens)]
+    cand = I.label_ids(cfg)
+    outs = []
+    for chunk in (512, 200):
+        ctx = B.Context(cfg, 1536, chunk)
+        try:
+            ctx.load_synthetic(31, threads=4)
+            zb, lpb = ctx.po_prefill_batch(reqs, cand, want_logits=True)
+            zp, lpp = ctx.po_prefill_packed(reqs, cand, want_logits=True)
+            assert np.array_equal(zp, zb) and np.array_equal(lpp, lpb)
+            ctx.po_set_lazy_last_layer(False)
+            zq, _ = ctx.po_prefill_batch(reqs, cand, want_logits=True)
+            assert np.array_equal(zq, zb)
+            outs.append(zb)
+        finally:
+            ctx.po_destroy()
+    assert np.all(np.isfinite(outs[0])) and np.array_equal(outs[0], outs[1])
+
+
+def test_fp8_weights_arena_is_smaller():
+    cfg = I.LLAMA8B
+    wb16, _ = B.po_workspace_bytes(cfg, 4096, 4096)
+    wb8, sb8 = B.po_workspace_bytes(cfg.replace(dtype=I.BF16_FP8), 4096, 4096)
+    lin = cfg.n_layers * ((cfg.q_dim + 2 * cfg.kv_dim) * cfg.d_model + cfg.d_model * cfg.q_dim + 3 * cfg.ffn_dim * cfg.d_model)
+    rows = cfg.n_layers * (cfg.q_dim + 2 * cfg.kv_dim + 2 * cfg.d_model + 2 * cfg.ffn_dim)
+    assert 0 <= wb8 - (wb16 - lin + 4 * rows) <= 256 * 4 * cfg.n_layers
