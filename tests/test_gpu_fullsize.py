@@ -172,3 +172,70 @@ def test_full_path_32k_bitwise_properties():
     assert np.all(np.isfinite(outs[0][0]))
     for z, lp in outs[1:]:
         assert np.array_equal(z, outs[0][0]) and np.array_equal(lp, outs[0][1])
+
+
+# ------------------------------------------------------------------ FP8-dynamic GEMMs at benchmark shapes
+
+def _fp8_operand(rng, rows, K, scale):
+    """bf16 random matrix -> (device codes, device scales, decoded codes float64 [rows, K], scales float64)"""
+    from oracle import fp8_oracle as F
+    t, _ = bf16_dev(rng.standard_normal((rows, K), dtype=np.float32) * scale)
+    q, s = B.po_op_quantize_rows(t)
+    return q, s, F.e4m3_decode(q.cpu().numpy()), s.cpu().numpy().astype(np.float64)
+
+
+def test_gemm_fp8_benchmark_shapes():
+    """The FP8 MFMA GEMM at the shapes `bench.py --fp8` times (O-projection, down projection with the residual
+    added in place, gate/up with the SiLU-multiply): whole sampled rows and columns against the exact sum of
+    the same codes.  Tolerance: bf16 rounding of the result (2^-8) plus fp32 accumulation of K products."""
+    for M, N, K, silu in ((4096, 4096, 4096, False), (4096, 4096, 14336, False), (4096, 2 * 14336, 4096, True)):
+        rng = np.random.default_rng(N + K)
+        qa, sa_d, aq, sa = _fp8_operand(rng, M, K, 1.0)
+        if silu:
+            Fd = N // 2
+            qg, sg_d, gq, sg = _fp8_operand(rng, Fd, K, 0.02)
+            qu, su_d, uq, su = _fp8_operand(rng, Fd, K, 0.02)
+            def pack(g, u):
+                return torch.stack((g.view(Fd // 32, 32, *g.shape[1:]), u.view(Fd // 32, 32, *u.shape[1:])),
+                                   dim=1).reshape(2 * Fd, *g.shape[1:]).contiguous()
+            got = host64(B.po_op_linear_fp8(qa, sa_d, pack(qg, qu), pack(sg_d, su_d), silu_mul=True))
+            cols = np.array([0, 31, 32, 63, 64, 7000, 14304, 14335])
+
+            def act(a_, sa_, gw, sgw, uw, suw):
+                gate = (a_ @ gw.T) * sa_[:, None] * sgw[None, :]
+                up = (a_ @ uw.T) * sa_[:, None] * suw[None, :]
+                return gate / (1 + np.exp(-gate)) * up
+            ref_rows = act(aq[ROWS], sa[ROWS], gq, sg, uq, su)
+            ref_cols = act(aq, sa, gq[cols], sg[cols], uq[cols], su[cols])
+            e = _check_rows_cols(got, ref_rows, ref_cols, ROWS, cols, 6e-3)
+        else:
+            qw, sw_d, wq, sw = _fp8_operand(rng, N, K, 0.02)
+            r, r64 = bf16_dev(rng.standard_normal((M, N), dtype=np.float32))
+            cols = np.array([0, 63, 64, 255, 256, 2049, 4032, 4095])
+            ref_rows = (aq[ROWS] @ wq.T) * sa[ROWS, None] * sw[None, :] + r64[ROWS]
+            ref_cols = (aq @ wq[cols].T) * sa[:, None] * sw[None, cols] + r64[:, cols]
+            B.po_op_linear_fp8(qa, sa_d, qw, sw_d, residual=r, out=r)
+            e = _check_rows_cols(host64(r), ref_rows, ref_cols, ROWS, cols, 6e-3)
+        print(f"fp8 GEMM {M}x{N}x{K}{' silu' if silu else ' +residual'}: {e:.2e}")
+
+
+def test_fp8_full_path_32k_bitwise_properties():
+    """Two layers of the 8B shape, FP8-dynamic, on the benchmark's 32768 tokens: finite logits, identical bit for
+    bit for MLP chunks 4096 and 3000 and across repeated runs."""
+    w = I.WORKLOADS["llama8b_32k"]
+    cfg = w["cfg"].replace(n_layers=2, dtype=I.BF16_FP8)
+    tokens = I.make_tokens(cfg, w["tseed"], 32768, request=0)
+    cand = I.label_ids(cfg)
+    outs = []
+    for chunk in (4096, 3000):
+        ctx = B.Context(cfg, 32768, chunk)
+        try:
+            ctx.load_synthetic(w["wseed"], threads=16)
+            z, lp = ctx.po_prefill(tokens, cand, want_logits=True)
+            if chunk == 4096:
+                z2, _ = ctx.po_prefill(tokens, cand, want_logits=True)
+                assert np.array_equal(z, z2)
+            outs.append(z)
+        finally:
+            ctx.po_destroy()
+    assert np.all(np.isfinite(outs[0])) and np.array_equal(outs[0], outs[1])
