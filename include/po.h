@@ -134,6 +134,18 @@ po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t m
 po_status po_load_tensor(po_ctx* ctx, int32_t tensor_kind, int32_t layer,
                          const void* host_data, size_t bytes);
 
+/* A whole model in host memory: tensor[kind] points at the tensor of a global kind
+ * (PO_T_EMBED, PO_T_FINAL_NORM, PO_T_LM_HEAD), or at an array of n_layers pointers, one per
+ * layer, for a per-layer kind (the three bias kinds may be NULL when qkv_bias == 0).  Every
+ * tensor has the size and layout po_load_tensor expects. */
+typedef struct {
+    const void* tensor[PO_T_COUNT];
+} po_host_weights;
+
+/* po_load_tensor for every tensor of the model.  Stops at the first error; tensors loaded
+ * before it stay loaded. */
+po_status po_load_weights(po_ctx* ctx, const po_host_weights* weights);
+
 /* 1 when every tensor the configuration needs has been loaded, else 0. */
 int32_t po_is_loaded(const po_ctx* ctx);
 

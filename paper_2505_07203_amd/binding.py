@@ -29,7 +29,7 @@ PO_F32, PO_BF16, PO_BF16_FP8 = 0, 1, 2
 KERNEL_CLASSES = ("attention", "qkv", "residual", "gate_up")   # po_kernel_class order
 
 EXPORTS = [
-    "po_workspace_bytes", "po_create", "po_load_tensor", "po_is_loaded", "po_prefill",
+    "po_workspace_bytes", "po_create", "po_load_tensor", "po_load_weights", "po_is_loaded", "po_prefill",
     "po_prefill_batch", "po_set_phase_timing", "po_get_stats", "po_destroy", "po_strerror",
     "po_last_device_error", "po_op_rmsnorm", "po_op_linear", "po_op_gate_up_silu",
     "po_op_pack_gate_up", "po_op_attention", "po_op_rope", "po_op_lm_head", "po_op_rope_table",
@@ -84,6 +84,7 @@ def lib() -> C.CDLL:
     L.po_profile.argtypes = [vp, i64, C.POINTER(C.c_double), C.POINTER(sz)]
     L.po_create.argtypes = [C.POINTER(ModelConfigC), i64, i32, vp, sz, vp, sz, vp, C.POINTER(vp)]
     L.po_load_tensor.argtypes = [vp, i32, i32, vp, sz]
+    L.po_load_weights.argtypes = [vp, vp]
     L.po_is_loaded.argtypes = [vp]
     L.po_prefill.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.po_prefill_batch.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
@@ -193,6 +194,22 @@ class Context:
     def po_load_tensor(self, kind: int, layer: int, host: np.ndarray) -> None:
         a = np.ascontiguousarray(host)
         check(lib().po_load_tensor(self._h, kind, layer, _host_ptr(a), a.nbytes))
+
+    def po_load_weights(self, tensors) -> None:
+        """tensors: {kind: array} for the global kinds, {kind: [array per layer]} for the per-layer kinds"""
+        keep = []
+        slots = (C.c_void_p * 15)()
+        for kind, t in tensors.items():
+            if isinstance(t, (list, tuple)):
+                arrs = [np.ascontiguousarray(a) for a in t]
+                ptrs = (C.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+                keep += arrs + [ptrs]
+                slots[kind] = C.cast(ptrs, C.c_void_p)
+            else:
+                a = np.ascontiguousarray(t)
+                keep.append(a)
+                slots[kind] = a.ctypes.data
+        check(lib().po_load_weights(self._h, C.byref(slots)))
 
     def po_is_loaded(self) -> bool:
         return bool(lib().po_is_loaded(self._h))

@@ -719,6 +719,33 @@ po_status po_load_tensor(po_ctx* c, int32_t kind, int32_t layer, const void* hos
     return PO_OK;
 }
 
+po_status po_load_weights(po_ctx* c, const po_host_weights* w) {
+    if (!c || !w) return PO_ERR_INVALID_ARG;
+    const po_model_config& m = c->cfg;
+    const size_t esz = m.dtype == PO_F32 ? 4 : 2;
+    const size_t d = m.d_model, F = m.ffn_dim, V = m.vocab_size;
+    const size_t qd = (size_t)m.n_q_heads * m.head_dim, kvd = (size_t)m.n_kv_heads * m.head_dim;
+    const size_t elems[PO_T_COUNT] = {V * d, d, qd * d, kvd * d, kvd * d, qd, kvd, kvd, d * qd, d, F * d, F * d, d * F, d, V * d};
+    for (int kind = 0; kind < PO_T_COUNT; ++kind) {
+        const bool is_global = kind == PO_T_EMBED || kind == PO_T_FINAL_NORM || kind == PO_T_LM_HEAD;
+        const bool is_bias = kind == PO_T_BQ || kind == PO_T_BK || kind == PO_T_BV;
+        if (is_bias && !m.qkv_bias) continue;
+        if (!w->tensor[kind]) return PO_ERR_INVALID_ARG;
+        if (is_global) {
+            po_status st = po_load_tensor(c, kind, -1, w->tensor[kind], elems[kind] * esz);
+            if (st != PO_OK) return st;
+            continue;
+        }
+        const void* const* per_layer = (const void* const*)w->tensor[kind];
+        for (int l = 0; l < m.n_layers; ++l) {
+            if (!per_layer[l]) return PO_ERR_INVALID_ARG;
+            po_status st = po_load_tensor(c, kind, l, per_layer[l], elems[kind] * esz);
+            if (st != PO_OK) return st;
+        }
+    }
+    return PO_OK;
+}
+
 int32_t po_is_loaded(const po_ctx* c) {
     if (!c) return 0;
     const uint32_t need = required_layer_mask(c->cfg);

@@ -462,3 +462,36 @@ def test_packed_rejects_bad_input_before_any_launch():
             ctx.po_prefill_packed([good, I.make_tokens(cfg, 41, 257)], I.label_ids(cfg))     # longer than max_input_len
     finally:
         ctx.po_destroy()
+
+
+def test_load_weights_at_once_equals_tensor_by_tensor():
+    cfg = I.ModelConfig(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=1, head_dim=128, ffn_dim=704, vocab_size=1024,
+                        rms_eps=1e-5, rope_theta=10000.0, dtype=I.BF16, qkv_bias=1)
+    tokens = I.make_tokens(cfg, 5, 300)
+    cand = I.label_ids(cfg)
+    a = make_ctx(cfg, 77, 512, 256)
+    b = B.Context(cfg, 512, 256)
+    try:
+        model = dict(I.global_tensors(cfg, 77))
+        per_layer = [I.layer_tensors(cfg, 77, l) for l in range(cfg.n_layers)]
+        for kind in per_layer[0]:
+            model[kind] = [per_layer[l][kind] for l in range(cfg.n_layers)]
+        assert not b.po_is_loaded()
+        b.po_load_weights(model)
+        assert b.po_is_loaded()
+        za, lpa = a.po_prefill(tokens, cand)
+        zb, lpb = b.po_prefill(tokens, cand)
+        assert np.array_equal(za, zb) and np.array_equal(lpa, lpb)
+        # a missing tensor is an error, not a crash
+        broken = dict(model)
+        del broken[I.KIND_WO]
+        c = B.Context(cfg, 512, 256)
+        try:
+            with pytest.raises(B.PoError):
+                c.po_load_weights(broken)
+            assert not c.po_is_loaded()
+        finally:
+            c.po_destroy()
+    finally:
+        a.po_destroy()
+        b.po_destroy()
