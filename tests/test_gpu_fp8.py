@@ -73,7 +73,8 @@ def _gemm_tol(aq, wq, sa, sw):
         (aq.shape[1] * 2.0 ** -22) * (np.abs(aq) @ np.abs(wq).T) * sa[:, None] * sw[None, :] + 1e-30
 
 
-@pytest.mark.parametrize("M,N,K", [(300, 320, 256), (1000, 4096 + 64, 512), (1, 64, 128), (257, 1024, 4096)])
+@pytest.mark.parametrize("M,N,K", [(300, 320, 256), (1000, 4096 + 64, 512), (1, 64, 128), (257, 1024, 4096),
+                                   (70, 128, 384), (70, 192, 640), (33, 64, 1280)])      # slice counts 3, 5, 10
 def test_linear_fp8(M, N, K):
     rng = np.random.default_rng(M + N + K)
     qa, sa_d, aq, sa, a64 = _quantised(rng, M, K)

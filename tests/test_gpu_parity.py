@@ -163,6 +163,7 @@ def test_llama8b_width_two_layers_bf16():
 # ------------------------------------------------------------------ single kernels vs their definitions
 
 @pytest.mark.parametrize("dtype,M,N,K", [(I.BF16, 300, 320, 256), (I.BF16, 1000, 4096 + 64, 512), (I.BF16, 1, 64, 64),
+                                          (I.BF16, 70, 128, 192), (I.BF16, 70, 192, 320), (I.BF16, 33, 64, 640),   # 3, 5, 10 slices
                                           (I.F32, 130, 100, 72)])
 def test_op_linear(dtype, M, N, K):
     rng = np.random.default_rng(M + N)
