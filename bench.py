@@ -90,6 +90,35 @@ def cpu_baseline(cfg, wseed, tseed, full_lens, sample_layers, sample_tokens):
                       f"same workload: {dt:.2f} s measured, extrapolated to the full workload by the flop model"}
 
 
+def sample_shader_clock(run_step, n_steps=2):
+    """Shader clock (MHz) reported by rocm-smi while `run_step` keeps the GPU busy; outside the timed region.
+    -> median of the samples, or None when the tool is not there."""
+    import re
+    import subprocess
+    import threading
+    samples, stop = [], threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            try:
+                r = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=5)
+                for line in r.stdout.splitlines():
+                    m = re.search(r"sclk clock level.*\((\d+)Mhz\)", line)
+                    if m:
+                        samples.append(int(m.group(1)))
+            except Exception:
+                return
+            time.sleep(0.15)
+    th = threading.Thread(target=poll, daemon=True)
+    th.start()
+    for _ in range(n_steps):
+        run_step()
+    stop.set()
+    th.join(timeout=10)
+    busy = sorted(samples[1:]) if len(samples) > 2 else sorted(samples)
+    return busy[len(busy) // 2] if busy else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,6 +128,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: override the layer count (invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-timing", action="store_true")
+    ap.add_argument("--no-clock-sample", action="store_true",
+                    help="skip the two extra, untimed steps during which the shader clock is read from rocm-smi")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one elementwise kernel that reads 1 GiB and writes 1 GiB, so that a "
                          "counter run of this command holds a dispatch of known HBM traffic")
@@ -176,6 +207,7 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
+    sclk = None if args.no_clock_sample else sample_shader_clock(step)
     tokens = sum(lens)
     value = tokens * args.steps / elapsed
     lin_f, att_f = flop_model(cfg, lens)
@@ -217,6 +249,8 @@ def main():
         "peak_hbm_bytes": {"weights_arena": ctx.weights_bytes, "workspace_arena": ctx.workspace_bytes,
                            "device_in_use_after_run": int(total_b - free_b)},
         "load_seconds": load_s,
+        # the nominal MFMA peak assumes 2400 MHz; the board runs this load at its power limit, below that
+        "shader_clock_mhz": {"during_untimed_steps": sclk, "nominal": 2400},
     }
     if sum(k_ms.values()) > 0:
         # `roofline` is the kernel with the largest share of the step; the others follow
