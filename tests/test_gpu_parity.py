@@ -341,7 +341,8 @@ def test_last_layer_shortcut_is_bitwise(cfg, n):
 
 
 @pytest.mark.parametrize("cfg,n,keep", [(I.TINY, 700, 300), (I.TINY.replace(dtype=I.BF16, ffn_dim=704), 900, 512),
-                                        (I.LLAMA8B.replace(n_layers=2, vocab_size=4096), 1500, 1000)])
+                                        (I.LLAMA8B.replace(n_layers=2, vocab_size=4096), 1500, 1000),
+                                        (I.TINY.replace(dtype=I.BF16_FP8, ffn_dim=768), 900, 500)])      # FP8-dynamic linear layers
 def test_prefix_cache_reuse_is_bitwise(cfg, n, keep):
     """Section 5.1: a request that shares a cached prefix computes only its suffix, and gets the same bits."""
     ctx = make_ctx(cfg, 19, n, 256)
