@@ -83,7 +83,8 @@ def test_activation_footprint_slope_is_one_layer_of_kv():
     assert slope < all_layer_kv / 5
 
 
-@pytest.mark.parametrize("cfg,chunk", [(I.LLAMA8B, 4096), (I.QWEN32B, 4096), (I.TINY, 512)])
+@pytest.mark.parametrize("cfg,chunk", [(I.LLAMA8B, 4096), (I.QWEN32B, 4096), (I.TINY, 512),
+                                       (I.QWEN32B.replace(dtype=I.BF16_FP8), 4096)])
 def test_max_input_len_is_the_largest_length_that_fits(cfg, chunk):
     """Section 3 / the paper's maximum-input-length metric: bisection on the closed form."""
     for budget in (24e9, 40e9, 80e9, 288e9):
@@ -157,3 +158,19 @@ def test_bad_arguments_rejected_before_any_launch():
     assert L.po_op_linear(3, 4096, 4096, 4096, None, 8, 64, 64, None) == B.PO_ERR_INVALID_ARG
     assert L.po_op_attention(B.PO_BF16, 4096, 4096, 4096, 4096, 4096, 8, 4, 2, 96, None) == B.PO_ERR_BAD_CONFIG
     assert L.po_op_attention(B.PO_BF16, 4096, 4096, 4096, 4096, 4096, 8, 4, 3, 128, None) == B.PO_ERR_INVALID_ARG
+
+
+def test_fp8_arenas():
+    """FP8-dynamic linear layers: one byte per weight of the decoder blocks' matrices plus a float32 scale per
+    output channel; the workspace grows by one float32 scale per row of a launch."""
+    cfg = I.LLAMA8B
+    wb16, _ = B.po_workspace_bytes(cfg, 4096, 4096)
+    wb8, sb8 = B.po_workspace_bytes(cfg.replace(dtype=I.BF16_FP8), 4096, 4096)
+    lin = cfg.n_layers * ((cfg.q_dim + 2 * cfg.kv_dim) * cfg.d_model + cfg.d_model * cfg.q_dim + 3 * cfg.ffn_dim * cfg.d_model)
+    rows = cfg.n_layers * (cfg.q_dim + 2 * cfg.kv_dim + 2 * cfg.d_model + 2 * cfg.ffn_dim)
+    assert 0 <= wb8 - (wb16 - lin + 4 * rows) <= 256 * 4 * cfg.n_layers
+    _, sb16 = B.po_workspace_bytes(cfg, 4096, 4096)
+    assert sb8 - sb16 == 4 * 4096 * cfg.ffn_dim // cfg.d_model
+    # shapes the FP8 kernels cannot take are refused up front
+    with pytest.raises(B.PoError):
+        B.po_workspace_bytes(I.TINY.replace(dtype=I.BF16_FP8, ffn_dim=704), 512, 128)      # 704 is not a multiple of 128
