@@ -83,6 +83,7 @@ def test_against_stored_oracle(path):
     ctx = B.Context(cfg, max(lens), doc["mlp_chunk"])
     try:
         ctx.load_synthetic(doc["wseed"], threads=16)
+        singles = []
         for i, r in enumerate(doc["requests"]):
             t = I.make_tokens(cfg, doc["tseed"], r["len"], request=i)
             assert hashlib.sha256(np.ascontiguousarray(t, dtype=np.int32).tobytes()).hexdigest() == r["tokens_sha256"]
@@ -98,5 +99,12 @@ def test_against_stored_oracle(path):
             err_e = _check_block(doc["case"], i, z, lp, ex, tol)
             print(f"{doc['case']} request {i} len {r['len']}: err vs stored_bf16 {err_s:.3e}, vs exact {err_e:.3e} "
                   f"(oracle stored-vs-exact {storage_dev:.3e}, tol {tol:.3e})")
+            singles.append((z, lp))
+        if len(singles) > 1:
+            # the same requests with their position-wise layers packed: the same bits, request by request
+            toks = [I.make_tokens(cfg, doc["tseed"], r["len"], request=i) for i, r in enumerate(doc["requests"])]
+            zp, lpp = ctx.po_prefill_packed(toks, cand, want_logits=True)
+            for i, (z, lp) in enumerate(singles):
+                assert np.array_equal(zp[i], z) and np.array_equal(lpp[i], lp), (doc["case"], i)
     finally:
         ctx.po_destroy()
