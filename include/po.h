@@ -198,13 +198,33 @@ po_status po_profile(po_ctx* ctx, int64_t len, double* elapsed_ms, size_t* touch
 po_status po_kv_cache_bytes(const po_model_config* cfg, int64_t prefix_capacity, size_t* bytes);
 po_status po_attach_kv_cache(po_ctx* ctx, void* dev_cache, size_t bytes, int64_t prefix_capacity);
 
+/* The same with n_slots entries of prefix_capacity positions each (bytes >= n_slots times
+ * what po_kv_cache_bytes reports).  A request reuses the entry with which it shares the
+ * longest prefix.  The prefix it asks to keep: if that entry already contains it, nothing
+ * is stored and the entry stays as long as it is; if the request shares everything the
+ * entry holds, the entry grows in place; otherwise (partial or no hit) the prefix replaces
+ * an empty or else the least recently used of the OTHER entries, so that a partial hit does
+ * not cut a longer entry short (with one entry it replaces that one).  "Used" = reused by a
+ * request or written. */
+po_status po_attach_kv_cache_slots(po_ctx* ctx, void* dev_cache, size_t bytes, int64_t prefix_capacity,
+                                   int32_t n_slots);
+
+/* What the cache would spare a request: the longest common prefix of tokens[0 .. len) with
+ * any entry, at most len - 1 (0 without a cache).  Host only. */
+po_status po_kv_cache_match(const po_ctx* ctx, const int32_t* tokens, int64_t len, int64_t* cached_len);
+
+/* The token ids whose K/V entry `slot` holds: *n_tokens receives their number, tokens_out
+ * (may be NULL; capacity >= *n_tokens otherwise) the ids.  Host only. */
+po_status po_kv_cache_slot(const po_ctx* ctx, int32_t slot, int32_t* tokens_out, int64_t capacity,
+                           int64_t* n_tokens);
+
 /* po_prefill with the prefix cache.  The longest common prefix of tokens[] with the tokens
  * whose K/V the cache holds (at most len - 1 positions) is NOT recomputed: embedding,
  * projections and MLP run on the remaining positions only, and attention reads the cached
  * K/V of the prefix next to the fresh K/V of the rest (rectangular block for the prefix keys,
  * causal block for the rest).  *reused_prefix_len (may be NULL) reports that length.
- * keep_prefix > 0: afterwards the cache holds the K/V of tokens[0 .. keep_prefix), replacing
- * what it held (keep_prefix <= len and <= prefix_capacity, else PO_ERR_TOO_LONG);
+ * keep_prefix > 0: afterwards some entry of the cache holds the K/V of tokens[0 .. keep_prefix)
+ * (see po_attach_kv_cache_slots for which; keep_prefix <= len and <= prefix_capacity, else PO_ERR_TOO_LONG);
  * keep_prefix = 0 leaves the cache as it is.  The outputs are bit-identical to po_prefill
  * on the same tokens (a row's result does not depend on which other rows are computed).
  * PO_ERR_INVALID_ARG without an attached cache. */
@@ -234,6 +254,10 @@ po_status po_sched_push(po_sched* s, int64_t id, const int32_t* tokens, int64_t 
 int64_t po_sched_size(const po_sched* s);
 po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cached_tokens, double now,
                         int64_t* id, int64_t* n_cached_hit);
+/* The same against a cache of several entries: n_cached of a request is the best any entry
+ * offers it (cached_tokens[e] / n_cached_tokens[e], e < n_entries). */
+po_status po_sched_pick_multi(po_sched* s, const int32_t* const* cached_tokens, const int64_t* n_cached_tokens,
+                              int32_t n_entries, double now, int64_t* id, int64_t* n_cached_hit);
 
 /* Last-layer shortcut, on by default.  A prefill-only request produces one token (Section 1),
  * so nothing reads the last layer's output except at the last position: with the shortcut

@@ -18,7 +18,7 @@ checkpoints follow:
 
 Only the decoder blocks' linear layers (Q/K/V, O, gate/up, down) are quantised; embedding,
 norms, rotary embedding, attention and the LM head are untouched.  Everything here is plain
-numpy; nothing is shared with the HIP library.  Pins: tests/test_oracle_pins.py (the decode
+numpy; nothing is shared with the HIP library.  Pins: tests/test_fp8_oracle_pins.py (the decode
 table against the format's definition and its published constants, the encoder against a
 library conversion and a brute-force nearest search, ties, subnormals, scaling invariants).
 """

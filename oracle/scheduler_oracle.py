@@ -12,8 +12,12 @@ cached tokens, capped at n_input - 1 (one position is always computed); ties go 
 that was pushed first; the JCT model is either the paper's default proxy n_input - n_cached or
 a linear model c0 + c_input * n_input + c_cached * n_cached fitted by least squares.
 
+pick_multi is the same selection when the cache holds several entries (n_cached = the best
+any entry offers); with one entry it is pick.
+
 Pinned by tests/test_scheduler.py: the paper's A/B/C/D example (orders and hit counts it
-states), brute-force enumeration of the score on small queues, and numpy's lstsq for the fit.
+states), brute-force enumeration of the score on small queues (one and several entries), and
+numpy's lstsq for the fit.
 """
 from __future__ import annotations
 
@@ -31,6 +35,11 @@ def common_prefix(a, b) -> int:
 
 def n_cached(tokens, cached) -> int:
     return min(common_prefix(tokens, cached), len(tokens) - 1)
+
+
+def n_cached_any(tokens, entries) -> int:
+    """With a cache of several entries a request reuses the one that spares it most."""
+    return max((n_cached(tokens, e) for e in entries), default=0)
 
 
 def proxy_jct(n_input: int, n_hit: int) -> float:
@@ -56,6 +65,17 @@ def pick(queue, cached, now: float, lam: float, jct=proxy_jct):
     best, best_score, best_hit = None, float("inf"), 0
     for i, (_, tokens, arrival) in enumerate(queue):
         hit = n_cached(tokens, cached)
+        score = jct(len(tokens), hit) - lam * (now - arrival)
+        if score < best_score:
+            best, best_score, best_hit = i, score, hit
+    return best, best_hit
+
+
+def pick_multi(queue, entries, now: float, lam: float, jct=proxy_jct):
+    """Algorithm 1 with n_cached taken over a cache of several entries (lists of token ids)."""
+    best, best_score, best_hit = None, float("inf"), 0
+    for i, (_, tokens, arrival) in enumerate(queue):
+        hit = n_cached_any(tokens, entries)
         score = jct(len(tokens), hit) - lam * (now - arrival)
         if score < best_score:
             best, best_score, best_hit = i, score, hit

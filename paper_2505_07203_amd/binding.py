@@ -36,6 +36,7 @@ EXPORTS = [
     "po_op_pack_qkv", "po_op_qkv_rope", "po_max_input_len", "po_profile", "po_set_lazy_last_layer",
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
     "po_op_quantize_rows", "po_op_rmsnorm_quantize", "po_op_linear_fp8", "po_op_qkv_rope_fp8",
+    "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick",
 ]
@@ -93,6 +94,10 @@ def lib() -> C.CDLL:
     L.po_set_lazy_last_layer.argtypes = [vp, i32]
     L.po_kv_cache_bytes.argtypes = [C.POINTER(ModelConfigC), i64, C.POINTER(sz)]
     L.po_attach_kv_cache.argtypes = [vp, vp, sz, i64]
+    L.po_attach_kv_cache_slots.argtypes = [vp, vp, sz, i64, i32]
+    L.po_kv_cache_match.argtypes = [vp, vp, i64, C.POINTER(i64)]
+    L.po_kv_cache_slot.argtypes = [vp, i32, vp, i64, C.POINTER(i64)]
+    L.po_sched_pick_multi.argtypes = [vp, vp, vp, i32, C.c_double, C.POINTER(i64), C.POINTER(i64)]
     L.po_prefill_prefix.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, C.POINTER(i64)]
     L.po_get_stats.argtypes = [vp, C.POINTER(StatsC)]
     L.po_destroy.argtypes = [vp]
@@ -250,14 +255,29 @@ class Context:
         check(lib().po_profile(self._h, length, C.byref(ms), C.byref(touched)))
         return ms.value, touched.value
 
-    def po_attach_kv_cache(self, prefix_capacity: int) -> int:
-        """Allocates (torch) and attaches a prefix K/V cache; returns its size in bytes."""
+    def po_attach_kv_cache(self, prefix_capacity: int, n_slots: int = 1) -> int:
+        """Allocates (torch) and attaches a prefix K/V cache of n_slots entries; returns its size in bytes."""
         n = C.c_size_t(0)
         cc = config_c(self.cfg)
         check(lib().po_kv_cache_bytes(C.byref(cc), prefix_capacity, C.byref(n)))
-        self._kvc = self._torch.empty(n.value, dtype=self._torch.uint8, device=self.device)
-        check(lib().po_attach_kv_cache(self._h, self._kvc.data_ptr(), n.value, prefix_capacity))
-        return n.value
+        total = n.value * n_slots
+        self._kvc = self._torch.empty(total, dtype=self._torch.uint8, device=self.device)
+        check(lib().po_attach_kv_cache_slots(self._h, self._kvc.data_ptr(), total, prefix_capacity, n_slots))
+        self._kv_slots = n_slots
+        return total
+
+    def po_kv_cache_match(self, tokens: np.ndarray) -> int:
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        out = C.c_int64(0)
+        check(lib().po_kv_cache_match(self._h, _host_ptr(tok), len(tok), C.byref(out)))
+        return out.value
+
+    def po_kv_cache_slot(self, slot: int) -> np.ndarray:
+        n = C.c_int64(0)
+        check(lib().po_kv_cache_slot(self._h, slot, None, 0, C.byref(n)))
+        out = np.empty(n.value, dtype=np.int32)
+        check(lib().po_kv_cache_slot(self._h, slot, _host_ptr(out), n.value, C.byref(n)))
+        return out
 
     def po_prefill_prefix(self, tokens: np.ndarray, keep_prefix: int, cand: Optional[Sequence[int]] = None,
                           want_logits: bool = True):
@@ -507,6 +527,16 @@ class Scheduler:
         c = np.ascontiguousarray(cached_tokens, dtype=np.int32)
         rid, hit = C.c_int64(-1), C.c_int64(0)
         check(lib().po_sched_pick(self._h, _host_ptr(c) if c.size else None, c.shape[0], now, C.byref(rid), C.byref(hit)))
+        return rid.value, hit.value
+
+    def po_sched_pick_multi(self, cached_entries, now: float):
+        """po_sched_pick against several cache entries (a list of token-id arrays)."""
+        ents = [np.ascontiguousarray(e, dtype=np.int32) for e in cached_entries]
+        n = len(ents)
+        ptrs = (C.c_void_p * max(n, 1))(*[e.ctypes.data if e.size else None for e in ents])
+        lens = (C.c_int64 * max(n, 1))(*[e.shape[0] for e in ents])
+        rid, hit = C.c_int64(-1), C.c_int64(0)
+        check(lib().po_sched_pick_multi(self._h, ptrs, lens, n, now, C.byref(rid), C.byref(hit)))
         return rid.value, hit.value
 
     def po_sched_destroy(self) -> None:

@@ -171,11 +171,19 @@ struct po_ctx {
     bool phase_timing;
     bool lazy_last_layer;             // last layer: queries, attention rows and MLP only where the last token needs them
     // prefix K/V cache (caller-provided device memory): per layer K [cap, kvd], then V^T [kvd, ldvc]
-    // (bf16) or V [cap, kvd] (fp32); kv_tokens are the token ids whose K/V it currently holds
+    // (bf16) or V [cap, kvd] (fp32); see kv_slots
     unsigned char* kvc;
     int64_t kv_cap, kv_ldv;
     size_t kv_layer_bytes, kv_v_off;
-    std::vector<int32_t> kv_tokens;
+    // the cache is kv_slots.size() slots of n_layers * kv_layer_bytes each; a slot remembers the token ids whose
+    // K/V it holds and when it was last used (replacement: least recently used)
+    struct KvSlot {
+        std::vector<int32_t> tokens;
+        uint64_t last_use;
+    };
+    std::vector<KvSlot> kv_slots;
+    uint64_t kv_tick;
+    int kv_src, kv_dst;               // slots the running request reads its prefix from / stores its prefix to
     std::vector<hipEvent_t> ev_pool;  // pairs
     std::vector<int> ev_kind;         // per pair: po_kernel_class
     size_t ev_used;
@@ -324,7 +332,9 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
         if (dt == PO_BF16 && cap_q > L.chunk) Cq = pick_chunk_rows(cap_q, {{qd + 2 * (int64_t)kvd, d}});
         else if (cap_q >= 2 * (int64_t)L.chunk) Cq = 2 * (int64_t)L.chunk;
         unsigned char* Xq = (Cq > L.chunk) ? H : Xn;
-        unsigned char* kc_l = c->kvc ? c->kvc + (size_t)l * c->kv_layer_bytes : nullptr;
+        const size_t slot_bytes = c->kv_layer_bytes * (size_t)m.n_layers;
+        const unsigned char* kc_l = c->kvc ? c->kvc + (size_t)c->kv_src * slot_bytes + (size_t)l * c->kv_layer_bytes : nullptr;
+        unsigned char* kd_l = c->kvc ? c->kvc + (size_t)c->kv_dst * slot_bytes + (size_t)l * c->kv_layer_bytes : nullptr;
         if (p_reuse > 0) {
             // cached prefix of this layer -> rows [0, p_reuse) of the one-layer K / V buffers
             PO_HIP(hipMemcpyAsync(K, kc_l, (size_t)p_reuse * kvd * esz, hipMemcpyDeviceToDevice, s));
@@ -369,15 +379,18 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                 launch_rope(dt, K + (size_t)r0 * kvd * esz, kvd, rc + t0, rs + t0, nr, m.n_kv_heads, hd, s);
             }
         }
-        if (p_store > p_reuse) {
-            // Section 5.1: keep the K/V of the prefix, discard the suffix's with the layer
-            const size_t r0 = (size_t)p_reuse, nr = (size_t)(p_store - p_reuse);
-            PO_HIP(hipMemcpyAsync(kc_l + r0 * kvd * esz, K + r0 * kvd * esz, nr * kvd * esz, hipMemcpyDeviceToDevice, s));
+        // Section 5.1: keep the K/V of the prefix, discard the suffix's with the layer.  Into the slot the
+        // prefix came from only the new rows go; another slot receives the whole prefix (the reused rows
+        // sit in the one-layer buffers by now).
+        const int64_t st0 = (c->kv_dst == c->kv_src) ? p_reuse : 0;
+        if (p_store > st0) {
+            const size_t r0 = (size_t)st0, nr = (size_t)(p_store - st0);
+            PO_HIP(hipMemcpyAsync(kd_l + r0 * kvd * esz, K + r0 * kvd * esz, nr * kvd * esz, hipMemcpyDeviceToDevice, s));
             if (dt == PO_BF16)
-                PO_HIP(hipMemcpy2DAsync(kc_l + c->kv_v_off + r0 * esz, (size_t)c->kv_ldv * esz, ws + L.Vt + r0 * esz,
+                PO_HIP(hipMemcpy2DAsync(kd_l + c->kv_v_off + r0 * esz, (size_t)c->kv_ldv * esz, ws + L.Vt + r0 * esz,
                                         (size_t)L.ldv * esz, nr * esz, kvd, hipMemcpyDeviceToDevice, s));
             else
-                PO_HIP(hipMemcpyAsync(kc_l + c->kv_v_off + r0 * kvd * esz, V + r0 * kvd * esz, nr * kvd * esz,
+                PO_HIP(hipMemcpyAsync(kd_l + c->kv_v_off + r0 * kvd * esz, V + r0 * kvd * esz, nr * kvd * esz,
                                       hipMemcpyDeviceToDevice, s));
         }
         // Nothing reads the last layer's output except the last position (one output token, Section 1):
@@ -593,6 +606,8 @@ po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t m
     c->kvc = nullptr;
     c->kv_cap = c->kv_ldv = 0;
     c->kv_layer_bytes = c->kv_v_off = 0;
+    c->kv_tick = 0;
+    c->kv_src = c->kv_dst = 0;
     c->ev_used = 0;
     memset(&c->stats, 0, sizeof(c->stats));
     c->stats.weights_bytes = c->lay.weights_bytes;
@@ -888,24 +903,70 @@ po_status po_kv_cache_bytes(const po_model_config* cfg, int64_t prefix_capacity,
     return PO_OK;
 }
 
-po_status po_attach_kv_cache(po_ctx* c, void* dev_cache, size_t bytes, int64_t prefix_capacity) {
+po_status po_attach_kv_cache_slots(po_ctx* c, void* dev_cache, size_t bytes, int64_t prefix_capacity, int32_t n_slots) {
     if (!c) return PO_ERR_INVALID_ARG;
     if (!dev_cache) {               // detach
         c->kvc = nullptr;
         c->kv_cap = 0;
-        c->kv_tokens.clear();
+        c->kv_slots.clear();
         return PO_OK;
     }
-    if (prefix_capacity <= 0 || ((uintptr_t)dev_cache % ALIGN)) return PO_ERR_INVALID_ARG;
+    if (prefix_capacity <= 0 || n_slots <= 0 || ((uintptr_t)dev_cache % ALIGN)) return PO_ERR_INVALID_ARG;
     if (prefix_capacity > c->max_len) return PO_ERR_TOO_LONG;
     size_t need = 0;
     po_status st = po_kv_cache_bytes(&c->cfg, prefix_capacity, &need);
     if (st != PO_OK) return st;
-    if (bytes < need) return PO_ERR_WORKSPACE_TOO_SMALL;
+    if (bytes / (size_t)n_slots < need) return PO_ERR_WORKSPACE_TOO_SMALL;
     c->kvc = (unsigned char*)dev_cache;
     c->kv_cap = prefix_capacity;
     kv_cache_geometry(&c->cfg, prefix_capacity, &c->kv_ldv, &c->kv_v_off, &c->kv_layer_bytes);
-    c->kv_tokens.clear();
+    c->kv_slots.assign((size_t)n_slots, po_ctx::KvSlot{{}, 0});
+    c->kv_tick = 0;
+    c->kv_src = c->kv_dst = 0;
+    return PO_OK;
+}
+
+po_status po_attach_kv_cache(po_ctx* c, void* dev_cache, size_t bytes, int64_t prefix_capacity) {
+    return po_attach_kv_cache_slots(c, dev_cache, bytes, prefix_capacity, 1);
+}
+
+namespace {
+// slot with the longest common prefix with tokens[0, len) (ties: the most recently used), and that length
+int best_slot(const po_ctx* c, const int32_t* tokens, int64_t len, int64_t* match) {
+    int best = 0;
+    int64_t best_m = -1;
+    for (size_t i = 0; i < c->kv_slots.size(); ++i) {
+        const std::vector<int32_t>& t = c->kv_slots[i].tokens;
+        const int64_t lim = std::min<int64_t>((int64_t)t.size(), len);
+        int64_t mm = 0;
+        while (mm < lim && t[(size_t)mm] == tokens[mm]) ++mm;
+        if (mm > best_m || (mm == best_m && c->kv_slots[i].last_use > c->kv_slots[(size_t)best].last_use)) {
+            best_m = mm;
+            best = (int)i;
+        }
+    }
+    *match = best_m < 0 ? 0 : best_m;
+    return best;
+}
+}  // namespace
+
+po_status po_kv_cache_match(const po_ctx* c, const int32_t* tokens, int64_t len, int64_t* cached_len) {
+    if (!c || !tokens || len <= 0 || !cached_len) return PO_ERR_INVALID_ARG;
+    int64_t mm = 0;
+    if (c->kvc) (void)best_slot(c, tokens, len, &mm);
+    *cached_len = std::min<int64_t>(mm, len - 1);          // one position is always computed
+    return PO_OK;
+}
+
+po_status po_kv_cache_slot(const po_ctx* c, int32_t slot, int32_t* tokens_out, int64_t capacity, int64_t* n_tokens) {
+    if (!c || !n_tokens || slot < 0) return PO_ERR_INVALID_ARG;
+    if ((size_t)slot >= c->kv_slots.size()) return PO_ERR_INVALID_ARG;
+    const std::vector<int32_t>& t = c->kv_slots[(size_t)slot].tokens;
+    *n_tokens = (int64_t)t.size();
+    if (tokens_out) {
+        if (capacity < (int64_t)t.size()) return PO_ERR_INVALID_ARG;
+        if (!t.empty()) memcpy(tokens_out, t.data(), t.size() * sizeof(int32_t));
+    }
     return PO_OK;
 }
 
@@ -918,16 +979,40 @@ po_status po_prefill_prefix(po_ctx* c, const int32_t* tokens, int64_t len, int64
     if (!c->kvc) return PO_ERR_INVALID_ARG;
     if (keep_prefix > len || keep_prefix > c->kv_cap) return PO_ERR_TOO_LONG;
     if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
-    // longest common prefix with what the cache holds; at least one position is always computed
-    int64_t m = 0;
-    const int64_t lim = std::min<int64_t>((int64_t)c->kv_tokens.size(), len - 1);
-    while (m < lim && c->kv_tokens[(size_t)m] == tokens[m]) ++m;
-    st = run_prefill(c, tokens, len, cand_ids, n_cand, out_logits, out_cand_logprobs, m, keep_prefix);
-    if (st != PO_OK) {              // the cache may be half written: forget it
-        c->kv_tokens.clear();
+    // the slot with the longest common prefix; at least one position is always computed
+    int64_t shared = 0;
+    const int src = best_slot(c, tokens, len, &shared);
+    const int64_t stored = (int64_t)c->kv_slots[(size_t)src].tokens.size();
+    const int64_t m = std::min<int64_t>(shared, len - 1);
+    // Where the prefix to keep goes.  Already inside the entry: nothing is stored and the entry stays as
+    // long as it is.  The request shares all the entry holds: the entry grows in place.  Otherwise (a
+    // partial or no hit) the prefix replaces the least recently used of the other entries, so that a
+    // partial hit does not cut a longer entry short; with one entry it replaces that one.
+    int dst = src;
+    int64_t store = keep_prefix;
+    if (keep_prefix <= shared) {
+        store = 0;
+    } else if (shared < stored && c->kv_slots.size() > 1) {
+        uint64_t oldest = ~0ull;
+        for (size_t i = 0; i < c->kv_slots.size(); ++i)
+            if ((int)i != src || shared == 0) {
+                const uint64_t u = c->kv_slots[i].tokens.empty() ? 0 : c->kv_slots[i].last_use;
+                if (u < oldest) { oldest = u; dst = (int)i; }
+            }
+    }
+    c->kv_src = src;
+    c->kv_dst = dst;
+    st = run_prefill(c, tokens, len, cand_ids, n_cand, out_logits, out_cand_logprobs, m, store);
+    if (st != PO_OK) {              // the destination may be half written: forget it
+        if (store > 0) c->kv_slots[(size_t)dst].tokens.clear();
         return st;
     }
-    if (keep_prefix > 0) c->kv_tokens.assign(tokens, tokens + keep_prefix);
+    ++c->kv_tick;
+    if (m > 0 || (keep_prefix > 0 && store == 0)) c->kv_slots[(size_t)src].last_use = c->kv_tick;
+    if (store > 0) {
+        c->kv_slots[(size_t)dst].tokens.assign(tokens, tokens + store);
+        c->kv_slots[(size_t)dst].last_use = c->kv_tick;
+    }
     if (reused_prefix_len) *reused_prefix_len = m;
     return PO_OK;
 }

@@ -7,6 +7,7 @@
 
 #include <stdint.h>
 
+#include <algorithm>
 #include <cmath>
 #include <limits>
 #include <new>
@@ -96,9 +97,11 @@ po_status po_sched_push(po_sched* s, int64_t id, const int32_t* tokens, int64_t 
 
 int64_t po_sched_size(const po_sched* s) { return s ? (int64_t)s->queue.size() : 0; }
 
-po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cached_tokens, double now, int64_t* id,
-                        int64_t* n_cached_hit) {
-    if (!s || !id || n_cached_tokens < 0 || (n_cached_tokens > 0 && !cached_tokens)) return PO_ERR_INVALID_ARG;
+po_status po_sched_pick_multi(po_sched* s, const int32_t* const* cached_tokens, const int64_t* n_cached_tokens,
+                              int32_t n_entries, double now, int64_t* id, int64_t* n_cached_hit) {
+    if (!s || !id || n_entries < 0 || (n_entries > 0 && (!cached_tokens || !n_cached_tokens))) return PO_ERR_INVALID_ARG;
+    for (int32_t e = 0; e < n_entries; ++e)
+        if (n_cached_tokens[e] < 0 || (n_cached_tokens[e] > 0 && !cached_tokens[e])) return PO_ERR_INVALID_ARG;
     *id = -1;
     if (n_cached_hit) *n_cached_hit = 0;
     size_t best = 0;
@@ -107,7 +110,8 @@ po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cac
     bool found = false;
     for (size_t i = 0; i < s->queue.size(); ++i) {
         const po_sched::Req& r = s->queue[i];
-        const int64_t hit = hit_len(r.tokens, cached_tokens, n_cached_tokens);
+        int64_t hit = 0;            // the best any cache entry offers this request
+        for (int32_t e = 0; e < n_entries; ++e) hit = std::max(hit, hit_len(r.tokens, cached_tokens[e], n_cached_tokens[e]));
         const double n_in = (double)r.tokens.size();
         const double jct = s->linear ? s->c0 + s->c_input * n_in + s->c_cached * (double)hit : n_in - (double)hit;
         const double score = jct - s->lambda * (now - r.arrival);
@@ -118,6 +122,12 @@ po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cac
     if (n_cached_hit) *n_cached_hit = best_hit;
     s->queue.erase(s->queue.begin() + (std::ptrdiff_t)best);
     return PO_OK;
+}
+
+po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cached_tokens, double now, int64_t* id,
+                        int64_t* n_cached_hit) {
+    if (n_cached_tokens < 0 || (n_cached_tokens > 0 && !cached_tokens)) return PO_ERR_INVALID_ARG;
+    return po_sched_pick_multi(s, &cached_tokens, &n_cached_tokens, 1, now, id, n_cached_hit);
 }
 
 #pragma GCC visibility pop

@@ -375,6 +375,74 @@ def test_prefix_cache_reuse_is_bitwise(cfg, n, keep):
         ctx.po_destroy()
 
 
+@pytest.mark.parametrize("cfg", [I.TINY, I.TINY.replace(dtype=I.BF16, ffn_dim=704), I.TINY.replace(dtype=I.BF16_FP8, ffn_dim=768)],
+                         ids=["f32", "bf16", "fp8"])
+def test_prefix_cache_with_several_entries(cfg):
+    """Section 5.1 with a cache of three entries: which entry a request reuses, where the prefix it keeps
+    goes (inside an entry: nothing stored; all of an entry shared: grows in place; otherwise the least
+    recently used other entry), and the same bits as an uncached run every time."""
+    rng = np.random.default_rng(23)
+    V = cfg.vocab_size
+    tok = lambda n: rng.integers(0, V, n).astype(np.int32)
+    p1, p2, p3, p4 = tok(300), tok(260), tok(200), tok(150)
+    ctx = make_ctx(cfg, 19, 800, 256)
+    try:
+        cand = I.label_ids(cfg)
+        calls = []
+
+        def run(t, keep, want_reuse):
+            ref = ctx.po_prefill(t, cand)
+            assert ctx.po_kv_cache_match(t) == want_reuse
+            z, lp, r = ctx.po_prefill_prefix(t, keep, cand)
+            calls.append(len(calls))
+            assert r == want_reuse, (len(calls), r, want_reuse)
+            assert np.array_equal(z, ref[0]) and np.array_equal(lp, ref[1]), len(calls)
+
+        slots = lambda: [ctx.po_kv_cache_slot(i).tolist() for i in range(3)]
+        ctx.po_attach_kv_cache(600, n_slots=3)
+        assert ctx.po_kv_cache_match(p1) == 0 and slots() == [[], [], []]
+        a = np.concatenate([p1, tok(100)])
+        run(a, 300, 0)                                          # cold -> an empty entry
+        b = np.concatenate([p2, tok(50)])
+        run(b, 260, 0)                                          # no hit -> the next empty entry
+        assert sorted(map(len, slots())) == [0, 260, 300]
+        c = np.concatenate([p1, tok(200)])
+        run(c, 450, 300)                                        # shares all of entry p1: grows in place
+        assert sorted(map(len, slots())) == [0, 260, 450]
+        assert c[:450].tolist() in slots()
+        d = np.concatenate([p1[:120], tok(90)])
+        run(d, 200, 120)                                        # partial hit -> the empty entry, p1's stays whole
+        assert sorted(map(len, slots())) == [200, 260, 450]
+        run(c, 0, 450)                                          # the long entry is still there
+        run(c[:400], 380, 399)                                  # inside the entry: nothing stored, nothing cut
+        assert sorted(map(len, slots())) == [200, 260, 450]
+        # use order now: b's entry (oldest), d's, c's.  A miss replaces b's.
+        e = np.concatenate([p3, tok(60)])
+        run(e, 200, 0)
+        assert sorted(map(len, slots())) == [200, 200, 450] and p2.tolist() not in [s[:260] for s in slots()]
+        run(b, 0, 0)                                            # gone
+        run(d, 0, 200)                                          # d's entry is used again; use order now: c's, e's, d's
+        # partial hit on c's entry (the longest match): goes to the least recently used OTHER entry, c's stays
+        f = np.concatenate([c[:150], tok(90)])
+        run(f, 240, 150)
+        got = slots()
+        assert c[:450].tolist() in got and f[:240].tolist() in got and d[:200].tolist() in got
+        run(np.concatenate([p4, tok(10)]), 150, 0)              # a miss: replaces d's entry, the least recently used
+        got = slots()
+        assert p4.tolist() in got and f[:240].tolist() in got and c[:450].tolist() in got
+        run(c, 0, 450)
+        run(d, 0, 120)                                          # what c's and f's entries share with d
+        with pytest.raises(B.PoError):
+            ctx.po_kv_cache_slot(3)
+        # one entry: a partial hit replaces it
+        ctx.po_attach_kv_cache(600)
+        run(a, 300, 0)
+        run(d, 200, 120)
+        assert ctx.po_kv_cache_slot(0).tolist() == d[:200].tolist()
+    finally:
+        ctx.po_destroy()
+
+
 def test_scheduler_with_prefix_cache_end_to_end():
     """Sections 5.1 + 6.3 together on the paper's example shape: four requests, two shared prefixes, a
     cache that holds the last request; the calibrated order reuses twice, arrival order once."""

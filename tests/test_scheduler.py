@@ -92,6 +92,55 @@ def test_library_scheduler_matches_oracle():
         sch.po_sched_destroy()
 
 
+def test_oracle_pick_multi_by_brute_force():
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        entries = [rng.integers(0, 3, rng.integers(0, 12)).tolist() for _ in range(rng.integers(0, 4))]
+        queue = [(i, rng.integers(0, 3, rng.integers(1, 12)).tolist(), float(rng.uniform(0, 5))) for i in range(rng.integers(1, 6))]
+        now, lam = 6.0, float(rng.choice([0.0, 0.5, 500.0]))
+        scores, hits = [], []
+        for _, t, arr in queue:
+            best = 0
+            for e in entries:
+                m = 0
+                while m < min(len(t) - 1, len(e)) and t[m] == e[m]:
+                    m += 1
+                best = max(best, m)
+            hits.append(best)
+            scores.append((len(t) - best) - lam * (now - arr))
+        i, hit = S.pick_multi(queue, entries, now, lam)
+        assert i == scores.index(min(scores)) and hit == hits[i]
+        if len(entries) == 1:
+            assert (i, hit) == S.pick(queue, entries[0], now, lam)
+
+
+def test_library_pick_multi_matches_oracle():
+    """A cache of three entries replaced least-recently-used first, as the library's K/V cache does."""
+    rng = np.random.default_rng(7)
+    for trial in range(20):
+        lam = float(rng.choice([0.0, 3.0]))
+        sch = B.Scheduler(lam)
+        queue, entries, now = [], [], 0.0
+        for step in range(50):
+            if rng.random() < 0.6 or not queue:
+                src = entries[rng.integers(0, len(entries))] if entries and rng.random() < 0.6 else []
+                tok = list(src[:rng.integers(0, len(src) + 1)]) + rng.integers(0, 50, rng.integers(1, 30)).tolist()
+                rid = 1000 * trial + step
+                queue.append((rid, tok, now))
+                sch.po_sched_push(rid, tok, now)
+            else:
+                i, hit = S.pick_multi(queue, entries, now, lam)
+                assert sch.po_sched_pick_multi(entries, now) == (queue[i][0], hit)
+                entries = (entries + [queue.pop(i)[1]])[-3:]
+            now += float(rng.uniform(0, 0.5))
+        assert sch.po_sched_size() == len(queue)
+        sch.po_sched_destroy()
+    sch = B.Scheduler(0.0)
+    assert sch.po_sched_pick_multi([], 0.0) == (-1, 0)
+    sch.po_sched_push(1, [1, 2, 3], 0.0)
+    assert sch.po_sched_pick_multi([], 0.0) == (1, 0)
+
+
 def test_library_scheduler_on_the_papers_example():
     want = golden_example()["calibrated"]
     sch = B.Scheduler(0.0)
