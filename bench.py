@@ -136,6 +136,10 @@ def main():
     ap.add_argument("--reuse-prefix", type=int, default=0,
                     help="also time the first request again with the K/V of its first P tokens in the prefix "
                          "cache (reported under prefix_reuse; not part of value)")
+    ap.add_argument("--jct-profile", type=int, default=0, metavar="STEP",
+                    help="also profile the request time over (n_input, n_cached) pairs at this granularity in tokens "
+                         "(the paper uses 1000), fit the scheduler's linear model and report how well the number of "
+                         "cache-miss tokens tracks the time (reported under jct_profile; not part of value)")
     ap.add_argument("--fp8", action="store_true",
                     help="variant: the decoder's linear layers run FP8-dynamic (E4M3 weights per output channel, "
                          "activations per token); reported under its own metric name and dtype, never as the bf16 metric")
@@ -271,6 +275,24 @@ def main():
         out["prefix_reuse"] = {"request_tokens": lens[0], "reused_prefix_tokens": int(reused),
                                "ms_per_request": 1e3 * (time.perf_counter() - t0) / args.steps,
                                "kv_cache_bytes": int(cache_bytes)}
+    if args.jct_profile > 0:
+        import numpy as np
+        n_max = max(lens)
+        cache_bytes = ctx.po_attach_kv_cache(n_max - 1)
+        t0 = time.perf_counter()
+        n_in, n_c, ms = ctx.po_profile_jct(n_max, args.jct_profile)
+        wall = time.perf_counter() - t0
+        sch = B.Scheduler(0.0)
+        c0, c_in, c_cached = sch.po_sched_fit_jct_model(n_in, n_c, ms)
+        fit = c0 + c_in * n_in + c_cached * n_c
+        ss_res, ss_tot = float(np.sum((ms - fit) ** 2)), float(np.sum((ms - ms.mean()) ** 2))
+        out["jct_profile"] = {"max_len": n_max, "step": args.jct_profile, "pairs": int(len(ms)), "profile_seconds": wall,
+                              "linear_model_ms": {"c0": c0, "c_input": c_in, "c_cached": c_cached},
+                              "linear_model_r2": 1.0 - ss_res / ss_tot,
+                              "linear_model_max_abs_err_ms": float(np.max(np.abs(ms - fit))),
+                              "pearson_miss_tokens_vs_jct": float(np.corrcoef((n_in - n_c).astype(np.float64), ms)[0, 1]),
+                              "jct_ms_min_max": [float(ms.min()), float(ms.max())],
+                              "kv_cache_bytes": int(cache_bytes)}
     ctx.po_destroy()
     del ctx
     torch.cuda.empty_cache()

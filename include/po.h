@@ -232,6 +232,19 @@ po_status po_prefill_prefix(po_ctx* ctx, const int32_t* tokens, int64_t len, int
                             const int32_t* cand_ids, int32_t n_cand,
                             float* out_logits, float* out_cand_logprobs, int64_t* reused_prefix_len);
 
+/* Profiles how the job completion time varies with (n_input, n_cached) (Section 6.3: pairs that
+ * cover the maximum input length at a granularity of `step` tokens, 1000 in the paper; the
+ * scheduler's linear model is fitted on them, see po_sched_fit_jct_model).  Runs one fake request
+ * of pseudo-random token ids for every n_input in {step, 2 step, ..., max_len} and every
+ * n_cached in {0, step, ...} below n_input and within the cache's capacity, through the same
+ * path as po_prefill_prefix with that many positions reused, and reports the device time of
+ * each in milliseconds.  *n_samples receives the number of pairs; with all three output arrays
+ * NULL nothing runs (size query), otherwise capacity must be at least that number.  Needs an
+ * attached cache (PO_ERR_INVALID_ARG without) and loaded weights; max_len <= the context's.
+ * Synchronous; afterwards the cache is empty. */
+po_status po_profile_jct(po_ctx* ctx, int64_t max_len, int64_t step, int64_t* n_input_out,
+                         int64_t* n_cached_out, double* jct_ms_out, int32_t capacity, int32_t* n_samples);
+
 /* Request scheduling on the host (Section 6.3, Algorithm 1: shortest-remaining-job-first with
  * continuous JCT calibration).  The scheduler keeps the waiting requests (copies of their
  * tokens); every pick recomputes, for each of them, n_cached = the length of its common

@@ -37,6 +37,7 @@ EXPORTS = [
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
     "po_op_quantize_rows", "po_op_rmsnorm_quantize", "po_op_linear_fp8", "po_op_qkv_rope_fp8",
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
+    "po_profile_jct",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick",
 ]
@@ -97,6 +98,7 @@ def lib() -> C.CDLL:
     L.po_attach_kv_cache_slots.argtypes = [vp, vp, sz, i64, i32]
     L.po_kv_cache_match.argtypes = [vp, vp, i64, C.POINTER(i64)]
     L.po_kv_cache_slot.argtypes = [vp, i32, vp, i64, C.POINTER(i64)]
+    L.po_profile_jct.argtypes = [vp, i64, i64, vp, vp, vp, i32, C.POINTER(i32)]
     L.po_sched_pick_multi.argtypes = [vp, vp, vp, i32, C.c_double, C.POINTER(i64), C.POINTER(i64)]
     L.po_prefill_prefix.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, C.POINTER(i64)]
     L.po_get_stats.argtypes = [vp, C.POINTER(StatsC)]
@@ -265,6 +267,15 @@ class Context:
         check(lib().po_attach_kv_cache_slots(self._h, self._kvc.data_ptr(), total, prefix_capacity, n_slots))
         self._kv_slots = n_slots
         return total
+
+    def po_profile_jct(self, max_len: int, step: int):
+        """-> (n_input int64[], n_cached int64[], jct_ms float64[]) over the profiling grid."""
+        n = C.c_int32(0)
+        check(lib().po_profile_jct(self._h, max_len, step, None, None, None, 0, C.byref(n)))
+        a, b = np.empty(n.value, dtype=np.int64), np.empty(n.value, dtype=np.int64)
+        t = np.empty(n.value, dtype=np.float64)
+        check(lib().po_profile_jct(self._h, max_len, step, _host_ptr(a), _host_ptr(b), _host_ptr(t), n.value, C.byref(n)))
+        return a, b, t
 
     def po_kv_cache_match(self, tokens: np.ndarray) -> int:
         tok = np.ascontiguousarray(tokens, dtype=np.int32)

@@ -1017,6 +1017,64 @@ po_status po_prefill_prefix(po_ctx* c, const int32_t* tokens, int64_t len, int64
     return PO_OK;
 }
 
+po_status po_profile_jct(po_ctx* c, int64_t max_len, int64_t step, int64_t* n_input_out, int64_t* n_cached_out,
+                         double* jct_ms_out, int32_t capacity, int32_t* n_samples) {
+    if (!c || max_len <= 0 || step <= 0 || !n_samples || capacity < 0) return PO_ERR_INVALID_ARG;
+    if (max_len > c->max_len) return PO_ERR_TOO_LONG;
+    if (!c->kvc) return PO_ERR_INVALID_ARG;
+    if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
+    const int32_t V = c->cfg.vocab_size;
+    if (V < 2) return PO_ERR_BAD_CONFIG;
+    // the grid: n_input = step, 2 step, ... and max_len itself; n_cached = 0, step, ... below n_input and
+    // within what the cache can hold
+    std::vector<int64_t> n_in;
+    for (int64_t n = step; n < max_len; n += step) n_in.push_back(n);
+    n_in.push_back(max_len);
+    int64_t p_max = 0, count = 0;
+    for (int64_t n : n_in)
+        for (int64_t p = 0; p < n && p <= c->kv_cap; p += step) {
+            p_max = std::max(p_max, p);
+            ++count;
+        }
+    if (count > INT32_MAX) return PO_ERR_INVALID_ARG;
+    *n_samples = (int32_t)count;
+    if (!n_input_out && !n_cached_out && !jct_ms_out) return PO_OK;          // size query
+    if (!n_input_out || !n_cached_out || !jct_ms_out || capacity < count) return PO_ERR_INVALID_ARG;
+    // two fake token sequences that differ at every position, so that a request made of the first p ids of
+    // one and the rest of the other shares exactly p positions with the cached one.  Pseudo-random ids:
+    // a run on constant data draws less power and clocks higher than a real request does.
+    std::vector<int32_t> base((size_t)max_len), req((size_t)max_len);
+    uint64_t x = 0x9E3779B97F4A7C15ull;
+    for (int64_t i = 0; i < max_len; ++i) {
+        x = x * 6364136223846793005ull + 1442695040888963407ull;
+        base[(size_t)i] = (int32_t)((x >> 33) % (uint64_t)V);
+    }
+    const int32_t cand[2] = {0, V - 1};
+    float lp[2];
+    for (auto& sl : c->kv_slots) sl.tokens.clear();
+    c->kv_src = c->kv_dst = 0;
+    po_status st = PO_OK;
+    if (p_max > 0) {                                                         // fills entry 0; also the warm-up
+        st = run_prefill(c, base.data(), p_max, cand, 2, nullptr, lp, 0, p_max);
+    } else {
+        st = run_prefill(c, base.data(), n_in[0], cand, 2, nullptr, lp);
+    }
+    int32_t k = 0;
+    for (size_t a = 0; st == PO_OK && a < n_in.size(); ++a) {
+        const int64_t n = n_in[a];
+        for (int64_t p = 0; st == PO_OK && p < n && p <= c->kv_cap; p += step) {
+            for (int64_t i = 0; i < n; ++i) req[(size_t)i] = i < p ? base[(size_t)i] : (base[(size_t)i] + 1) % V;
+            st = run_prefill(c, req.data(), n, cand, 2, nullptr, lp, p, 0);
+            n_input_out[k] = n;
+            n_cached_out[k] = p;
+            jct_ms_out[k] = c->stats.last_prefill_ms;
+            ++k;
+        }
+    }
+    for (auto& sl : c->kv_slots) sl.tokens.clear();                          // the fake prefix serves nobody
+    return st;
+}
+
 po_status po_set_lazy_last_layer(po_ctx* c, int32_t on) {
     if (!c) return PO_ERR_INVALID_ARG;
     c->lazy_last_layer = on != 0;

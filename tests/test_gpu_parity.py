@@ -443,6 +443,48 @@ def test_prefix_cache_with_several_entries(cfg):
         ctx.po_destroy()
 
 
+def test_jct_profile_grid_and_fit():
+    """Section 6.3: JCT profiled over (n_input, n_cached) pairs at a fixed granularity, a linear model fitted
+    on them; the number of cache-miss tokens tracks the measured JCT (the paper reports a Pearson coefficient
+    of 0.987 on its hardware; the bar here is 0.9, on a 2-layer model where launch overheads weigh more)."""
+    cfg = I.LLAMA8B.replace(n_layers=2, vocab_size=4096)
+    ctx = make_ctx(cfg, 19, 8192, 4096)
+    try:
+        with pytest.raises(B.PoError):
+            ctx.po_profile_jct(8192, 1024)                       # no cache attached
+        ctx.po_attach_kv_cache(6144, n_slots=2)
+        n_in, n_c, ms = ctx.po_profile_jct(8192, 1024)
+        want = [(n, p) for n in range(1024, 8193, 1024) for p in range(0, min(n, 6145), 1024)]
+        assert list(zip(n_in.tolist(), n_c.tolist())) == want and len(want) == 35
+        assert np.all(ms > 0)
+        miss = (n_in - n_c).astype(np.float64)
+        r = float(np.corrcoef(miss, ms)[0, 1])
+        print(f"Pearson(miss tokens, JCT) = {r:.4f}; JCT {ms.min():.2f} .. {ms.max():.2f} ms")
+        assert r > 0.9
+        sch = B.Scheduler(0.0)
+        c0, c_in, c_cached = sch.po_sched_fit_jct_model(n_in, n_c, ms)
+        assert c_in > 0 and c_cached < 0
+        # at a fixed n_input more cached positions is never slower by more than noise
+        full = {(n, p): t for n, p, t in zip(n_in.tolist(), n_c.tolist(), ms.tolist())}
+        assert full[(8192, 6144)] < full[(8192, 0)] and full[(4096, 3072)] < full[(4096, 0)]
+        assert [len(ctx.po_kv_cache_slot(i)) for i in range(2)] == [0, 0]     # the fake prefix is gone
+        # a ragged maximum is covered too
+        n_in2, n_c2, _ = ctx.po_profile_jct(2500, 1000)
+        assert list(zip(n_in2.tolist(), n_c2.tolist())) == [(1000, 0), (2000, 0), (2000, 1000), (2500, 0), (2500, 1000), (2500, 2000)]
+        with pytest.raises(B.PoError):
+            ctx.po_profile_jct(8193, 1024)
+        # and the cache still serves real requests afterwards
+        t = I.make_tokens(cfg, 7, 1500)
+        cand = I.label_ids(cfg)
+        ref = ctx.po_prefill(t, cand)
+        z, lp, reused = ctx.po_prefill_prefix(t, 1000, cand)
+        assert reused == 0 and np.array_equal(z, ref[0])
+        z, lp, reused = ctx.po_prefill_prefix(t, 0, cand)
+        assert reused == 1000 and np.array_equal(z, ref[0]) and np.array_equal(lp, ref[1])
+    finally:
+        ctx.po_destroy()
+
+
 def test_scheduler_with_prefix_cache_end_to_end():
     """Sections 5.1 + 6.3 together on the paper's example shape: four requests, two shared prefixes, a
     cache that holds the last request; the calibrated order reuses twice, arrival order once."""
