@@ -119,6 +119,73 @@ def sample_shader_clock(run_step, n_steps=2):
     return busy[len(busy) // 2] if busy else None
 
 
+def serve(args, cfg, w, B, I):
+    """Section 7's evaluation loop on one GPU with synthetic requests: users arrive (all at once, or as a
+    Poisson process), each with all of its requests; every step the engine takes one waiting request.  The
+    service times are real (wall clock around po_engine_step, host scheduling included), the arrival
+    clock is simulated: it advances by each step's duration, or jumps to the next arrival when idle."""
+    import numpy as np
+    trace = I.make_serving_trace(cfg, args.serve, w["tseed"], args.serve_users, args.serve_posts)
+    users = [u for u, _ in trace]
+    n_users = len(set(users))
+    max_len = max(len(t) for _, t in trace)
+    cand = I.label_ids(cfg)
+    ctx = B.Context(cfg, max_len, w["chunk"])
+    ctx.load_synthetic(w["wseed"], threads=16)
+    cache_bytes = 0
+
+    def drain(lam, user_arrival):
+        nonlocal cache_bytes
+        cache_bytes = ctx.po_attach_kv_cache(max_len, n_slots=args.serve_slots)     # a fresh, empty cache
+        sch = B.Scheduler(lam)
+        # requests of one arrival instant keep the trace's order: a nanosecond apart
+        arr = [user_arrival[u] + 1e-9 * i for i, u in enumerate(users)]
+        todo = sorted(range(len(trace)), key=lambda i: arr[i])
+        now, k, done, busy, hits, tokens, computed = 0.0, 0, {}, 0.0, 0, 0, 0
+        while k < len(todo) or sch.po_sched_size():
+            while k < len(todo) and arr[todo[k]] <= now:
+                sch.po_sched_push(todo[k], trace[todo[k]][1], arr[todo[k]])
+                k += 1
+            if not sch.po_sched_size():
+                now = arr[todo[k]]
+                continue
+            t0 = time.perf_counter()
+            rid, n, reused, _, _ = ctx.po_engine_step(sch, now, cand)
+            dt = time.perf_counter() - t0
+            now += dt
+            busy += dt
+            done[rid] = now - arr[rid]
+            hits += reused > 0
+            tokens += n
+            computed += n - reused
+        lat = np.asarray([done[i] for i in range(len(trace))])
+        return {"requests_per_s": len(trace) / busy, "tokens_per_s": tokens / busy, "computed_tokens_per_s": computed / busy,
+                "busy_s": busy, "makespan_s": now, "mean_latency_s": float(lat.mean()), "p99_latency_s": float(np.percentile(lat, 99)),
+                "requests_that_reused_a_prefix": int(hits)}
+
+    x = drain(500.0, [0.0] * n_users)["requests_per_s"]                             # warm-up; sets the rate unit
+    rows = []
+    for rate in [float(r) for r in args.serve_rates.split(",")]:
+        if rate == 0:
+            ua = [0.0] * n_users
+        else:
+            ua = I.poisson_user_arrivals(w["tseed"], n_users, rate * x * n_users / len(trace)).tolist()
+        for policy, lam in (("arrival_order", 1e12), ("srjf_calibrated_lambda500", 500.0)):
+            r = drain(lam, ua)
+            r.update(policy=policy, arrival="all_at_once" if rate == 0 else f"poisson_{rate:g}x")
+            rows.append(r)
+    ctx.po_destroy()
+    best = max(r["requests_per_s"] for r in rows)
+    print(json.dumps({"metric": "prefill_only_serving_requests_per_s", "value": best, "unit": "requests/s", "n_gpus": 1,
+                      "higher_is_better": True, "dtype": "fp8_e4m3 linear layers, bf16 elsewhere" if args.fp8 else "bf16",
+                      "data": "synthetic", "vs_baseline": None,
+                      "config": {"workload": f"{args.serve} trace on the {args.workload} model shape", "users": n_users,
+                                 "requests": len(trace), "max_request_tokens": max_len,
+                                 "total_tokens": int(sum(len(t) for _, t in trace)),
+                                 "prefix_cache_entries": args.serve_slots, "prefix_cache_bytes": int(cache_bytes)},
+                      "runs": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +207,16 @@ def main():
                     help="also profile the request time over (n_input, n_cached) pairs at this granularity in tokens "
                          "(the paper uses 1000), fit the scheduler's linear model and report how well the number of "
                          "cache-miss tokens tracks the time (reported under jct_profile; not part of value)")
+    ap.add_argument("--serve", default="", choices=["", "postrec", "credit"],
+                    help="instead of the prefill metric: drain a synthetic serving trace with the structure of one of the "
+                         "paper's two evaluation workloads through po_engine_step (scheduler + prefix cache + prefill), "
+                         "arrival order against the calibrated schedule; prints its own JSON line")
+    ap.add_argument("--serve-users", type=int, default=0, help="override the trace's number of users")
+    ap.add_argument("--serve-posts", type=int, default=0, help="override the trace's requests per user")
+    ap.add_argument("--serve-slots", type=int, default=4, help="entries of the prefix cache")
+    ap.add_argument("--serve-rates", default="0,1",
+                    help="arrival rates to run, as multiples of the drain throughput measured with everything "
+                         "arriving at once (0 = all at once); users arrive as a Poisson process")
     ap.add_argument("--fp8", action="store_true",
                     help="variant: the decoder's linear layers run FP8-dynamic (E4M3 weights per output channel, "
                          "activations per token); reported under its own metric name and dtype, never as the bf16 metric")
@@ -165,6 +242,9 @@ def main():
         cfg = cfg.replace(n_layers=args.layers)
     if args.fp8:
         cfg = cfg.replace(dtype=I.BF16_FP8)
+    if args.serve:
+        serve(args, cfg, w, B, I)
+        return
     lens = [int(x) for x in I.workload_lengths(args.workload)]
     cand = I.label_ids(cfg)
     reqs = [I.make_tokens(cfg, w["tseed"], n, request=i) for i, n in enumerate(lens)]

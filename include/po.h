@@ -225,9 +225,11 @@ po_status po_kv_cache_slot(const po_ctx* ctx, int32_t slot, int32_t* tokens_out,
  * causal block for the rest).  *reused_prefix_len (may be NULL) reports that length.
  * keep_prefix > 0: afterwards some entry of the cache holds the K/V of tokens[0 .. keep_prefix)
  * (see po_attach_kv_cache_slots for which; keep_prefix <= len and <= prefix_capacity, else PO_ERR_TOO_LONG);
- * keep_prefix = 0 leaves the cache as it is.  The outputs are bit-identical to po_prefill
+ * keep_prefix = 0 leaves the cache as it is; keep_prefix = PO_KEEP_ALL keeps as much of the
+ * request as an entry holds, min(len, prefix_capacity).  The outputs are bit-identical to po_prefill
  * on the same tokens (a row's result does not depend on which other rows are computed).
  * PO_ERR_INVALID_ARG without an attached cache. */
+#define PO_KEEP_ALL (-1)
 po_status po_prefill_prefix(po_ctx* ctx, const int32_t* tokens, int64_t len, int64_t keep_prefix,
                             const int32_t* cand_ids, int32_t n_cand,
                             float* out_logits, float* out_cand_logprobs, int64_t* reused_prefix_len);
@@ -271,6 +273,19 @@ po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cac
  * offers it (cached_tokens[e] / n_cached_tokens[e], e < n_entries). */
 po_status po_sched_pick_multi(po_sched* s, const int32_t* const* cached_tokens, const int64_t* n_cached_tokens,
                               int32_t n_entries, double now, int64_t* id, int64_t* n_cached_hit);
+
+/* One step of the serving loop (Section 3: the scheduler hands the executor one request per
+ * step; Section 6.3: which one).  Scores every waiting request of `s` as po_sched_pick does,
+ * n_cached being what ctx's prefix cache would spare it at this moment (po_kv_cache_match; 0
+ * without a cache), removes the one with the lowest score from the queue and runs it: with a
+ * cache attached through po_prefill_prefix with keep_prefix = PO_KEEP_ALL, otherwise through
+ * po_prefill.  Outputs as there; *id receives the request's id (-1, and nothing runs, when
+ * the queue is empty), *len and *reused_prefix_len (both may be NULL) its length and the
+ * positions it did not compute.  A request whose run fails is NOT put back: the error is
+ * returned with *id set. */
+po_status po_engine_step(po_ctx* ctx, po_sched* s, double now, const int32_t* cand_ids, int32_t n_cand,
+                         float* out_logits, float* out_cand_logprobs, int64_t* id, int64_t* len,
+                         int64_t* reused_prefix_len);
 
 /* Last-layer shortcut, on by default.  A prefill-only request produces one token (Section 1),
  * so nothing reads the last layer's output except at the last position: with the shortcut

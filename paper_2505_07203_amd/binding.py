@@ -26,6 +26,7 @@ PO_ERR_OOM = 7
 PO_ERR_DEVICE = 8
 
 PO_F32, PO_BF16, PO_BF16_FP8 = 0, 1, 2
+PO_KEEP_ALL = -1
 KERNEL_CLASSES = ("attention", "qkv", "residual", "gate_up")   # po_kernel_class order
 
 EXPORTS = [
@@ -37,7 +38,7 @@ EXPORTS = [
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
     "po_op_quantize_rows", "po_op_rmsnorm_quantize", "po_op_linear_fp8", "po_op_qkv_rope_fp8",
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
-    "po_profile_jct",
+    "po_profile_jct", "po_engine_step",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick",
 ]
@@ -98,6 +99,7 @@ def lib() -> C.CDLL:
     L.po_attach_kv_cache_slots.argtypes = [vp, vp, sz, i64, i32]
     L.po_kv_cache_match.argtypes = [vp, vp, i64, C.POINTER(i64)]
     L.po_kv_cache_slot.argtypes = [vp, i32, vp, i64, C.POINTER(i64)]
+    L.po_engine_step.argtypes = [vp, vp, C.c_double, vp, i32, vp, vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     L.po_profile_jct.argtypes = [vp, i64, i64, vp, vp, vp, i32, C.POINTER(i32)]
     L.po_sched_pick_multi.argtypes = [vp, vp, vp, i32, C.c_double, C.POINTER(i64), C.POINTER(i64)]
     L.po_prefill_prefix.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, C.POINTER(i64)]
@@ -268,6 +270,11 @@ class Context:
         self._kv_slots = n_slots
         return total
 
+    def po_detach_kv_cache(self) -> None:
+        """po_attach_kv_cache with a NULL cache: detaches and releases it."""
+        check(lib().po_attach_kv_cache(self._h, None, 0, 0))
+        self._kvc = None
+
     def po_profile_jct(self, max_len: int, step: int):
         """-> (n_input int64[], n_cached int64[], jct_ms float64[]) over the profiling grid."""
         n = C.c_int32(0)
@@ -302,6 +309,18 @@ class Context:
         check(lib().po_prefill_prefix(self._h, _host_ptr(tok), tok.shape[0], keep_prefix, _host_ptr(cand_a), n_cand,
                                       _host_ptr(logits), _host_ptr(lp), C.byref(reused)))
         return logits, lp, reused.value
+
+    def po_engine_step(self, sched: "Scheduler", now: float, cand: Optional[Sequence[int]] = None,
+                       want_logits: bool = False):
+        """-> (id or -1, length, reused prefix length, logits or None, candidate log-probs or None)"""
+        n_cand = 0 if cand is None else len(cand)
+        cand_a = None if cand is None else np.ascontiguousarray(cand, dtype=np.int32)
+        logits = np.empty(self.cfg.vocab_size, dtype=np.float32) if want_logits else None
+        lp = np.empty(n_cand, dtype=np.float32) if n_cand else None
+        rid, n, reused = C.c_int64(-1), C.c_int64(0), C.c_int64(0)
+        check(lib().po_engine_step(self._h, sched._h, now, _host_ptr(cand_a), n_cand, _host_ptr(logits), _host_ptr(lp),
+                                   C.byref(rid), C.byref(n), C.byref(reused)))
+        return rid.value, n.value, reused.value, logits, lp
 
     def po_set_lazy_last_layer(self, on: bool) -> None:
         check(lib().po_set_lazy_last_layer(self._h, 1 if on else 0))

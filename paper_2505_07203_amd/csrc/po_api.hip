@@ -973,10 +973,11 @@ po_status po_kv_cache_slot(const po_ctx* c, int32_t slot, int32_t* tokens_out, i
 po_status po_prefill_prefix(po_ctx* c, const int32_t* tokens, int64_t len, int64_t keep_prefix,
                             const int32_t* cand_ids, int32_t n_cand, float* out_logits, float* out_cand_logprobs,
                             int64_t* reused_prefix_len) {
-    if (!c || keep_prefix < 0) return PO_ERR_INVALID_ARG;
+    if (!c || (keep_prefix < 0 && keep_prefix != PO_KEEP_ALL)) return PO_ERR_INVALID_ARG;
     po_status st = validate_request(c, tokens, len, cand_ids, n_cand);
     if (st != PO_OK) return st;
     if (!c->kvc) return PO_ERR_INVALID_ARG;
+    if (keep_prefix == PO_KEEP_ALL) keep_prefix = std::min<int64_t>(len, c->kv_cap);
     if (keep_prefix > len || keep_prefix > c->kv_cap) return PO_ERR_TOO_LONG;
     if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
     // the slot with the longest common prefix; at least one position is always computed

@@ -2,7 +2,8 @@
 // (Section 6.3, Algorithm 1).  Every pick re-evaluates the job completion time of every waiting
 // request against what the prefix cache holds NOW, so that requests that can hit the prefix a
 // just-finished request left behind are taken before the cache moves on; the queuing time, scaled
-// by lambda, is subtracted against starvation.  No device code: plain C++ behind the C ABI.
+// by lambda, is subtracted against starvation.  No device code: plain C++ behind the C ABI;
+// po_engine_step joins the scheduler to a context through the library's own public calls.
 #include "../../include/po.h"
 
 #include <stdint.h>
@@ -122,6 +123,40 @@ po_status po_sched_pick_multi(po_sched* s, const int32_t* const* cached_tokens, 
     if (n_cached_hit) *n_cached_hit = best_hit;
     s->queue.erase(s->queue.begin() + (std::ptrdiff_t)best);
     return PO_OK;
+}
+
+po_status po_engine_step(po_ctx* ctx, po_sched* s, double now, const int32_t* cand_ids, int32_t n_cand,
+                         float* out_logits, float* out_cand_logprobs, int64_t* id, int64_t* len,
+                         int64_t* reused_prefix_len) {
+    if (!ctx || !s || !id) return PO_ERR_INVALID_ARG;
+    *id = -1;
+    if (len) *len = 0;
+    if (reused_prefix_len) *reused_prefix_len = 0;
+    if (s->queue.empty()) return PO_OK;
+    int64_t n_slot0 = 0;
+    const bool cached = po_kv_cache_slot(ctx, 0, nullptr, 0, &n_slot0) == PO_OK;      // a cache is attached
+    size_t best = 0;
+    double best_score = std::numeric_limits<double>::infinity();
+    for (size_t i = 0; i < s->queue.size(); ++i) {
+        const po_sched::Req& r = s->queue[i];
+        int64_t hit = 0;
+        if (cached) {
+            const po_status st = po_kv_cache_match(ctx, r.tokens.data(), (int64_t)r.tokens.size(), &hit);
+            if (st != PO_OK) return st;
+        }
+        const double n_in = (double)r.tokens.size();
+        const double jct = s->linear ? s->c0 + s->c_input * n_in + s->c_cached * (double)hit : n_in - (double)hit;
+        const double score = jct - s->lambda * (now - r.arrival);
+        if (i == 0 || score < best_score) { best = i; best_score = score; }
+    }
+    po_sched::Req r = std::move(s->queue[best]);
+    s->queue.erase(s->queue.begin() + (std::ptrdiff_t)best);
+    *id = r.id;
+    if (len) *len = (int64_t)r.tokens.size();
+    if (cached)
+        return po_prefill_prefix(ctx, r.tokens.data(), (int64_t)r.tokens.size(), PO_KEEP_ALL, cand_ids, n_cand, out_logits,
+                                 out_cand_logprobs, reused_prefix_len);
+    return po_prefill(ctx, r.tokens.data(), (int64_t)r.tokens.size(), cand_ids, n_cand, out_logits, out_cand_logprobs);
 }
 
 po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cached_tokens, double now, int64_t* id,

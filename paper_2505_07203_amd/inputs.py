@@ -241,3 +241,44 @@ def workload_lengths(name: str) -> np.ndarray:
     if "lens" in w:
         return np.asarray(w["lens"], dtype=np.int64)
     return make_lengths(w["lseed"], w["n_req"])
+
+
+# Serving traces with the structure of the paper's two evaluation workloads (Section 7.1, dataset
+# table): synthetic token ids, the table's user counts, lengths and sharing pattern.
+#   postrec: every user has a profile of profile_lo..profile_hi tokens and posts_per_user requests,
+#            each the profile followed by one post of post_len tokens (so a user's requests share the profile);
+#   credit:  every user has one request of profile_lo..profile_hi tokens, nothing shared.
+SERVING = {
+    "postrec": dict(n_users=20, posts_per_user=50, profile_lo=11000, profile_hi=17000, post_len=150),
+    "credit": dict(n_users=60, posts_per_user=1, profile_lo=40000, profile_hi=60000, post_len=0),
+}
+
+
+def make_serving_trace(cfg: ModelConfig, name: str, seed: int, n_users: int = 0, posts_per_user: int = 0,
+                       scale: float = 1.0):
+    """-> list of (user, tokens), user by user; `scale` shrinks every length (tests), the two counts
+    override the table's."""
+    r = dict(SERVING[name])
+    if n_users:
+        r["n_users"] = n_users
+    if posts_per_user:
+        r["posts_per_user"] = posts_per_user
+    g = np.random.Generator(np.random.Philox(key=[int(seed), (3 << 48)]))
+    out = []
+    for u in range(r["n_users"]):
+        n_prof = max(1, int(round(int(g.integers(r["profile_lo"], r["profile_hi"] + 1)) * scale)))
+        profile = make_tokens(cfg, seed, n_prof, request=1_000_000 + u)
+        n_post = int(round(r["post_len"] * scale)) if r["post_len"] else 0
+        for k in range(r["posts_per_user"]):
+            if n_post:
+                post = make_tokens(cfg, seed, n_post, request=2_000_000 + u * 10_000 + k)
+                out.append((u, np.concatenate([profile, post])))
+            else:
+                out.append((u, profile))
+    return out
+
+
+def poisson_user_arrivals(seed: int, n_users: int, users_per_second: float) -> np.ndarray:
+    """Arrival time of each user (all of a user's requests arrive with the user): a Poisson process."""
+    g = np.random.Generator(np.random.Philox(key=[int(seed), (4 << 48)]))
+    return np.cumsum(g.exponential(1.0 / users_per_second, size=int(n_users)))

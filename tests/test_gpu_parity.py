@@ -485,6 +485,78 @@ def test_jct_profile_grid_and_fit():
         ctx.po_destroy()
 
 
+def test_engine_step_matches_a_hand_driven_loop():
+    """Sections 3 + 5.1 + 6.3 in one call: po_engine_step must take the request the oracle's scheduler takes
+    against the cache's current entries, run it with the prefix cache, and return the bits of an uncached
+    run.  Trace: the paper's post-recommendation structure scaled down (users with a profile, several posts
+    each), requests pushed interleaved over users so that arrival order is the worst order for the cache."""
+    from oracle import scheduler_oracle as S
+    cfg = I.TINY.replace(dtype=I.BF16, ffn_dim=704)
+    trace = I.make_serving_trace(cfg, "postrec", 11, n_users=4, posts_per_user=4, scale=0.03)
+    by_user = {}
+    for u, t in trace:
+        by_user.setdefault(u, []).append(t)
+    reqs = [by_user[u][k] for k in range(4) for u in range(4)]                 # round robin over users
+    arrival = [0.001 * i for i in range(len(reqs))]
+    cand = I.label_ids(cfg)
+    ctx = make_ctx(cfg, 19, max(len(t) for t in reqs), 256)
+    try:
+        ref = [ctx.po_prefill(t, cand, want_logits=False)[1] for t in reqs]
+
+        def engine(lam, slots):
+            if slots:
+                ctx.po_attach_kv_cache(ctx.max_input_len, n_slots=slots)
+            sch = B.Scheduler(lam)
+            for i, t in enumerate(reqs):
+                sch.po_sched_push(i, t, arrival[i])
+            order, reuse = [], []
+            while True:
+                rid, n, reused, _, lp = ctx.po_engine_step(sch, 1.0, cand)
+                if rid < 0:
+                    break
+                assert n == len(reqs[rid]) and np.array_equal(lp, ref[rid]), rid
+                order.append(rid)
+                reuse.append(reused)
+            assert sch.po_sched_size() == 0 and sorted(order) == list(range(len(reqs)))
+            return order, reuse
+
+        def by_hand(lam, slots):
+            ctx.po_attach_kv_cache(ctx.max_input_len, n_slots=slots)
+            queue = [(i, t.tolist(), arrival[i]) for i, t in enumerate(reqs)]
+            order, reuse = [], []
+            while queue:
+                entries = [ctx.po_kv_cache_slot(k).tolist() for k in range(slots)]
+                i, hit = S.pick_multi(queue, entries, 1.0, lam)
+                rid = queue.pop(i)[0]
+                _, lp, reused = ctx.po_prefill_prefix(reqs[rid], B.PO_KEEP_ALL, cand, want_logits=False)
+                assert reused == hit and np.array_equal(lp, ref[rid])
+                order.append(rid)
+                reuse.append(reused)
+            return order, reuse
+
+        for lam, slots in ((0.0, 2), (0.0, 1), (1e9, 2), (500.0, 3)):
+            assert engine(lam, slots) == by_hand(lam, slots), (lam, slots)
+        # calibrated: once a user's profile is cached the user's other posts come next -> 12 of 16 reuse it;
+        # arrival order over 4 users thrashes a 2-entry cache
+        hits = lambda r: sum(x > 0 for x in r)
+        assert hits(engine(0.0, 2)[1]) == 12 and hits(engine(1e9, 2)[1]) == 0
+        assert engine(1e9, 2)[0] == list(range(len(reqs)))                     # lambda -> infinity is arrival order
+        # without a cache the step still schedules (shortest first) and runs po_prefill
+        ctx.po_detach_kv_cache()
+        order, reuse = engine(0.0, 0)
+        assert reuse == [0] * len(reqs) and [len(reqs[i]) for i in order] == sorted(len(t) for t in reqs)
+        # a request the context cannot run is dropped with an error, the queue moves on
+        sch = B.Scheduler(0.0)
+        sch.po_sched_push(7, np.zeros(ctx.max_input_len + 1, dtype=np.int32), 0.0)
+        sch.po_sched_push(8, reqs[0], 0.0)
+        with pytest.raises(B.PoError):
+            ctx.po_engine_step(sch, 0.0, cand)          # shortest first: request 8 runs ...
+            ctx.po_engine_step(sch, 0.0, cand)          # ... then 7 fails
+        assert sch.po_sched_size() == 0
+    finally:
+        ctx.po_destroy()
+
+
 def test_scheduler_with_prefix_cache_end_to_end():
     """Sections 5.1 + 6.3 together on the paper's example shape: four requests, two shared prefixes, a
     cache that holds the last request; the calibrated order reuses twice, arrival order once."""
