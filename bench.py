@@ -132,6 +132,7 @@ def serve(args, cfg, w, B, I):
     cand = I.label_ids(cfg)
     ctx = B.Context(cfg, max_len, w["chunk"])
     ctx.load_synthetic(w["wseed"], threads=16)
+    ctx.po_set_few_rows_split(not args.serve_default_path)
     cache_bytes = 0
 
     def drain(lam, user_arrival):
@@ -182,7 +183,8 @@ def serve(args, cfg, w, B, I):
                       "config": {"workload": f"{args.serve} trace on the {args.workload} model shape", "users": n_users,
                                  "requests": len(trace), "max_request_tokens": max_len,
                                  "total_tokens": int(sum(len(t) for _, t in trace)),
-                                 "prefix_cache_entries": args.serve_slots, "prefix_cache_bytes": int(cache_bytes)},
+                                 "prefix_cache_entries": args.serve_slots, "prefix_cache_bytes": int(cache_bytes),
+                                 "few_rows_split": not args.serve_default_path},
                       "runs": rows}))
 
 
@@ -214,6 +216,8 @@ def main():
     ap.add_argument("--serve-users", type=int, default=0, help="override the trace's number of users")
     ap.add_argument("--serve-posts", type=int, default=0, help="override the trace's requests per user")
     ap.add_argument("--serve-slots", type=int, default=4, help="entries of the prefix cache")
+    ap.add_argument("--serve-default-path", action="store_true",
+                    help="serve on the default (bit-reproducible across row sets) path instead of few-rows mode")
     ap.add_argument("--serve-rates", default="0,1",
                     help="arrival rates to run, as multiples of the drain throughput measured with everything "
                          "arriving at once (0 = all at once); users arrive as a Poisson process")

@@ -102,6 +102,8 @@ typedef struct {
     uint64_t weights_bytes;               /* size of the weight arena in use                               */
     uint64_t workspace_bytes;             /* size of the activation arena in use (peak; static)            */
     int64_t last_len;                     /* tokens in the last request                                    */
+    int64_t split_launches;               /* GEMM / attention launches of the last request that ran split
+                                             (po_set_few_rows_split); 0 on the default path               */
 } po_stats;
 
 typedef struct po_ctx po_ctx;
@@ -293,6 +295,20 @@ po_status po_engine_step(po_ctx* ctx, po_sched* s, double now, const int32_t* ca
  * row block that holds the last position and the O-projection and MLP only for that row.
  * Logits and log-probs are bit-identical with the shortcut on and off. */
 po_status po_set_lazy_last_layer(po_ctx* ctx, int32_t on);
+
+/* Few-rows mode, off by default (bf16 contexts; FP8-dynamic contexts split only attention, fp32 ignores it).  A request that computes few
+ * positions -- a short one, or the suffix behind a long cached prefix, the paper's post
+ * recommendation case (Sections 2.2, 5.1) -- gives the QKV, O- and MLP down projections too
+ * few output tiles, and attention too few query tiles, to occupy the chip.  With the mode on,
+ * launches of those GEMMs whose tiles would fill at most half the compute units split their
+ * reduction over K between workgroups, and attention over at most 1024 query rows splits each
+ * query tile's keys between workgroups (fp32 partial results in the free part of the chunk
+ * buffer, merged in a fixed order by a second kernel: deterministic; the footprint
+ * po_workspace_bytes reports is unchanged).  A split sum is rounded differently
+ * from the single running sum of the default path: results stay within the library's
+ * tolerance against the definition but are no longer bit-identical to the default path's,
+ * nor between a request run alone and the same rows computed as part of a larger chunk. */
+po_status po_set_few_rows_split(po_ctx* ctx, int32_t on);
 
 /* When on, po_prefill brackets the attention and GEMM launches with HIP events on its stream
  * so that po_get_stats can split the time per kernel class (adds event overhead; off by

@@ -38,7 +38,7 @@ EXPORTS = [
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
     "po_op_quantize_rows", "po_op_rmsnorm_quantize", "po_op_linear_fp8", "po_op_qkv_rope_fp8",
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
-    "po_profile_jct", "po_engine_step",
+    "po_profile_jct", "po_engine_step", "po_set_few_rows_split",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick",
 ]
@@ -54,7 +54,8 @@ class ModelConfigC(C.Structure):
 class StatsC(C.Structure):
     _fields_ = [("last_prefill_ms", C.c_double), ("kernel_ms", C.c_double * 4),
                 ("kernel_launches", C.c_int64 * 4), ("weights_bytes", C.c_uint64),
-                ("workspace_bytes", C.c_uint64), ("last_len", C.c_int64)]
+                ("workspace_bytes", C.c_uint64), ("last_len", C.c_int64),
+                ("split_launches", C.c_int64)]
 
 
 class PoError(RuntimeError):
@@ -99,6 +100,7 @@ def lib() -> C.CDLL:
     L.po_attach_kv_cache_slots.argtypes = [vp, vp, sz, i64, i32]
     L.po_kv_cache_match.argtypes = [vp, vp, i64, C.POINTER(i64)]
     L.po_kv_cache_slot.argtypes = [vp, i32, vp, i64, C.POINTER(i64)]
+    L.po_set_few_rows_split.argtypes = [vp, i32]
     L.po_engine_step.argtypes = [vp, vp, C.c_double, vp, i32, vp, vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     L.po_profile_jct.argtypes = [vp, i64, i64, vp, vp, vp, i32, C.POINTER(i32)]
     L.po_sched_pick_multi.argtypes = [vp, vp, vp, i32, C.c_double, C.POINTER(i64), C.POINTER(i64)]
@@ -321,6 +323,9 @@ class Context:
         check(lib().po_engine_step(self._h, sched._h, now, _host_ptr(cand_a), n_cand, _host_ptr(logits), _host_ptr(lp),
                                    C.byref(rid), C.byref(n), C.byref(reused)))
         return rid.value, n.value, reused.value, logits, lp
+
+    def po_set_few_rows_split(self, on: bool) -> None:
+        check(lib().po_set_few_rows_split(self._h, 1 if on else 0))
 
     def po_set_lazy_last_layer(self, on: bool) -> None:
         check(lib().po_set_lazy_last_layer(self._h, 1 if on else 0))

@@ -24,6 +24,8 @@
 // that XCD's L2.
 #include "po_internal.h"
 
+#include <algorithm>
+
 namespace po {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -35,11 +37,16 @@ constexpr int BNK = 64;   // keys per tile
 
 __device__ __forceinline__ int swz8(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-template <int HD, int QT, int NW>
+// SPLIT (few query rows against many keys, e.g. a short suffix behind a long cached prefix): query tiles
+// start at row q_row0, and the key tiles of a query tile are divided between n_split workgroups; each
+// writes its unnormalised fp32 accumulators to opart[split][row - q_row0][head][HD] and its running
+// maximum and row sum to mlpart[split][row - q_row0][head][2]; attn_combine_kernel merges them.
+template <int HD, int QT, int NW, bool SPLIT>
 __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, const bf16_t* __restrict__ k,
                                                            const bf16_t* __restrict__ vt, int64_t ldv, bf16_t* o,
                                                            int N, int Hq, int Hkv, float sc_log2e, int nqt,
-                                                           int hpx) {
+                                                           int hpx, int q_row0, int n_split, float* opart,
+                                                           float* mlpart) {
     constexpr int NT = NW * 64;
     constexpr int BMQ = NW * QT * 32;
     constexpr int KS = HD / 16;            // k-steps of S^T = K Q^T
@@ -51,8 +58,13 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
     constexpr int VLD = (HD * 8) / NT;         // ... for V^T
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    int qtile, head;
-    if (hpx > 0) {
+    int qtile, head, split = 0;
+    if (SPLIT) {
+        split = blockIdx.x % n_split;
+        const int rest = blockIdx.x / n_split;
+        head = rest % Hq;
+        qtile = rest / Hq;
+    } else if (hpx > 0) {
         const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
         qtile = nqt - 1 - j / hpx;
         head = xcd * hpx + j % hpx;
@@ -63,11 +75,15 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
     const int kvh = head / (Hq / Hkv);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l31 = lane & 31, lhi = lane >> 5;
-    const int qb = qtile * BMQ;
+    const int qb = (SPLIT ? q_row0 : 0) + qtile * BMQ;
     const int qw = qb + wave * (QT * 32);
     const int blk_last = min(N, qb + BMQ) - 1;
     const int n_kv_blk = blk_last / BNK + 1;
     const int n_kv_wave = (qw < N) ? (min(N, qw + QT * 32) - 1) / BNK + 1 : 0;
+    // this workgroup's key tiles [j_begin, j_end)
+    const int per_split = SPLIT ? (n_kv_blk + n_split - 1) / n_split : n_kv_blk;
+    const int j_begin = SPLIT ? min(split * per_split, n_kv_blk) : 0;
+    const int j_end = SPLIT ? min(j_begin + per_split, n_kv_blk) : n_kv_blk;
 
     // ---- Q fragments (B operand: lane = query column, 8 consecutive head-dim values)
     bf16x8 qf[QT][KS];
@@ -144,14 +160,14 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) { mrow[qt] = -1.0e30f; lrow[qt] = 0.f; }
 
-    PO_GLOAD(r, 0);
+    PO_GLOAD(r, j_begin);
     PO_SSTORE(0);
-    PO_GLOAD(r, 1);
-    PO_GLOAD(n, 2);
+    PO_GLOAD(r, j_begin + 1);
+    PO_GLOAD(n, j_begin + 2);
     __syncthreads();
-    for (int j = 0; j < n_kv_blk; ++j) {
+    for (int j = j_begin; j < j_end; ++j) {
         if (j < n_kv_wave) {
-            const unsigned char* sk = smem + (j & 1) * STAGE_BYTES;
+            const unsigned char* sk = smem + ((j - j_begin) & 1) * STAGE_BYTES;
             const unsigned char* sv = sk + TILE_BYTES;
             const int kv0 = j * BNK;
             // ---- S^T = K Q^T  (2 key tiles x QT query tiles)
@@ -239,7 +255,7 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
                 }
             }
         }
-        PO_SSTORE((j + 1) & 1);              // tile j+1 (loaded two iterations ago)
+        PO_SSTORE((j - j_begin + 1) & 1);    // tile j+1 (loaded two iterations ago)
         rk0 = nk0; rk1 = nk1; rk2 = nk2; rk3 = nk3;
         rv0 = nv0; rv1 = nv1; rv2 = nv2; rv3 = nv3;
         PO_GLOAD(n, j + 3);
@@ -258,6 +274,22 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
         const float ltot = lrow[qt] + __shfl_xor(lrow[qt], 32);
         const float inv = 1.0f / ltot;
         const int qrow = qw + qt * 32 + l31;
+        if (SPLIT) {
+            if (qrow < N) {
+                const int64_t slot = ((int64_t)split * (N - q_row0) + (qrow - q_row0)) * Hq + head;
+                float* op = opart + slot * HD + 4 * lhi;
+#pragma unroll
+                for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const float4 v = {oacc[ht][qt][rg * 4 + 0], oacc[ht][qt][rg * 4 + 1], oacc[ht][qt][rg * 4 + 2],
+                                          oacc[ht][qt][rg * 4 + 3]};
+                        *(float4*)(op + ht * 32 + rg * 8) = v;
+                    }
+                if (lhi == 0) *(float2*)(mlpart + slot * 2) = make_float2(mrow[qt], ltot);
+            }
+            continue;
+        }
         if (qrow < N) {
             bf16_t* op = o + ((int64_t)qrow * Hq + head) * HD + 4 * lhi;
 #pragma unroll
@@ -667,6 +699,37 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
     }
 }
 
+// o[row][head][:] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^((m_s - max m) sc_log2e); one thread per 4 values.
+template <int HD>
+__global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restrict__ opart, const float* __restrict__ mlpart,
+                                                           int n_split, int nq, int Hq, float sc_log2e, bf16_t* o,
+                                                           int q_row0) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    constexpr int PER = HD / 4;
+    if (i >= (int64_t)nq * Hq * PER) return;
+    const int64_t rh = i / PER;                       // (row - q_row0) * Hq + head
+    const int f = (int)(i - rh * PER) * 4;
+    const int64_t plane = (int64_t)nq * Hq;
+    float mx = -1.0e30f;
+    for (int sp = 0; sp < n_split; ++sp) mx = fmaxf(mx, mlpart[(sp * plane + rh) * 2]);
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+    float l = 0.f;
+    for (int sp = 0; sp < n_split; ++sp) {
+        const float2 ml = *(const float2*)(mlpart + (sp * plane + rh) * 2);
+        const float w = __builtin_amdgcn_exp2f((ml.x - mx) * sc_log2e);
+        const float4 v = *(const float4*)(opart + (sp * plane + rh) * HD + f);
+        acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+        l += w * ml.y;
+    }
+    const float inv = 1.0f / l;
+    const int64_t row = q_row0 + rh / Hq;
+    const int head = (int)(rh % Hq);
+    uint2 w2;
+    w2.x = (uint32_t)f2bf(acc.x * inv) | ((uint32_t)f2bf(acc.y * inv) << 16);
+    w2.y = (uint32_t)f2bf(acc.z * inv) | ((uint32_t)f2bf(acc.w * inv) << 16);
+    *(uint2*)(o + (row * Hq + head) * HD + f) = w2;
+}
+
 void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
                   int Hkv, int64_t q_row0, hipStream_t s) {
     constexpr int SMEM = 2 * A64_NSTAGE * A64_TILE;
@@ -691,7 +754,7 @@ void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, b
     constexpr int SMEM = 2 * 2 * BNK * HD * 2;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)attn_fwd_kernel<HD, QT, NW>,
+        (void)hipFuncSetAttribute((const void*)attn_fwd_kernel<HD, QT, NW, false>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
         attr_set = true;
     }
@@ -700,14 +763,54 @@ void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, b
     const float sc_log2e = (float)(1.4426950408889634 / sqrt((double)HD));
     // workgroups enumerate query tiles from the last one down: fewer of them = only the last tiles
     const int nsel = nqt - (int)((q_row0 > 0 && q_row0 < N) ? q_row0 / BMQ : 0);
-    hipLaunchKernelGGL((attn_fwd_kernel<HD, QT, NW>), dim3((unsigned)(nsel * Hq)), dim3(NW * 64), SMEM, s, q, k, vt,
-                       ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, hpx);
+    hipLaunchKernelGGL((attn_fwd_kernel<HD, QT, NW, false>), dim3((unsigned)(nsel * Hq)), dim3(NW * 64), SMEM, s, q, k, vt,
+                       ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, hpx, 0, 1, nullptr, nullptr);
+}
+
+template <int HD>
+int launch_split_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
+                   int Hkv, int64_t q_row0, float* scratch, size_t scratch_bytes, bool launch, hipStream_t s) {
+    constexpr int NW = 8, BMQ = NW * 32;
+    constexpr int SMEM = 2 * 2 * BNK * HD * 2;
+    const int64_t nq = N - q_row0;
+    if (nq <= 0 || nq > 4 * BMQ) return 0;
+    const int nqt = (int)((nq + BMQ - 1) / BMQ);
+    const int n_kv_first = (int)((std::min<int64_t>(N, q_row0 + BMQ) - 1) / BNK + 1);     // key tiles of the first query tile
+    // enough workgroups for 256 compute units, at least two key tiles per split
+    int n_split = 1;
+    while (n_split < 32 && (int64_t)nqt * Hq * n_split < 512 && n_kv_first >= 4 * n_split) n_split *= 2;
+    const size_t o_bytes = (size_t)n_split * nq * Hq * HD * sizeof(float), ml_bytes = (size_t)n_split * nq * Hq * 2 * sizeof(float);
+    if (n_split < 2 || o_bytes + ml_bytes > scratch_bytes) return 0;
+    if (!launch) return n_split;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)attn_fwd_kernel<HD, 1, NW, true>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+        attr_set = true;
+    }
+    float* opart = scratch;
+    float* mlpart = scratch + o_bytes / sizeof(float);
+    const float sc_log2e = (float)(1.4426950408889634 / sqrt((double)HD));
+    hipLaunchKernelGGL((attn_fwd_kernel<HD, 1, NW, true>), dim3((unsigned)(nqt * Hq * n_split)), dim3(NW * 64), SMEM, s, q,
+                       k, vt, ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, 0, (int)q_row0, n_split, opart, mlpart);
+    const int64_t n = nq * Hq * (HD / 4);
+    hipLaunchKernelGGL(attn_combine_kernel<HD>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, opart, mlpart, n_split,
+                       (int)nq, Hq, sc_log2e, o, (int)q_row0);
+    return n_split;
 }
 
 }  // namespace
 
 bool attention_mfma_supported(int Hq, int Hkv, int hd) {
     return (hd == 128 || hd == 64) && Hkv > 0 && Hq % Hkv == 0;
+}
+
+int launch_attention_mfma_split(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N,
+                                int Hq, int Hkv, int hd, int64_t q_row0, float* scratch, size_t scratch_bytes,
+                                bool launch, hipStream_t s) {
+    if (hd == 128) return launch_split_t<128>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, s);
+    if (hd == 64) return launch_split_t<64>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, s);
+    return 0;
 }
 
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N,

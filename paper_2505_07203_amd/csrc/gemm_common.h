@@ -216,6 +216,43 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams& p, const f32x16 
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_sched_barrier(0);
             }
+    } else if (EPI == EPI_PARTIAL) {
+        // split-K partial sums: staged like the residual epilogue, stored as fp32 (32 bytes per lane, a
+        // wavefront covering 8 rows x 256 bytes); p.dst is the split's float plane, p.ld its row pitch in floats
+        float* part = (float*)p.dst;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+#pragma unroll
+                for (int n2 = 0; n2 < 2; ++n2)
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        const f32x16& cc = acc[mi][2 * hf + n2];
+                        float4 v = {cc[4 * g4], cc[4 * g4 + 1], cc[4 * g4 + 2], cc[4 * g4 + 3]};
+                        const int grp = n2 * 8 + 2 * g4 + ehi;
+                        *(float4*)(stg + e31 * 256 + ((grp ^ (e31 & 15)) << 4)) = v;
+                    }
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                const int col = col_base + hf * 64 + (elane & 7) * 8;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int rl = i * 8 + (elane >> 3);
+                    const int row = row_base + mi * 32 + rl;
+                    const int g0 = (elane & 7) * 2;
+                    const float4 x0 = *(const float4*)(stg + rl * 256 + ((g0 ^ (rl & 15)) << 4));
+                    const float4 x1 = *(const float4*)(stg + rl * 256 + (((g0 + 1) ^ (rl & 15)) << 4));
+                    if (row < p.M && col < p.N) {
+                        *(float4*)(part + (int64_t)row * p.ld + col) = x0;
+                        *(float4*)(part + (int64_t)row * p.ld + col + 4) = x1;
+                    }
+                }
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
     } else if (EPI == EPI_STORE) {
         // 32 rows x 128 features at a time as bf16 (256-byte rows, 16 groups)
 #pragma unroll

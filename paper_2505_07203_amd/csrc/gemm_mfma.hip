@@ -88,11 +88,15 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     // Each operand is addressed through a buffer resource that starts at the tile's first row and ends with
     // the matrix: the per-lane byte offset never changes, the slice offset is one scalar, and rows of a
     // ragged last tile beyond the matrix read as zero instead of needing a clamp (they are never stored).
-    const uint64_t a_bytes = (uint64_t)(p.M - m0) * (uint64_t)p.lda * 2, w_bytes = (uint64_t)(p.N - n0) * (uint64_t)p.ldw * 2;
+    // (split-K launches: workgroup row blockIdx.y works on columns [k0, k0 + K) of both operands; the
+    // resources start k0 elements later and end with the matrix all the same)
+    const int64_t k0 = (EPI == EPI_PARTIAL) ? (int64_t)blockIdx.y * p.K : 0;
+    const uint64_t a_bytes = (uint64_t)(p.M - m0) * (uint64_t)p.lda * 2 - (uint64_t)k0 * 2,
+                   w_bytes = (uint64_t)(p.N - n0) * (uint64_t)p.ldw * 2 - (uint64_t)k0 * 2;
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(p.A + (int64_t)m0 * p.lda), 0, (int)(uint32_t)(a_bytes > 0xffffffffull ? 0xffffffffull : a_bytes), 0x00020000);
+        (void*)(p.A + (int64_t)m0 * p.lda + k0), 0, (int)(uint32_t)(a_bytes > 0xffffffffull ? 0xffffffffull : a_bytes), 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(p.W + (int64_t)n0 * p.ldw), 0, (int)(uint32_t)(w_bytes > 0xffffffffull ? 0xffffffffull : w_bytes), 0x00020000);
+        (void*)(p.W + (int64_t)n0 * p.ldw + k0), 0, (int)(uint32_t)(w_bytes > 0xffffffffull ? 0xffffffffull : w_bytes), 0x00020000);
     uint32_t voa[8], vow[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -214,11 +218,81 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     // the clamped tail loads have landed and every wavefront has finished reading the ring
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-    tile_epilogue<EPI>(p, acc, smem, m0, n0, wave, lane);
+    if (EPI == EPI_PARTIAL) {
+        GemmParams q = p;
+        q.dst = (bf16_t*)((float*)p.dst + (int64_t)blockIdx.y * p.ldr);     // this split's plane
+        tile_epilogue<EPI>(q, acc, smem, m0, n0, wave, lane);
+    } else {
+        tile_epilogue<EPI>(p, acc, smem, m0, n0, wave, lane);
+    }
+}
+
+// C[row][col .. col+7] = bf16(sum over splits of part[s][row][col ..] + R[row][col ..]); one thread per 8 features.
+__global__ void __launch_bounds__(256) splitk_reduce_residual_kernel(const float* __restrict__ part, int64_t plane,
+                                                                     int splits, const bf16_t* R, int64_t ldr,
+                                                                     bf16_t* C, int64_t ldc, int M, int N) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int n8 = N >> 3;
+    if (i >= (int64_t)M * n8) return;
+    const int row = (int)(i / n8), col = (int)(i - (int64_t)row * n8) * 8;
+    const float* pp = part + (int64_t)row * N + col;
+    float4 a = *(const float4*)pp, b = *(const float4*)(pp + 4);
+    for (int sidx = 1; sidx < splits; ++sidx) {
+        const float4 x = *(const float4*)(pp + sidx * plane), y = *(const float4*)(pp + sidx * plane + 4);
+        a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w;
+        b.x += y.x; b.y += y.y; b.z += y.z; b.w += y.w;
+    }
+    const uint4 r = *(const uint4*)(R + (int64_t)row * ldr + col);
+    uint4 o;
+    o.x = (uint32_t)f2bf(a.x + __uint_as_float(r.x << 16)) | ((uint32_t)f2bf(a.y + __uint_as_float(r.x & 0xffff0000u)) << 16);
+    o.y = (uint32_t)f2bf(a.z + __uint_as_float(r.y << 16)) | ((uint32_t)f2bf(a.w + __uint_as_float(r.y & 0xffff0000u)) << 16);
+    o.z = (uint32_t)f2bf(b.x + __uint_as_float(r.z << 16)) | ((uint32_t)f2bf(b.y + __uint_as_float(r.z & 0xffff0000u)) << 16);
+    o.w = (uint32_t)f2bf(b.z + __uint_as_float(r.w << 16)) | ((uint32_t)f2bf(b.w + __uint_as_float(r.w & 0xffff0000u)) << 16);
+    *(uint4*)(C + (int64_t)row * ldc + col) = o;
+}
+
+// QKV after a split-K GEMM: one workgroup = one 64-column patch x 8 token rows.  Sums the splits' partials,
+// then does what the fused QKV epilogue does with an accumulator patch: + bias, rotary embedding of the
+// pair (column j, column j + 32) of a Q / K patch, V stored transposed.  Thread mapping: Q / K patches
+// column-fastest (row stores are contiguous), V patches row-fastest (V^T columns are contiguous).
+__global__ void __launch_bounds__(256) splitk_reduce_qkv_kernel(const float* __restrict__ part, int64_t plane, int splits,
+                                                                const GemmParams p) {
+    const int cb = blockIdx.x * 64;
+    const bool is_v = cb >= p.qd + p.kvd;
+    const int j = is_v ? (int)(threadIdx.x >> 3) : (int)(threadIdx.x & 31);
+    const int row = blockIdx.y * 8 + (is_v ? (int)(threadIdx.x & 7) : (int)(threadIdx.x >> 5));
+    if (row >= p.M) return;
+    const float* pp = part + (int64_t)row * p.N + cb + j;
+    float a = pp[0], b = pp[32];
+    for (int sidx = 1; sidx < splits; ++sidx) {
+        a += pp[sidx * plane];
+        b += pp[sidx * plane + 32];
+    }
+    if (p.bias) {
+        a += bf2f(p.bias[cb + j]);
+        b += bf2f(p.bias[cb + 32 + j]);
+    }
+    if (!is_v) {
+        const bool is_q = cb < p.qd;
+        const int c = is_q ? cb : cb - p.qd;
+        const int head = c / p.hd;
+        const int half = p.hd >> 1;
+        const int i0 = (((c - head * p.hd) >> 6) << 5) + j;                  // rotary index
+        const int64_t pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
+        const float cs = p.rope_cos[pos * half + i0], sn = p.rope_sin[pos * half + i0];
+        bf16_t* drow = (is_q ? p.dst + (int64_t)row * p.qd : p.dst_k + (int64_t)row * p.kvd) + head * p.hd + i0;
+        drow[0] = f2bf(a * cs - b * sn);
+        drow[half] = f2bf(b * cs + a * sn);
+    } else {
+        const int f = cb - p.qd - p.kvd + j;
+        bf16_t* dcol = p.dst_vt + p.pos0 + row;
+        dcol[(int64_t)f * p.ldv] = f2bf(a);
+        dcol[(int64_t)(f + 32) * p.ldv] = f2bf(b);
+    }
 }
 
 template <int EPI>
-void launch_t(const GemmParams& p, hipStream_t s) {
+void launch_t(const GemmParams& p, hipStream_t s, int splits = 1) {
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI>,
@@ -227,7 +301,7 @@ void launch_t(const GemmParams& p, hipStream_t s) {
     }
     const int total = p.mt * p.nt;
     const int per_xcd = (total + 7) / 8;
-    hipLaunchKernelGGL(gemm_bf16_mfma_kernel<EPI>, dim3((unsigned)(per_xcd * 8)), dim3(NTHREADS), SMEM_BYTES, s, p);
+    hipLaunchKernelGGL(gemm_bf16_mfma_kernel<EPI>, dim3((unsigned)(per_xcd * 8), (unsigned)splits), dim3(NTHREADS), SMEM_BYTES, s, p);
 }
 
 GemmParams base_params(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, int64_t M, int N, int K) {
@@ -256,6 +330,60 @@ void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, in
         case EPI_SILU_MUL: launch_t<EPI_SILU_MUL>(p, s); break;
         default: break;
     }
+}
+
+namespace {
+// splits of the reduction for a GEMM with few output tiles: enough workgroups for the chip's 256 compute
+// units, whole slices, at least two per split, partials within part_bytes; 1 = do not split
+int pick_splits(int64_t M, int N, int K, size_t part_bytes) {
+    const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    const int KT = K / BK;
+    int splits = 1;
+    while (splits < 16 && tiles * splits * 2 <= 256 && KT % (splits * 2) == 0 && KT / (splits * 2) >= 2) splits *= 2;
+    while (splits > 1 && (size_t)splits * (size_t)M * (size_t)N * sizeof(float) > part_bytes) splits /= 2;
+    return splits;
+}
+}  // namespace
+
+int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
+                                bf16_t* Q, bf16_t* Kd, bf16_t* Vt, int64_t ldv, const float* rope_cos,
+                                const float* rope_sin, int64_t pos0, const int32_t* row_pos, int64_t M, int qd, int kvd,
+                                int hd, int K, float* part, size_t part_bytes, bool launch, hipStream_t s) {
+    const int N = qd + 2 * kvd;
+    if (M <= 0 || !gemm_mfma_supported(N, K) || (qd & 63) || (kvd & 63) || (hd & 63)) return 0;
+    const int splits = pick_splits(M, N, K, part_bytes);
+    if (splits < 2) return 0;
+    if (!launch) return splits;
+    GemmParams p = base_params(A, lda, Wqkv, ldw, M, N, K / splits);
+    p.dst = (bf16_t*)part;
+    p.ld = N;
+    p.ldr = M * (int64_t)N;
+    launch_t<EPI_PARTIAL>(p, s, splits);
+    GemmParams r = base_params(A, lda, Wqkv, ldw, M, N, K);
+    r.bias = bias; r.dst = Q; r.dst_k = Kd; r.dst_vt = Vt; r.ldv = ldv;
+    r.rope_cos = rope_cos; r.rope_sin = rope_sin; r.pos0 = pos0; r.row_pos = row_pos;
+    r.qd = qd; r.kvd = kvd; r.hd = hd;
+    hipLaunchKernelGGL(splitk_reduce_qkv_kernel, dim3((unsigned)(N / 64), (unsigned)((M + 7) / 8)), dim3(256), 0, s, part,
+                       M * (int64_t)N, splits, r);
+    return splits;
+}
+
+int launch_gemm_mfma_splitk_residual(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* C,
+                                     int64_t ldc, const bf16_t* R, int64_t ldr, int64_t M, int N, int K,
+                                     float* part, size_t part_bytes, bool launch, hipStream_t s) {
+    if (M <= 0 || N <= 0 || !gemm_mfma_supported(N, K) || (N & 7) || (ldc & 7) || (ldr & 7)) return 0;
+    const int splits = pick_splits(M, N, K, part_bytes);
+    if (splits < 2) return 0;
+    if (!launch) return splits;
+    GemmParams p = base_params(A, lda, W, ldw, M, N, K / splits);
+    p.dst = (bf16_t*)part;
+    p.ld = N;
+    p.ldr = M * (int64_t)N;              // floats between two splits' planes
+    launch_t<EPI_PARTIAL>(p, s, splits);
+    const int64_t n = M * (int64_t)(N >> 3);
+    hipLaunchKernelGGL(splitk_reduce_residual_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part,
+                       M * (int64_t)N, splits, R, ldr, C, ldc, (int)M, N);
+    return splits;
 }
 
 void launch_gemm_qkv_rope(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,

@@ -169,6 +169,7 @@ struct po_ctx {
     std::vector<uint32_t> loaded;     // per layer bitmask of tensor kinds; index n_layers = globals
     hipEvent_t ev_start, ev_stop;
     bool phase_timing;
+    bool split_few_rows;              // requests of few rows: split reductions for occupancy (not bit-identical)
     bool lazy_last_layer;             // last layer: queries, attention rows and MLP only where the last token needs them
     // prefix K/V cache (caller-provided device memory): per layer K [cap, kvd], then V^T [kvd, ldvc]
     // (bf16) or V [cap, kvd] (fp32); see kv_slots
@@ -304,6 +305,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
     PO_HIP(hipMemcpyAsync(d_tok, tokens, (size_t)total * 4, hipMemcpyHostToDevice, s));
     if (n_cand > 0) PO_HIP(hipMemcpyAsync(ws + L.cand, cand, (size_t)n_cand * 4, hipMemcpyHostToDevice, s));
     PO_HIP(hipEventRecord(c->ev_start, s));
+    int64_t n_split_launches = 0;
     launch_embed(dt, d_tok + p_reuse, c->w + L.embed, X + (size_t)p_reuse * d * esz, total - p_reuse, d, s);
     // Packed: the sequence position of every buffer row, for the rotary embedding in the QKV epilogue.  The
     // token ids are dead once the embedding has been gathered, so the positions take over their buffer.
@@ -358,10 +360,20 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                                          (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
                                          (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, s);
             } else if (dt == PO_BF16) {
-                // one GEMM: RoPE applied to Q and K in the epilogue, V written as V^T
-                launch_gemm_qkv_rope((const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, (const bf16_t*)bqkv,
-                                     (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
-                                     (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, s);
+                // one GEMM: RoPE applied to Q and K in the epilogue, V written as V^T (few rows: split over K,
+                // partials in the chunk buffer H behind the norm output if that sits there)
+                const size_t h_bytes = (size_t)L.chunk * F * esz;
+                const size_t h_used = (Xn == H) ? (((size_t)rows * d * esz) + ALIGN - 1) / ALIGN * ALIGN : 0;
+                if (c->split_few_rows && h_used < h_bytes &&
+                    launch_gemm_qkv_rope_splitk((const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, (const bf16_t*)bqkv,
+                                                  (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
+                                                  (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d,
+                                                (float*)(H + h_used), h_bytes - h_used, true, s) > 1)
+                    ++n_split_launches;
+                else
+                    launch_gemm_qkv_rope((const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, (const bf16_t*)bqkv,
+                                         (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
+                                         (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, s);
             } else {
                 launch_gemm_basic(dt, Xn, d, wqkv, d, Q + (size_t)c0 * qd * esz, qd, bqkv, nullptr, 0, rows, qd, d, s);
                 launch_gemm_basic(dt, Xn, d, wqkv + (size_t)qd * d * esz, d, K + (size_t)c0 * kvd * esz, kvd,
@@ -404,9 +416,18 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
             const int64_t q_row0 = last_only ? g.len - 1 : p_reuse;
             unsigned char* Qg = Q + (size_t)g.start * qd * esz;
             if (dt == PO_BF16) {
-                launch_attention_mfma((const bf16_t*)Qg, (const bf16_t*)(K + (size_t)g.start * kvd * esz),
-                                      (const bf16_t*)(ws + L.Vt) + g.start, L.ldv, (bf16_t*)Qg, g.len, m.n_q_heads,
-                                      m.n_kv_heads, hd, q_row0, s);
+                // few query rows against many keys: key tiles split between workgroups (scratch: the chunk
+                // buffer H, idle during attention)
+                if (c->split_few_rows &&
+                    launch_attention_mfma_split((const bf16_t*)Qg, (const bf16_t*)(K + (size_t)g.start * kvd * esz),
+                                                (const bf16_t*)(ws + L.Vt) + g.start, L.ldv, (bf16_t*)Qg, g.len,
+                                                m.n_q_heads, m.n_kv_heads, hd, q_row0, (float*)H,
+                                                (size_t)L.chunk * F * esz, true, s) > 1)
+                    ++n_split_launches;
+                else
+                    launch_attention_mfma((const bf16_t*)Qg, (const bf16_t*)(K + (size_t)g.start * kvd * esz),
+                                          (const bf16_t*)(ws + L.Vt) + g.start, L.ldv, (bf16_t*)Qg, g.len, m.n_q_heads,
+                                          m.n_kv_heads, hd, q_row0, s);
             } else {
                 launch_attention_basic(dt, Qg, K + (size_t)g.start * kvd * esz, V + (size_t)g.start * kvd * esz, Qg,
                                        g.len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
@@ -456,10 +477,19 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                 launch_gemm_fp8(EPI_RESIDUAL, H, 2 * (int64_t)F, sx, c->w + o.wd, F, (const float*)(c->w + o.s_wd), (bf16_t*)Xc, d,
                                 nullptr, (const bf16_t*)Xc, d, rows, d, F, s);
             } else if (dt == PO_BF16) {
+                // few rows (a short request, or the suffix behind a long cached prefix): the two GEMMs with
+                // only d output columns split their reduction over K so that the whole chip streams the
+                // weights; scratch = the part of the chunk buffer H that this chunk's rows leave free
+                const size_t h_bytes = (size_t)L.chunk * F * esz;
                 {
                     PhaseTimer pt(c, PO_K_RESIDUAL);
-                    launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)Oc, qd, (const bf16_t*)(c->w + o.wo), qd,
-                                     (bf16_t*)Xc, d, nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
+                    if (c->split_few_rows &&
+                        launch_gemm_mfma_splitk_residual((const bf16_t*)Oc, qd, (const bf16_t*)(c->w + o.wo), qd, (bf16_t*)Xc, d,
+                                                         (const bf16_t*)Xc, d, rows, d, qd, (float*)H, h_bytes, true, s) > 1)
+                        ++n_split_launches;
+                    else
+                        launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)Oc, qd, (const bf16_t*)(c->w + o.wo), qd,
+                                         (bf16_t*)Xc, d, nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
                 }
                 launch_rmsnorm(dt, Xc, c->w + o.mlp_norm, Xn, rows, d, m.rms_eps, s);
                 {
@@ -468,8 +498,15 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                                      nullptr, nullptr, 0, rows, 2 * F, d, s);
                 }
                 PhaseTimer pt(c, PO_K_RESIDUAL);
-                launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)H, F, (const bf16_t*)(c->w + o.wd), F, (bf16_t*)Xc, d,
-                                 nullptr, (const bf16_t*)Xc, d, rows, d, F, s);
+                const size_t h_used = (((size_t)rows * F * esz) + ALIGN - 1) / ALIGN * ALIGN;
+                if (c->split_few_rows && h_used < h_bytes &&
+                    launch_gemm_mfma_splitk_residual((const bf16_t*)H, F, (const bf16_t*)(c->w + o.wd), F, (bf16_t*)Xc, d,
+                                                     (const bf16_t*)Xc, d, rows, d, F, (float*)(H + h_used), h_bytes - h_used,
+                                                     true, s) > 1)
+                    ++n_split_launches;
+                else
+                    launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)H, F, (const bf16_t*)(c->w + o.wd), F, (bf16_t*)Xc, d,
+                                     nullptr, (const bf16_t*)Xc, d, rows, d, F, s);
             } else {
                 unsigned char* GU = ws + L.GU;
                 {
@@ -511,6 +548,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
     PO_HIP(hipEventElapsedTime(&ms, c->ev_start, c->ev_stop));
     c->stats.last_prefill_ms = ms;
     c->stats.last_len = total;
+    c->stats.split_launches = n_split_launches;
     for (int kc = 0; kc < PO_K_COUNT; ++kc) { c->stats.kernel_ms[kc] = 0; c->stats.kernel_launches[kc] = 0; }
     for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
         float t = 0.f;
@@ -608,6 +646,7 @@ po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t m
     c->kv_layer_bytes = c->kv_v_off = 0;
     c->kv_tick = 0;
     c->kv_src = c->kv_dst = 0;
+    c->split_few_rows = false;
     c->ev_used = 0;
     memset(&c->stats, 0, sizeof(c->stats));
     c->stats.weights_bytes = c->lay.weights_bytes;
@@ -1074,6 +1113,12 @@ po_status po_profile_jct(po_ctx* c, int64_t max_len, int64_t step, int64_t* n_in
     }
     for (auto& sl : c->kv_slots) sl.tokens.clear();                          // the fake prefix serves nobody
     return st;
+}
+
+po_status po_set_few_rows_split(po_ctx* c, int32_t on) {
+    if (!c) return PO_ERR_INVALID_ARG;
+    c->split_few_rows = on != 0;
+    return PO_OK;
 }
 
 po_status po_set_lazy_last_layer(po_ctx* c, int32_t on) {

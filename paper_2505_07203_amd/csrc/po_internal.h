@@ -51,7 +51,7 @@ void launch_pack_gate_up(int dtype, const void* wg, const void* wu, void* wgu, i
                          hipStream_t s);
 
 // ---- launchers: bf16 MFMA kernels ------------------------------------------------------
-enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SILU_MUL = 2, EPI_QKV_ROPE = 3 };
+enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SILU_MUL = 2, EPI_QKV_ROPE = 3, EPI_PARTIAL = 4 };
 // C[M,N] = A[M,K] W[N,K]^T with bf16 MFMA, fp32 accumulation.
 //   EPI_STORE    : C = acc (+ bias[N], bf16)
 //   EPI_RESIDUAL : C = acc + R  (added in fp32; R may alias C)
@@ -80,7 +80,30 @@ void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int6
 // causal GQA flash attention; q [N,Hq,hd], k [N,Hkv,hd], vt [Hkv*hd][ldv]; o may alias q
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
                            int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, hipStream_t s);
+// The same for query rows [q_row0, N) when they are few and the keys many: the key tiles of a query tile are
+// divided between workgroups (fp32 partial results in `scratch`, merged by a second kernel).  Sums are formed
+// in a different order than in launch_attention_mfma: equal to rounding, not bit for bit.  Returns the
+// number of key splits (0 or 1: not worth it or scratch too small, nothing launched); launch = false only asks.
+int launch_attention_mfma_split(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
+                                int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, float* scratch,
+                                size_t scratch_bytes, bool launch, hipStream_t s);
 bool gemm_mfma_supported(int N, int K);
+// C = A W^T + R for a GEMM with few rows, the reduction over K split between workgroups (a GEMM with few
+// output tiles leaves most of the chip idle and every workgroup streaming a whole K range of both operands):
+// split s of `splits` writes its fp32 partial tile sums to part[s][M][N], a second kernel adds them up in
+// split order, adds R and rounds once.  The sum order differs from launch_gemm_mfma's (there one fp32
+// accumulator runs over all of K), so the results agree to rounding, not bit for bit.  Returns the number
+// of splits it would use for this shape and `part_bytes` of scratch memory; 0 or 1 = not worth it or does
+// not fit (then nothing is launched).  With launch = false only that number is computed.
+// launch_gemm_qkv_rope the same way (partials, then one kernel that sums them and applies bias, rotary
+// embedding and the V^T store)
+int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
+                                bf16_t* Q, bf16_t* Kd, bf16_t* Vt, int64_t ldv, const float* rope_cos,
+                                const float* rope_sin, int64_t pos0, const int32_t* row_pos, int64_t M, int qd,
+                                int kvd, int hd, int K, float* part, size_t part_bytes, bool launch, hipStream_t s);
+int launch_gemm_mfma_splitk_residual(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* C,
+                                     int64_t ldc, const bf16_t* R, int64_t ldr, int64_t M, int N, int K,
+                                     float* part, size_t part_bytes, bool launch, hipStream_t s);
 
 // ---- FP8-dynamic linear layers (OCP E4M3 codes + float32 scales) -----------------------------------
 // rows of bf16 -> codes + one scale per row; source row r goes to destination row

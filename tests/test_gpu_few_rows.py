@@ -1,0 +1,134 @@
+"""Few-rows mode (po_set_few_rows_split): requests that compute few positions -- short ones, or the
+suffix behind a long cached prefix -- run their narrow GEMMs split over K and their attention split over
+the keys.  Sums are formed in another order than on the default path, so the bar is the one every bf16
+result meets: within 2e-2 of the float64 oracle (normalised by the logit range) with the oracle's top-1
+and preferred label; plus closeness to the default path's own result, and bit-identity between repeated
+runs (the partial sums are added in a fixed order, no atomics)."""
+import numpy as np
+import pytest
+
+from paper_2505_07203_amd import inputs as I
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+# widths chosen so that every split kernel engages at the tiny shape: K of the O-projection / QKV = 256
+# (4 slices -> 2 splits), of the down projection = 768 (12 slices -> 4 splits); head dimension 64
+TINY_BF16 = I.TINY.replace(dtype=I.BF16, ffn_dim=768)
+
+
+def _ctx(cfg, wseed, max_len, chunk):
+    from paper_2505_07203_amd import binding as B
+    ctx = B.Context(cfg, max_len, chunk)
+    ctx.load_synthetic(wseed, threads=4)
+    return ctx
+
+
+def _screened(cfg, wseed, tseed, n, min_gap=0.05):
+    """First token seed whose ORACLE logits have a clear top-1 (no GPU value involved)."""
+    for k in range(8):
+        t = I.make_tokens(cfg, tseed + 1000 * k, n)
+        z, _ = H.oracle_prefill(cfg, wseed, t)
+        top2 = np.sort(z)[-2:]
+        if top2[1] - top2[0] >= min_gap * np.max(np.abs(z)):
+            return t, z
+    raise AssertionError("no screened seed")
+
+
+@pytest.mark.parametrize("n", [40, 150, 256, 600])
+def test_short_request_against_oracle(n):
+    cfg = TINY_BF16
+    tokens, ref = _screened(cfg, 31, 500 + n, n)
+    cand = I.label_ids(cfg)
+    ctx = _ctx(cfg, 31, 1024, 512)
+    try:
+        z0, lp0 = ctx.po_prefill(tokens, cand)
+        ctx.po_set_few_rows_split(True)
+        z1, lp1 = ctx.po_prefill(tokens, cand)
+        z2, lp2 = ctx.po_prefill(tokens, cand)
+        assert np.array_equal(z1, z2) and np.array_equal(lp1, lp2)              # deterministic
+        for z in (z0, z1):
+            rel = H.normalised_max_rel(z, ref)
+            assert rel <= 2e-2, rel
+            assert int(np.argmax(z)) == int(np.argmax(ref))
+            assert int(np.argmax(z[cand])) == int(np.argmax(ref[cand]))
+        assert H.normalised_max_rel(z1, z0) <= 1e-2
+        assert abs(float(np.sum(np.exp(lp1.astype(np.float64)))) - 1.0) < 1e-5
+        assert ctx.po_get_stats()["split_launches"] > 0                          # the split kernels did run
+        ctx.po_set_few_rows_split(False)
+        ctx.po_prefill(tokens, cand)
+        assert ctx.po_get_stats()["split_launches"] == 0
+    finally:
+        ctx.po_destroy()
+
+
+@pytest.mark.parametrize("prefix,suffix", [(700, 100), (512, 1), (300, 257), (1000, 24)])
+def test_suffix_behind_cached_prefix_against_oracle(prefix, suffix):
+    cfg = TINY_BF16
+    n = prefix + suffix
+    tokens, ref = _screened(cfg, 32, 900 + n, n)
+    cand = I.label_ids(cfg)
+    ctx = _ctx(cfg, 32, 1024, 512)
+    try:
+        z0, _ = ctx.po_prefill(tokens, cand)
+        ctx.po_attach_kv_cache(1024)
+        ctx.po_prefill_prefix(tokens, prefix, cand)                              # stores the prefix (default path)
+        ctx.po_set_few_rows_split(True)
+        z1, lp1, reused = ctx.po_prefill_prefix(tokens, 0, cand)
+        assert reused == prefix
+        rel = H.normalised_max_rel(z1, ref)
+        assert rel <= 2e-2, rel
+        assert int(np.argmax(z1)) == int(np.argmax(ref))
+        assert int(np.argmax(z1[cand])) == int(np.argmax(ref[cand]))
+        assert H.normalised_max_rel(z1, z0) <= 1e-2
+        assert ctx.po_get_stats()["split_launches"] > 0
+        # a prefix stored in this mode serves the default path and the other way round
+        ctx.po_attach_kv_cache(1024)
+        ctx.po_prefill_prefix(tokens, prefix, cand)
+        ctx.po_set_few_rows_split(False)
+        z2, _, reused = ctx.po_prefill_prefix(tokens, 0, cand)
+        assert reused == prefix and H.normalised_max_rel(z2, ref) <= 2e-2
+    finally:
+        ctx.po_destroy()
+
+
+def test_full_width_two_layers_against_default_path():
+    """8B widths (d 4096, 32 / 8 heads of 128, F 14336), two layers: the split kernels at the shapes the
+    serving trace runs them at, against the default path (itself held to the oracle elsewhere)."""
+    cfg = I.LLAMA8B.replace(n_layers=2, vocab_size=4096)
+    cand = I.label_ids(cfg)
+    ctx = _ctx(cfg, 7, 10240, 4096)
+    try:
+        for prefix, suffix in ((9000, 150), (4000, 300), (0, 200), (8192, 1000)):
+            t = I.make_tokens(cfg, 5 + prefix, prefix + suffix)
+            ctx.po_set_few_rows_split(False)
+            ref, ref_lp = ctx.po_prefill(t, cand)
+            ctx.po_attach_kv_cache(10240)
+            if prefix:
+                ctx.po_prefill_prefix(t, prefix, cand, want_logits=False)
+            ctx.po_set_few_rows_split(True)
+            z, lp, reused = ctx.po_prefill_prefix(t, 0, cand)
+            assert reused == prefix
+            rel = H.normalised_max_rel(z, ref)
+            print(f"prefix {prefix} suffix {suffix}: split vs default {rel:.3e}")
+            assert rel <= 2e-2 and int(np.argmax(z)) == int(np.argmax(ref))
+            assert abs((lp[0] - lp[1]) - (ref_lp[0] - ref_lp[1])) <= 2e-2 * float(np.max(np.abs(ref)))
+    finally:
+        ctx.po_destroy()
+
+
+def test_packed_short_requests_in_few_rows_mode():
+    cfg = TINY_BF16
+    cand = I.label_ids(cfg)
+    lens = [300, 90, 512, 40]
+    toks = [I.make_tokens(cfg, 77, n, request=i) for i, n in enumerate(lens)]
+    ctx = _ctx(cfg, 33, 1024, 512)
+    try:
+        ref = [ctx.po_prefill(t, cand) for t in toks]
+        ctx.po_set_few_rows_split(True)
+        zp, lpp = ctx.po_prefill_packed(toks, cand, want_logits=True)
+        for i, (z, lp) in enumerate(ref):
+            assert H.normalised_max_rel(zp[i], z) <= 1e-2, i
+            assert int(np.argmax(zp[i])) == int(np.argmax(z))
+    finally:
+        ctx.po_destroy()

@@ -20,6 +20,9 @@ by the oracle alone (no GPU value enters it), and the GPU path may not be furthe
 evaluation than twice it.  The per-operator tests in test_gpu_parity.py hold every kernel to
 its tight, un-amplified tolerance at the same widths.
 
+Requests of up to 2048 tokens are also run in few-rows mode (po_set_few_rows_split) and held to the
+same bar: that mode sums in another order, so it is compared with the oracle, not with the default path.
+
 Top-1 rule: when the oracle's own gap between its two largest logits is below the error the
 tolerance allows (2 * 2e-2 * max|oracle|) several answers are correct; then the GPU's
 top-1 only has to be one of the oracle's 16 largest whose logit lies within that margin.
@@ -100,6 +103,15 @@ def test_against_stored_oracle(path):
             print(f"{doc['case']} request {i} len {r['len']}: err vs stored_bf16 {err_s:.3e}, vs exact {err_e:.3e} "
                   f"(oracle stored-vs-exact {storage_dev:.3e}, tol {tol:.3e})")
             singles.append((z, lp))
+            if r["len"] <= 2048:
+                # few-rows mode (split reductions, another summation order): the same bar against the oracle
+                ctx.po_set_few_rows_split(True)
+                zs, lps = ctx.po_prefill(t, cand, want_logits=True)
+                assert ctx.po_get_stats()["split_launches"] > 0
+                ctx.po_set_few_rows_split(False)
+                err_ss = _check_block(doc["case"], i, zs, lps, sb, tol)
+                err_se = _check_block(doc["case"], i, zs, lps, ex, tol)
+                print(f"    few-rows mode: err vs stored_bf16 {err_ss:.3e}, vs exact {err_se:.3e}")
         if len(singles) > 1:
             # the same requests with their position-wise layers packed: the same bits, request by request
             toks = [I.make_tokens(cfg, doc["tseed"], r["len"], request=i) for i, r in enumerate(doc["requests"])]
