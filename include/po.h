@@ -204,10 +204,12 @@ po_status po_attach_kv_cache(po_ctx* ctx, void* dev_cache, size_t bytes, int64_t
  * what po_kv_cache_bytes reports).  A request reuses the entry with which it shares the
  * longest prefix.  The prefix it asks to keep: if that entry already contains it, nothing
  * is stored and the entry stays as long as it is; if the request shares everything the
- * entry holds, the entry grows in place; otherwise (partial or no hit) the prefix replaces
- * an empty or else the least recently used of the OTHER entries, so that a partial hit does
- * not cut a longer entry short (with one entry it replaces that one).  "Used" = reused by a
- * request or written. */
+ * entry holds, or at least half of it, the entry is cut to the shared part and grows in
+ * place (requests that differ only in their tails keep one entry and rewrite the tail);
+ * otherwise (a hit on less than half of the entry, or none) the prefix replaces an empty or
+ * else the least recently used of the OTHER entries, so that a short partial hit does not
+ * destroy a long entry (with one entry it replaces that one).  "Used" = reused by a request
+ * or written. */
 po_status po_attach_kv_cache_slots(po_ctx* ctx, void* dev_cache, size_t bytes, int64_t prefix_capacity,
                                    int32_t n_slots);
 

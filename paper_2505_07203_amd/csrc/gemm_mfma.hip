@@ -291,6 +291,23 @@ __global__ void __launch_bounds__(256) splitk_reduce_qkv_kernel(const float* __r
     }
 }
 
+// Gate/up after a split-K GEMM: H[row][cb/2 + j] = silu(sum gate column cb + j) * (sum up column cb + 32 + j),
+// the interleaving of the fused SiLU-multiply epilogue; one thread per output feature.
+__global__ void __launch_bounds__(256) splitk_reduce_silu_kernel(const float* __restrict__ part, int64_t plane, int splits,
+                                                                 bf16_t* H, int64_t ldh, int M, int N) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int nf = N >> 1;
+    if (i >= (int64_t)M * nf) return;
+    const int row = (int)(i / nf), f = (int)(i - (int64_t)row * nf);
+    const float* pp = part + (int64_t)row * N + ((f >> 5) << 6) + (f & 31);
+    float g = pp[0], u = pp[32];
+    for (int sidx = 1; sidx < splits; ++sidx) {
+        g += pp[sidx * plane];
+        u += pp[sidx * plane + 32];
+    }
+    H[(int64_t)row * ldh + f] = f2bf(silu_f(g) * u);
+}
+
 template <int EPI>
 void launch_t(const GemmParams& p, hipStream_t s, int splits = 1) {
     static bool attr_set = false;
@@ -365,6 +382,23 @@ int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv
     r.qd = qd; r.kvd = kvd; r.hd = hd;
     hipLaunchKernelGGL(splitk_reduce_qkv_kernel, dim3((unsigned)(N / 64), (unsigned)((M + 7) / 8)), dim3(256), 0, s, part,
                        M * (int64_t)N, splits, r);
+    return splits;
+}
+
+int launch_gemm_mfma_splitk_silu(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* H, int64_t ldh,
+                                 int64_t M, int N, int K, float* part, size_t part_bytes, bool launch, hipStream_t s) {
+    if (M <= 0 || !gemm_mfma_supported(N, K)) return 0;
+    const int splits = pick_splits(M, N, K, part_bytes);
+    if (splits < 2) return 0;
+    if (!launch) return splits;
+    GemmParams p = base_params(A, lda, W, ldw, M, N, K / splits);
+    p.dst = (bf16_t*)part;
+    p.ld = N;
+    p.ldr = M * (int64_t)N;
+    launch_t<EPI_PARTIAL>(p, s, splits);
+    const int64_t n = M * (int64_t)(N >> 1);
+    hipLaunchKernelGGL(splitk_reduce_silu_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part, M * (int64_t)N,
+                       splits, H, ldh, (int)M, N);
     return splits;
 }
 

@@ -458,6 +458,55 @@ void launch_vt_pad_zero(bf16_t* Vt, int rows, int64_t ldv, int64_t n, hipStream_
 // Highest 32-bit word of an arena that differs from a fill pattern: per-thread strided scan,
 // wavefront/workgroup maximum, one 64-bit atomic maximum per workgroup.  *out must start at 0 and
 // receives (index of that word + 1), or stays 0 when nothing differs.
+// K rows and V^T columns of a position range between the one-layer buffers and a prefix-cache entry, in one
+// launch: workgroup row 0 copies the K rows (contiguous), workgroup row 1 + f copies row f of V^T (src and dst
+// start at the same column, so they are misaligned alike).  16 bytes per thread where a 16-byte block lies
+// wholly inside the range, single elements at its two ends.
+__global__ void __launch_bounds__(256) kv_copy_kernel(unsigned char* dk, const unsigned char* sk, size_t k_bytes,
+                                                      unsigned char* dv, size_t dpitch, const unsigned char* sv,
+                                                      size_t spitch, size_t v_bytes, unsigned gk, unsigned gv) {
+    unsigned char* d;
+    const unsigned char* s;
+    size_t n, first, stride;
+    if (blockIdx.x < gk) {                      // workgroups [0, gk): the K rows, grid-stride
+        d = dk; s = sk; n = k_bytes;
+        first = (size_t)blockIdx.x * 256 + threadIdx.x;
+        stride = (size_t)gk * 256;
+    } else {                                    // then gv workgroups per V^T row
+        const unsigned r = (blockIdx.x - gk) / gv, part = (blockIdx.x - gk) % gv;
+        d = dv + (size_t)r * dpitch; s = sv + (size_t)r * spitch; n = v_bytes;
+        first = (size_t)part * 256 + threadIdx.x;
+        stride = (size_t)gv * 256;
+    }
+    // 16-byte blocks counted from the aligned address at or below the start (same misalignment on both sides)
+    const size_t mis = (size_t)((uintptr_t)d & 15);
+    const size_t nblk = n ? (mis + n + 15) >> 4 : 0;
+    for (size_t b = first; b < nblk; b += stride) {
+        const ptrdiff_t lo = (ptrdiff_t)(b << 4) - (ptrdiff_t)mis;            // byte offset of the block from d
+        if (lo >= 0 && (size_t)lo + 16 <= n) {
+            *(uint4*)(d + lo) = *(const uint4*)(s + lo);
+        } else {
+            for (int e = 0; e < 16; e += 2) {
+                const ptrdiff_t o = lo + e;
+                if (o >= 0 && (size_t)o + 2 <= n) *(uint16_t*)(d + o) = *(const uint16_t*)(s + o);
+            }
+        }
+    }
+}
+
+void launch_kv_copy(void* dk, const void* sk, size_t k_bytes, void* dv, size_t dpitch, const void* sv, size_t spitch,
+                    size_t v_bytes, int v_rows, hipStream_t s) {
+    if (k_bytes == 0 && (v_bytes == 0 || v_rows <= 0)) return;
+    size_t gk = (k_bytes / 16 + 255) / 256, gv = ((v_bytes + 30) / 16 + 255) / 256;
+    if (gk > 2048) gk = 2048;
+    if (gv > 8) gv = 8;
+    if (gk == 0) gk = 1;
+    if (gv == 0) gv = 1;
+    hipLaunchKernelGGL(kv_copy_kernel, dim3((unsigned)(gk + gv * (size_t)v_rows)), dim3(256), 0, s, (unsigned char*)dk,
+                       (const unsigned char*)sk, k_bytes, (unsigned char*)dv, dpitch, (const unsigned char*)sv, spitch,
+                       v_bytes, (unsigned)gk, (unsigned)gv);
+}
+
 __global__ void __launch_bounds__(256) high_water_kernel(const uint32_t* ws, size_t n_words, uint32_t pattern,
                                                          unsigned long long* out) {
     __shared__ unsigned long long part[4];

@@ -339,12 +339,13 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
         unsigned char* kd_l = c->kvc ? c->kvc + (size_t)c->kv_dst * slot_bytes + (size_t)l * c->kv_layer_bytes : nullptr;
         if (p_reuse > 0) {
             // cached prefix of this layer -> rows [0, p_reuse) of the one-layer K / V buffers
-            PO_HIP(hipMemcpyAsync(K, kc_l, (size_t)p_reuse * kvd * esz, hipMemcpyDeviceToDevice, s));
-            if (dt == PO_BF16)
-                PO_HIP(hipMemcpy2DAsync(ws + L.Vt, (size_t)L.ldv * esz, kc_l + c->kv_v_off, (size_t)c->kv_ldv * esz,
-                                        (size_t)p_reuse * esz, kvd, hipMemcpyDeviceToDevice, s));
-            else
+            if (dt == PO_BF16) {
+                launch_kv_copy(K, kc_l, (size_t)p_reuse * kvd * esz, ws + L.Vt, (size_t)L.ldv * esz, kc_l + c->kv_v_off,
+                               (size_t)c->kv_ldv * esz, (size_t)p_reuse * esz, kvd, s);
+            } else {
+                PO_HIP(hipMemcpyAsync(K, kc_l, (size_t)p_reuse * kvd * esz, hipMemcpyDeviceToDevice, s));
                 PO_HIP(hipMemcpyAsync(V, kc_l + c->kv_v_off, (size_t)p_reuse * kvd * esz, hipMemcpyDeviceToDevice, s));
+            }
         }
         for (int64_t c0 = p_reuse; c0 < total; c0 += Cq) {
             const int64_t rows = (total - c0 < Cq) ? total - c0 : Cq;
@@ -397,13 +398,14 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
         const int64_t st0 = (c->kv_dst == c->kv_src) ? p_reuse : 0;
         if (p_store > st0) {
             const size_t r0 = (size_t)st0, nr = (size_t)(p_store - st0);
-            PO_HIP(hipMemcpyAsync(kd_l + r0 * kvd * esz, K + r0 * kvd * esz, nr * kvd * esz, hipMemcpyDeviceToDevice, s));
-            if (dt == PO_BF16)
-                PO_HIP(hipMemcpy2DAsync(kd_l + c->kv_v_off + r0 * esz, (size_t)c->kv_ldv * esz, ws + L.Vt + r0 * esz,
-                                        (size_t)L.ldv * esz, nr * esz, kvd, hipMemcpyDeviceToDevice, s));
-            else
+            if (dt == PO_BF16) {
+                launch_kv_copy(kd_l + r0 * kvd * esz, K + r0 * kvd * esz, nr * kvd * esz, kd_l + c->kv_v_off + r0 * esz,
+                               (size_t)c->kv_ldv * esz, ws + L.Vt + r0 * esz, (size_t)L.ldv * esz, nr * esz, kvd, s);
+            } else {
+                PO_HIP(hipMemcpyAsync(kd_l + r0 * kvd * esz, K + r0 * kvd * esz, nr * kvd * esz, hipMemcpyDeviceToDevice, s));
                 PO_HIP(hipMemcpyAsync(kd_l + c->kv_v_off + r0 * kvd * esz, V + r0 * kvd * esz, nr * kvd * esz,
                                       hipMemcpyDeviceToDevice, s));
+            }
         }
         // Nothing reads the last layer's output except the last position (one output token, Section 1):
         // there the keys and values of every position are still needed, but attention, O-projection and
@@ -492,13 +494,18 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                                          (bf16_t*)Xc, d, nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
                 }
                 launch_rmsnorm(dt, Xc, c->w + o.mlp_norm, Xn, rows, d, m.rms_eps, s);
+                const size_t h_used = (((size_t)rows * F * esz) + ALIGN - 1) / ALIGN * ALIGN;
                 {
                     PhaseTimer pt(c, PO_K_GATE_UP);
-                    launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)Xn, d, (const bf16_t*)(c->w + o.wgu), d, (bf16_t*)H, F,
-                                     nullptr, nullptr, 0, rows, 2 * F, d, s);
+                    if (c->split_few_rows && h_used < h_bytes &&
+                        launch_gemm_mfma_splitk_silu((const bf16_t*)Xn, d, (const bf16_t*)(c->w + o.wgu), d, (bf16_t*)H, F, rows,
+                                                     2 * F, d, (float*)(H + h_used), h_bytes - h_used, true, s) > 1)
+                        ++n_split_launches;
+                    else
+                        launch_gemm_mfma(EPI_SILU_MUL, (const bf16_t*)Xn, d, (const bf16_t*)(c->w + o.wgu), d, (bf16_t*)H, F,
+                                         nullptr, nullptr, 0, rows, 2 * F, d, s);
                 }
                 PhaseTimer pt(c, PO_K_RESIDUAL);
-                const size_t h_used = (((size_t)rows * F * esz) + ALIGN - 1) / ALIGN * ALIGN;
                 if (c->split_few_rows && h_used < h_bytes &&
                     launch_gemm_mfma_splitk_residual((const bf16_t*)H, F, (const bf16_t*)(c->w + o.wd), F, (bf16_t*)Xc, d,
                                                      (const bf16_t*)Xc, d, rows, d, F, (float*)(H + h_used), h_bytes - h_used,
@@ -978,6 +985,7 @@ int best_slot(const po_ctx* c, const int32_t* tokens, int64_t len, int64_t* matc
         const std::vector<int32_t>& t = c->kv_slots[i].tokens;
         const int64_t lim = std::min<int64_t>((int64_t)t.size(), len);
         int64_t mm = 0;
+        while (mm + 64 <= lim && memcmp(t.data() + mm, tokens + mm, 64 * sizeof(int32_t)) == 0) mm += 64;   // whole blocks first
         while (mm < lim && t[(size_t)mm] == tokens[mm]) ++mm;
         if (mm > best_m || (mm == best_m && c->kv_slots[i].last_use > c->kv_slots[(size_t)best].last_use)) {
             best_m = mm;
@@ -1025,14 +1033,16 @@ po_status po_prefill_prefix(po_ctx* c, const int32_t* tokens, int64_t len, int64
     const int64_t stored = (int64_t)c->kv_slots[(size_t)src].tokens.size();
     const int64_t m = std::min<int64_t>(shared, len - 1);
     // Where the prefix to keep goes.  Already inside the entry: nothing is stored and the entry stays as
-    // long as it is.  The request shares all the entry holds: the entry grows in place.  Otherwise (a
-    // partial or no hit) the prefix replaces the least recently used of the other entries, so that a
-    // partial hit does not cut a longer entry short; with one entry it replaces that one.
+    // long as it is.  The request shares all the entry holds, or at least half of it: the entry is cut to
+    // the shared part and grows in place (a sequence of requests that differ in their tails keeps ONE entry
+    // and rewrites only the tail).  Otherwise (a hit on less than half, or none) the prefix replaces the
+    // least recently used of the other entries, so that a short partial hit does not destroy a long entry;
+    // with one entry it replaces that one.
     int dst = src;
     int64_t store = keep_prefix;
     if (keep_prefix <= shared) {
         store = 0;
-    } else if (shared < stored && c->kv_slots.size() > 1) {
+    } else if (shared < stored && c->kv_slots.size() > 1 && shared * 2 < stored) {
         uint64_t oldest = ~0ull;
         for (size_t i = 0; i < c->kv_slots.size(); ++i)
             if ((int)i != src || shared == 0) {

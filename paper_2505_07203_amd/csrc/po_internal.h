@@ -76,6 +76,10 @@ void launch_pack_rope_rows(bf16_t* W, int n_heads, int hd, int64_t row_elems, hi
 void launch_vt_pad_zero(bf16_t* Vt, int rows, int64_t ldv, int64_t n, hipStream_t s);
 void launch_high_water(const void* ws, size_t bytes, uint32_t pattern, unsigned long long* out, hipStream_t s);
 // Vt[Hkv*hd][ldv] = transpose of V[n, Hkv*hd]; columns n..round_up(n,64)-1 are zero-filled
+// K rows (k_bytes contiguous bytes) and v_rows rows of V^T (v_bytes each, pitches in bytes) between the one-layer
+// buffers and a prefix-cache entry; bf16 data, the V^T source and destination misaligned alike (same column)
+void launch_kv_copy(void* dk, const void* sk, size_t k_bytes, void* dv, size_t dpitch, const void* sv, size_t spitch,
+                    size_t v_bytes, int v_rows, hipStream_t s);
 void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int64_t ldv, hipStream_t s);
 // causal GQA flash attention; q [N,Hq,hd], k [N,Hkv,hd], vt [Hkv*hd][ldv]; o may alias q
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
@@ -101,6 +105,9 @@ int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv
                                 bf16_t* Q, bf16_t* Kd, bf16_t* Vt, int64_t ldv, const float* rope_cos,
                                 const float* rope_sin, int64_t pos0, const int32_t* row_pos, int64_t M, int qd,
                                 int kvd, int hd, int K, float* part, size_t part_bytes, bool launch, hipStream_t s);
+// launch_gemm_mfma(EPI_SILU_MUL) the same way; part must not overlap H's rows [0, M)
+int launch_gemm_mfma_splitk_silu(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* H, int64_t ldh,
+                                 int64_t M, int N, int K, float* part, size_t part_bytes, bool launch, hipStream_t s);
 int launch_gemm_mfma_splitk_residual(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* C,
                                      int64_t ldc, const bf16_t* R, int64_t ldr, int64_t M, int N, int K,
                                      float* part, size_t part_bytes, bool launch, hipStream_t s);

@@ -7,6 +7,7 @@
 #include "../../include/po.h"
 
 #include <stdint.h>
+#include <string.h>
 
 #include <algorithm>
 #include <cmath>
@@ -32,6 +33,7 @@ int64_t hit_len(const std::vector<int32_t>& t, const int32_t* cached, int64_t n_
     // common prefix with the cache; one position of a request is always computed
     const int64_t lim = std::min<int64_t>((int64_t)t.size() - 1, n_cached_tokens);
     int64_t m = 0;
+    while (m + 64 <= lim && memcmp(t.data() + m, cached + m, 64 * sizeof(int32_t)) == 0) m += 64;   // whole blocks first
     while (m < lim && t[(size_t)m] == cached[m]) ++m;
     return m;
 }

@@ -379,8 +379,8 @@ def test_prefix_cache_reuse_is_bitwise(cfg, n, keep):
                          ids=["f32", "bf16", "fp8"])
 def test_prefix_cache_with_several_entries(cfg):
     """Section 5.1 with a cache of three entries: which entry a request reuses, where the prefix it keeps
-    goes (inside an entry: nothing stored; all of an entry shared: grows in place; otherwise the least
-    recently used other entry), and the same bits as an uncached run every time."""
+    goes (inside an entry: nothing stored; all or most of an entry shared: cut to the shared part and
+    regrown in place; otherwise the least recently used other entry), and the same bits as an uncached run."""
     rng = np.random.default_rng(23)
     V = cfg.vocab_size
     tok = lambda n: rng.integers(0, V, n).astype(np.int32)
@@ -432,6 +432,12 @@ def test_prefix_cache_with_several_entries(cfg):
         assert p4.tolist() in got and f[:240].tolist() in got and c[:450].tolist() in got
         run(c, 0, 450)
         run(d, 0, 120)                                          # what c's and f's entries share with d
+        g = np.concatenate([c[:400], tok(60)])
+        run(g, 450, 400)                                        # shares most of c's entry: that entry is cut to
+        got = slots()                                           # the shared part and regrown in place
+        assert g[:450].tolist() in got and c[:450].tolist() not in got
+        assert p4.tolist() in got and f[:240].tolist() in got
+        run(c, 0, 400)
         with pytest.raises(B.PoError):
             ctx.po_kv_cache_slot(3)
         # one entry: a partial hit replaces it
