@@ -298,7 +298,7 @@ po_status po_engine_step(po_ctx* ctx, po_sched* s, double now, const int32_t* ca
  * Logits and log-probs are bit-identical with the shortcut on and off. */
 po_status po_set_lazy_last_layer(po_ctx* ctx, int32_t on);
 
-/* Few-rows mode, off by default (bf16 contexts; FP8-dynamic contexts split only attention, fp32 ignores it).  A request that computes few
+/* Few-rows mode, off by default (bf16 and FP8-dynamic contexts; fp32 ignores it).  A request that computes few
  * positions -- a short one, or the suffix behind a long cached prefix, the paper's post
  * recommendation case (Sections 2.2, 5.1) -- gives the QKV, O- and MLP down projections too
  * few output tiles, and attention too few query tiles, to occupy the chip.  With the mode on,

@@ -322,5 +322,16 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams& p, const f32x16 
     }
 }
 
+// ---- split-K support shared by the bf16 and the FP8 GEMM (defined with the bf16 kernel)
+// splits of the reduction for a GEMM with few output tiles whose K range has kt slices: enough workgroups for
+// the chip's 256 compute units, whole slices, at least two per split, fp32 partials within part_bytes; 1 = none
+int pick_splits(int64_t M, int N, int kt, size_t part_bytes);
+// the kernels that add up part[split][M][N] in split order and apply an epilogue
+void launch_splitk_reduce_residual(const float* part, int splits, const bf16_t* R, int64_t ldr, bf16_t* C, int64_t ldc,
+                                   int64_t M, int N, hipStream_t s);
+void launch_splitk_reduce_silu(const float* part, int splits, bf16_t* H, int64_t ldh, int64_t M, int N, hipStream_t s);
+// r: the parameters launch_gemm_qkv_rope would pass (bias, destinations, rotary table, positions, widths)
+void launch_splitk_reduce_qkv(const float* part, int splits, const GemmParams& r, hipStream_t s);
+
 }  // namespace gemm
 }  // namespace po

@@ -59,11 +59,13 @@ __global__ void __launch_bounds__(NTHREADS) gemm_fp8_mfma_kernel(const GemmParam
     // Each operand is addressed through a buffer resource that starts at the tile's first row and ends with
     // the matrix: the per-lane byte offset never changes, the slice offset is one scalar, and rows of a
     // ragged last tile beyond the matrix read as zero instead of needing a clamp (they are never stored).
-    const uint64_t a_bytes = (uint64_t)(p.M - m0) * (uint64_t)p.lda, w_bytes = (uint64_t)(p.N - n0) * (uint64_t)p.ldw;
+    // (split-K launches: workgroup row blockIdx.y works on codes [k0, k0 + K) of both operands)
+    const int64_t k0 = (EPI == EPI_PARTIAL) ? (int64_t)blockIdx.y * p.K : 0;
+    const uint64_t a_bytes = (uint64_t)(p.M - m0) * (uint64_t)p.lda - (uint64_t)k0, w_bytes = (uint64_t)(p.N - n0) * (uint64_t)p.ldw - (uint64_t)k0;
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)((const unsigned char*)p.A + (int64_t)m0 * p.lda), 0, (int)(uint32_t)(a_bytes > 0xffffffffull ? 0xffffffffull : a_bytes), 0x00020000);
+        (void*)((const unsigned char*)p.A + (int64_t)m0 * p.lda + k0), 0, (int)(uint32_t)(a_bytes > 0xffffffffull ? 0xffffffffull : a_bytes), 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)((const unsigned char*)p.W + (int64_t)n0 * p.ldw), 0, (int)(uint32_t)(w_bytes > 0xffffffffull ? 0xffffffffull : w_bytes), 0x00020000);
+        (void*)((const unsigned char*)p.W + (int64_t)n0 * p.ldw + k0), 0, (int)(uint32_t)(w_bytes > 0xffffffffull ? 0xffffffffull : w_bytes), 0x00020000);
     uint32_t voa[8], vow[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -200,11 +202,17 @@ __global__ void __launch_bounds__(NTHREADS) gemm_fp8_mfma_kernel(const GemmParam
                 acc[mi][ni][4 * g4 + 3] = acc[mi][ni][4 * g4 + 3] * sx * sw.w;
             }
     }
-    tile_epilogue<EPI>(p, acc, smem, m0, n0, wave, lane);
+    if (EPI == EPI_PARTIAL) {
+        GemmParams q = p;
+        q.dst = (bf16_t*)((float*)p.dst + (int64_t)blockIdx.y * p.ldr);     // this split's plane of partial sums
+        tile_epilogue<EPI>(q, acc, smem, m0, n0, wave, lane);
+    } else {
+        tile_epilogue<EPI>(p, acc, smem, m0, n0, wave, lane);
+    }
 }
 
 template <int EPI>
-void launch_t(const GemmParams& p, hipStream_t s) {
+void launch_t(const GemmParams& p, hipStream_t s, int splits = 1) {
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void*)gemm_fp8_mfma_kernel<EPI>,
@@ -213,7 +221,7 @@ void launch_t(const GemmParams& p, hipStream_t s) {
     }
     const int total = p.mt * p.nt;
     const int per_xcd = (total + 7) / 8;
-    hipLaunchKernelGGL(gemm_fp8_mfma_kernel<EPI>, dim3((unsigned)(per_xcd * 8)), dim3(NTHREADS), SMEM_BYTES, s, p);
+    hipLaunchKernelGGL(gemm_fp8_mfma_kernel<EPI>, dim3((unsigned)(per_xcd * 8), (unsigned)splits), dim3(NTHREADS), SMEM_BYTES, s, p);
 }
 
 GemmParams base_params(const unsigned char* A, int64_t lda, const float* sa, const unsigned char* W, int64_t ldw,
@@ -245,6 +253,47 @@ void launch_gemm_fp8(int epi, const unsigned char* A, int64_t lda, const float* 
         case EPI_SILU_MUL: launch_t<EPI_SILU_MUL>(p, s); break;
         default: break;
     }
+}
+
+// The split-K forms (few rows): partial sums already carry the row and column scales, so the reduce kernels
+// of the bf16 GEMM finish them.  epi: EPI_RESIDUAL (C = sum + R) or EPI_SILU_MUL (C = H [M, N / 2]).
+int launch_gemm_fp8_splitk(int epi, const unsigned char* A, int64_t lda, const float* sa, const unsigned char* W,
+                           int64_t ldw, const float* sw, bf16_t* C, int64_t ldc, const bf16_t* R, int64_t ldr, int64_t M,
+                           int N, int K, float* part, size_t part_bytes, hipStream_t s) {
+    if (M <= 0 || !gemm_fp8_supported(N, K) || (epi != EPI_RESIDUAL && epi != EPI_SILU_MUL)) return 0;
+    if (epi == EPI_RESIDUAL && ((N & 7) || (ldc & 7) || (ldr & 7))) return 0;
+    const int splits = pick_splits(M, N, K / BKB, part_bytes);
+    if (splits < 2) return 0;
+    GemmParams p = base_params(A, lda, sa, W, ldw, sw, M, N, K / splits);
+    p.dst = (bf16_t*)part;
+    p.ld = N;
+    p.ldr = M * (int64_t)N;
+    launch_t<EPI_PARTIAL>(p, s, splits);
+    if (epi == EPI_RESIDUAL) launch_splitk_reduce_residual(part, splits, R, ldr, C, ldc, M, N, s);
+    else launch_splitk_reduce_silu(part, splits, C, ldc, M, N, s);
+    return splits;
+}
+
+int launch_gemm_fp8_qkv_rope_splitk(const unsigned char* A, int64_t lda, const float* sa, const unsigned char* Wqkv,
+                                    int64_t ldw, const float* sw, const bf16_t* bias, bf16_t* Q, bf16_t* Kd, bf16_t* Vt,
+                                    int64_t ldv, const float* rope_cos, const float* rope_sin, int64_t pos0,
+                                    const int32_t* row_pos, int64_t M, int qd, int kvd, int hd, int K, float* part,
+                                    size_t part_bytes, hipStream_t s) {
+    const int N = qd + 2 * kvd;
+    if (M <= 0 || !gemm_fp8_supported(N, K) || (qd & 63) || (kvd & 63) || (hd & 63)) return 0;
+    const int splits = pick_splits(M, N, K / BKB, part_bytes);
+    if (splits < 2) return 0;
+    GemmParams p = base_params(A, lda, sa, Wqkv, ldw, sw, M, N, K / splits);
+    p.dst = (bf16_t*)part;
+    p.ld = N;
+    p.ldr = M * (int64_t)N;
+    launch_t<EPI_PARTIAL>(p, s, splits);
+    GemmParams r = base_params(A, lda, sa, Wqkv, ldw, sw, M, N, K);
+    r.bias = bias; r.dst = Q; r.dst_k = Kd; r.dst_vt = Vt; r.ldv = ldv;
+    r.rope_cos = rope_cos; r.rope_sin = rope_sin; r.pos0 = pos0; r.row_pos = row_pos;
+    r.qd = qd; r.kvd = kvd; r.hd = hd;
+    launch_splitk_reduce_qkv(part, splits, r, s);
+    return splits;
 }
 
 void launch_gemm_fp8_qkv_rope(const unsigned char* A, int64_t lda, const float* sa, const unsigned char* Wqkv, int64_t ldw,

@@ -349,18 +349,35 @@ void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, in
     }
 }
 
-namespace {
-// splits of the reduction for a GEMM with few output tiles: enough workgroups for the chip's 256 compute
-// units, whole slices, at least two per split, partials within part_bytes; 1 = do not split
-int pick_splits(int64_t M, int N, int K, size_t part_bytes) {
+namespace gemm {
+
+int pick_splits(int64_t M, int N, int kt, size_t part_bytes) {
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-    const int KT = K / BK;
     int splits = 1;
-    while (splits < 16 && tiles * splits * 2 <= 256 && KT % (splits * 2) == 0 && KT / (splits * 2) >= 2) splits *= 2;
+    while (splits < 16 && tiles * splits * 2 <= 256 && kt % (splits * 2) == 0 && kt / (splits * 2) >= 2) splits *= 2;
     while (splits > 1 && (size_t)splits * (size_t)M * (size_t)N * sizeof(float) > part_bytes) splits /= 2;
     return splits;
 }
-}  // namespace
+
+void launch_splitk_reduce_residual(const float* part, int splits, const bf16_t* R, int64_t ldr, bf16_t* C, int64_t ldc,
+                                   int64_t M, int N, hipStream_t s) {
+    const int64_t n = M * (int64_t)(N >> 3);
+    hipLaunchKernelGGL(splitk_reduce_residual_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part,
+                       M * (int64_t)N, splits, R, ldr, C, ldc, (int)M, N);
+}
+
+void launch_splitk_reduce_silu(const float* part, int splits, bf16_t* H, int64_t ldh, int64_t M, int N, hipStream_t s) {
+    const int64_t n = M * (int64_t)(N >> 1);
+    hipLaunchKernelGGL(splitk_reduce_silu_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part, M * (int64_t)N,
+                       splits, H, ldh, (int)M, N);
+}
+
+void launch_splitk_reduce_qkv(const float* part, int splits, const GemmParams& r, hipStream_t s) {
+    hipLaunchKernelGGL(splitk_reduce_qkv_kernel, dim3((unsigned)(r.N / 64), (unsigned)((r.M + 7) / 8)), dim3(256), 0, s, part,
+                       (int64_t)r.M * r.N, splits, r);
+}
+
+}  // namespace gemm
 
 int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
                                 bf16_t* Q, bf16_t* Kd, bf16_t* Vt, int64_t ldv, const float* rope_cos,
@@ -368,7 +385,7 @@ int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv
                                 int hd, int K, float* part, size_t part_bytes, bool launch, hipStream_t s) {
     const int N = qd + 2 * kvd;
     if (M <= 0 || !gemm_mfma_supported(N, K) || (qd & 63) || (kvd & 63) || (hd & 63)) return 0;
-    const int splits = pick_splits(M, N, K, part_bytes);
+    const int splits = pick_splits(M, N, K / BK, part_bytes);
     if (splits < 2) return 0;
     if (!launch) return splits;
     GemmParams p = base_params(A, lda, Wqkv, ldw, M, N, K / splits);
@@ -380,15 +397,14 @@ int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv
     r.bias = bias; r.dst = Q; r.dst_k = Kd; r.dst_vt = Vt; r.ldv = ldv;
     r.rope_cos = rope_cos; r.rope_sin = rope_sin; r.pos0 = pos0; r.row_pos = row_pos;
     r.qd = qd; r.kvd = kvd; r.hd = hd;
-    hipLaunchKernelGGL(splitk_reduce_qkv_kernel, dim3((unsigned)(N / 64), (unsigned)((M + 7) / 8)), dim3(256), 0, s, part,
-                       M * (int64_t)N, splits, r);
+    launch_splitk_reduce_qkv(part, splits, r, s);
     return splits;
 }
 
 int launch_gemm_mfma_splitk_silu(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* H, int64_t ldh,
                                  int64_t M, int N, int K, float* part, size_t part_bytes, bool launch, hipStream_t s) {
     if (M <= 0 || !gemm_mfma_supported(N, K)) return 0;
-    const int splits = pick_splits(M, N, K, part_bytes);
+    const int splits = pick_splits(M, N, K / BK, part_bytes);
     if (splits < 2) return 0;
     if (!launch) return splits;
     GemmParams p = base_params(A, lda, W, ldw, M, N, K / splits);
@@ -396,9 +412,7 @@ int launch_gemm_mfma_splitk_silu(const bf16_t* A, int64_t lda, const bf16_t* W, 
     p.ld = N;
     p.ldr = M * (int64_t)N;
     launch_t<EPI_PARTIAL>(p, s, splits);
-    const int64_t n = M * (int64_t)(N >> 1);
-    hipLaunchKernelGGL(splitk_reduce_silu_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part, M * (int64_t)N,
-                       splits, H, ldh, (int)M, N);
+    launch_splitk_reduce_silu(part, splits, H, ldh, M, N, s);
     return splits;
 }
 
@@ -406,7 +420,7 @@ int launch_gemm_mfma_splitk_residual(const bf16_t* A, int64_t lda, const bf16_t*
                                      int64_t ldc, const bf16_t* R, int64_t ldr, int64_t M, int N, int K,
                                      float* part, size_t part_bytes, bool launch, hipStream_t s) {
     if (M <= 0 || N <= 0 || !gemm_mfma_supported(N, K) || (N & 7) || (ldc & 7) || (ldr & 7)) return 0;
-    const int splits = pick_splits(M, N, K, part_bytes);
+    const int splits = pick_splits(M, N, K / BK, part_bytes);
     if (splits < 2) return 0;
     if (!launch) return splits;
     GemmParams p = base_params(A, lda, W, ldw, M, N, K / splits);
@@ -414,9 +428,7 @@ int launch_gemm_mfma_splitk_residual(const bf16_t* A, int64_t lda, const bf16_t*
     p.ld = N;
     p.ldr = M * (int64_t)N;              // floats between two splits' planes
     launch_t<EPI_PARTIAL>(p, s, splits);
-    const int64_t n = M * (int64_t)(N >> 3);
-    hipLaunchKernelGGL(splitk_reduce_residual_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part,
-                       M * (int64_t)N, splits, R, ldr, C, ldc, (int)M, N);
+    launch_splitk_reduce_residual(part, splits, R, ldr, C, ldc, M, N, s);
     return splits;
 }
 

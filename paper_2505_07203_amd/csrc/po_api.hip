@@ -357,9 +357,18 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                 launch_rmsnorm(dt, X + (size_t)c0 * d * esz, c->w + o.attn_norm, Xn, rows, d, m.rms_eps, s);
             PhaseTimer pt(c, PO_K_QKV);
             if (fp8) {
-                launch_gemm_fp8_qkv_rope(Xn, d, sx, wqkv, d, (const float*)(c->w + o.s_wqkv), (const bf16_t*)bqkv,
-                                         (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
-                                         (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, s);
+                const size_t h_bytes = (size_t)L.chunk * F * esz;
+                const size_t h_used = (Xn == H) ? (((size_t)rows * d) + ALIGN - 1) / ALIGN * ALIGN : 0;   // codes: one byte each
+                if (c->split_few_rows && h_used < h_bytes &&
+                    launch_gemm_fp8_qkv_rope_splitk(Xn, d, sx, wqkv, d, (const float*)(c->w + o.s_wqkv), (const bf16_t*)bqkv,
+                                                    (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
+                                                    (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d,
+                                                    (float*)(H + h_used), h_bytes - h_used, s) > 1)
+                    ++n_split_launches;
+                else
+                    launch_gemm_fp8_qkv_rope(Xn, d, sx, wqkv, d, (const float*)(c->w + o.s_wqkv), (const bf16_t*)bqkv,
+                                             (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
+                                             (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, s);
             } else if (dt == PO_BF16) {
                 // one GEMM: RoPE applied to Q and K in the epilogue, V written as V^T (few rows: split over K,
                 // partials in the chunk buffer H behind the norm output if that sits there)
@@ -460,24 +469,41 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
             unsigned char* Xc = X + (size_t)c0 * d * esz;
             const unsigned char* Oc = Q + (size_t)c0 * qd * esz;
             if (fp8) {
+                // few rows: the same split over K as on the bf16 path; scratch = H behind this chunk's rows
+                const size_t h_bytes = (size_t)L.chunk * F * esz;
+                const size_t h_used = (((size_t)rows * F * esz) + ALIGN - 1) / ALIGN * ALIGN;
+                const bool split = c->split_few_rows && h_used < h_bytes;
+                float* part = (float*)(H + h_used);
                 // attention output -> codes (into the norm buffer), O-projection + residual
                 launch_quant_rows((const bf16_t*)Oc, qd, Xn, qd, sx, rows, qd, 0, 0, 0, s);
                 {
                     PhaseTimer pt(c, PO_K_RESIDUAL);
-                    launch_gemm_fp8(EPI_RESIDUAL, Xn, qd, sx, c->w + o.wo, qd, (const float*)(c->w + o.s_wo), (bf16_t*)Xc, d,
-                                    nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
+                    if (split && launch_gemm_fp8_splitk(EPI_RESIDUAL, Xn, qd, sx, c->w + o.wo, qd, (const float*)(c->w + o.s_wo),
+                                                        (bf16_t*)Xc, d, (const bf16_t*)Xc, d, rows, d, qd, part, h_bytes - h_used, s) > 1)
+                        ++n_split_launches;
+                    else
+                        launch_gemm_fp8(EPI_RESIDUAL, Xn, qd, sx, c->w + o.wo, qd, (const float*)(c->w + o.s_wo), (bf16_t*)Xc, d,
+                                        nullptr, (const bf16_t*)Xc, d, rows, d, qd, s);
                 }
                 launch_rmsnorm_quant((const bf16_t*)Xc, (const bf16_t*)(c->w + o.mlp_norm), Xn, sx, rows, d, m.rms_eps, s);
                 {
                     PhaseTimer pt(c, PO_K_GATE_UP);
-                    launch_gemm_fp8(EPI_SILU_MUL, Xn, d, sx, c->w + o.wgu, d, (const float*)(c->w + o.s_wgu), (bf16_t*)H, F,
-                                    nullptr, nullptr, 0, rows, 2 * F, d, s);
+                    if (split && launch_gemm_fp8_splitk(EPI_SILU_MUL, Xn, d, sx, c->w + o.wgu, d, (const float*)(c->w + o.s_wgu),
+                                                        (bf16_t*)H, F, nullptr, 0, rows, 2 * F, d, part, h_bytes - h_used, s) > 1)
+                        ++n_split_launches;
+                    else
+                        launch_gemm_fp8(EPI_SILU_MUL, Xn, d, sx, c->w + o.wgu, d, (const float*)(c->w + o.s_wgu), (bf16_t*)H, F,
+                                        nullptr, nullptr, 0, rows, 2 * F, d, s);
                 }
                 // the gated intermediate -> codes in place (a row's codes take the first half of the row)
                 launch_quant_rows((const bf16_t*)H, F, H, 2 * (int64_t)F, sx, rows, F, 0, 0, 0, s);
                 PhaseTimer pt(c, PO_K_RESIDUAL);
-                launch_gemm_fp8(EPI_RESIDUAL, H, 2 * (int64_t)F, sx, c->w + o.wd, F, (const float*)(c->w + o.s_wd), (bf16_t*)Xc, d,
-                                nullptr, (const bf16_t*)Xc, d, rows, d, F, s);
+                if (split && launch_gemm_fp8_splitk(EPI_RESIDUAL, H, 2 * (int64_t)F, sx, c->w + o.wd, F, (const float*)(c->w + o.s_wd),
+                                                    (bf16_t*)Xc, d, (const bf16_t*)Xc, d, rows, d, F, part, h_bytes - h_used, s) > 1)
+                    ++n_split_launches;
+                else
+                    launch_gemm_fp8(EPI_RESIDUAL, H, 2 * (int64_t)F, sx, c->w + o.wd, F, (const float*)(c->w + o.s_wd), (bf16_t*)Xc, d,
+                                    nullptr, (const bf16_t*)Xc, d, rows, d, F, s);
             } else if (dt == PO_BF16) {
                 // few rows (a short request, or the suffix behind a long cached prefix): the two GEMMs with
                 // only d output columns split their reduction over K so that the whole chip streams the

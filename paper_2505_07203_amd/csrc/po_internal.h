@@ -128,6 +128,16 @@ void launch_gemm_fp8_qkv_rope(const unsigned char* A, int64_t lda, const float* 
                               const float* sw, const bf16_t* bias, bf16_t* Q, bf16_t* K, bf16_t* Vt, int64_t ldv,
                               const float* rope_cos, const float* rope_sin, int64_t pos0, const int32_t* row_pos,
                               int64_t M, int qd, int kvd, int hd, int Kdim, hipStream_t s);
+// split-K forms of the two above for launches with few rows (see launch_gemm_mfma_splitk_residual): return the
+// number of splits used, 0 = nothing launched (not worth it, or part_bytes of scratch too small)
+int launch_gemm_fp8_splitk(int epi, const unsigned char* A, int64_t lda, const float* sa, const unsigned char* W,
+                           int64_t ldw, const float* sw, bf16_t* C, int64_t ldc, const bf16_t* R, int64_t ldr, int64_t M,
+                           int N, int K, float* part, size_t part_bytes, hipStream_t s);
+int launch_gemm_fp8_qkv_rope_splitk(const unsigned char* A, int64_t lda, const float* sa, const unsigned char* Wqkv,
+                                    int64_t ldw, const float* sw, const bf16_t* bias, bf16_t* Q, bf16_t* Kd, bf16_t* Vt,
+                                    int64_t ldv, const float* rope_cos, const float* rope_sin, int64_t pos0,
+                                    const int32_t* row_pos, int64_t M, int qd, int kvd, int hd, int K, float* part,
+                                    size_t part_bytes, hipStream_t s);
 // q, scales = quantise(bf16(rmsnorm(x; g)))   (d % 8 == 0, d <= 8192)
 void launch_rmsnorm_quant(const bf16_t* x, const bf16_t* g, unsigned char* q, float* scales, int64_t rows, int d,
                           float eps, hipStream_t s);

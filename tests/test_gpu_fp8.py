@@ -185,6 +185,16 @@ def test_fp8_full_path_against_the_oracle(cfg, n, chunk):
         assert abs(float(np.sum(np.exp(lp.astype(np.float64)))) - 1.0) < 1e-5
         if np.sort(z_s)[-1] - np.sort(z_s)[-2] > 2 * tol * scale:
             assert int(np.argmax(z)) == int(np.argmax(z_s))
+        # few-rows mode (split reductions): another summation order, the same bar
+        ctx.po_set_few_rows_split(True)
+        z2, lp2 = ctx.po_prefill(tokens, cand)
+        assert ctx.po_get_stats()["split_launches"] > 0
+        z2 = z2.astype(np.float64)
+        e2_s, e2_e = np.max(np.abs(z2 - z_s)) / scale, np.max(np.abs(z2 - z_e)) / scale
+        print(f"    few-rows mode: vs stored {e2_s:.3e}, vs exact {e2_e:.3e}")
+        assert e2_s <= tol and e2_e <= tol
+        if np.sort(z_s)[-1] - np.sort(z_s)[-2] > 2 * tol * scale:
+            assert int(np.argmax(z2)) == int(np.argmax(z_s))
     finally:
         ctx.po_destroy()
 
