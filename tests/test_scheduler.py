@@ -141,6 +141,21 @@ def test_library_pick_multi_matches_oracle():
     assert sch.po_sched_pick_multi([], 0.0) == (1, 0)
 
 
+def test_library_matches_long_prefixes_exactly():
+    """Common prefixes longer than the library's 64-token compare blocks, ending at every offset inside a block."""
+    rng = np.random.default_rng(11)
+    base = rng.integers(0, 1000, 700).tolist()
+    for m in (0, 1, 63, 64, 65, 127, 128, 129, 191, 300, 511, 512, 513, 699):
+        sch = B.Scheduler(0.0)
+        req = base[:m] + [1001] + rng.integers(0, 1000, 40).tolist()         # differs from the cache at position m
+        sch.po_sched_push(5, req, 0.0)
+        assert sch.po_sched_pick(base, 0.0) == (5, m)
+        assert S.n_cached(req, base) == m
+        sch.po_sched_push(6, base[:m + 1] if m < 699 else base, 0.0)          # wholly inside the cache: capped at len - 1
+        rid, hit = sch.po_sched_pick_multi([base[:10], base], 0.0)
+        assert rid == 6 and hit == (m if m < 699 else 699)
+
+
 def test_library_scheduler_on_the_papers_example():
     want = golden_example()["calibrated"]
     sch = B.Scheduler(0.0)
