@@ -224,6 +224,8 @@ def main():
     ap.add_argument("--fp8", action="store_true",
                     help="variant: the decoder's linear layers run FP8-dynamic (E4M3 weights per output channel, "
                          "activations per token); reported under its own metric name and dtype, never as the bf16 metric")
+    ap.add_argument("--few-rows", action="store_true",
+                    help="variant: few-rows mode (po_set_few_rows_split) for launches with few rows; reported in config")
     ap.add_argument("--packed", type=int, default=0,
                     help="variant: run the workload's requests through po_prefill_packed with buffers of this many "
                          "rows (consecutive short requests share the launches of the position-wise layers)")
@@ -258,6 +260,7 @@ def main():
     ctx.load_synthetic(w["wseed"], threads=16)
     load_s = time.perf_counter() - t0
     ctx.po_set_phase_timing(not args.no_phase_timing)
+    ctx.po_set_few_rows_split(args.few_rows)
 
     classes = B.KERNEL_CLASSES
 
@@ -323,14 +326,14 @@ def main():
                 "share_of_step_time": (k_ms[k] / args.steps) / ms_per_step}
 
     out = {
-        "metric": "prefill tokens/s on 1 MI355X (8B-shape, 32k ctx)" if args.workload == "llama8b_32k" and not args.layers and not args.fp8
+        "metric": "prefill tokens/s on 1 MI355X (8B-shape, 32k ctx)" if args.workload == "llama8b_32k" and not args.layers and not args.fp8 and not args.few_rows
                   else f"prefill tokens/s on 1 MI355X ({args.workload}" + (", FP8-dynamic linear layers)" if args.fp8 else ")"),
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {I.BF16: "bf16", I.F32: "f32", I.BF16_FP8: "fp8 e4m3 linear layers, bf16 elsewhere"}[cfg.dtype], "data": "synthetic",
         "config": {"workload": args.workload, "layers": cfg.n_layers, "d_model": cfg.d_model,
                    "requests": len(lens), "tokens": tokens, "mlp_chunk": chunk, "packed_rows": args.packed,
-                   "weights": "random-init N(0,0.02), seeded"},
+                   "few_rows_split": bool(args.few_rows), "weights": "random-init N(0,0.02), seeded"},
         "end_to_end": {"algorithmic_tflop": (lin_f + att_f) / 1e12,
                        "achieved_tflops": (lin_f + att_f) / 1e12 / (ms_per_step / 1e3),
                        "frac_of_bf16_mfma_peak": (lin_f + att_f) / 1e12 / (ms_per_step / 1e3) / PEAK_BF16_TFLOPS},
