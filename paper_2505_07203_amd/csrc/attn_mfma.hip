@@ -776,9 +776,10 @@ int launch_split_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t l
     if (nq <= 0 || nq > 4 * BMQ) return 0;
     const int nqt = (int)((nq + BMQ - 1) / BMQ);
     const int n_kv_first = (int)((std::min<int64_t>(N, q_row0 + BMQ) - 1) / BNK + 1);     // key tiles of the first query tile
-    // enough workgroups for 256 compute units, at least two key tiles per split
+    // at most 8 splits (measured at 32 heads of 128: 150 rows behind 14 000 keys take 116 / 73 / 84 / 104 us per
+    // layer with 4 / 8 / 16 / 32 splits, 600 rows 213 / 195 with 4 / 8), at least two key tiles per split
     int n_split = 1;
-    while (n_split < 32 && (int64_t)nqt * Hq * n_split < 512 && n_kv_first >= 4 * n_split) n_split *= 2;
+    while (n_split < 8 && (int64_t)nqt * Hq * n_split < 1024 && n_kv_first >= 4 * n_split) n_split *= 2;
     const size_t o_bytes = (size_t)n_split * nq * Hq * HD * sizeof(float), ml_bytes = (size_t)n_split * nq * Hq * 2 * sizeof(float);
     if (n_split < 2 || o_bytes + ml_bytes > scratch_bytes) return 0;
     if (!launch) return n_split;

@@ -354,7 +354,8 @@ namespace gemm {
 int pick_splits(int64_t M, int N, int kt, size_t part_bytes) {
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     int splits = 1;
-    while (splits < 16 && tiles * splits * 2 <= 256 && kt % (splits * 2) == 0 && kt / (splits * 2) >= 2) splits *= 2;
+    // (8 against 16 splits measured equal on the 8B shape's O / down projections at 150 rows, 4 a quarter slower)
+    while (splits < 8 && tiles * splits * 2 <= 256 && kt % (splits * 2) == 0 && kt / (splits * 2) >= 2) splits *= 2;
     while (splits > 1 && (size_t)splits * (size_t)M * (size_t)N * sizeof(float) > part_bytes) splits /= 2;
     return splits;
 }
