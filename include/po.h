@@ -231,7 +231,8 @@ po_status po_kv_cache_slot(const po_ctx* ctx, int32_t slot, int32_t* tokens_out,
  * (see po_attach_kv_cache_slots for which; keep_prefix <= len and <= prefix_capacity, else PO_ERR_TOO_LONG);
  * keep_prefix = 0 leaves the cache as it is; keep_prefix = PO_KEEP_ALL keeps as much of the
  * request as an entry holds, min(len, prefix_capacity).  The outputs are bit-identical to po_prefill
- * on the same tokens (a row's result does not depend on which other rows are computed).
+ * on the same tokens (a row's result does not depend on which other rows are computed; in
+ * few-rows mode, see po_set_few_rows_split, equal within tolerance instead).
  * PO_ERR_INVALID_ARG without an attached cache. */
 #define PO_KEEP_ALL (-1)
 po_status po_prefill_prefix(po_ctx* ctx, const int32_t* tokens, int64_t len, int64_t keep_prefix,
