@@ -342,6 +342,13 @@ po_status po_op_rmsnorm(int32_t dtype, const void* dev_x, const void* dev_g, voi
  * dev_residual may be NULL, or a [M, N] tensor added before the store (may alias dev_c). */
 po_status po_op_linear(int32_t dtype, const void* dev_a, const void* dev_w, void* dev_c,
                        const void* dev_residual, int64_t M, int32_t N, int32_t K, void* hip_stream);
+/* The few-rows form of po_op_linear with a residual (bf16 only; see po_set_few_rows_split): C = A W^T + R with
+ * the reduction over K split between workgroups, fp32 partial sums in dev_scratch (scratch_bytes; 256-byte
+ * aligned).  *splits_used receives the number of splits; 0 or 1 means the shape is not worth splitting or the
+ * scratch is too small, and then NOTHING was computed. */
+po_status po_op_linear_split(const void* dev_a, const void* dev_w, void* dev_c, const void* dev_residual,
+                             void* dev_scratch, size_t scratch_bytes, int64_t M, int32_t N, int32_t K,
+                             void* stream, int32_t* splits_used);
 
 /* Gate/up projection with the SiLU-multiply of the MLP (Section 4.1's MLP figure):
  * H[M, F] = silu(A Wg^T) * (A Wu^T); dev_wgu is [2F, K] in the library's interleaved

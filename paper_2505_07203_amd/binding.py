@@ -38,7 +38,7 @@ EXPORTS = [
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
     "po_op_quantize_rows", "po_op_rmsnorm_quantize", "po_op_linear_fp8", "po_op_qkv_rope_fp8",
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
-    "po_profile_jct", "po_engine_step", "po_set_few_rows_split",
+    "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_op_linear_split",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick",
 ]
@@ -114,6 +114,7 @@ def lib() -> C.CDLL:
     L.po_last_device_error.restype = C.c_char_p
     L.po_op_rmsnorm.argtypes = [i32, vp, vp, vp, i64, i32, f32, vp]
     L.po_op_linear.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, vp]
+    L.po_op_linear_split.argtypes = [vp, vp, vp, vp, vp, sz, i64, i32, i32, vp, C.POINTER(i32)]
     L.po_op_gate_up_silu.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, vp]
     L.po_op_pack_gate_up.argtypes = [i32, vp, vp, vp, i32, i32, vp]
     L.po_op_attention.argtypes = [i32, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
@@ -392,6 +393,20 @@ def po_op_linear(a, w, residual=None, out=None):
     check(lib().po_op_linear(_dt(a), a.data_ptr(), w.data_ptr(), c.data_ptr(),
                              None if residual is None else residual.data_ptr(), M, N, K, _stream()))
     return c
+
+
+def po_op_linear_split(a, w, residual, scratch_bytes=1 << 28):
+    """-> (C or None, splits): the split-K form of po_op_linear with a residual; None when nothing was split"""
+    import torch
+    M, K = a.shape
+    N = w.shape[0]
+    c = torch.empty((M, N), dtype=a.dtype, device=a.device)
+    scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device=a.device)
+    n = C.c_int32(0)
+    check(lib().po_op_linear_split(a.data_ptr(), w.data_ptr(), c.data_ptr(), residual.data_ptr(), scratch.data_ptr(),
+                                   scratch_bytes, M, N, K, _stream(), C.byref(n)))
+    torch.cuda.synchronize()
+    return (c if n.value > 1 else None), n.value
 
 
 def po_op_quantize_rows(x, in_place=False):

@@ -1226,6 +1226,17 @@ po_status po_op_linear(int32_t dtype, const void* a, const void* w, void* cc, co
     return PO_OK;
 }
 
+po_status po_op_linear_split(const void* a, const void* w, void* cc, const void* residual, void* scratch,
+                             size_t scratch_bytes, int64_t M, int32_t N, int32_t K, void* stream, int32_t* splits_used) {
+    if (!a || !w || !cc || !residual || !scratch || !splits_used || M <= 0 || N <= 0 || K <= 0) return PO_ERR_INVALID_ARG;
+    if (!gemm_mfma_supported(N, K)) return PO_ERR_BAD_CONFIG;
+    *splits_used = launch_gemm_mfma_splitk_residual((const bf16_t*)a, K, (const bf16_t*)w, K, (bf16_t*)cc, N,
+                                                    (const bf16_t*)residual, N, M, N, K, (float*)scratch, scratch_bytes, true,
+                                                    (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
 po_status po_op_gate_up_silu(int32_t dtype, const void* a, const void* wgu, void* h, void* scratch, int64_t M,
                              int32_t F, int32_t K, void* stream) {
     if (bad_dtype(dtype) || !a || !wgu || !h || M <= 0 || F <= 0 || K <= 0) return PO_ERR_INVALID_ARG;

@@ -132,3 +132,39 @@ def test_packed_short_requests_in_few_rows_mode():
             assert int(np.argmax(zp[i])) == int(np.argmax(z))
     finally:
         ctx.po_destroy()
+
+
+@pytest.mark.parametrize("M,N,K", [(150, 4096, 4096), (1, 4096, 14336), (32, 256, 2048), (256, 512, 4096), (100, 320, 1024),
+                                   (600, 4096, 4096), (257, 1024, 14336), (2000, 4096, 4096)])
+def test_split_linear_against_float64(M, N, K):
+    """The split-K residual GEMM by itself: C = A W^T + R against numpy float64 on the stored bf16 operands.
+    Bar: the fp32 accumulation error of K products plus ONE bf16 rounding of the result, as for po_op_linear."""
+    import torch
+    from paper_2505_07203_amd import binding as B
+    g = torch.Generator(device="cpu").manual_seed(M * 7 + N + K)
+    a = torch.randn(M, K, generator=g).to(torch.bfloat16).cuda()
+    w = (torch.randn(N, K, generator=g) * 0.05).to(torch.bfloat16).cuda()
+    r = torch.randn(M, N, generator=g).to(torch.bfloat16).cuda()
+    c, splits = B.po_op_linear_split(a, w, r)
+    assert splits >= 2 and c is not None, "this shape was meant to split"
+    ref = a.double().cpu().numpy() @ w.double().cpu().numpy().T + r.double().cpu().numpy()
+    got = c.double().cpu().numpy()
+    tol = 2.0 ** -8 * np.abs(ref) + 1e-5 * K ** 0.5 * np.max(np.abs(ref))      # half an ulp of bf16, plus accumulation
+    assert np.all(np.abs(got - ref) <= tol), float(np.max(np.abs(got - ref) - tol))
+    # the unsplit kernel on the same operands: equal up to the rounding of the summation order
+    c0 = B.po_op_linear(a, w, residual=r)
+    d = (c.double() - c0.double()).abs().cpu().numpy()
+    assert np.all(d <= 2.0 ** -7 * np.abs(ref) + 2e-5 * K ** 0.5 * np.max(np.abs(ref))), float(d.max())
+
+
+def test_split_linear_declines_large_shapes():
+    import torch
+    from paper_2505_07203_amd import binding as B
+    a = torch.zeros(4096, 4096, dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros(4096, 4096, dtype=torch.bfloat16, device="cuda")
+    r = torch.zeros(4096, 4096, dtype=torch.bfloat16, device="cuda")
+    c, splits = B.po_op_linear_split(a, w, r)
+    assert c is None and splits <= 1                        # 256 tiles fill the chip: nothing to split
+    a = torch.zeros(64, 4096, dtype=torch.bfloat16, device="cuda")
+    c, splits = B.po_op_linear_split(a, w, r[:64].contiguous(), scratch_bytes=4096)
+    assert c is None and splits <= 1                        # scratch too small for even two planes
