@@ -174,3 +174,37 @@ def test_fp8_arenas():
     # shapes the FP8 kernels cannot take are refused up front
     with pytest.raises(B.PoError):
         B.po_workspace_bytes(I.TINY.replace(dtype=I.BF16_FP8, ffn_dim=704), 512, 128)      # 704 is not a multiple of 128
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N > 1 exits with a message instead of measuring something else."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_serving_traces_have_the_papers_structure():
+    """Section 7.1 dataset table: users x posts, profile and post lengths, what is shared."""
+    cfg = I.TINY
+    post = I.make_serving_trace(cfg, "postrec", 5)
+    assert len(post) == 20 * 50
+    by_user = {}
+    for u, t in post:
+        by_user.setdefault(u, []).append(t)
+    assert len(by_user) == 20 and all(len(v) == 50 for v in by_user.values())
+    for v in by_user.values():
+        n_prof = len(v[0]) - 150
+        assert 11000 <= n_prof <= 17000
+        assert all(len(t) == n_prof + 150 and np.array_equal(t[:n_prof], v[0][:n_prof]) for t in v)   # shared profile
+        assert not np.array_equal(v[0][n_prof:], v[1][n_prof:])                                       # own post
+    a, b = by_user[0][0], by_user[1][0]
+    assert not np.array_equal(a[:1000], b[:1000])                                                     # nothing shared across users
+    credit = I.make_serving_trace(cfg, "credit", 5)
+    assert len(credit) == 60 and all(40000 <= len(t) <= 60000 for _, t in credit)
+    assert all(0 <= t.min() and t.max() < cfg.vocab_size for _, t in credit[:3])
+    small = I.make_serving_trace(cfg, "postrec", 5, n_users=3, posts_per_user=2, scale=0.01)
+    assert len(small) == 6 and all(110 + 2 <= len(t) <= 170 + 2 for _, t in small)
+    arr = I.poisson_user_arrivals(9, 1000, 4.0)
+    assert np.all(np.diff(arr) > 0) and abs(arr[-1] / 1000 - 0.25) < 0.03                             # mean gap 1 / rate
