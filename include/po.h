@@ -271,6 +271,10 @@ po_status po_sched_set_jct_model(po_sched* s, double c0, double c_input, double 
 po_status po_sched_fit_jct_model(po_sched* s, const int64_t* n_input, const int64_t* n_cached,
                                  const double* jct, int32_t n, double coef[3]);
 po_status po_sched_push(po_sched* s, int64_t id, const int32_t* tokens, int64_t len, double arrival_time);
+/* The same with the request's own acceptable output tokens (a request is a token sequence plus that
+ * list, Section 2.2); po_engine_step uses them when it is given none. */
+po_status po_sched_push_request(po_sched* s, int64_t id, const int32_t* tokens, int64_t len, const int32_t* cand_ids,
+                                int32_t n_cand, double arrival_time);
 int64_t po_sched_size(const po_sched* s);
 po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cached_tokens, double now,
                         int64_t* id, int64_t* n_cached_hit);
@@ -284,13 +288,17 @@ po_status po_sched_pick_multi(po_sched* s, const int32_t* const* cached_tokens, 
  * n_cached being what ctx's prefix cache would spare it at this moment (po_kv_cache_match; 0
  * without a cache), removes the one with the lowest score from the queue and runs it: with a
  * cache attached through po_prefill_prefix with keep_prefix = PO_KEEP_ALL, otherwise through
- * po_prefill.  Outputs as there; *id receives the request's id (-1, and nothing runs, when
- * the queue is empty), *len and *reused_prefix_len (both may be NULL) its length and the
- * positions it did not compute.  A request whose run fails is NOT put back: the error is
- * returned with *id set. */
+ * po_prefill.  The acceptable output tokens are cand_ids[0 .. n_cand) for whichever request
+ * runs, or, with cand_ids = NULL, the list the request was pushed with (po_sched_push_request;
+ * possibly none).  out_cand_logprobs (may be NULL) holds cand_capacity floats; a longer list is
+ * PO_ERR_INVALID_ARG and leaves the queue as it is.  *n_cand_used (may be NULL) receives the
+ * number of log-probs written.  Other outputs as in po_prefill; *id receives the request's id
+ * (-1, and nothing runs, when the queue is empty), *len and *reused_prefix_len (both may be
+ * NULL) its length and the positions it did not compute.  A request whose run fails is NOT put
+ * back: the error is returned with *id set. */
 po_status po_engine_step(po_ctx* ctx, po_sched* s, double now, const int32_t* cand_ids, int32_t n_cand,
-                         float* out_logits, float* out_cand_logprobs, int64_t* id, int64_t* len,
-                         int64_t* reused_prefix_len);
+                         float* out_logits, float* out_cand_logprobs, int32_t cand_capacity, int64_t* id,
+                         int64_t* len, int64_t* reused_prefix_len, int32_t* n_cand_used);
 
 /* Last-layer shortcut, on by default.  A prefill-only request produces one token (Section 1),
  * so nothing reads the last layer's output except at the last position: with the shortcut

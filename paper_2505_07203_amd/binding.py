@@ -38,7 +38,7 @@ EXPORTS = [
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
     "po_op_quantize_rows", "po_op_rmsnorm_quantize", "po_op_linear_fp8", "po_op_qkv_rope_fp8",
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
-    "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_op_linear_split",
+    "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_op_linear_split", "po_sched_push_request",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick",
 ]
@@ -101,7 +101,9 @@ def lib() -> C.CDLL:
     L.po_kv_cache_match.argtypes = [vp, vp, i64, C.POINTER(i64)]
     L.po_kv_cache_slot.argtypes = [vp, i32, vp, i64, C.POINTER(i64)]
     L.po_set_few_rows_split.argtypes = [vp, i32]
-    L.po_engine_step.argtypes = [vp, vp, C.c_double, vp, i32, vp, vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    L.po_engine_step.argtypes = [vp, vp, C.c_double, vp, i32, vp, vp, i32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64),
+                                 C.POINTER(i32)]
+    L.po_sched_push_request.argtypes = [vp, i64, vp, i64, vp, i32, C.c_double]
     L.po_profile_jct.argtypes = [vp, i64, i64, vp, vp, vp, i32, C.POINTER(i32)]
     L.po_sched_pick_multi.argtypes = [vp, vp, vp, i32, C.c_double, C.POINTER(i64), C.POINTER(i64)]
     L.po_prefill_prefix.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, C.POINTER(i64)]
@@ -314,16 +316,18 @@ class Context:
         return logits, lp, reused.value
 
     def po_engine_step(self, sched: "Scheduler", now: float, cand: Optional[Sequence[int]] = None,
-                       want_logits: bool = False):
-        """-> (id or -1, length, reused prefix length, logits or None, candidate log-probs or None)"""
+                       want_logits: bool = False, cand_capacity: int = 64):
+        """-> (id or -1, length, reused prefix length, logits or None, candidate log-probs or None).
+        cand=None: the list each request was pushed with (at most cand_capacity ids)."""
         n_cand = 0 if cand is None else len(cand)
         cand_a = None if cand is None else np.ascontiguousarray(cand, dtype=np.int32)
+        cap = max(n_cand, cand_capacity)
         logits = np.empty(self.cfg.vocab_size, dtype=np.float32) if want_logits else None
-        lp = np.empty(n_cand, dtype=np.float32) if n_cand else None
-        rid, n, reused = C.c_int64(-1), C.c_int64(0), C.c_int64(0)
-        check(lib().po_engine_step(self._h, sched._h, now, _host_ptr(cand_a), n_cand, _host_ptr(logits), _host_ptr(lp),
-                                   C.byref(rid), C.byref(n), C.byref(reused)))
-        return rid.value, n.value, reused.value, logits, lp
+        lp = np.empty(cap, dtype=np.float32)
+        rid, n, reused, used = C.c_int64(-1), C.c_int64(0), C.c_int64(0), C.c_int32(0)
+        check(lib().po_engine_step(self._h, sched._h, now, _host_ptr(cand_a), n_cand, _host_ptr(logits), _host_ptr(lp), cap,
+                                   C.byref(rid), C.byref(n), C.byref(reused), C.byref(used)))
+        return rid.value, n.value, reused.value, logits, (lp[:used.value] if used.value else None)
 
     def po_set_few_rows_split(self, on: bool) -> None:
         check(lib().po_set_few_rows_split(self._h, 1 if on else 0))
@@ -568,6 +572,12 @@ class Scheduler:
     def po_sched_push(self, rid: int, tokens, arrival_time: float) -> None:
         t = np.ascontiguousarray(tokens, dtype=np.int32)
         check(lib().po_sched_push(self._h, rid, _host_ptr(t), t.shape[0], arrival_time))
+
+    def po_sched_push_request(self, rid: int, tokens, cand, arrival_time: float) -> None:
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        c = np.ascontiguousarray(cand, dtype=np.int32)
+        check(lib().po_sched_push_request(self._h, rid, _host_ptr(t), t.shape[0], _host_ptr(c) if c.size else None, c.shape[0],
+                                          arrival_time))
 
     def po_sched_size(self) -> int:
         return int(lib().po_sched_size(self._h))

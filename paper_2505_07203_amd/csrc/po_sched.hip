@@ -23,6 +23,7 @@ struct po_sched {
         int64_t id;
         double arrival;
         std::vector<int32_t> tokens;
+        std::vector<int32_t> cand;      // the request's own acceptable output tokens (may be empty)
     };
     std::vector<Req> queue;   // push order
 };
@@ -88,14 +89,21 @@ po_status po_sched_fit_jct_model(po_sched* s, const int64_t* n_input, const int6
     return PO_OK;
 }
 
-po_status po_sched_push(po_sched* s, int64_t id, const int32_t* tokens, int64_t len, double arrival_time) {
-    if (!s || !tokens || len <= 0 || !std::isfinite(arrival_time)) return PO_ERR_INVALID_ARG;
+po_status po_sched_push_request(po_sched* s, int64_t id, const int32_t* tokens, int64_t len, const int32_t* cand_ids,
+                                int32_t n_cand, double arrival_time) {
+    if (!s || !tokens || len <= 0 || !std::isfinite(arrival_time) || n_cand < 0 || (n_cand > 0 && !cand_ids))
+        return PO_ERR_INVALID_ARG;
     po_sched::Req r;
     r.id = id;
     r.arrival = arrival_time;
     r.tokens.assign(tokens, tokens + len);
+    if (n_cand > 0) r.cand.assign(cand_ids, cand_ids + n_cand);
     s->queue.push_back(std::move(r));
     return PO_OK;
+}
+
+po_status po_sched_push(po_sched* s, int64_t id, const int32_t* tokens, int64_t len, double arrival_time) {
+    return po_sched_push_request(s, id, tokens, len, nullptr, 0, arrival_time);
 }
 
 int64_t po_sched_size(const po_sched* s) { return s ? (int64_t)s->queue.size() : 0; }
@@ -128,10 +136,11 @@ po_status po_sched_pick_multi(po_sched* s, const int32_t* const* cached_tokens, 
 }
 
 po_status po_engine_step(po_ctx* ctx, po_sched* s, double now, const int32_t* cand_ids, int32_t n_cand,
-                         float* out_logits, float* out_cand_logprobs, int64_t* id, int64_t* len,
-                         int64_t* reused_prefix_len) {
-    if (!ctx || !s || !id) return PO_ERR_INVALID_ARG;
+                         float* out_logits, float* out_cand_logprobs, int32_t cand_capacity, int64_t* id, int64_t* len,
+                         int64_t* reused_prefix_len, int32_t* n_cand_used) {
+    if (!ctx || !s || !id || n_cand < 0 || cand_capacity < 0 || (cand_ids && n_cand == 0)) return PO_ERR_INVALID_ARG;
     *id = -1;
+    if (n_cand_used) *n_cand_used = 0;
     if (len) *len = 0;
     if (reused_prefix_len) *reused_prefix_len = 0;
     if (s->queue.empty()) return PO_OK;
@@ -151,10 +160,17 @@ po_status po_engine_step(po_ctx* ctx, po_sched* s, double now, const int32_t* ca
         const double score = jct - s->lambda * (now - r.arrival);
         if (i == 0 || score < best_score) { best = i; best_score = score; }
     }
+    // the acceptable-token list: the caller's for whichever request runs, else the request's own; the output
+    // buffer must hold it (checked before the request leaves the queue)
+    const bool own = cand_ids == nullptr;
+    if (own) n_cand = (int32_t)s->queue[best].cand.size();
+    if (out_cand_logprobs && n_cand > cand_capacity) return PO_ERR_INVALID_ARG;
     po_sched::Req r = std::move(s->queue[best]);
     s->queue.erase(s->queue.begin() + (std::ptrdiff_t)best);
+    if (own) cand_ids = r.cand.empty() ? nullptr : r.cand.data();
     *id = r.id;
     if (len) *len = (int64_t)r.tokens.size();
+    if (n_cand_used) *n_cand_used = out_cand_logprobs ? n_cand : 0;
     if (cached)
         return po_prefill_prefix(ctx, r.tokens.data(), (int64_t)r.tokens.size(), PO_KEEP_ALL, cand_ids, n_cand, out_logits,
                                  out_cand_logprobs, reused_prefix_len);

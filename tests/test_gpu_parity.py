@@ -551,6 +551,24 @@ def test_engine_step_matches_a_hand_driven_loop():
         ctx.po_detach_kv_cache()
         order, reuse = engine(0.0, 0)
         assert reuse == [0] * len(reqs) and [len(reqs[i]) for i in order] == sorted(len(t) for t in reqs)
+        # requests that carry their own acceptable-token lists (a request = tokens + that list, Section 2.2)
+        own = [[5, 9], [100, 7, 33], [], [1, 2, 3, 4, 5, 6, 7, 8]]
+        sch = B.Scheduler(1e9)                                                     # arrival order
+        for i, c_i in enumerate(own):
+            sch.po_sched_push_request(i, reqs[i], c_i, 0.001 * i)
+        for i, c_i in enumerate(own[:3]):
+            rid, n, _, _, lp = ctx.po_engine_step(sch, 1.0)
+            assert rid == i
+            if c_i:
+                want = ctx.po_prefill(reqs[i], c_i, want_logits=False)[1]
+                assert np.array_equal(lp, want) and len(lp) == len(c_i)
+            else:
+                assert lp is None
+        with pytest.raises(B.PoError):
+            ctx.po_engine_step(sch, 1.0, cand_capacity=4)                          # 8 ids do not fit 4 floats ...
+        assert sch.po_sched_size() == 1                                            # ... and the request stays queued
+        rid, _, _, _, lp = ctx.po_engine_step(sch, 1.0, cand=[11, 12])             # the caller's list overrides
+        assert rid == 3 and np.array_equal(lp, ctx.po_prefill(reqs[3], [11, 12], want_logits=False)[1])
         # a request the context cannot run is dropped with an error, the queue moves on
         sch = B.Scheduler(0.0)
         sch.po_sched_push(7, np.zeros(ctx.max_input_len + 1, dtype=np.int32), 0.0)
