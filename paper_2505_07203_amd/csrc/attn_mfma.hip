@@ -41,12 +41,15 @@ __device__ __forceinline__ int swz8(int row) { return (row & 7) ^ ((row >> 3) & 
 // start at row q_row0, and the key tiles of a query tile are divided between n_split workgroups; each
 // writes its unnormalised fp32 accumulators to opart[split][row - q_row0][head][HD] and its running
 // maximum and row sum to mlpart[split][row - q_row0][head][2]; attn_combine_kernel merges them.
+// The first n_tiles2 key tiles are read from a second K / V^T pair (k2, vt2 with pitch ldv2: a prefix-cache
+// entry, same layouts), so that a cached prefix need not be copied next to the fresh keys first.
 template <int HD, int QT, int NW, bool SPLIT>
 __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, const bf16_t* __restrict__ k,
                                                            const bf16_t* __restrict__ vt, int64_t ldv, bf16_t* o,
                                                            int N, int Hq, int Hkv, float sc_log2e, int nqt,
                                                            int hpx, int q_row0, int n_split, float* opart,
-                                                           float* mlpart) {
+                                                           float* mlpart, const bf16_t* __restrict__ k2,
+                                                           const bf16_t* __restrict__ vt2, int64_t ldv2, int n_tiles2) {
     constexpr int NT = NW * 64;
     constexpr int BMQ = NW * QT * 32;
     constexpr int KS = HD / 16;            // k-steps of S^T = K Q^T
@@ -103,17 +106,24 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
     const int vseg = tid & 7, vrow0 = tid >> 3;                // rows vrow0 + (NT/8) i
     const bf16_t* kbase = k + (int64_t)kvh * HD + kseg * 8;
     const bf16_t* vbase = vt + (int64_t)kvh * HD * ldv + vseg * 8;
+    const bf16_t* kbase2 = SPLIT ? k2 + (int64_t)kvh * HD + kseg * 8 : kbase;
+    const bf16_t* vbase2 = SPLIT ? vt2 + (int64_t)kvh * HD * ldv2 + vseg * 8 : vbase;
     const int64_t krs = (int64_t)Hkv * HD;
     // Prefetch registers, plain scalars so that they stay in VGPRs: set r holds the tile that
     // goes to LDS next, set n the one after it (prefetch distance 2, which covers the HBM/L2
     // latency of the K/V stream).  Loads are unconditional; tile indices clamp to the last tile.
     uint4 rk0, rk1, rk2, rk3, rv0, rv1, rv2, rv3, nk0, nk1, nk2, nk3, nv0, nv1, nv2, nv3;
     rk1 = rv1 = nk1 = nv1 = rk2 = rk3 = rv2 = rv3 = nk2 = nk3 = nv2 = nv3 = make_uint4(0, 0, 0, 0);
-#define PO_KLOAD(i_) (*(const uint4*)(kbase + (int64_t)min(kv0_ + krow0 + (NT / KSEG) * (i_), N - 1) * krs))
-#define PO_VLOAD(i_) (*(const uint4*)(vbase + (int64_t)(vrow0 + (NT / 8) * (i_)) * ldv + kv0_))
+#define PO_KLOAD(i_) (*(const uint4*)(kb_ + (int64_t)min(kv0_ + krow0 + (NT / KSEG) * (i_), N - 1) * krs))
+#define PO_VLOAD(i_) (*(const uint4*)(vb_ + (int64_t)(vrow0 + (NT / 8) * (i_)) * ld_ + kv0_))
 #define PO_GLOAD(P, j_)                                       \
     {                                                         \
-        const int kv0_ = min((j_), n_kv_blk - 1) * BNK;       \
+        const int jt_ = min((j_), n_kv_blk - 1);              \
+        const int kv0_ = jt_ * BNK;                           \
+        const bool second_ = SPLIT && jt_ < n_tiles2;         \
+        const bf16_t* kb_ = second_ ? kbase2 : kbase;         \
+        const bf16_t* vb_ = second_ ? vbase2 : vbase;         \
+        const int64_t ld_ = second_ ? ldv2 : ldv;             \
         P##k0 = PO_KLOAD(0);                                  \
         if (KLD > 1) P##k1 = PO_KLOAD(1);                     \
         if (KLD > 2) { P##k2 = PO_KLOAD(2); P##k3 = PO_KLOAD(3); } \
@@ -764,12 +774,13 @@ void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, b
     // workgroups enumerate query tiles from the last one down: fewer of them = only the last tiles
     const int nsel = nqt - (int)((q_row0 > 0 && q_row0 < N) ? q_row0 / BMQ : 0);
     hipLaunchKernelGGL((attn_fwd_kernel<HD, QT, NW, false>), dim3((unsigned)(nsel * Hq)), dim3(NW * 64), SMEM, s, q, k, vt,
-                       ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, hpx, 0, 1, nullptr, nullptr);
+                       ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, hpx, 0, 1, nullptr, nullptr, nullptr, nullptr, 0, 0);
 }
 
 template <int HD>
 int launch_split_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
-                   int Hkv, int64_t q_row0, float* scratch, size_t scratch_bytes, bool launch, hipStream_t s) {
+                   int Hkv, int64_t q_row0, float* scratch, size_t scratch_bytes, bool launch, const bf16_t* k2,
+                   const bf16_t* vt2, int64_t ldv2, int64_t n2, hipStream_t s) {
     constexpr int NW = 8, BMQ = NW * 32;
     constexpr int SMEM = 2 * 2 * BNK * HD * 2;
     const int64_t nq = N - q_row0;
@@ -793,7 +804,8 @@ int launch_split_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t l
     float* mlpart = scratch + o_bytes / sizeof(float);
     const float sc_log2e = (float)(1.4426950408889634 / sqrt((double)HD));
     hipLaunchKernelGGL((attn_fwd_kernel<HD, 1, NW, true>), dim3((unsigned)(nqt * Hq * n_split)), dim3(NW * 64), SMEM, s, q,
-                       k, vt, ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, 0, (int)q_row0, n_split, opart, mlpart);
+                       k, vt, ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, 0, (int)q_row0, n_split, opart, mlpart,
+                       k2 ? k2 : k, vt2 ? vt2 : vt, vt2 ? ldv2 : ldv, (k2 && vt2) ? (int)(n2 / BNK) : 0);
     const int64_t n = nq * Hq * (HD / 4);
     hipLaunchKernelGGL(attn_combine_kernel<HD>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, opart, mlpart, n_split,
                        (int)nq, Hq, sc_log2e, o, (int)q_row0);
@@ -808,9 +820,12 @@ bool attention_mfma_supported(int Hq, int Hkv, int hd) {
 
 int launch_attention_mfma_split(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N,
                                 int Hq, int Hkv, int hd, int64_t q_row0, float* scratch, size_t scratch_bytes,
-                                bool launch, hipStream_t s) {
-    if (hd == 128) return launch_split_t<128>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, s);
-    if (hd == 64) return launch_split_t<64>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, s);
+                                bool launch, const bf16_t* k2, const bf16_t* vt2, int64_t ldv2, int64_t n2,
+                                hipStream_t s) {
+    if (hd == 128)
+        return launch_split_t<128>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, k2, vt2, ldv2, n2, s);
+    if (hd == 64)
+        return launch_split_t<64>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, k2, vt2, ldv2, n2, s);
     return 0;
 }
 

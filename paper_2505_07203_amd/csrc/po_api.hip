@@ -337,11 +337,23 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
         const size_t slot_bytes = c->kv_layer_bytes * (size_t)m.n_layers;
         const unsigned char* kc_l = c->kvc ? c->kvc + (size_t)c->kv_src * slot_bytes + (size_t)l * c->kv_layer_bytes : nullptr;
         unsigned char* kd_l = c->kvc ? c->kvc + (size_t)c->kv_dst * slot_bytes + (size_t)l * c->kv_layer_bytes : nullptr;
-        if (p_reuse > 0) {
-            // cached prefix of this layer -> rows [0, p_reuse) of the one-layer K / V buffers
+        // Few-rows mode: the split attention reads whole key tiles of the cached prefix from the cache entry
+        // itself, so only the prefix's last, partial tile is copied next to the fresh keys -- unless the prefix
+        // is about to be stored into ANOTHER entry, which takes it from the one-layer buffers.
+        int64_t p_direct = 0;
+        if (p_reuse >= 64 && dt == PO_BF16 && c->split_few_rows && !packed && (c->kv_dst == c->kv_src || p_store == 0)) {
+            const int64_t q0 = (c->lazy_last_layer && l == m.n_layers - 1) ? total - 1 : p_reuse;
+            if (launch_attention_mfma_split((const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)(ws + L.Vt), L.ldv, (bf16_t*)Q, total,
+                                            m.n_q_heads, m.n_kv_heads, hd, q0, (float*)H, (size_t)L.chunk * F * esz, false,
+                                            nullptr, nullptr, 0, 0, s) > 1)
+                p_direct = p_reuse / 64 * 64;
+        }
+        if (p_reuse > p_direct) {
+            // cached prefix of this layer -> rows [p_direct, p_reuse) of the one-layer K / V buffers
             if (dt == PO_BF16) {
-                launch_kv_copy(K, kc_l, (size_t)p_reuse * kvd * esz, ws + L.Vt, (size_t)L.ldv * esz, kc_l + c->kv_v_off,
-                               (size_t)c->kv_ldv * esz, (size_t)p_reuse * esz, kvd, s);
+                const size_t r0 = (size_t)p_direct, nr = (size_t)(p_reuse - p_direct);
+                launch_kv_copy(K + r0 * kvd * esz, kc_l + r0 * kvd * esz, nr * kvd * esz, ws + L.Vt + r0 * esz, (size_t)L.ldv * esz,
+                               kc_l + c->kv_v_off + r0 * esz, (size_t)c->kv_ldv * esz, nr * esz, kvd, s);
             } else {
                 PO_HIP(hipMemcpyAsync(K, kc_l, (size_t)p_reuse * kvd * esz, hipMemcpyDeviceToDevice, s));
                 PO_HIP(hipMemcpyAsync(V, kc_l + c->kv_v_off, (size_t)p_reuse * kvd * esz, hipMemcpyDeviceToDevice, s));
@@ -433,7 +445,9 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                     launch_attention_mfma_split((const bf16_t*)Qg, (const bf16_t*)(K + (size_t)g.start * kvd * esz),
                                                 (const bf16_t*)(ws + L.Vt) + g.start, L.ldv, (bf16_t*)Qg, g.len,
                                                 m.n_q_heads, m.n_kv_heads, hd, q_row0, (float*)H,
-                                                (size_t)L.chunk * F * esz, true, s) > 1)
+                                                (size_t)L.chunk * F * esz, true, p_direct ? (const bf16_t*)kc_l : nullptr,
+                                                p_direct ? (const bf16_t*)(kc_l + c->kv_v_off) : nullptr, c->kv_ldv, p_direct,
+                                                s) > 1)
                     ++n_split_launches;
                 else
                     launch_attention_mfma((const bf16_t*)Qg, (const bf16_t*)(K + (size_t)g.start * kvd * esz),

@@ -88,9 +88,12 @@ void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, i
 // divided between workgroups (fp32 partial results in `scratch`, merged by a second kernel).  Sums are formed
 // in a different order than in launch_attention_mfma: equal to rounding, not bit for bit.  Returns the
 // number of key splits (0 or 1: not worth it or scratch too small, nothing launched); launch = false only asks.
+// k2 / vt2 (pitch ldv2; may be null): a second K / V^T pair of the same layouts that holds the first n2 positions
+// (n2 a multiple of 64) -- a prefix-cache entry read in place; positions from n2 on come from k / vt.
 int launch_attention_mfma_split(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
                                 int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, float* scratch,
-                                size_t scratch_bytes, bool launch, hipStream_t s);
+                                size_t scratch_bytes, bool launch, const bf16_t* k2, const bf16_t* vt2, int64_t ldv2,
+                                int64_t n2, hipStream_t s);
 bool gemm_mfma_supported(int N, int K);
 // C = A W^T + R for a GEMM with few rows, the reduction over K split between workgroups (a GEMM with few
 // output tiles leaves most of the chip idle and every workgroup streaming a whole K range of both operands):
