@@ -377,6 +377,15 @@ po_status po_op_pack_gate_up(int32_t dtype, const void* dev_wg, const void* dev_
 po_status po_op_attention(int32_t dtype, const void* dev_q, const void* dev_k, const void* dev_v,
                           void* dev_o, void* dev_scratch, int64_t N, int32_t n_q_heads,
                           int32_t n_kv_heads, int32_t head_dim, void* hip_stream);
+/* The few-rows form of po_op_attention (bf16 only; see po_set_few_rows_split): rows [q_row0, N) of the causal
+ * attention, each query tile's keys divided between workgroups and merged by a second kernel.  dev_scratch_vt as
+ * dev_scratch there; dev_scratch_part (part_bytes, 256-byte aligned) takes the fp32 partial results.  Rows below
+ * q_row0 of dev_o are left as they are.  *splits_used receives the number of key splits; 0 or 1 means too few keys
+ * or rows too many (> 1024) or the scratch too small, and then NOTHING was computed. */
+po_status po_op_attention_split(const void* dev_q, const void* dev_k, const void* dev_v, void* dev_o,
+                                void* dev_scratch_vt, void* dev_scratch_part, size_t part_bytes, int64_t N,
+                                int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int64_t q_row0,
+                                void* hip_stream, int32_t* splits_used);
 
 /* Rotary embedding in place on x [N, H, hd] for positions 0..N-1 (angles formed in
  * double precision). */

@@ -38,7 +38,7 @@ EXPORTS = [
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
     "po_op_quantize_rows", "po_op_rmsnorm_quantize", "po_op_linear_fp8", "po_op_qkv_rope_fp8",
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
-    "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_op_linear_split", "po_sched_push_request",
+    "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_op_linear_split", "po_sched_push_request", "po_op_attention_split",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick",
 ]
@@ -116,6 +116,7 @@ def lib() -> C.CDLL:
     L.po_last_device_error.restype = C.c_char_p
     L.po_op_rmsnorm.argtypes = [i32, vp, vp, vp, i64, i32, f32, vp]
     L.po_op_linear.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, vp]
+    L.po_op_attention_split.argtypes = [vp, vp, vp, vp, vp, vp, sz, i64, i32, i32, i32, i64, vp, C.POINTER(i32)]
     L.po_op_linear_split.argtypes = [vp, vp, vp, vp, vp, sz, i64, i32, i32, vp, C.POINTER(i32)]
     L.po_op_gate_up_silu.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, vp]
     L.po_op_pack_gate_up.argtypes = [i32, vp, vp, vp, i32, i32, vp]
@@ -496,6 +497,21 @@ def po_op_attention(q, k, v, out=None):
     check(lib().po_op_attention(_dt(q), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
                                 None if scratch is None else scratch.data_ptr(), N, Hq, Hkv, hd, _stream()))
     return o
+
+
+def po_op_attention_split(q, k, v, q_row0: int, part_bytes: int = 1 << 28):
+    """-> (o or None, splits): rows [q_row0, N) by the split-key kernel; None when nothing was split"""
+    import torch
+    N, Hq, hd = q.shape
+    Hkv = k.shape[1]
+    o = torch.zeros_like(q)
+    vt = torch.empty(Hkv * hd * ((N + 63) // 64 * 64), dtype=q.dtype, device=q.device)
+    part = torch.empty(part_bytes, dtype=torch.uint8, device=q.device)
+    n = C.c_int32(0)
+    check(lib().po_op_attention_split(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), vt.data_ptr(), part.data_ptr(),
+                                      part_bytes, N, Hq, Hkv, hd, q_row0, _stream(), C.byref(n)))
+    torch.cuda.synchronize()
+    return (o if n.value > 1 else None), n.value
 
 
 def po_op_rope(x, theta: float):

@@ -1296,6 +1296,23 @@ po_status po_op_attention(int32_t dtype, const void* q, const void* k, const voi
     return PO_OK;
 }
 
+po_status po_op_attention_split(const void* q, const void* k, const void* v, void* o, void* scratch_vt, void* scratch_part,
+                                size_t part_bytes, int64_t N, int32_t Hq, int32_t Hkv, int32_t hd, int64_t q_row0,
+                                void* stream, int32_t* splits_used) {
+    if (!q || !k || !v || !o || !scratch_vt || !scratch_part || !splits_used || N <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv ||
+        q_row0 < 0 || q_row0 >= N)
+        return PO_ERR_INVALID_ARG;
+    if (!attention_mfma_supported(Hq, Hkv, hd)) return PO_ERR_BAD_CONFIG;
+    if (N > (int64_t)1 << 24 || (N + 64) * Hkv * hd * 2 >= ((int64_t)1 << 32)) return PO_ERR_TOO_LONG;
+    const int64_t ldv = round_up64(N, 64);
+    launch_v_transpose((const bf16_t*)v, (bf16_t*)scratch_vt, N, Hkv * hd, ldv, (hipStream_t)stream);
+    *splits_used = launch_attention_mfma_split((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)scratch_vt, ldv, (bf16_t*)o, N,
+                                               Hq, Hkv, hd, q_row0, (float*)scratch_part, part_bytes, true, nullptr, nullptr, 0,
+                                               0, (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
 po_status po_op_rope(int32_t dtype, void* x, int64_t N, int32_t H, int32_t hd, float theta, void* stream) {
     if (bad_dtype(dtype) || !x || N <= 0 || H <= 0 || hd <= 0 || hd % 2 || !(theta > 0.f)) return PO_ERR_INVALID_ARG;
     float* tab = nullptr;

@@ -168,3 +168,25 @@ def test_split_linear_declines_large_shapes():
     a = torch.zeros(64, 4096, dtype=torch.bfloat16, device="cuda")
     c, splits = B.po_op_linear_split(a, w, r[:64].contiguous(), scratch_bytes=4096)
     assert c is None and splits <= 1                        # scratch too small for even two planes
+
+
+@pytest.mark.parametrize("N,q_row0,Hq,Hkv,hd", [(600, 450, 4, 2, 64), (1500, 1499, 8, 2, 128), (2000, 1000, 8, 2, 128),
+                                                 (4097, 4000, 5, 1, 128), (700, 0, 4, 4, 64), (3000, 2900, 32, 8, 128)])
+def test_split_attention_against_float64(N, q_row0, Hq, Hkv, hd):
+    """The split-key attention by itself: rows [q_row0, N) against the oracle's plain causal GQA attention."""
+    import torch
+    from oracle import prefill_oracle as O
+    from paper_2505_07203_amd import binding as B
+    rng = np.random.default_rng(N + q_row0)
+    def stored(shape, scale=1.0):
+        return I.f32_to_bf16_bits((rng.standard_normal(shape) * scale).astype(np.float32))
+    q, k, v = stored((N, Hq, hd)), stored((N, Hkv, hd)), stored((N, Hkv, hd))
+    dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    o, splits = B.po_op_attention_split(dev(q), dev(k), dev(v), q_row0)
+    assert splits >= 2 and o is not None, "this shape was meant to split"
+    ref = O.causal_gqa_attention(I.stored_to_f64(q), I.stored_to_f64(k), I.stored_to_f64(v))[q_row0:]
+    got = o[q_row0:].double().cpu().numpy()
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    print(f"split attention N={N} rows from {q_row0} Hq={Hq} Hkv={Hkv} hd={hd} splits={splits}: {err:.3e}")
+    assert err <= 1.5e-2
+    assert not o[:q_row0].any()                      # rows below q_row0 untouched
