@@ -333,13 +333,17 @@ void launch_attention_basic(int dtype, const void* q, const void* k, const void*
 
 // ------------------------------------------------------------------ last-row LM head
 // logits[v] = sum_i x[i] W[v, i]; one wavefront per vocabulary row, 16-byte loads of W.
+// rows: null = every vocabulary row; else the n_rows ids to compute (the acceptable output tokens, when nobody
+// asked for the whole distribution): the same dot product per row, so those logits are the same bits either way
 template <typename T>
 __global__ void __launch_bounds__(256) lm_head_kernel(const T* __restrict__ x, const T* __restrict__ W,
-                                                      float* __restrict__ logits, int V, int d) {
+                                                      float* __restrict__ logits, int V, int d,
+                                                      const int32_t* __restrict__ rows, int n_rows) {
     constexpr int VEC = 16 / sizeof(T);
     const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= V) return;
+    const int idx = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (idx >= (rows ? n_rows : V)) return;
+    const int row = rows ? rows[idx] : idx;
     const T* wr = W + (int64_t)row * d;
     float acc = 0.f;
     for (int i = lane * VEC; i < d; i += 64 * VEC) {
@@ -354,14 +358,15 @@ __global__ void __launch_bounds__(256) lm_head_kernel(const T* __restrict__ x, c
     if (lane == 0) logits[row] = acc;
 }
 
-void launch_lm_head(int dtype, const void* x, const void* W, float* logits, int V, int d, hipStream_t s) {
-    const dim3 grid((unsigned)((V + 3) / 4));
+void launch_lm_head(int dtype, const void* x, const void* W, float* logits, int V, int d, const int32_t* rows, int n_rows,
+                    hipStream_t s) {
+    const dim3 grid((unsigned)(((rows ? n_rows : V) + 3) / 4));
     if (dtype == 0)
         hipLaunchKernelGGL(lm_head_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (const float*)W, logits,
-                           V, d);
+                           V, d, rows, n_rows);
     else
         hipLaunchKernelGGL(lm_head_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)W,
-                           logits, V, d);
+                           logits, V, d, rows, n_rows);
 }
 
 // ------------------------------------------------------------------ candidate log-probs

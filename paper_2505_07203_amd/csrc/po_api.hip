@@ -576,7 +576,10 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
     for (int64_t j = 0; j < n_seg; ++j) {
         const int64_t r = gathered ? j : segs[j].start + segs[j].len - 1;
         launch_rmsnorm(dt, X + (size_t)r * d * esz, c->w + L.final_norm, ws + L.xn_last, 1, d, m.rms_eps, s);
-        launch_lm_head(dt, ws + L.xn_last, c->w + L.lm_head, d_logits, m.vocab_size, d, s);
+        // nobody asked for the whole distribution: only the acceptable tokens' rows of the LM head
+        const bool cand_only = !out_logits && n_cand > 0;
+        launch_lm_head(dt, ws + L.xn_last, c->w + L.lm_head, d_logits, m.vocab_size, d,
+                       cand_only ? (const int32_t*)(ws + L.cand) : nullptr, cand_only ? n_cand : 0, s);
         if (n_cand > 0)
             launch_cand_logprobs(d_logits, (const int32_t*)(ws + L.cand), n_cand, (float*)(ws + L.cand_lp), s);
         if (j == n_seg - 1) {
@@ -1425,7 +1428,7 @@ po_status po_op_qkv_rope_fp8(const void* a_codes, const float* a_scales, const v
 po_status po_op_lm_head(int32_t dtype, const void* x, const void* w, float* logits, int32_t V, int32_t d,
                         void* stream) {
     if (bad_dtype(dtype) || !x || !w || !logits || V <= 0 || d <= 0 || d % 8) return PO_ERR_INVALID_ARG;
-    launch_lm_head(dtype, x, w, logits, V, d, (hipStream_t)stream);
+    launch_lm_head(dtype, x, w, logits, V, d, nullptr, 0, (hipStream_t)stream);
     PO_HIP(hipGetLastError());
     return PO_OK;
 }

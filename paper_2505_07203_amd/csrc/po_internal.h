@@ -43,7 +43,9 @@ void launch_silu_mul(int dtype, const void* GU, void* H, int64_t M, int F, hipSt
 void launch_attention_basic(int dtype, const void* q, const void* k, const void* v, void* o, int64_t N,
                             int Hq, int Hkv, int hd, int64_t q_row0, hipStream_t s);
 // logits[V] = x[d] . W[V,d]^T
-void launch_lm_head(int dtype, const void* x, const void* W, float* logits, int V, int d, hipStream_t s);
+// logits[r] = x . W[r] for every vocabulary row r, or (rows != null) only for r = rows[0 .. n_rows)
+void launch_lm_head(int dtype, const void* x, const void* W, float* logits, int V, int d, const int32_t* rows, int n_rows,
+                    hipStream_t s);
 // lp[i] = logits[cand[i]] - logsumexp_j logits[cand[j]]
 void launch_cand_logprobs(const float* logits, const int32_t* cand, int n_cand, float* lp, hipStream_t s);
 // interleave gate/up rows in blocks of `il` rows: dst rows [2b*il, 2b*il+il) = Wg block b, next il = Wu block b

@@ -581,6 +581,30 @@ def test_engine_step_matches_a_hand_driven_loop():
         ctx.po_destroy()
 
 
+@pytest.mark.parametrize("cfg", [I.TINY, I.TINY.replace(dtype=I.BF16, ffn_dim=704), I.TINY.replace(dtype=I.BF16_FP8, ffn_dim=768)],
+                         ids=["f32", "bf16", "fp8"])
+def test_candidate_only_lm_head_gives_the_same_bits(cfg):
+    """Without a request for the whole distribution only the acceptable tokens' rows of the LM head are
+    computed (steps a10 / a11: candidate columns only): the same log-probs, bit for bit, incl. repeated ids."""
+    ctx = make_ctx(cfg, 23, 600, 256)
+    try:
+        t = I.make_tokens(cfg, 77, 333)
+        for cand in (I.label_ids(cfg), [0, cfg.vocab_size - 1, 17, 17, 5], list(range(0, cfg.vocab_size, 7))):
+            z, lp_full = ctx.po_prefill(t, cand, want_logits=True)
+            _, lp_only = ctx.po_prefill(t, cand, want_logits=False)
+            assert np.array_equal(lp_full, lp_only)
+            zc = z[np.asarray(cand)].astype(np.float64)
+            want = zc - (np.max(zc) + np.log(np.sum(np.exp(zc - np.max(zc)))))
+            assert np.max(np.abs(lp_only - want)) < 1e-5
+        toks = [I.make_tokens(cfg, 78, n, request=i) for i, n in enumerate((40, 200, 90))]
+        cand = I.label_ids(cfg)
+        _, lp_a = ctx.po_prefill_packed(toks, cand, want_logits=True)
+        _, lp_b = ctx.po_prefill_packed(toks, cand, want_logits=False)
+        assert np.array_equal(lp_a, lp_b)
+    finally:
+        ctx.po_destroy()
+
+
 def test_scheduler_with_prefix_cache_end_to_end():
     """Sections 5.1 + 6.3 together on the paper's example shape: four requests, two shared prefixes, a
     cache that holds the last request; the calibrated order reuses twice, arrival order once."""
