@@ -208,3 +208,18 @@ def test_serving_traces_have_the_papers_structure():
     assert len(small) == 6 and all(110 + 2 <= len(t) <= 170 + 2 for _, t in small)
     arr = I.poisson_user_arrivals(9, 1000, 4.0)
     assert np.all(np.diff(arr) > 0) and abs(arr[-1] / 1000 - 0.25) < 0.03                             # mean gap 1 / rate
+
+
+def test_public_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: include/po.h must compile as C99 (and as C++) with nothing but the standard headers."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "po.h"\nint main(void) { return (int)sizeof(po_stats) == 0; }\n')
+    for cc, std in (("gcc", ["-std=c99", "-pedantic"]), ("g++", ["-std=c++17", "-x", "c++"])):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} not installed")
+        r = subprocess.run([cc, *std, "-Wall", "-Werror", "-I", os.path.join(root, "include"), "-fsyntax-only", str(src)],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
