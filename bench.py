@@ -135,12 +135,23 @@ def serve(args, cfg, w, B, I):
     ctx.po_set_few_rows_split(not args.serve_default_path)
     cache_bytes = 0
 
-    def drain(lam, user_arrival):
+    def drain(lam, user_arrival, request_arrival=None):
         nonlocal cache_bytes
         cache_bytes = ctx.po_attach_kv_cache(max_len, n_slots=args.serve_slots)     # a fresh, empty cache
         sch = B.Scheduler(lam)
         # requests of one arrival instant keep the trace's order: a nanosecond apart
         arr = [user_arrival[u] + 1e-9 * i for i, u in enumerate(users)]
+        if args.serve_interleave:
+            # round robin over users: post k of every user before post k + 1 of any; with a rate, one request per
+            # arrival of the Poisson process instead of one user
+            seen, rank = {}, []
+            for u in users:
+                rank.append(seen.get(u, 0))
+                seen[u] = rank[-1] + 1
+            order = sorted(range(len(users)), key=lambda i: (rank[i], users[i]))
+            times = request_arrival if request_arrival is not None else [0.0] * len(users)
+            for pos, i in enumerate(order):
+                arr[i] = times[pos] + 1e-9 * pos
         todo = sorted(range(len(trace)), key=lambda i: arr[i])
         now, k, done, busy, hits, tokens, computed = 0.0, 0, {}, 0.0, 0, 0, 0
         while k < len(todo) or sch.po_sched_size():
@@ -167,12 +178,16 @@ def serve(args, cfg, w, B, I):
     x = drain(500.0, [0.0] * n_users)["requests_per_s"]                             # warm-up; sets the rate unit
     rows = []
     for rate in [float(r) for r in args.serve_rates.split(",")]:
+        ra = None
         if rate == 0:
             ua = [0.0] * n_users
         else:
             ua = I.poisson_user_arrivals(w["tseed"], n_users, rate * x * n_users / len(trace)).tolist()
-        for policy, lam in (("arrival_order", 1e12), ("srjf_calibrated_lambda500", 500.0)):
-            r = drain(lam, ua)
+            if args.serve_interleave:
+                ra = I.poisson_user_arrivals(w["tseed"], len(trace), rate * x).tolist()
+        # (arrival order = lambda so large that a nanosecond of queuing outweighs any JCT)
+        for policy, lam in (("arrival_order", 1e18), ("srjf_calibrated_lambda500", 500.0)):
+            r = drain(lam, ua, ra)
             r.update(policy=policy, arrival="all_at_once" if rate == 0 else f"poisson_{rate:g}x")
             rows.append(r)
     ctx.po_destroy()
@@ -184,7 +199,7 @@ def serve(args, cfg, w, B, I):
                                  "requests": len(trace), "max_request_tokens": max_len,
                                  "total_tokens": int(sum(len(t) for _, t in trace)),
                                  "prefix_cache_entries": args.serve_slots, "prefix_cache_bytes": int(cache_bytes),
-                                 "few_rows_split": not args.serve_default_path},
+                                 "few_rows_split": not args.serve_default_path, "interleaved_arrivals": bool(args.serve_interleave)},
                       "runs": rows}))
 
 
@@ -216,6 +231,9 @@ def main():
     ap.add_argument("--serve-users", type=int, default=0, help="override the trace's number of users")
     ap.add_argument("--serve-posts", type=int, default=0, help="override the trace's requests per user")
     ap.add_argument("--serve-slots", type=int, default=4, help="entries of the prefix cache")
+    ap.add_argument("--serve-interleave", action="store_true",
+                    help="the requests of different users arrive interleaved (round robin over users, one request at a "
+                         "time) instead of user by user: arrival order then loses the cached prefixes (Section 6.2)")
     ap.add_argument("--serve-default-path", action="store_true",
                     help="serve on the default (bit-reproducible across row sets) path instead of few-rows mode")
     ap.add_argument("--serve-rates", default="0,1",
