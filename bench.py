@@ -27,10 +27,25 @@ PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096
 PEAK_FP8_TFLOPS = 5033.2       # dense fp8 MFMA: twice the bf16 rate
 PEAK_HBM_GBS = 8000.0
 
-# Memory traffic per launch in bytes, from two counter runs of this command at the default
-# workload (FETCH_SIZE x 2.0 and WRITE_SIZE x 1.0 KiB per dispatch, the factors a 1 GiB
-# elementwise kernel calibrates; summary under profiles/).  Other workloads report null.
-MEASURED_TRAFFIC = {"llama8b_32k": {"attention": 1.628e9, "gate_up": 1.523e9, "residual": 0.519e9, "qkv": 0.814e9}}
+def load_traffic(workload, kernel_functions):
+    """Measured HBM-side traffic per launch of each kernel class, from the committed summary of two rocprofv3
+    counter runs of this command (FETCH_SIZE, then WRITE_SIZE; see profiles/<...>_pmc_counters.txt, which
+    paper_2505_07203_amd/pmc_summary.py writes).  The summary names the kernel functions it measured; it is used
+    only if those are the functions this library runs today, else every traffic is null.
+    -> ({class: bytes per launch}, file name) or ({}, None)"""
+    path = os.path.join(ROOT, "profiles", f"prefill_{workload}_pmc_counters.txt")
+    if not os.path.exists(path):
+        return {}, None
+    out = {}
+    with open(path) as f:
+        for line in f:
+            if not line.startswith("traffic_bytes_per_launch\t"):
+                continue
+            _, cls, fn, nbytes = line.rstrip("\n").split("\t")[:4]
+            if kernel_functions.get(cls) != fn:
+                return {}, None                       # measured on other kernels than today's: stale
+            out[cls] = float(nbytes)
+    return out, (os.path.relpath(path, ROOT) if out else None)
 
 
 def flop_model(cfg, lens, lazy_last_layer=True):
@@ -88,6 +103,81 @@ def cpu_baseline(cfg, wseed, tseed, full_lens, sample_layers, sample_tokens):
             "kind": "oracle",
             "sample": f"fp64 numpy oracle, first {sample_layers} layer(s) x first {sample_tokens} tokens of the "
                       f"same workload: {dt:.2f} s measured, extrapolated to the full workload by the flop model"}
+
+
+def cpu_baseline_full_tiny():
+    """The oracle timed IN FULL on the small fp32 configuration (2 layers, 512 tokens), nothing extrapolated."""
+    from oracle import prefill_oracle as O   # noqa: F401  (imported by helpers below; named here for the reader)
+    import helpers as H
+    from paper_2505_07203_amd import inputs as I
+    w = I.WORKLOADS["tiny_512"]
+    tokens = I.make_tokens(w["cfg"], w["tseed"], w["lens"][0])
+    t0 = time.perf_counter()
+    H.oracle_prefill(w["cfg"], w["wseed"], tokens, cand=I.label_ids(w["cfg"]))
+    dt = time.perf_counter() - t0
+    return {"workload": "tiny_512", "value": w["lens"][0] / dt, "unit": "tokens/s", "seconds": dt, "kind": "oracle",
+            "sample": "the whole configuration (weights generated inside the timed region)"}
+
+
+def micro_peaks(B, torch):
+    """Measured micro-peaks beside the nominal ones: matrix-instruction loops on random bf16 operands (no memory
+    traffic inside the loop; the rate is what the board's power limit grants) and a 1 GiB streaming copy."""
+    out = {}
+    n_op = 1024 * 512 * 32
+    operands = (torch.randn(n_op // 2, device="cuda") * 0.5).to(torch.bfloat16)
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for name, kind, wps in (("mfma_32x32x16_bf16_1_wave_per_simd", 0, 1), ("mfma_32x32x16_bf16_2_waves_per_simd", 0, 2),
+                            ("mfma_16x16x32_bf16_1_wave_per_simd", 1, 1), ("mfma_16x16x32_bf16_2_waves_per_simd", 1, 2)):
+        B.po_op_mfma_peak(kind, wps, 2000, operands, sink)               # warm-up, also brings the clock down
+        torch.cuda.synchronize()
+        e0.record()
+        flop = B.po_op_mfma_peak(kind, wps, 20000, operands, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_tflops"] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    B.po_op_stream_copy(src, dst)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        B.po_op_stream_copy(src, dst)
+    e1.record()
+    torch.cuda.synchronize()
+    out["stream_copy_gbs_read_plus_write"] = 10 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    out["nominal"] = {"bf16_mfma_tflops": PEAK_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS}
+    return out
+
+
+def footprint_sweep(B, I, cfg, chunk, main_ctx, main_len):
+    """Peak HBM against input length: the closed form (po_workspace_bytes) for 4 k .. 128 k tokens beside the
+    model of an engine that keeps every layer's K/V and does not chunk the MLP, and the profile run's measured
+    high-water mark at three lengths (the main context's, and one-layer contexts for the others: the activation
+    arena does not depend on the layer count)."""
+    d, F, L = cfg.d_model, cfg.ffn_dim, cfg.n_layers
+    naive_slope = 2 * (L * 2 * cfg.kv_dim + 4 * d + 3 * F)      # bytes per token: all-layer K/V + X, Xn, Q, O + GU + H
+    rows = []
+    for n in (4096, 8192, 16384, 32768, 65536, 131072):
+        wb, sb = B.po_workspace_bytes(cfg, n, chunk)
+        rows.append({"tokens": n, "weights_bytes": wb, "workspace_bytes": sb, "naive_activation_bytes": naive_slope * n})
+    measured = []
+    for n in (4096, main_len, 131072):
+        if n == main_len:
+            _, touched = main_ctx.po_profile(n)
+            measured.append({"tokens": n, "layers": cfg.n_layers, "touched_bytes": touched, "closed_form_bytes": main_ctx.workspace_bytes})
+            continue
+        c1 = cfg.replace(n_layers=1)
+        ctx = B.Context(c1, n, chunk)
+        try:
+            ctx.load_synthetic(1, threads=16)
+            _, touched = ctx.po_profile(n)
+            measured.append({"tokens": n, "layers": 1, "touched_bytes": touched, "closed_form_bytes": ctx.workspace_bytes})
+        finally:
+            ctx.po_destroy()
+    return {"mlp_chunk": chunk, "closed_form": rows, "profile_run": measured,
+            "bytes_per_token": {"this_path": (rows[-1]["workspace_bytes"] - rows[-2]["workspace_bytes"]) / 65536.0,
+                                "all_layer_kv_unchunked_mlp": naive_slope}}
 
 
 def sample_shader_clock(run_step, n_steps=2):
@@ -212,6 +302,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: override the layer count (invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-timing", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the untimed extras: micro-peaks (matrix loop, streaming copy) and the footprint sweep")
     ap.add_argument("--no-clock-sample", action="store_true",
                     help="skip the two extra, untimed steps during which the shader clock is read from rocm-smi")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -277,7 +369,7 @@ def main():
     ctx = B.Context(cfg, max(max(lens), args.packed), w["chunk"])
     ctx.load_synthetic(w["wseed"], threads=16)
     load_s = time.perf_counter() - t0
-    ctx.po_set_phase_timing(not args.no_phase_timing)
+    ctx.po_set_phase_timing(False)
     ctx.po_set_few_rows_split(args.few_rows)
 
     classes = B.KERNEL_CLASSES
@@ -302,20 +394,36 @@ def main():
         torch.add(src, 1.0, out=dst)          # 2^30 bytes fetched, 2^30 bytes written
         torch.cuda.synchronize()
         del src, dst
+    # ---- pass 1, the metric: K steps with nothing but the path on the stream (no per-launch events)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    k_ms = dict.fromkeys(classes, 0.0)
-    k_n = dict.fromkeys(classes, 0)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ms, n = step()
-        for k in classes:
-            k_ms[k] += ms[k]
-            k_n[k] += n[k]
+        step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
+    # ---- pass 2, the per-kernel split: the same steps again with a HIP event pair around every attention and
+    # GEMM launch, recorded on the path's stream (about 900 pairs per step; this pass is not part of `value`)
+    k_ms = dict.fromkeys(classes, 0.0)
+    k_n = dict.fromkeys(classes, 0)
+    split_steps = 0
+    ms_per_step_with_events = None
+    if not args.no_phase_timing:
+        ctx.po_set_phase_timing(True)
+        step()
+        torch.cuda.synchronize()
+        split_steps = max(1, min(args.steps, 5))
+        t1 = time.perf_counter()
+        for _ in range(split_steps):
+            ms, n = step()
+            for k in classes:
+                k_ms[k] += ms[k]
+                k_n[k] += n[k]
+        torch.cuda.synchronize()
+        ms_per_step_with_events = 1e3 * (time.perf_counter() - t1) / split_steps
+        ctx.po_set_phase_timing(False)
     sclk = None if args.no_clock_sample else sample_shader_clock(step)
     tokens = sum(lens)
     value = tokens * args.steps / elapsed
@@ -324,24 +432,27 @@ def main():
     free_b, total_b = torch.cuda.mem_get_info()
     # algorithmic flops per step of each kernel class (causal half only for attention)
     k_flop = flop_classes(cfg, lens)
-    gk = "gemm_fp8_mfma_kernel" if args.fp8 else "gemm_bf16_mfma_kernel"
+    gk = "gemm_fp8_mfma_kernel" if args.fp8 else "gemm_bf16_mfma16_kernel"
     k_name = {"attention": ("attn_fwd64_kernel" if cfg.head_dim == 128 else "attn_fwd_kernel<64>") +
                            " (causal GQA flash attention, one launch per layer)",
               "qkv": gk + "<3> (QKV projection + RoPE + transposed V)",
               "residual": gk + "<1> (O-projection and MLP down projection + residual)",
               "gate_up": gk + "<2> (MLP gate/up projection + SiLU-multiply)"}
 
+    k_fn = {"attention": "attn_fwd64_kernel" if cfg.head_dim == 128 else "attn_fwd_kernel",
+            "qkv": gk + "<3>", "residual": gk + "<1>", "gate_up": gk + "<2>"}
+    traffic, traffic_file = ({}, None) if (args.layers or args.fp8 or args.packed or args.few_rows) else load_traffic(args.workload, k_fn)
+
     def roof(k):
-        launches = k_n[k] / args.steps
+        launches = k_n[k] / max(split_steps, 1)
         avg_ms = k_ms[k] / max(k_n[k], 1)
         ach = k_flop[k] / max(launches, 1) / 1e12 / (avg_ms / 1e3) if avg_ms > 0 else 0.0
         peak = PEAK_FP8_TFLOPS if (args.fp8 and k != "attention") else PEAK_BF16_TFLOPS
         return {"kernel": k_name[k], "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": ach / peak,
-                "traffic": None if (args.layers or args.fp8) else MEASURED_TRAFFIC.get(args.workload, {}).get(k),
+                "frac": ach / peak, "traffic": traffic.get(k), "traffic_source": traffic_file,
                 "launches_per_step": launches,
                 "avg_launch_ms": avg_ms, "algorithmic_flop_per_launch": k_flop[k] / max(launches, 1),
-                "share_of_step_time": (k_ms[k] / args.steps) / ms_per_step}
+                "share_of_step_time": (k_ms[k] / max(split_steps, 1)) / ms_per_step_with_events if ms_per_step_with_events else None}
 
     out = {
         "metric": "prefill tokens/s on 1 MI355X (8B-shape, 32k ctx)" if args.workload == "llama8b_32k" and not args.layers and not args.fp8 and not args.few_rows
@@ -357,6 +468,8 @@ def main():
                        "frac_of_bf16_mfma_peak": (lin_f + att_f) / 1e12 / (ms_per_step / 1e3) / PEAK_BF16_TFLOPS},
         "peak_hbm_bytes": {"weights_arena": ctx.weights_bytes, "workspace_arena": ctx.workspace_bytes,
                            "device_in_use_after_run": int(total_b - free_b)},
+        "timing": {"value_pass": "no per-launch events", "ms_per_step_with_per_launch_events": ms_per_step_with_events,
+                   "per_kernel_split_steps": split_steps},
         "load_seconds": load_s,
         # the nominal MFMA peak assumes 2400 MHz; the board runs this load at its power limit, below that
         "shader_clock_mhz": {"during_untimed_steps": sclk, "nominal": 2400},
@@ -398,11 +511,16 @@ def main():
                               "pearson_miss_tokens_vs_jct": float(np.corrcoef((n_in - n_c).astype(np.float64), ms)[0, 1]),
                               "jct_ms_min_max": [float(ms.min()), float(ms.max())],
                               "kv_cache_bytes": int(cache_bytes)}
+    if args.workload == "llama8b_32k" and not (args.layers or args.fp8 or args.packed or args.few_rows or args.no_extras):
+        out["footprint_sweep"] = footprint_sweep(B, I, cfg, chunk, ctx, max(lens))
     ctx.po_destroy()
     del ctx
     torch.cuda.empty_cache()
+    if not args.no_extras:
+        out["micro_peak"] = micro_peaks(B, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w["wseed"], w["tseed"], lens, 2, 4096)
+        out["cpu_baseline_full"] = cpu_baseline_full_tiny()
     print(json.dumps(out))
 
 

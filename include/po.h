@@ -372,8 +372,11 @@ po_status po_op_pack_gate_up(int32_t dtype, const void* dev_wg, const void* dev_
 
 /* Causal grouped-query attention over one whole sequence (Section 4.2: attention is not
  * chunked).  q [N, Hq, hd] (already rotated), k [N, Hkv, hd] (rotated), v [N, Hkv, hd];
- * o [N, Hq, hd] may alias q.  dev_scratch: PO_BF16 needs Hkv*hd*round_up(N,64) elements
- * (a transposed copy of V); PO_F32 needs none (NULL). */
+ * o [N, Hq, hd] may alias q.  dev_scratch (256-byte aligned): PO_BF16 needs
+ * round_up(2*Hkv*hd*round_up(N,64), 256) + 4*Hq*ceil(N/256) bytes (a transposed copy of V, then one word
+ * per 256-row query tile and head in which the kernel marks tiles whose scores outgrow its fixed reference
+ * exponent; those are recomputed with a running maximum, so the result is softmax for every finite input);
+ * PO_F32 needs none (NULL). */
 po_status po_op_attention(int32_t dtype, const void* dev_q, const void* dev_k, const void* dev_v,
                           void* dev_o, void* dev_scratch, int64_t N, int32_t n_q_heads,
                           int32_t n_kv_heads, int32_t head_dim, void* hip_stream);
@@ -447,6 +450,19 @@ po_status po_op_qkv_rope_fp8(const void* dev_a_codes, const float* dev_a_scales,
                              const float* dev_w_scales, const void* dev_bqkv, void* dev_q, void* dev_k, void* dev_vt,
                              int64_t ldv, const float* dev_cos, const float* dev_sin, int64_t pos0, int64_t M,
                              int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t K, void* hip_stream);
+
+/* ---- Micro-peaks of the machine, for the benchmark to report beside the nominal peaks (measurement only; the
+ * paper's claim that the workload is compute-bound, Section 2.3, is priced against what the board sustains).
+ * po_op_mfma_peak: every wavefront of a chip-filling grid (1024 workgroups of 256 * waves_per_simd threads)
+ * multiplies one pair of bf16 fragments, read once from dev_operands (32 bytes per thread: operand_bytes >=
+ * 1024 * 256 * waves_per_simd * 32; give it random data, the clock under matrix load depends on the operands),
+ * `iters` times into independent accumulators with kind 0: v_mfma_f32_32x32x16_bf16, 1: v_mfma_f32_16x16x32_bf16;
+ * nothing but the matrix pipe works inside the loop.  *flop receives the flop executed; dev_sink is one float
+ * (never written in practice).  Asynchronous on hip_stream; time it with events.
+ * po_op_stream_copy: dev_dst[0 .. bytes) = dev_src[0 .. bytes), 16 bytes per lane, bytes % 16 == 0. */
+po_status po_op_mfma_peak(int32_t kind, int32_t waves_per_simd, int32_t iters, const void* dev_operands,
+                          size_t operand_bytes, void* dev_sink, void* hip_stream, double* flop);
+po_status po_op_stream_copy(const void* dev_src, void* dev_dst, size_t bytes, void* hip_stream);
 
 /* Last-position LM head: logits[V] = x[d] . W[V, d]^T  (fp32 output). */
 po_status po_op_lm_head(int32_t dtype, const void* dev_x, const void* dev_w, float* dev_logits,

@@ -40,7 +40,7 @@ EXPORTS = [
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
     "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_op_linear_split", "po_sched_push_request", "po_op_attention_split",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
-    "po_sched_size", "po_sched_pick",
+    "po_sched_size", "po_sched_pick", "po_op_mfma_peak", "po_op_stream_copy",
 ]
 
 
@@ -122,6 +122,8 @@ def lib() -> C.CDLL:
     L.po_op_pack_gate_up.argtypes = [i32, vp, vp, vp, i32, i32, vp]
     L.po_op_attention.argtypes = [i32, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
     L.po_op_rope.argtypes = [i32, vp, i64, i32, i32, f32, vp]
+    L.po_op_mfma_peak.argtypes = [i32, i32, i32, vp, sz, vp, vp, C.POINTER(C.c_double)]
+    L.po_op_stream_copy.argtypes = [vp, vp, sz, vp]
     L.po_op_lm_head.argtypes = [i32, vp, vp, vp, i32, i32, vp]
     L.po_op_rope_table.argtypes = [vp, vp, i64, i32, f32, vp]
     L.po_op_pack_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
@@ -493,7 +495,8 @@ def po_op_attention(q, k, v, out=None):
     o = out if out is not None else torch.empty_like(q)
     scratch = None
     if q.dtype == torch.bfloat16:
-        scratch = torch.empty(Hkv * hd * ((N + 63) // 64 * 64), dtype=q.dtype, device=q.device)
+        vt_bytes = (2 * Hkv * hd * ((N + 63) // 64 * 64) + 255) // 256 * 256
+        scratch = torch.empty(vt_bytes + 4 * Hq * ((N + 255) // 256), dtype=torch.uint8, device=q.device)
     check(lib().po_op_attention(_dt(q), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
                                 None if scratch is None else scratch.data_ptr(), N, Hq, Hkv, hd, _stream()))
     return o
@@ -519,6 +522,18 @@ def po_op_rope(x, theta: float):
     N, H, hd = x.shape
     check(lib().po_op_rope(_dt(x), x.data_ptr(), N, H, hd, theta, _stream()))
     return x
+
+
+def po_op_mfma_peak(kind: int, waves_per_simd: int, iters: int, operands, sink) -> float:
+    """launches the matrix-instruction loop on the current stream -> flop executed"""
+    f = C.c_double(0)
+    check(lib().po_op_mfma_peak(kind, waves_per_simd, iters, operands.data_ptr(), operands.numel() * operands.element_size(),
+                                sink.data_ptr(), _stream(), C.byref(f)))
+    return f.value
+
+
+def po_op_stream_copy(src, dst) -> None:
+    check(lib().po_op_stream_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), _stream()))
 
 
 def po_op_lm_head(x, w):

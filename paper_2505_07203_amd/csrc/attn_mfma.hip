@@ -49,7 +49,8 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
                                                            int N, int Hq, int Hkv, float sc_log2e, int nqt,
                                                            int hpx, int q_row0, int n_split, float* opart,
                                                            float* mlpart, const bf16_t* __restrict__ k2,
-                                                           const bf16_t* __restrict__ vt2, int64_t ldv2, int n_tiles2) {
+                                                           const bf16_t* __restrict__ vt2, int64_t ldv2, int n_tiles2,
+                                                           int* redo) {
     constexpr int NT = NW * 64;
     constexpr int BMQ = NW * QT * 32;
     constexpr int KS = HD / 16;            // k-steps of S^T = K Q^T
@@ -61,8 +62,14 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
     constexpr int VLD = (HD * 8) / NT;         // ... for V^T
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
+    // redo (not SPLIT): one word per (query tile, head); only the workgroups whose word is set run (the tiles the
+    // 64-row kernel below gave up on), and they clear it again
     int qtile, head, split = 0;
-    if (SPLIT) {
+    if (!SPLIT && redo) {
+        if (redo[blockIdx.x] == 0) return;
+        qtile = (int)(blockIdx.x / Hq);
+        head = (int)(blockIdx.x % Hq);
+    } else if (SPLIT) {
         split = blockIdx.x % n_split;
         const int rest = blockIdx.x / n_split;
         head = rest % Hq;
@@ -313,6 +320,7 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
                 }
         }
     }
+    if (!SPLIT && redo && tid == 0) redo[blockIdx.x] = 0;
 }
 
 
@@ -340,9 +348,14 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
 // when it passes 2^40 the sums and accumulators are multiplied by an exact power of two and
 // r moves by that exponent (rare: not once with the workloads here).  Terms below 2^-126
 // relative to r underflow exactly as they would against the true maximum once it is larger.
-// A score more than 87 (in log2 units; 60 nats) above everything seen before it, within a
-// single block, would overflow before the watch sees it; scores of that size do not come out
-// of bf16 attention inputs of the kind this path serves.
+// A score more than about 127 log2 units (88 nats) above the reference, within a single block, makes its
+// exponential overflow before the watch can move the reference.  The row sum then is infinite (every p is
+// non-negative, so nothing cancels), which the same watch sees: a row sum that is not below 2^100 after a block
+// marks the wavefront's tile as given up.  At the end the four wavefronts agree (one word of LDS); a workgroup
+// that gave up stores NOTHING (its query rows, which the output overwrites, stay intact) and sets its word in
+// `redo`, and a second launch right behind this one recomputes exactly those (query tile, head) pairs with the
+// running-maximum kernel above, which is total on finite inputs.  With `redo` all zero, as it is for attention
+// inputs of ordinary size, that launch is a few thousand workgroups that read one word and exit.
 //
 // LDS holds the K tiles of the four stages in its first 64 KiB and the V^T tiles in the second: with
 // the stage number known at compile time (main loop unrolled over the four stages) every fragment
@@ -368,7 +381,7 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
 __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const bf16_t* __restrict__ k,
                                                          const bf16_t* __restrict__ vt, int64_t ldv, bf16_t* o, int N,
-                                                         int Hq, int Hkv, float sc_log2e, int nqt, int hpx) {
+                                                         int Hq, int Hkv, float sc_log2e, int nqt, int hpx, int* redo) {
     constexpr int HD = 128, KS = 8, HT = 4;
     constexpr int TILE_BYTES = 64 * HD * 2;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -459,6 +472,9 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
             for (int r = 0; r < 16; ++r) oacc[ht][qt][r] = 0.f;
     float mb[2], lrow[2] = {0.f, 0.f};      // reference exponents (log2 domain) and row sums per query tile
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    int gave_up = 0;                        // wavefront-uniform: a row sum left the range the reference scheme covers
+    int* const lds_gave_up = (int*)(smem + 2 * A64_NSTAGE * A64_TILE);     // one word behind the ring
+    if (tid == 0) *lds_gave_up = 0;         // (read only after the last of the barriers below)
 
     // causal mask of a 32-key block on the accumulators of one query tile
 #define PO_MASK(S, kb_, qt_)                                                                     \
@@ -619,8 +635,10 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
             }                                                                                                   \
         }                                                                                                       \
         /* ---- renormalise when a row sum has grown past 2^40 (rare; see the note on the reference) */         \
-        if (__any(lrow[0] > 0x1p40f || lrow[1] > 0x1p40f)) {                                                    \
-            int e0_ = ilogbf(half_swap_sum(lrow[0])), e1_ = ilogbf(half_swap_sum(lrow[1]));                     \
+        if (__any(!(lrow[0] <= 0x1p40f) || !(lrow[1] <= 0x1p40f))) {                                            \
+            const float t0_ = half_swap_sum(lrow[0]), t1_ = half_swap_sum(lrow[1]);                             \
+            if (__any(!(t0_ < 0x1p100f) || !(t1_ < 0x1p100f))) gave_up = 1;                                     \
+            int e0_ = ilogbf(t0_), e1_ = ilogbf(t1_);                                                           \
             asm volatile("" : "+v"(e0_), "+v"(e1_));   /* keeps the rescale inside this rarely taken branch */  \
             PO_MFMA_DRAIN();                                                                                    \
             const float a0_ = ldexpf(1.0f, -e0_), a1_ = ldexpf(1.0f, -e1_);                                     \
@@ -689,6 +707,14 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
 #undef PO_MFMA_ACC
 #undef PO_MFMA_DRAIN
 
+    // ---- did any wavefront give up?  (every wavefront has met the same number of barriers and arrives here)
+    if (gave_up && lane == 0) *(volatile int*)lds_gave_up = 1;
+    __syncthreads();
+    if (*(volatile int*)lds_gave_up) {
+        if (tid == 0) redo[qtile * Hq + head] = 1;
+        return;
+    }
+
     // ---- normalise and store: lane = query row, registers = head-dim rows
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
@@ -741,11 +767,14 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
 }
 
 void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
-                  int Hkv, int64_t q_row0, hipStream_t s) {
-    constexpr int SMEM = 2 * A64_NSTAGE * A64_TILE;
+                  int Hkv, int64_t q_row0, int* redo, hipStream_t s) {
+    constexpr int SMEM = 2 * A64_NSTAGE * A64_TILE + 16;             // the ring and the give-up word
+    constexpr int SMEM_REDO = 2 * 2 * BNK * 128 * 2;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void*)attn_fwd64_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+        (void)hipFuncSetAttribute((const void*)attn_fwd_kernel<128, 1, 8, false>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_REDO);
         attr_set = true;
     }
     const int nqt = (int)((N + 255) / 256);
@@ -754,7 +783,11 @@ void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ld
     // workgroups enumerate query tiles from the last one down: fewer of them = only the last tiles
     const int nsel = nqt - (int)((q_row0 > 0 && q_row0 < N) ? q_row0 / 256 : 0);
     hipLaunchKernelGGL(attn_fwd64_kernel, dim3((unsigned)(nsel * Hq)), dim3(256), SMEM, s, q, k, vt, ldv, o, (int)N, Hq,
-                       Hkv, sc_log2e, nqt, hpx);
+                       Hkv, sc_log2e, nqt, hpx, redo);
+    // the (query tile, head) pairs given up above, by the running-maximum kernel with the same 256-row tiles
+    // (8 wavefronts x 32 rows); workgroup b looks at redo[b], b = query tile * Hq + head
+    hipLaunchKernelGGL((attn_fwd_kernel<128, 1, 8, false>), dim3((unsigned)(nqt * Hq)), dim3(512), SMEM_REDO, s, q, k, vt, ldv,
+                       o, (int)N, Hq, Hkv, sc_log2e, nqt, 0, 0, 1, nullptr, nullptr, nullptr, nullptr, 0, 0, redo);
 }
 
 template <int HD, int QT, int NW>
@@ -774,7 +807,7 @@ void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, b
     // workgroups enumerate query tiles from the last one down: fewer of them = only the last tiles
     const int nsel = nqt - (int)((q_row0 > 0 && q_row0 < N) ? q_row0 / BMQ : 0);
     hipLaunchKernelGGL((attn_fwd_kernel<HD, QT, NW, false>), dim3((unsigned)(nsel * Hq)), dim3(NW * 64), SMEM, s, q, k, vt,
-                       ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, hpx, 0, 1, nullptr, nullptr, nullptr, nullptr, 0, 0);
+                       ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, hpx, 0, 1, nullptr, nullptr, nullptr, nullptr, 0, 0, nullptr);
 }
 
 template <int HD>
@@ -805,7 +838,7 @@ int launch_split_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t l
     const float sc_log2e = (float)(1.4426950408889634 / sqrt((double)HD));
     hipLaunchKernelGGL((attn_fwd_kernel<HD, 1, NW, true>), dim3((unsigned)(nqt * Hq * n_split)), dim3(NW * 64), SMEM, s, q,
                        k, vt, ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, 0, (int)q_row0, n_split, opart, mlpart,
-                       k2 ? k2 : k, vt2 ? vt2 : vt, vt2 ? ldv2 : ldv, (k2 && vt2) ? (int)(n2 / BNK) : 0);
+                       k2 ? k2 : k, vt2 ? vt2 : vt, vt2 ? ldv2 : ldv, (k2 && vt2) ? (int)(n2 / BNK) : 0, nullptr);
     const int64_t n = nq * Hq * (HD / 4);
     hipLaunchKernelGGL(attn_combine_kernel<HD>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, opart, mlpart, n_split,
                        (int)nq, Hq, sc_log2e, o, (int)q_row0);
@@ -829,10 +862,12 @@ int launch_attention_mfma_split(const bf16_t* q, const bf16_t* k, const bf16_t* 
     return 0;
 }
 
+size_t attention_mfma_redo_bytes(int64_t N, int Hq) { return (size_t)((N + 255) / 256) * (size_t)Hq * sizeof(int); }
+
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N,
-                           int Hq, int Hkv, int hd, int64_t q_row0, hipStream_t s) {
+                           int Hq, int Hkv, int hd, int64_t q_row0, int* redo, hipStream_t s) {
     if (N <= 0) return;
-    if (hd == 128) launch_fwd64(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, s);
+    if (hd == 128) launch_fwd64(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, redo, s);
     else if (hd == 64) launch_t<64, 1, 8>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, s);
 }
 

@@ -322,6 +322,187 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams& p, const f32x16 
     }
 }
 
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+// Epilogue of a 256 x 256 block tile whose accumulators sit in the layout of the bf16 GEMM: eight wavefronts
+// arranged 2 x 4, each a 128-row x 64-column patch of 8 x 4 MFMA 16x16 tiles; in tile (u, t) a lane holds token
+// row 16 u + (lane & 15) and the four consecutive features 16 t + 4 (lane >> 4) + r.  A wavefront's 64 columns are
+// exactly one patch of the packed weights: tiles 0, 1 hold the gate values / the first rotary halves of 32
+// features, tiles 2, 3 the up values / second halves, so a lane finds a pair in the same register of tiles t, t + 2.
+// The position-wise results pass through LDS (8 KiB per wavefront, wave-private, 16-byte groups XOR-swizzled with
+// the row so that the writes, lane = row, and the reads, lanes along a row, are free of bank conflicts) and leave
+// as 16 bytes per lane covering whole row segments; QKV keeps a per-lane path (rotary pairs, V^T).
+// smem: at least 8 KiB per wavefront, free to overwrite (callers synchronise the workgroup before).
+template <int EPI>
+__device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4 (&acc)[8][4], unsigned char* smem,
+                                                int m0, int n0, int wave, int lane) {
+    const int l15 = lane & 15, l4 = lane >> 4;
+    const int wm = wave >> 2, wn = wave & 3;
+    unsigned char* stg = smem + wave * 8192;
+    const int row_base = m0 + wm * 128, col_base = n0 + wn * 64;
+    if (col_base >= p.N) return;                       // (N is a multiple of 64: a patch is wholly in or out)
+    if (EPI == EPI_QKV_ROPE) {
+        const int half = p.hd >> 1;
+        const int cb = col_base;
+        if (cb < p.qd + p.kvd) {
+            const bool is_q = cb < p.qd;
+            const int c = is_q ? cb : cb - p.qd;
+            const int head = c / p.hd;
+            const int patch = (c - head * p.hd) >> 6;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int row = row_base + u * 16 + l15;
+                if (row >= p.M) continue;
+                const int64_t pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
+                bf16_t* drow = (is_q ? p.dst + (int64_t)row * p.qd : p.dst_k + (int64_t)row * p.kvd) + head * p.hd;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int i0 = patch * 32 + t * 16 + 4 * l4;             // rotary index of register 0
+                    const float4 cs = *(const float4*)(p.rope_cos + pos * half + i0);
+                    const float4 sn = *(const float4*)(p.rope_sin + pos * half + i0);
+                    const float cv[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
+                    float lo[4], hi[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float a = acc[u][t][e], b = acc[u][t + 2][e];
+                        if (p.bias) { a += bf2f(p.bias[cb + t * 16 + 4 * l4 + e]); b += bf2f(p.bias[cb + 32 + t * 16 + 4 * l4 + e]); }
+                        lo[e] = a * cv[e] - b * sv[e];
+                        hi[e] = b * cv[e] + a * sv[e];
+                    }
+                    *(uint2*)(drow + i0) = pack4(lo[0], lo[1], lo[2], lo[3]);
+                    *(uint2*)(drow + half + i0) = pack4(hi[0], hi[1], hi[2], hi[3]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+            // V patch: stored transposed, V^T[feature][position]; consecutive lanes are consecutive positions
+            const int f0 = cb - p.qd - p.kvd;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int row = row_base + u * 16 + l15;
+                if (row >= p.M) continue;
+                bf16_t* dcol = p.dst_vt + p.pos0 + row;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int f = f0 + t * 16 + 4 * l4 + e;
+                        float v = acc[u][t][e];
+                        if (p.bias) v += bf2f(p.bias[p.qd + p.kvd + f]);
+                        dcol[(int64_t)f * p.ldv] = f2bf(v);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else if (EPI == EPI_RESIDUAL || EPI == EPI_PARTIAL) {
+        // 16 rows x 64 features at a time as fp32 (256-byte rows, 16 groups of 4 features = one accumulator tile
+        // register quad), then 8 consecutive features per lane, 8 rows per pass
+        const int col = col_base + (lane & 7) * 8;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                *(f32x4*)(stg + l15 * 256 + (((t * 4 + l4) ^ l15) << 4)) = acc[u][t];
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            uint4 rr[2];
+            if (EPI == EPI_RESIDUAL) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int row = row_base + u * 16 + i * 8 + (lane >> 3);
+                    rr[i] = make_uint4(0, 0, 0, 0);
+                    if (row < p.M) rr[i] = *(const uint4*)(p.R + (int64_t)row * p.ldr + col);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int rl = i * 8 + (lane >> 3);
+                const int row = row_base + u * 16 + rl;
+                const int g0 = (lane & 7) * 2;
+                const float4 x0 = *(const float4*)(stg + rl * 256 + ((g0 ^ rl) << 4));
+                const float4 x1 = *(const float4*)(stg + rl * 256 + (((g0 + 1) ^ rl) << 4));
+                if (EPI == EPI_PARTIAL) {
+                    float* part = (float*)p.dst;                 // this split's float plane, p.ld its row pitch in floats
+                    if (row < p.M) {
+                        *(float4*)(part + (int64_t)row * p.ld + col) = x0;
+                        *(float4*)(part + (int64_t)row * p.ld + col + 4) = x1;
+                    }
+                } else {
+                    uint4 o;
+                    o.x = (uint32_t)f2bf(x0.x + __uint_as_float(rr[i].x << 16)) | ((uint32_t)f2bf(x0.y + __uint_as_float(rr[i].x & 0xffff0000u)) << 16);
+                    o.y = (uint32_t)f2bf(x0.z + __uint_as_float(rr[i].y << 16)) | ((uint32_t)f2bf(x0.w + __uint_as_float(rr[i].y & 0xffff0000u)) << 16);
+                    o.z = (uint32_t)f2bf(x1.x + __uint_as_float(rr[i].z << 16)) | ((uint32_t)f2bf(x1.y + __uint_as_float(rr[i].z & 0xffff0000u)) << 16);
+                    o.w = (uint32_t)f2bf(x1.z + __uint_as_float(rr[i].w << 16)) | ((uint32_t)f2bf(x1.w + __uint_as_float(rr[i].w & 0xffff0000u)) << 16);
+                    if (row < p.M) *(uint4*)(p.dst + (int64_t)row * p.ld + col) = o;
+                }
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else if (EPI == EPI_STORE) {
+        // 16 rows x 64 features at a time as bf16 (128-byte rows, 8 groups of 8 features; two rows per 256 bytes of
+        // banks: swizzle with row / 2), then 8 features per lane, 8 rows per pass
+        const int col = col_base + (lane & 7) * 8;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float v[4] = {acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]};
+                if (p.bias) {
+                    const uint2 bw = *(const uint2*)(p.bias + col_base + t * 16 + 4 * l4);
+                    v[0] += __uint_as_float(bw.x << 16); v[1] += __uint_as_float(bw.x & 0xffff0000u);
+                    v[2] += __uint_as_float(bw.y << 16); v[3] += __uint_as_float(bw.y & 0xffff0000u);
+                }
+                const int grp = t * 2 + (l4 >> 1);
+                *(uint2*)(stg + l15 * 128 + ((grp ^ ((l15 >> 1) & 7)) << 4) + (l4 & 1) * 8) = pack4(v[0], v[1], v[2], v[3]);
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int rl = i * 8 + (lane >> 3);
+                const int row = row_base + u * 16 + rl;
+                const uint4 o = *(const uint4*)(stg + rl * 128 + (((lane & 7) ^ ((rl >> 1) & 7)) << 4));
+                if (row < p.M) *(uint4*)(p.dst + (int64_t)row * p.ld + col) = o;
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+        // SiLU-multiply: the patch (32 gate, 32 up) gives 32 features; 16 rows x 32 features at a time as bf16
+        // (64-byte rows, 4 groups of 8 features; four rows per 256 bytes of banks: swizzle with row / 4), then 8
+        // features per lane: one pass stores all 16 rows, 64 contiguous bytes each
+        const int col = col_base / 2 + (lane & 3) * 8;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const f32x4& g = acc[u][t];
+                const f32x4& up = acc[u][t + 2];
+                const int grp = t * 2 + (l4 >> 1);
+                *(uint2*)(stg + l15 * 64 + ((grp ^ ((l15 >> 2) & 3)) << 4) + (l4 & 1) * 8) =
+                    pack4(silu_f(g[0]) * up[0], silu_f(g[1]) * up[1], silu_f(g[2]) * up[2], silu_f(g[3]) * up[3]);
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                const int rl = lane >> 2;
+                const int row = row_base + u * 16 + rl;
+                const uint4 o = *(const uint4*)(stg + rl * 64 + (((lane & 3) ^ ((rl >> 2) & 3)) << 4));
+                if (row < p.M) *(uint4*)(p.dst + (int64_t)row * p.ld + col) = o;
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
 // ---- split-K support shared by the bf16 and the FP8 GEMM (defined with the bf16 kernel)
 // splits of the reduction for a GEMM with few output tiles whose K range has kt slices: enough workgroups for
 // the chip's 256 compute units, whole slices, at least two per split, fp32 partials within part_bytes; 1 = none

@@ -36,6 +36,7 @@
 // chunked, which is what makes the chunk-by-chunk evaluation of Section 4.2 bit-exact.
 #include "gemm_common.h"
 
+#include <stdlib.h>
 #include <string.h>
 
 namespace po {
@@ -227,6 +228,132 @@ __global__ void __launch_bounds__(NTHREADS) gemm_bf16_mfma_kernel(const GemmPara
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The same GEMM on v_mfma_f32_16x16x32_bf16 with eight wavefronts (two per SIMD).
+//
+// Why: the board runs these GEMMs at its power limit, so what counts is energy per flop, and the matrix
+// instruction with the smaller accumulator tile does 15-20 % more work per joule (bare loops on random operands:
+// 2.12-2.16 PFLOP/s against 1.78-1.88 for 32x32x16).  One wavefront per SIMD cannot issue it at full rate, two can;
+// with two, each has half the registers, so a wavefront owns a 128-row x 64-column patch (8 x 4 tiles, 128 fp32
+// accumulators per lane) and reads 12 fragments per 32 MFMAs.  Block tile, K slices of 64, the ring of five
+// 32 KiB units filled by global->LDS loads, the swizzle, the XCD-aware tile order and the reduction order over K
+// (one fp32 accumulator per output runs over K in steps of 32) do not depend on how M is tiled, as before.
+// Schedule of a slice (two k-steps x eight 16-row blocks = 16 groups of 4 MFMAs): the four W fragments of a k-step
+// stay in registers, the A fragment of the next group is read while this group multiplies, and every group issues
+// at most one more memory instruction (a W fragment of the next k-step, or one of the 4 + 4 global->LDS loads of
+// W(s+1) and A(s+2)); the second wavefront of the SIMD fills the issue gaps, so nothing finer is needed.
+constexpr int NTHREADS16 = 512;
+
+template <int EPI>
+__global__ void __launch_bounds__(NTHREADS16) gemm_bf16_mfma16_kernel(const GemmParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    // ---- XCD-aware tile assignment
+    const int total = p.mt * p.nt;
+    const int per_xcd = (total + 7) >> 3;
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int li = xcd * per_xcd + local;
+    if (local >= per_xcd || li >= total) return;
+    const int group_sz = GROUP_M * p.nt;
+    const int g = li / group_sz;
+    const int within = li - g * group_sz;
+    const int gm_this = min(GROUP_M, p.mt - g * GROUP_M);
+    const int tn = within / gm_this;
+    const int tm = g * GROUP_M + (within - tn * gm_this);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l15 = lane & 15, l4 = lane >> 4;
+    const int wm = wave >> 2, wn = wave & 3;
+
+    // ---- global -> LDS map: a unit is 32 one-KiB loads, wavefront w issues loads 4w .. 4w+3; load q fills rows
+    // 8q .. 8q+7 (lane l -> row 8q + l/8, physical segment l & 7 <- logical segment (l & 7) ^ ((row >> 1) & 7))
+    const int64_t k0 = (EPI == EPI_PARTIAL) ? (int64_t)blockIdx.y * p.K : 0;
+    const uint64_t a_bytes = (uint64_t)(p.M - m0) * (uint64_t)p.lda * 2 - (uint64_t)k0 * 2,
+                   w_bytes = (uint64_t)(p.N - n0) * (uint64_t)p.ldw * 2 - (uint64_t)k0 * 2;
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.A + (int64_t)m0 * p.lda + k0), 0, (int)(uint32_t)(a_bytes > 0xffffffffull ? 0xffffffffull : a_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.W + (int64_t)n0 * p.ldw + k0), 0, (int)(uint32_t)(w_bytes > 0xffffffffull ? 0xffffffffull : w_bytes), 0x00020000);
+    uint32_t voa[4], vow[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = (wave * 4 + i) * 8 + (lane >> 3);
+        const int lseg = (lane & 7) ^ ((row >> 1) & 7);
+        voa[i] = (uint32_t)row * (uint32_t)(p.lda * 2) + lseg * 16;
+        vow[i] = (uint32_t)row * (uint32_t)(p.ldw * 2) + lseg * 16;
+    }
+    const int KT = p.K / BK;
+#define PO_DMA16(is_w_, slice_, pos_, i_)                                                                              \
+    {                                                                                                                  \
+        unsigned char* d_ = smem + (pos_) * UNIT_BYTES + (wave * 4 + (i_)) * 1024;                                     \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds((is_w_) ? rw : ra, (__attribute__((address_space(3))) void*)d_, 16,   \
+                                                 (is_w_) ? vow[(i_)] : voa[(i_)], min((slice_), KT - 1) * (BK * 2), 0, 0); \
+    }
+    // fragment offsets: row l15 of a 16-row block, logical segment 4 ks + l4 of its 128 bytes
+    int f_off[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) f_off[ks] = l15 * 128 + (((ks * 4 + l4) ^ ((l15 >> 1) & 7)) << 4);
+    const int a_base = wm * 128 * 128, w_base = wn * 64 * 128;     // byte offset of the wavefront's rows inside a unit
+
+    f32x4 acc[8][4];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // prologue: A0 W0 A1 in flight; W1 follows at the top of slice 0
+#pragma unroll
+    for (int i = 0; i < 4; ++i) PO_DMA16(0, 0, 0, i)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) PO_DMA16(1, 0, 1, i)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) PO_DMA16(0, 1, 2, i)
+    asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");      // slice 0 has landed
+    int pa = 0;                                                        // ring position of slice s's A unit; W at pa + 1
+    for (int s = 0; s < KT; ++s) {
+        const int pw = pa + 1 >= NUNIT ? pa + 1 - NUNIT : pa + 1;
+        const int pw1 = pa + 3 >= NUNIT ? pa + 3 - NUNIT : pa + 3;    // W(s+1): the position A(s-1) left
+        const int pa2 = pa + 4 >= NUNIT ? pa + 4 - NUNIT : pa + 4;    // A(s+2): the position W(s-1) left
+        const unsigned char* ua = smem + pa * UNIT_BYTES + a_base;
+        const unsigned char* uw = smem + pw * UNIT_BYTES + w_base;
+        bf16x8 wf[2][4], afc, afn;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) wf[0][t] = *(const bf16x8*)(uw + t * 2048 + f_off[0]);
+        afc = *(const bf16x8*)(ua + f_off[0]);
+#pragma unroll
+        for (int gi = 0; gi < 16; ++gi) {                              // group gi: k-step gi / 8, row block gi % 8
+            const int ks = gi >> 3, u = gi & 7;
+            if (gi < 15) afn = *(const bf16x8*)(ua + ((gi + 1) & 7) * 2048 + f_off[(gi + 1) >> 3]);
+            if (gi >= 4 && gi < 8) wf[1][gi - 4] = *(const bf16x8*)(uw + (gi - 4) * 2048 + f_off[1]);
+            if (gi < 4) PO_DMA16(1, s + 1, pw1, gi)
+            if (gi >= 8 && gi < 12) PO_DMA16(0, s + 2, pa2, gi - 8)
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks][t], afc, acc[u][t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            afc = afn;
+        }
+        // hand-over: slice s+1 has landed (everything but the 4 loads of A(s+2)), nobody reads slice s any more
+        asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        pa = pa + 2 >= NUNIT ? pa + 2 - NUNIT : pa + 2;
+    }
+#undef PO_DMA16
+    // the clamped tail loads have landed and every wavefront has finished reading the ring
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+
+    if (EPI == EPI_PARTIAL) {
+        GemmParams q = p;
+        q.dst = (bf16_t*)((float*)p.dst + (int64_t)blockIdx.y * p.ldr);     // this split's plane
+        tile_epilogue16<EPI>(q, acc, smem, m0, n0, wave, lane);
+    } else {
+        tile_epilogue16<EPI>(p, acc, smem, m0, n0, wave, lane);
+    }
+}
+
 // C[row][col .. col+7] = bf16(sum over splits of part[s][row][col ..] + R[row][col ..]); one thread per 8 features.
 __global__ void __launch_bounds__(256) splitk_reduce_residual_kernel(const float* __restrict__ part, int64_t plane,
                                                                      int splits, const bf16_t* R, int64_t ldr,
@@ -308,17 +435,31 @@ __global__ void __launch_bounds__(256) splitk_reduce_silu_kernel(const float* __
     H[(int64_t)row * ldh + f] = f2bf(silu_f(g) * u);
 }
 
+int gemm_variant() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("PO_GEMM_VARIANT");
+        v = e ? atoi(e) : 16;
+    }
+    return v;
+}
+
 template <int EPI>
 void launch_t(const GemmParams& p, hipStream_t s, int splits = 1) {
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+        (void)hipFuncSetAttribute((const void*)gemm_bf16_mfma16_kernel<EPI>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
         attr_set = true;
     }
     const int total = p.mt * p.nt;
     const int per_xcd = (total + 7) / 8;
-    hipLaunchKernelGGL(gemm_bf16_mfma_kernel<EPI>, dim3((unsigned)(per_xcd * 8), (unsigned)splits), dim3(NTHREADS), SMEM_BYTES, s, p);
+    if (gemm_variant() == 32)
+        hipLaunchKernelGGL(gemm_bf16_mfma_kernel<EPI>, dim3((unsigned)(per_xcd * 8), (unsigned)splits), dim3(NTHREADS), SMEM_BYTES, s, p);
+    else
+        hipLaunchKernelGGL(gemm_bf16_mfma16_kernel<EPI>, dim3((unsigned)(per_xcd * 8), (unsigned)splits), dim3(NTHREADS16), SMEM_BYTES, s, p);
 }
 
 GemmParams base_params(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, int64_t M, int N, int K) {

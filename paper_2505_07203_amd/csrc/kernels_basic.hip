@@ -454,6 +454,16 @@ __global__ void __launch_bounds__(64) vt_pad_zero_kernel(bf16_t* Vt, int64_t ldv
     if ((int)threadIdx.x < pad) Vt[(int64_t)blockIdx.x * ldv + n + threadIdx.x] = 0;
 }
 
+__global__ void __launch_bounds__(256) fill_zero32_kernel(uint32_t* dst, size_t n) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = 0u;
+}
+
+void launch_fill_zero32(void* dst, size_t n_words, hipStream_t s) {
+    if (n_words == 0) return;
+    hipLaunchKernelGGL(fill_zero32_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, s, (uint32_t*)dst, n_words);
+}
+
 void launch_vt_pad_zero(bf16_t* Vt, int rows, int64_t ldv, int64_t n, hipStream_t s) {
     const int pad = (int)(round_up64(n, 64) - n);
     if (pad <= 0 || rows <= 0) return;

@@ -47,6 +47,8 @@ struct Layout {
     size_t weights_bytes;
     // workspace arena
     size_t tokens, X, Q, K, V, Vt, Xn, H, GU, rope_cos, rope_sin, logits, xn_last, cand, cand_lp;
+    size_t attn_redo;   // bf16: one word per 256-row query tile and head (see launch_attention_mfma)
+    size_t profile_mark;  // the last 256 bytes: where po_profile's scan leaves its result (not part of what it scans)
     size_t sx;          // PO_BF16_FP8: float32 scale per row of the activation being multiplied
     size_t workspace_bytes;
     int64_t ldv;
@@ -141,8 +143,10 @@ po_status make_layout(const po_model_config* c, int64_t max_len, int32_t mlp_chu
     L->xn_last = take(d * esz);
     L->cand = take(MAX_CAND * 4);
     L->cand_lp = take(MAX_CAND * 4);
+    L->attn_redo = is_bf16(c->dtype) ? take(attention_mfma_redo_bytes(max_len, c->n_q_heads)) : 0;
     // one scale per row of a launch: at most the rows of d values the MLP chunk buffer holds
     L->sx = fp8 ? take(std::max(C, C * F / d) * 4) : 0;
+    L->profile_mark = take(sizeof(unsigned long long));
     L->workspace_bytes = off;
     return PO_OK;
 }
@@ -320,6 +324,9 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
     }
     // the last key tile of the attention reads V^T up to the next multiple of 64 positions
     if (dt == PO_BF16) launch_vt_pad_zero((bf16_t*)(ws + L.Vt), kvd, L.ldv, total, s);
+    // the attention's give-up words start every request at zero (its second launch leaves them so)
+    int* attn_redo = (int*)(ws + L.attn_redo);
+    if (dt == PO_BF16) launch_fill_zero32(attn_redo, attention_mfma_redo_bytes(c->max_len, m.n_q_heads) / 4, s);
 
     for (int l = 0; l < m.n_layers; ++l) {
         const LayerOff& o = L.layers[l];
@@ -452,7 +459,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                 else
                     launch_attention_mfma((const bf16_t*)Qg, (const bf16_t*)(K + (size_t)g.start * kvd * esz),
                                           (const bf16_t*)(ws + L.Vt) + g.start, L.ldv, (bf16_t*)Qg, g.len, m.n_q_heads,
-                                          m.n_kv_heads, hd, q_row0, s);
+                                          m.n_kv_heads, hd, q_row0, attn_redo, s);
             } else {
                 launch_attention_basic(dt, Qg, K + (size_t)g.start * kvd * esz, V + (size_t)g.start * kvd * esz, Qg,
                                        g.len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
@@ -777,14 +784,48 @@ po_status po_load_tensor(po_ctx* c, int32_t kind, int32_t layer, const void* hos
                 dst_off = kind == PO_T_WU ? GU_INTERLEAVE_BF16 : 0;
                 break;
         }
-        void* tmp = nullptr;
-        if (hipMalloc(&tmp, bytes) != hipSuccess) return PO_ERR_OOM;
-        hipError_t e = hipMemcpy(tmp, host, bytes, hipMemcpyHostToDevice);
+        // Staging area: the per-request buffers at the head of the activation arena (residual stream up to the
+        // chunk buffers; nothing in them outlives a request, and no request runs during a load), so loading
+        // allocates nothing and the footprint stays what po_workspace_bytes reports.  It holds at least one row
+        // of any of these matrices (the chunk buffer alone holds ffn_dim values); larger tensors go row block
+        // by row block.
+        unsigned char* stage = c->ws + L.X;
+        const size_t stage_bytes = L.rope_cos - L.X;
+        const size_t row_bytes = k_in * 2;
+        const size_t fit = stage_bytes / row_bytes;
+        if (fit == 0) return PO_ERR_WORKSPACE_TOO_SMALL;
+        unsigned char* codes = c->w + off + row0 * k_in;
+        float* scales = (float*)(c->w + s_off) + row0;
+        hipError_t e = hipSuccess;
+        for (size_t r0 = 0; r0 < rows && e == hipSuccess;) {
+            size_t n;
+            int blk_c = 0;
+            int64_t stride_c = 0, dst_c;
+            unsigned char* codes_c = codes;
+            float* scales_c = scales;
+            if (blk == 0) {
+                n = std::min(fit, rows - r0);
+                dst_c = (int64_t)r0;
+            } else if (fit >= (size_t)blk && r0 % (size_t)blk == 0) {
+                // whole interleave blocks: the destination base moves by whole block strides
+                n = std::min(fit / (size_t)blk * (size_t)blk, rows - r0);
+                codes_c = codes + (r0 / (size_t)blk) * (size_t)blk_stride * k_in;
+                scales_c = scales + (r0 / (size_t)blk) * (size_t)blk_stride;
+                blk_c = blk; stride_c = blk_stride; dst_c = dst_off;
+            } else {
+                // fewer rows than one interleave block fit: a run of rows inside one block, kept in order
+                n = std::min(std::min(fit, (size_t)blk - r0 % (size_t)blk), rows - r0);
+                dst_c = (int64_t)((r0 / (size_t)blk) * (size_t)blk_stride + r0 % (size_t)blk) + dst_off;
+            }
+            e = hipMemcpyAsync(stage, (const unsigned char*)host + r0 * row_bytes, n * row_bytes, hipMemcpyHostToDevice, c->stream);
+            if (e != hipSuccess) break;
+            launch_quant_rows((const bf16_t*)stage, (int64_t)k_in, codes_c, (int64_t)k_in, scales_c, (int64_t)n, (int)k_in, blk_c,
+                              stride_c, dst_c, c->stream);
+            // (the host buffer is pageable: the copy has left it when the call returns, and the next block's copy
+            // is ordered behind this block's kernel on the stream)
+            r0 += n;
+        }
         if (e == hipSuccess) {
-            unsigned char* codes = c->w + off + row0 * k_in;
-            float* scales = (float*)(c->w + s_off) + row0;
-            launch_quant_rows((const bf16_t*)tmp, (int64_t)k_in, codes, (int64_t)k_in, scales, (int64_t)rows, (int)k_in, blk,
-                              blk_stride, dst_off, c->stream);
             if (kind == PO_T_WQ || kind == PO_T_WK) {
                 // the rotary row order of the bf16 path, applied to the rows of codes (k_in bytes = k_in / 2
                 // two-byte units) and to their scales (4 bytes = 2 units)
@@ -795,7 +836,6 @@ po_status po_load_tensor(po_ctx* c, int32_t kind, int32_t layer, const void* hos
             e = hipStreamSynchronize(c->stream);
             if (e == hipSuccess) e = hipGetLastError();
         }
-        (void)hipFree(tmp);
         if (e != hipSuccess) {
             snprintf(g_dev_err, sizeof(g_dev_err), "po_load_tensor: %s", hipGetErrorString(e));
             return PO_ERR_DEVICE;
@@ -951,9 +991,9 @@ po_status po_profile(po_ctx* c, int64_t len, double* elapsed_ms, size_t* touched
     if (!c || len <= 0) return PO_ERR_INVALID_ARG;
     if (len > c->max_len) return PO_ERR_TOO_LONG;
     if (!po_is_loaded(c)) return PO_ERR_NOT_LOADED;
-    const size_t ws_bytes = c->lay.workspace_bytes;
-    unsigned long long* d_mark = nullptr;
-    if (hipMalloc(&d_mark, sizeof(unsigned long long)) != hipSuccess) return PO_ERR_OOM;
+    // everything in front of the mark word is filled and scanned; the word itself is the arena's last 256 bytes
+    const size_t ws_bytes = c->lay.profile_mark;
+    unsigned long long* d_mark = (unsigned long long*)(c->ws + c->lay.profile_mark);
     std::vector<int32_t> tokens((size_t)len, 0);
     const int32_t cand[2] = {0, c->cfg.vocab_size - 1};
     float lp[2];
@@ -976,7 +1016,6 @@ po_status po_profile(po_ctx* c, int64_t len, double* elapsed_ms, size_t* touched
             }
         }
     }
-    (void)hipFree(d_mark);
     return st;
 }
 
@@ -1288,9 +1327,12 @@ po_status po_op_attention(int32_t dtype, const void* q, const void* k, const voi
         if (!scratch) return PO_ERR_INVALID_ARG;
         if ((N + 64) * Hkv * hd * 2 >= ((int64_t)1 << 32)) return PO_ERR_TOO_LONG;
         const int64_t ldv = round_up64(N, 64);
+        // scratch: V^T, then (256-byte aligned) the give-up words of the attention kernel
+        int* redo = (int*)((unsigned char*)scratch + align_up((size_t)Hkv * hd * (size_t)ldv * 2));
+        launch_fill_zero32(redo, attention_mfma_redo_bytes(N, Hq) / 4, (hipStream_t)stream);
         launch_v_transpose((const bf16_t*)v, (bf16_t*)scratch, N, Hkv * hd, ldv, (hipStream_t)stream);
         launch_attention_mfma((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)scratch, ldv, (bf16_t*)o, N, Hq, Hkv,
-                              hd, 0, (hipStream_t)stream);
+                              hd, 0, redo, (hipStream_t)stream);
     } else {
         if (hd != 32 && hd != 64 && hd != 128) return PO_ERR_BAD_CONFIG;
         launch_attention_basic(dtype, q, k, v, o, N, Hq, Hkv, hd, 0, (hipStream_t)stream);
@@ -1421,6 +1463,23 @@ po_status po_op_qkv_rope_fp8(const void* a_codes, const float* a_scales, const v
     launch_gemm_fp8_qkv_rope((const unsigned char*)a_codes, K, a_scales, (const unsigned char*)w_codes, K, w_scales,
                              (const bf16_t*)bqkv, (bf16_t*)q, (bf16_t*)k, (bf16_t*)vt, ldv, cos_t, sin_t, pos0, nullptr, M,
                              Hq * hd, Hkv * hd, hd, K, (hipStream_t)stream);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_mfma_peak(int32_t kind, int32_t waves_per_simd, int32_t iters, const void* operands, size_t operand_bytes,
+                          void* sink, void* stream, double* flop) {
+    if (!operands || !sink || !flop) return PO_ERR_INVALID_ARG;
+    const double f = launch_mfma_peak(kind, waves_per_simd, iters, operands, operand_bytes, (float*)sink, (hipStream_t)stream);
+    if (f == 0.0) return PO_ERR_INVALID_ARG;
+    *flop = f;
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+po_status po_op_stream_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst || bytes == 0 || bytes % 16) return PO_ERR_INVALID_ARG;
+    launch_stream_copy(src, dst, bytes, (hipStream_t)stream);
     PO_HIP(hipGetLastError());
     return PO_OK;
 }

@@ -83,9 +83,15 @@ void launch_high_water(const void* ws, size_t bytes, uint32_t pattern, unsigned 
 void launch_kv_copy(void* dk, const void* sk, size_t k_bytes, void* dv, size_t dpitch, const void* sv, size_t spitch,
                     size_t v_bytes, int v_rows, hipStream_t s);
 void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int64_t ldv, hipStream_t s);
-// causal GQA flash attention; q [N,Hq,hd], k [N,Hkv,hd], vt [Hkv*hd][ldv]; o may alias q
+// causal GQA flash attention; q [N,Hq,hd], k [N,Hkv,hd], vt [Hkv*hd][ldv]; o may alias q.
+// redo: attention_mfma_redo_bytes(N, Hq) bytes of device memory, all zero on entry and left all zero (one word
+// per 256-row query tile and head: the tiles whose scores leave the range of the fast kernel's fixed reference
+// exponent are marked there and recomputed by the running-maximum kernel in a second launch)
+size_t attention_mfma_redo_bytes(int64_t N, int Hq);
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
-                           int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, hipStream_t s);
+                           int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, int* redo, hipStream_t s);
+// n 32-bit words of zeros (a kernel, not a memset node, so that it can be captured into a graph)
+void launch_fill_zero32(void* dst, size_t n_words, hipStream_t s);
 // The same for query rows [q_row0, N) when they are few and the keys many: the key tiles of a query tile are
 // divided between workgroups (fp32 partial results in `scratch`, merged by a second kernel).  Sums are formed
 // in a different order than in launch_attention_mfma: equal to rounding, not bit for bit.  Returns the
@@ -147,5 +153,10 @@ int launch_gemm_fp8_qkv_rope_splitk(const unsigned char* A, int64_t lda, const f
 void launch_rmsnorm_quant(const bf16_t* x, const bf16_t* g, unsigned char* q, float* scales, int64_t rows, int d,
                           float eps, hipStream_t s);
 bool attention_mfma_supported(int Hq, int Hkv, int hd);
+
+// ---- micro-peaks (measurement only)
+double launch_mfma_peak(int kind, int waves_per_simd, int iters, const void* operands, size_t operand_bytes, float* sink,
+                        hipStream_t s);
+void launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 
 }  // namespace po

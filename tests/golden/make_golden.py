@@ -41,7 +41,10 @@ N_EVEN = 509          # evenly spaced sample ids
 N_TOP = 16
 
 # case -> (workload whose config and seeds are used, layer count or None for all,
-#          request lengths or None for the workload's own, lazy last layer)
+#          request lengths or None for the workload's own, lazy last layer[, "f32"])
+# "f32": the same shape and seeds as a float32 model (weights not rounded to bf16; "exact" evaluation only).
+# At full depth this is the comparison in which a structural error cannot hide behind the amplified
+# bf16 storage noise: the library's float32 path has to match it to a few 1e-4 of the logit range.
 CASES = {
     # reduced-cost rungs at full width
     "llama8b_L32_N2048": ("llama8b_32k", None, [2048], False),
@@ -51,6 +54,9 @@ CASES = {
     "qwen32b_L2_N16384": ("qwen32b_8x16k", 2, [16384], False),
     # a full configuration (16 requests of 256..8192 tokens)
     "llama8b_mixed16": ("llama8b_mixed16", None, None, False),
+    # full depth and width in float32
+    "llama8b_f32_L32_N2048": ("llama8b_32k", None, [2048], False, "f32"),
+    "qwen32b_f32_L64_N1024": ("qwen32b_8x16k", None, [1024], False, "f32"),
 }
 
 
@@ -61,9 +67,12 @@ def sample_ids(V, cand, z):
 
 
 def run_case(name):
-    wl, layers, lens, lazy = CASES[name]
+    wl, layers, lens, lazy = CASES[name][:4]
+    f32 = len(CASES[name]) > 4 and CASES[name][4] == "f32"
     w = I.WORKLOADS[wl]
     cfg = w["cfg"]
+    if f32:
+        cfg = cfg.replace(dtype=I.F32)
     if layers:
         cfg = cfg.replace(n_layers=layers)
     if lens is None:
@@ -72,7 +81,7 @@ def run_case(name):
     t_all = time.perf_counter()
     reqs = [I.make_tokens(cfg, w["tseed"], n, request=i) for i, n in enumerate(lens)]
     embed = I.make_tensor(cfg, w["wseed"], I.KIND_EMBED, -1)
-    modes = {"exact": None, "stored_bf16": O.round_bf16}
+    modes = {"exact": None} if f32 else {"exact": None, "stored_bf16": O.round_bf16}
     xs = {m: [I.stored_to_f64(embed[t]) for t in reqs] for m in modes}
     del embed
     t_layers = 0.0
@@ -113,6 +122,7 @@ def run_case(name):
         "citation": "Section 4.2: chunked position-wise layers leave the result unchanged; "
                     "Section 2.2: acceptable-token probabilities sum to 1",
         "case": name, "workload": wl, "layers": cfg.n_layers, "lazy_last_layer": bool(lazy),
+        "model_dtype": "f32" if f32 else "bf16",
         "wseed": w["wseed"], "tseed": w["tseed"], "mlp_chunk": w["chunk"],
         "cand_ids": [int(c) for c in cand],
         "oracle_layer_seconds_exact_mode": t_layers, "oracle_total_seconds": time.perf_counter() - t_all,

@@ -7,7 +7,12 @@ at any size.
     definition evaluated for exactly those rows;
   * the three fused GEMMs at their benchmark shapes: whole sampled rows (every column tile)
     and whole sampled columns (every row tile) against float64 matrix products;
-  * the whole path: bit-identical logits across MLP chunk sizes and across repeated runs.
+  * the whole path: bit-identical logits across MLP chunk sizes and across repeated runs;
+  * the same for the other two large workloads' launch shapes: attention over 131072 tokens (sampled rows in
+    the first, middle and last query tiles), attention with five query heads per KV head over 16384 tokens,
+    the Qwen-32B-shaped GEMMs, and a two-layer whole-path run at 131072 tokens with every layer computed in full;
+  * attention inputs with one key far above all earlier ones inside a key block (the case in which the fast
+    kernel's fixed reference exponent gives up and the tile is recomputed with a running maximum).
 """
 import numpy as np
 import pytest
@@ -76,6 +81,75 @@ def test_attention_large_scores_renormalise():
     assert err <= 1.5e-2
 
 
+@pytest.mark.parametrize("nats", [70.0, 150.0, 400.0])
+def test_attention_outlier_key_mid_block(nats):
+    """One key, in the middle of a 32-key block, scores `nats` above everything before it for every query.
+    70 nats (101 in log2 units) is inside what one block's exponentials hold: the row sums are renormalised.
+    150 and 400 nats overflow the exponential against the reference taken from the first block: those query
+    tiles must be recomputed with a running maximum.  The definition (oracle) gives, for rows at or after the
+    outlier, almost exactly that key's value; the output must be finite and match, also when it overwrites Q."""
+    N, Hq, Hkv, hd = 1024, 8, 2, 128
+    pos = 19 * 32 + 13
+    rng = np.random.default_rng(int(nats))
+    qs = rng.standard_normal((N, Hq, hd), dtype=np.float32)
+    ks = rng.standard_normal((N, Hkv, hd), dtype=np.float32)
+    qs[:, :, 0] = 8.0
+    ks[pos, :, 0] = np.float32(nats) * np.sqrt(np.float32(hd)) / 8.0
+    q, q64 = bf16_dev(qs)
+    k, k64 = bf16_dev(ks)
+    v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    ref = O.causal_gqa_attention(q64, k64, v64)
+    # the oracle itself: behind the outlier the softmax is that key alone
+    assert np.max(np.abs(ref[pos:] - v64[pos][None].repeat(Hq // Hkv, axis=1))) < 1e-6
+    got = host64(B.po_op_attention(q, k, v))
+    assert np.all(np.isfinite(got))
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    print(f"attention with a key {nats} nats above its predecessors: {err:.3e}")
+    assert err <= 1.5e-2
+    dq = q.clone()
+    B.po_op_attention(dq, k, v, out=dq)
+    assert np.array_equal(host64(dq), got)
+    # and the next call on ordinary inputs is unaffected (the give-up words were left clean)
+    k2, k264 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    ref2 = O.causal_gqa_attention(q64, k264, v64)
+    got2 = host64(B.po_op_attention(q, k2, v))
+    assert np.max(np.abs(got2 - ref2)) / np.max(np.abs(ref2)) <= 1.5e-2
+
+
+def test_attention_128k_sampled_rows():
+    """The 131072-token workload's attention launch (32 query heads, 8 KV heads): rows of the first, middle
+    and last query tiles against the definition evaluated for exactly those rows."""
+    N, Hq, Hkv, hd = 131072, 32, 8, 128
+    rng = np.random.default_rng(131072)
+    q, q64 = bf16_dev(rng.standard_normal((N, Hq, hd), dtype=np.float32))
+    k, k64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    rows = np.array([0, 1, 63, 64, 255, 256, 257, 511, 32767, 32768, 65535, 65536, 65537, 65599, 65791, 70001,
+                     98304, 130815, 130816, 130879, 130880, 131007, 131070, 131071])
+    ref = O.causal_gqa_attention(q64, k64, v64, query_rows=rows)
+    del q64
+    got = host64(B.po_op_attention(q, k, v)[torch.from_numpy(rows).cuda()])
+    err = np.max(np.abs(got - ref), axis=(1, 2)) / np.max(np.abs(ref))
+    print("attention N=131072, per sampled row:", " ".join(f"{r}:{e:.1e}" for r, e in zip(rows, err)))
+    assert np.max(err) <= 1.5e-2
+
+
+def test_attention_qwen_heads_16k_sampled_rows():
+    """Five query heads per KV head (40 and 8) over 16384 tokens: the Qwen-32B-shaped workload's launch."""
+    N, Hq, Hkv, hd = 16384, 40, 8, 128
+    rng = np.random.default_rng(16384)
+    q, q64 = bf16_dev(rng.standard_normal((N, Hq, hd), dtype=np.float32))
+    k, k64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    rows = np.array([0, 31, 32, 255, 256, 1000, 4095, 4096, 8191, 8192, 12345, 16127, 16128, 16191, 16382, 16383])
+    ref = O.causal_gqa_attention(q64, k64, v64, query_rows=rows)
+    got = host64(B.po_op_attention(q, k, v)[torch.from_numpy(rows).cuda()])
+    # every query head must have read ITS KV head: compare head by head
+    err = np.max(np.abs(got - ref), axis=(0, 2)) / np.max(np.abs(ref))
+    print("attention N=16384, 40/8 heads, per query head:", " ".join(f"{e:.1e}" for e in err))
+    assert np.max(err) <= 1.5e-2
+
+
 # ------------------------------------------------------------------ GEMMs at benchmark shapes
 
 ROWS = np.array([0, 1, 255, 256, 257, 2047, 4094, 4095])
@@ -89,14 +163,19 @@ def _check_rows_cols(got, ref_rows, ref_cols, rows, cols, tol):
     return max(e_r, e_c)
 
 
-def test_gemm_residual_benchmark_shapes():
-    """O-projection (K = 4096) and MLP down projection (K = 14336) with the residual added in place."""
-    for M, N, K in ((4096, 4096, 4096), (4096, 4096, 14336)):
+@pytest.mark.parametrize("shape", [(4096, 4096, 4096), (4096, 4096, 14336), (4096, 5120, 5120), (4096, 5120, 27648),
+                                   (3072, 5120, 27648)],
+                         ids=lambda t: "x".join(map(str, t)))
+def test_gemm_residual_benchmark_shapes(shape):
+    """O-projection and MLP down projection with the residual added in place: Llama-3-8B shape (K = 4096,
+    14336) and Qwen2.5-32B shape (N = 5120, K = 5120, 27648; 3072 rows is what the path launches there)."""
+    for M, N, K in (shape,):
         rng = np.random.default_rng(K)
         a, a64 = bf16_dev(rng.standard_normal((M, K), dtype=np.float32))
         w, w64 = bf16_dev(rng.standard_normal((N, K), dtype=np.float32) * 0.02)
         r, r64 = bf16_dev(rng.standard_normal((M, N), dtype=np.float32))
-        cols = np.array([0, 63, 64, 255, 256, 2049, 4032, 4095])
+        cols = np.array([0, 63, 64, 255, 256, 2049, N - 64, N - 1])
+        ROWS = np.array([0, 1, 255, 256, 257, 2047, M - 2, M - 1])
         ref_rows = a64[ROWS] @ w64.T + r64[ROWS]
         ref_cols = a64 @ w64[cols].T + r64[:, cols]
         B.po_op_linear(a, w, residual=r, out=r)
@@ -104,13 +183,15 @@ def test_gemm_residual_benchmark_shapes():
         print(f"residual GEMM {M}x{N}x{K}: {e:.2e}")
 
 
-def test_gemm_gate_up_silu_benchmark_shape():
-    M, F, K = 4096, 14336, 4096
+@pytest.mark.parametrize("shape", [(4096, 14336, 4096), (4096, 27648, 5120)], ids=lambda t: "x".join(map(str, t)))
+def test_gemm_gate_up_silu_benchmark_shape(shape):
+    """Gate/up projection with the SiLU-multiply: Llama-3-8B shape and Qwen2.5-32B shape (4096 x 55296 x 5120)."""
+    M, F, K = shape
     rng = np.random.default_rng(F)
     a, a64 = bf16_dev(rng.standard_normal((M, K), dtype=np.float32))
     wg, g64 = bf16_dev(rng.standard_normal((F, K), dtype=np.float32) * 0.02)
     wu, u64 = bf16_dev(rng.standard_normal((F, K), dtype=np.float32) * 0.02)
-    cols = np.array([0, 31, 32, 63, 64, 7000, 14304, 14335])
+    cols = np.array([0, 31, 32, 63, 64, 7000, F - 32, F - 1])
 
     def mlp_act(x, gw, uw):
         gate, up = x @ gw.T, x @ uw.T
@@ -122,10 +203,13 @@ def test_gemm_gate_up_silu_benchmark_shape():
     print(f"gate/up GEMM {M}x{2 * F}x{K}: {e:.2e}")
 
 
-def test_gemm_qkv_rope_benchmark_shape():
-    """8192-row QKV projection with RoPE at positions 24576 .. 32767, V written transposed."""
-    M, Hq, Hkv, hd, K, pos0 = 8192, 32, 8, 128, 4096, 24576
-    theta = 500000.0
+@pytest.mark.parametrize("shape", [(8192, 32, 8, 4096, 24576, 500000.0), (8192, 40, 8, 5120, 8192, 1000000.0)],
+                         ids=["llama8b", "qwen32b"])
+def test_gemm_qkv_rope_benchmark_shape(shape):
+    """8192-row QKV projection with RoPE (Llama-3-8B shape at positions 24576 .. 32767; Qwen2.5-32B shape,
+    8192 x 7168 x 5120, at positions 8192 .. 16383), V written transposed."""
+    M, Hq, Hkv, K, pos0, theta = shape
+    hd = 128
     rng = np.random.default_rng(M)
     a, a64 = bf16_dev(rng.standard_normal((M, K), dtype=np.float32))
     wq, q64 = bf16_dev(rng.standard_normal((Hq * hd, K), dtype=np.float32) * 0.02)
@@ -167,6 +251,28 @@ def test_full_path_32k_bitwise_properties():
                 z2, lp2 = ctx.po_prefill(tokens, cand, want_logits=True)
                 assert np.array_equal(z, z2) and np.array_equal(lp, lp2)
             outs.append((z, lp))
+        finally:
+            ctx.po_destroy()
+    assert np.all(np.isfinite(outs[0][0]))
+    for z, lp in outs[1:]:
+        assert np.array_equal(z, outs[0][0]) and np.array_equal(lp, outs[0][1])
+
+
+def test_full_path_128k_bitwise_properties():
+    """Two layers of the 8B shape on the 131072-token workload, BOTH computed in full (last-layer shortcut off,
+    so the second layer's attention runs all 512 query tiles over the first layer's output): finite logits,
+    identical bit for bit for MLP chunks 8192 (that workload's) and 4096, and with the shortcut on."""
+    w = I.WORKLOADS["llama8b_128k"]
+    cfg = w["cfg"].replace(n_layers=2)
+    tokens = I.make_tokens(cfg, w["tseed"], 131072, request=0)
+    cand = I.label_ids(cfg)
+    outs = []
+    for chunk, lazy in ((8192, False), (4096, False), (8192, True)):
+        ctx = B.Context(cfg, 131072, chunk)
+        try:
+            ctx.load_synthetic(w["wseed"], threads=16)
+            ctx.po_set_lazy_last_layer(lazy)
+            outs.append(ctx.po_prefill(tokens, cand, want_logits=True))
         finally:
             ctx.po_destroy()
     assert np.all(np.isfinite(outs[0][0]))
