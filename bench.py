@@ -132,7 +132,7 @@ def micro_peaks(B, torch):
         B.po_op_mfma_peak(kind, wps, 2000, operands, sink)               # warm-up, also brings the clock down
         torch.cuda.synchronize()
         e0.record()
-        flop = B.po_op_mfma_peak(kind, wps, 20000, operands, sink)
+        flop = B.po_op_mfma_peak(kind, wps, 20000 if kind else 40000, operands, sink)
         e1.record()
         torch.cuda.synchronize()
         out[name + "_tflops"] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12

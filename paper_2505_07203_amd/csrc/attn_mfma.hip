@@ -62,13 +62,19 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
     constexpr int VLD = (HD * 8) / NT;         // ... for V^T
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    // redo (not SPLIT): one word per (query tile, head); only the workgroups whose word is set run (the tiles the
-    // 64-row kernel below gave up on), and they clear it again
+    // redo (not SPLIT): one word per (query tile, head), set for the tiles the 64-row kernel below gave up on.  A small
+    // grid walks the words (workgroup b looks at b, b + gridDim.x, ...), recomputes the tiles whose word is set and
+    // clears it again; with no word set, as for attention inputs of ordinary size, every workgroup reads a few words
+    // and exits.
+    int redo_item = (int)blockIdx.x;
+next_redo_item:
     int qtile, head, split = 0;
     if (!SPLIT && redo) {
-        if (redo[blockIdx.x] == 0) return;
-        qtile = (int)(blockIdx.x / Hq);
-        head = (int)(blockIdx.x % Hq);
+        const int total = nqt * Hq;
+        while (redo_item < total && redo[redo_item] == 0) redo_item += (int)gridDim.x;
+        if (redo_item >= total) return;
+        qtile = redo_item / Hq;
+        head = redo_item % Hq;
     } else if (SPLIT) {
         split = blockIdx.x % n_split;
         const int rest = blockIdx.x / n_split;
@@ -320,7 +326,12 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
                 }
         }
     }
-    if (!SPLIT && redo && tid == 0) redo[blockIdx.x] = 0;
+    if (!SPLIT && redo) {
+        if (tid == 0) redo[redo_item] = 0;
+        __syncthreads();                 // every wavefront is done with the LDS stages before the next tile refills them
+        redo_item += (int)gridDim.x;
+        goto next_redo_item;
+    }
 }
 
 
@@ -356,6 +367,14 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const bf16_t* q, cons
 // `redo`, and a second launch right behind this one recomputes exactly those (query tile, head) pairs with the
 // running-maximum kernel above, which is total on finite inputs.  With `redo` all zero, as it is for attention
 // inputs of ordinary size, that launch is a few thousand workgroups that read one word and exit.
+//
+// Two wavefronts per SIMD do not help here.  A copy of this kernel with eight wavefronts of 32 query rows (each K /
+// V^T fragment then feeds one MFMA) was built and is exact, but 7 % slower: vector instructions of one wavefront do
+// not run under the MFMAs of the other either (timing-only copies: the exponentials cost 0.20, the multiply-adds
+// 0.13, conversions and row sums 0.12 of the MFMA time, all of it added on top), and with one fragment read per MFMA
+// the LDS, not the softmax, bounds that layout (74 % MFMA-busy with NO softmax arithmetic at all).  Folding the
+// softmax scale into Q (to drop the multiply-add per score) rounds Q to bf16 a second time, which scores of a few
+// hundred make visible (2.5e-2 against 3e-3), so the scale stays in fp32.
 //
 // LDS holds the K tiles of the four stages in its first 64 KiB and the V^T tiles in the second: with
 // the stage number known at compile time (main loop unrolled over the four stages) every fragment
@@ -785,8 +804,8 @@ void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ld
     hipLaunchKernelGGL(attn_fwd64_kernel, dim3((unsigned)(nsel * Hq)), dim3(256), SMEM, s, q, k, vt, ldv, o, (int)N, Hq,
                        Hkv, sc_log2e, nqt, hpx, redo);
     // the (query tile, head) pairs given up above, by the running-maximum kernel with the same 256-row tiles
-    // (8 wavefronts x 32 rows); workgroup b looks at redo[b], b = query tile * Hq + head
-    hipLaunchKernelGGL((attn_fwd_kernel<128, 1, 8, false>), dim3((unsigned)(nqt * Hq)), dim3(512), SMEM_REDO, s, q, k, vt, ldv,
+    // (8 wavefronts x 32 rows); item b = query tile * Hq + head
+    hipLaunchKernelGGL((attn_fwd_kernel<128, 1, 8, false>), dim3((unsigned)std::min(nqt * Hq, 256)), dim3(512), SMEM_REDO, s, q, k, vt, ldv,
                        o, (int)N, Hq, Hkv, sc_log2e, nqt, 0, 0, 1, nullptr, nullptr, nullptr, nullptr, 0, 0, redo);
 }
 

@@ -13,7 +13,7 @@ namespace {
 
 // Every wavefront loads one A and one B fragment (16 bytes per lane each) from `operands` and multiplies them
 // `iters` times into independent accumulators: KIND 0 = 8 accumulators of v_mfma_f32_32x32x16_bf16, KIND 1 = 32
-// of v_mfma_f32_16x16x32_bf16 (both 262 144 flop per wavefront and iteration... x the accumulator count below).
+// of v_mfma_f32_16x16x32_bf16 (262 144 and 524 288 flop per wavefront and iteration).
 template <int NT, int KIND>
 __global__ void __launch_bounds__(NT) mfma_peak_kernel(const uint4* __restrict__ operands, float* sink, int iters) {
     const size_t i = ((size_t)blockIdx.x * NT + threadIdx.x) * 2;
@@ -62,12 +62,23 @@ double launch_mfma_peak(int kind, int waves_per_simd, int iters, const void* ope
     const int nt = 256 * waves_per_simd, blocks = 256 * 4;             // four workgroups per compute unit, in turn
     if (operand_bytes < (size_t)blocks * nt * 32) return 0.0;
     const uint4* op = (const uint4*)operands;
-    if (kind == 0 && nt == 256) hipLaunchKernelGGL((mfma_peak_kernel<256, 0>), dim3(blocks), dim3(256), 0, s, op, sink, iters);
-    if (kind == 0 && nt == 512) hipLaunchKernelGGL((mfma_peak_kernel<512, 0>), dim3(blocks), dim3(512), 0, s, op, sink, iters);
-    if (kind == 1 && nt == 256) hipLaunchKernelGGL((mfma_peak_kernel<256, 1>), dim3(blocks), dim3(256), 0, s, op, sink, iters);
-    if (kind == 1 && nt == 512) hipLaunchKernelGGL((mfma_peak_kernel<512, 1>), dim3(blocks), dim3(512), 0, s, op, sink, iters);
-    // 8 x 32x32x16 = 32 x 16x16x32 = 262 144 multiply-adds = 524 288 flop per wavefront and iteration
-    return (double)blocks * (nt / 64) * (double)iters * 524288.0;
+    // 96 KiB of (unused) dynamic LDS per workgroup: one workgroup per compute unit at a time, so that the number of
+    // wavefronts per SIMD is what the caller asked for
+    constexpr int LDS = 96 * 1024;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)mfma_peak_kernel<256, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        (void)hipFuncSetAttribute((const void*)mfma_peak_kernel<512, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        (void)hipFuncSetAttribute((const void*)mfma_peak_kernel<256, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        (void)hipFuncSetAttribute((const void*)mfma_peak_kernel<512, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        attr_set = true;
+    }
+    if (kind == 0 && nt == 256) hipLaunchKernelGGL((mfma_peak_kernel<256, 0>), dim3(blocks), dim3(256), LDS, s, op, sink, iters);
+    if (kind == 0 && nt == 512) hipLaunchKernelGGL((mfma_peak_kernel<512, 0>), dim3(blocks), dim3(512), LDS, s, op, sink, iters);
+    if (kind == 1 && nt == 256) hipLaunchKernelGGL((mfma_peak_kernel<256, 1>), dim3(blocks), dim3(256), LDS, s, op, sink, iters);
+    if (kind == 1 && nt == 512) hipLaunchKernelGGL((mfma_peak_kernel<512, 1>), dim3(blocks), dim3(512), LDS, s, op, sink, iters);
+    // per wavefront and iteration: 8 x (32 x 32 x 16) = 131 072 multiply-adds, or 32 x (16 x 16 x 32) = 262 144
+    return (double)blocks * (nt / 64) * (double)iters * (kind == 0 ? 262144.0 : 524288.0);
 }
 
 void launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
