@@ -395,6 +395,17 @@ po_status po_op_attention_split(const void* dev_q, const void* dev_k, const void
 po_status po_op_rope(int32_t dtype, void* dev_x, int64_t N, int32_t n_heads, int32_t head_dim,
                      float theta, void* hip_stream);
 
+/* po_op_rope for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same arithmetic and bit-identical results, but the
+ * rotary table lives in a device array inside the library (8 MiB per GPU, held until the process ends) instead
+ * of a buffer allocated and freed per call, and the call does not synchronise: it is asynchronous on
+ * hip_stream.  N * head_dim * 4 bytes of table must fit: N * head_dim <= 2 097 152 (e.g. 16 384 positions of
+ * head_dim 128), else PO_ERR_WORKSPACE_TOO_SMALL and nothing is launched.  The table is rewritten in full by
+ * every call before it is read.  All calls on one GPU share that GPU's array: calls that overlap on one GPU
+ * (different streams, different threads) race; calls on different GPUs do not. */
+po_status po_op_rope_static(int32_t dtype, void* dev_x, int64_t N, int32_t n_heads, int32_t head_dim,
+                            float theta, void* hip_stream);
+
 /* cos/sin tables, fp32 [n, head_dim/2] each, of pos * theta^(-2i/head_dim) for positions
  * 0..n-1 (angles formed in double precision). */
 po_status po_op_rope_table(float* dev_cos, float* dev_sin, int64_t n, int32_t head_dim, float theta,

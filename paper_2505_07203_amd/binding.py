@@ -40,7 +40,7 @@ EXPORTS = [
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
     "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_op_linear_split", "po_sched_push_request", "po_op_attention_split",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
-    "po_sched_size", "po_sched_pick", "po_op_mfma_peak", "po_op_stream_copy",
+    "po_sched_size", "po_sched_pick", "po_op_rope_static", "po_op_mfma_peak", "po_op_stream_copy",
 ]
 
 
@@ -122,6 +122,7 @@ def lib() -> C.CDLL:
     L.po_op_pack_gate_up.argtypes = [i32, vp, vp, vp, i32, i32, vp]
     L.po_op_attention.argtypes = [i32, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
     L.po_op_rope.argtypes = [i32, vp, i64, i32, i32, f32, vp]
+    L.po_op_rope_static.argtypes = [i32, vp, i64, i32, i32, f32, vp]
     L.po_op_mfma_peak.argtypes = [i32, i32, i32, vp, sz, vp, vp, C.POINTER(C.c_double)]
     L.po_op_stream_copy.argtypes = [vp, vp, sz, vp]
     L.po_op_lm_head.argtypes = [i32, vp, vp, vp, i32, i32, vp]
@@ -521,6 +522,13 @@ def po_op_rope(x, theta: float):
     """in place on x [N, H, hd]"""
     N, H, hd = x.shape
     check(lib().po_op_rope(_dt(x), x.data_ptr(), N, H, hd, theta, _stream()))
+    return x
+
+
+def po_op_rope_static(x, theta: float):
+    """in place on x [N, H, hd]; the variant that allocates nothing (asynchronous on the current stream)"""
+    N, H, hd = x.shape
+    check(lib().po_op_rope_static(_dt(x), x.data_ptr(), N, H, hd, theta, _stream()))
     return x
 
 

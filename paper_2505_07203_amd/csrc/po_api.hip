@@ -9,6 +9,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1368,6 +1369,48 @@ po_status po_op_rope(int32_t dtype, void* x, int64_t N, int32_t H, int32_t hd, f
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(tab);
     PO_HIP(e);
+    PO_HIP(hipGetLastError());
+    return PO_OK;
+}
+
+// ---- po_op_rope for callers that cannot allocate: its rotary table sits in a file-scope device array
+// instead of a hipMalloc'd buffer.  Every GPU the library runs on holds its own copy of the array, at its own
+// address, until the process ends; in host code the array's NAME is only a stand-in (not a device address), so
+// the address is looked up once per device with hipGetSymbolAddress and kept, and only that pointer is ever
+// handed to a kernel.
+constexpr size_t PO_STATIC_SCRATCH_BYTES = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char po_static_scratch[PO_STATIC_SCRATCH_BYTES];
+constexpr int PO_MAX_DEVICES = 64;
+static void* g_static_scratch_ptr[PO_MAX_DEVICES];       // per device; null until looked up
+static std::mutex g_static_scratch_mu;
+
+// device address of po_static_scratch on the CURRENT device (looked up on first use there)
+static po_status static_scratch_ptr(void** out) {
+    int dev = -1;
+    PO_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= PO_MAX_DEVICES) return PO_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mu);
+    if (!g_static_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        PO_HIP(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(po_static_scratch)));
+        if (!ptr) return PO_ERR_DEVICE;
+        g_static_scratch_ptr[dev] = ptr;
+    }
+    *out = g_static_scratch_ptr[dev];
+    return PO_OK;
+}
+
+po_status po_op_rope_static(int32_t dtype, void* x, int64_t N, int32_t H, int32_t hd, float theta, void* stream) {
+    if (bad_dtype(dtype) || !x || N <= 0 || H <= 0 || hd <= 0 || hd % 2 || !(theta > 0.f)) return PO_ERR_INVALID_ARG;
+    // cos and sin tables [N, hd/2] of float32 each
+    if ((uint64_t)N * (uint64_t)hd * 4 > PO_STATIC_SCRATCH_BYTES) return PO_ERR_WORKSPACE_TOO_SMALL;
+    void* ptr = nullptr;
+    po_status st = static_scratch_ptr(&ptr);
+    if (st != PO_OK) return st;
+    // the table kernel writes every entry the rotation reads, so nothing of an earlier call's contents is seen
+    float* tab = (float*)ptr;
+    launch_rope_table(tab, tab + (size_t)N * (hd / 2), N, hd, theta, (hipStream_t)stream);
+    launch_rope(dtype, x, (int64_t)H * hd, tab, tab + (size_t)N * (hd / 2), N, H, hd, (hipStream_t)stream);
     PO_HIP(hipGetLastError());
     return PO_OK;
 }
