@@ -27,25 +27,27 @@ PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096
 PEAK_FP8_TFLOPS = 5033.2       # dense fp8 MFMA: twice the bf16 rate
 PEAK_HBM_GBS = 8000.0
 
-def load_traffic(workload, kernel_functions):
+def load_traffic(workload):
     """Measured HBM-side traffic per launch of each kernel class, from the committed summary of two rocprofv3
-    counter runs of this command (FETCH_SIZE, then WRITE_SIZE; see profiles/<...>_pmc_counters.txt, which
-    paper_2505_07203_amd/pmc_summary.py writes).  The summary names the kernel functions it measured; it is used
-    only if those are the functions this library runs today, else every traffic is null.
+    counter runs of this command (FETCH_SIZE, then WRITE_SIZE; profiles/prefill_<workload>_pmc_counters.txt, written
+    by paper_2505_07203_amd/pmc_summary.py).  The summary records a hash of the kernel sources it measured; it is
+    used only if the sources are unchanged, else every traffic is null.
     -> ({class: bytes per launch}, file name) or ({}, None)"""
+    from paper_2505_07203_amd import pmc_summary
     path = os.path.join(ROOT, "profiles", f"prefill_{workload}_pmc_counters.txt")
     if not os.path.exists(path):
         return {}, None
-    out = {}
+    out, sha = {}, None
     with open(path) as f:
         for line in f:
-            if not line.startswith("traffic_bytes_per_launch\t"):
-                continue
-            _, cls, fn, nbytes = line.rstrip("\n").split("\t")[:4]
-            if kernel_functions.get(cls) != fn:
-                return {}, None                       # measured on other kernels than today's: stale
-            out[cls] = float(nbytes)
-    return out, (os.path.relpath(path, ROOT) if out else None)
+            part = line.rstrip("\n").split("\t")
+            if part[0] == "traffic_bytes_per_launch" and len(part) >= 4:
+                out[part[1]] = float(part[3])
+            elif part[0] == "kernel_sources_sha256" and len(part) >= 2:
+                sha = part[1]
+    if not out or sha != pmc_summary.kernel_sources_sha256():
+        return {}, None                               # measured on other kernels than today's: stale
+    return out, os.path.relpath(path, ROOT)
 
 
 def flop_model(cfg, lens, lazy_last_layer=True):
@@ -391,7 +393,7 @@ def main():
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
-        torch.add(src, 1.0, out=dst)          # 2^30 bytes fetched, 2^30 bytes written
+        B.po_op_stream_copy(src, dst)         # 2^30 bytes fetched, 2^30 bytes written
         torch.cuda.synchronize()
         del src, dst
     # ---- pass 1, the metric: K steps with nothing but the path on the stream (no per-launch events)
@@ -432,16 +434,14 @@ def main():
     free_b, total_b = torch.cuda.mem_get_info()
     # algorithmic flops per step of each kernel class (causal half only for attention)
     k_flop = flop_classes(cfg, lens)
-    gk = "gemm_fp8_mfma_kernel" if args.fp8 else "gemm_bf16_mfma16_kernel"
+    gk = "gemm_fp8_mfma_kernel" if args.fp8 else "gemm_bf16_mfma_kernel"
     k_name = {"attention": ("attn_fwd64_kernel" if cfg.head_dim == 128 else "attn_fwd_kernel<64>") +
                            " (causal GQA flash attention, one launch per layer)",
               "qkv": gk + "<3> (QKV projection + RoPE + transposed V)",
               "residual": gk + "<1> (O-projection and MLP down projection + residual)",
               "gate_up": gk + "<2> (MLP gate/up projection + SiLU-multiply)"}
 
-    k_fn = {"attention": "attn_fwd64_kernel" if cfg.head_dim == 128 else "attn_fwd_kernel",
-            "qkv": gk + "<3>", "residual": gk + "<1>", "gate_up": gk + "<2>"}
-    traffic, traffic_file = ({}, None) if (args.layers or args.fp8 or args.packed or args.few_rows) else load_traffic(args.workload, k_fn)
+    traffic, traffic_file = ({}, None) if (args.layers or args.fp8 or args.packed or args.few_rows) else load_traffic(args.workload)
 
     def roof(k):
         launches = k_n[k] / max(split_steps, 1)

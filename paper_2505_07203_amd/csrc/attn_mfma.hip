@@ -374,7 +374,10 @@ next_redo_item:
 // 0.13, conversions and row sums 0.12 of the MFMA time, all of it added on top), and with one fragment read per MFMA
 // the LDS, not the softmax, bounds that layout (74 % MFMA-busy with NO softmax arithmetic at all).  Folding the
 // softmax scale into Q (to drop the multiply-add per score) rounds Q to bf16 a second time, which scores of a few
-// hundred make visible (2.5e-2 against 3e-3), so the scale stays in fp32.
+// hundred make visible (2.5e-2 against 3e-3), so the scale stays in fp32; and with Q scaled before its one rounding
+// (in the projection's epilogue) and the S accumulators started from minus the reference exponent, the multiply-adds
+// do go, but the first MFMA of a block then needs its addend copied into the accumulator registers (the two are
+// tied in this register form), 32 moves for 32 multiply-adds: measured 6 % slower in this kernel's schedule.
 //
 // LDS holds the K tiles of the four stages in its first 64 KiB and the V^T tiles in the second: with
 // the stage number known at compile time (main loop unrolled over the four stages) every fragment

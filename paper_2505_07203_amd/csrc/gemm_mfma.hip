@@ -14,8 +14,9 @@
 //    sit one behind each MFMA.
 //  * K is consumed in slices of 64, so that a row of an operand slice is one whole 128-byte cache line: eight
 //    lanes of a load fetch one line.  Operand slices go straight from global memory into LDS (buffer_load ... lds,
-//    16 bytes per lane, no staging registers; a copy of this kernel that stages them through registers clocks 6 %
-//    higher but keeps the matrix pipe 14 % less busy).  One operand's slice is a 32 KiB unit; LDS (160 KiB) is a
+//    16 bytes per lane, no staging registers; copies of this kernel that stage them through registers, with the
+//    ds_writes early or late in the slice, clock 5 % higher but keep the matrix pipe 9-11 points less busy: vector
+//    memory returns and LDS writes take issue slots that MFMAs of neither wavefront of the SIMD can use).  One operand's slice is a 32 KiB unit; LDS (160 KiB) is a
 //    ring of five units filled in the order A0 W0 A1 W1 ...: two are being multiplied while up to three are in
 //    flight.  These loads are the largest single item of the energy bill (a timing-only copy without them runs
 //    15-18 % faster, one without the LDS fragment reads 7 %); their bytes per flop are fixed by the 256 x 256 tile,

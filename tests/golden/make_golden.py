@@ -49,6 +49,7 @@ CASES = {
     # reduced-cost rungs at full width
     "llama8b_L32_N2048": ("llama8b_32k", None, [2048], False),
     "llama8b_L2_N32768": ("llama8b_32k", 2, [32768], False),
+    "llama8b_L8_N32768": ("llama8b_32k", 8, [32768], False),      # a quarter of the benchmark's depth at its full length
     "llama8b_L1_N131072": ("llama8b_128k", 1, [131072], True),
     "qwen32b_L64_N1024": ("qwen32b_8x16k", None, [1024], False),
     "qwen32b_L2_N16384": ("qwen32b_8x16k", 2, [16384], False),
