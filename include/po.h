@@ -376,10 +376,15 @@ po_status po_op_pack_gate_up(int32_t dtype, const void* dev_wg, const void* dev_
  * round_up(2*Hkv*hd*round_up(N,64), 256) + 4*Hq*ceil(N/256) bytes (a transposed copy of V, then one word
  * per 256-row query tile and head in which the kernel marks tiles whose scores outgrow its fixed reference
  * exponent; those are recomputed with a running maximum, so the result is softmax for every finite input);
- * PO_F32 needs none (NULL). */
+ * PO_F32 needs none (NULL).
+ * q_prescaled (0 | 1; PO_BF16 only): 1 = dev_q holds the queries times log2(e) / sqrt(head_dim), which is how the
+ * full path hands them over (po_op_qkv_rope's q_scale applies the factor in fp32 before Q's one rounding): the
+ * kernel then exponentiates K Q^T as it comes out of the matrix pipe, with no multiply-add per score and no
+ * reference exponent; rows whose probabilities would leave the float range that way (scores beyond about +-60
+ * nats as a whole row) are recomputed with a running maximum, like overflowing ones with q_prescaled = 0. */
 po_status po_op_attention(int32_t dtype, const void* dev_q, const void* dev_k, const void* dev_v,
                           void* dev_o, void* dev_scratch, int64_t N, int32_t n_q_heads,
-                          int32_t n_kv_heads, int32_t head_dim, void* hip_stream);
+                          int32_t n_kv_heads, int32_t head_dim, int32_t q_prescaled, void* hip_stream);
 /* The few-rows form of po_op_attention (bf16 only; see po_set_few_rows_split): rows [q_row0, N) of the causal
  * attention, each query tile's keys divided between workgroups and merged by a second kernel.  dev_scratch_vt as
  * dev_scratch there; dev_scratch_part (part_bytes, 256-byte aligned) takes the fp32 partial results.  Rows below
@@ -423,11 +428,13 @@ po_status po_op_pack_qkv(const void* dev_wq, const void* dev_wk, const void* dev
  * sequence position pos0: [Q|K|V] = A Wqkv^T (+bias), rotary embedding applied to Q and K in
  * fp32 before rounding; q [M, Hq*hd] and k [M, Hkv*hd] are written row-major, V is written
  * transposed into columns pos0..pos0+M-1 of vt [Hkv*hd][ldv] (the layout the attention
- * kernel reads).  dev_bqkv may be NULL. */
+ * kernel reads).  dev_bqkv may be NULL.  q_scale (> 0): factor on the rotated Q values, applied in fp32 before
+ * they are rounded; 1 gives the rotated queries themselves, log2(e) / sqrt(head_dim) what po_op_attention
+ * expects with q_prescaled = 1 (the full path's choice).  K and V are never scaled. */
 po_status po_op_qkv_rope(const void* dev_a, const void* dev_wqkv, const void* dev_bqkv, void* dev_q, void* dev_k,
                          void* dev_vt, int64_t ldv, const float* dev_cos, const float* dev_sin, int64_t pos0,
                          int64_t M, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t K,
-                         void* hip_stream);
+                         float q_scale, void* hip_stream);
 
 /* ---- FP8-dynamic variant of the decoder's linear layers (Section 7.1 names FP8-dynamic
  * checkpoints; the scheme is the public convention: OCP E4M3 codes, one float32 scale per
@@ -460,7 +467,8 @@ po_status po_op_linear_fp8(int32_t epilogue, const void* dev_a_codes, const floa
 po_status po_op_qkv_rope_fp8(const void* dev_a_codes, const float* dev_a_scales, const void* dev_w_codes,
                              const float* dev_w_scales, const void* dev_bqkv, void* dev_q, void* dev_k, void* dev_vt,
                              int64_t ldv, const float* dev_cos, const float* dev_sin, int64_t pos0, int64_t M,
-                             int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t K, void* hip_stream);
+                             int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t K, float q_scale,
+                             void* hip_stream);
 
 /* ---- Micro-peaks of the machine, for the benchmark to report beside the nominal peaks (measurement only; the
  * paper's claim that the workload is compute-bound, Section 2.3, is priced against what the board sustains).

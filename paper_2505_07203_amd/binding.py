@@ -120,7 +120,7 @@ def lib() -> C.CDLL:
     L.po_op_linear_split.argtypes = [vp, vp, vp, vp, vp, sz, i64, i32, i32, vp, C.POINTER(i32)]
     L.po_op_gate_up_silu.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, vp]
     L.po_op_pack_gate_up.argtypes = [i32, vp, vp, vp, i32, i32, vp]
-    L.po_op_attention.argtypes = [i32, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
+    L.po_op_attention.argtypes = [i32, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
     L.po_op_rope.argtypes = [i32, vp, i64, i32, i32, f32, vp]
     L.po_op_rope_static.argtypes = [i32, vp, i64, i32, i32, f32, vp]
     L.po_op_mfma_peak.argtypes = [i32, i32, i32, vp, sz, vp, vp, C.POINTER(C.c_double)]
@@ -128,11 +128,11 @@ def lib() -> C.CDLL:
     L.po_op_lm_head.argtypes = [i32, vp, vp, vp, i32, i32, vp]
     L.po_op_rope_table.argtypes = [vp, vp, i64, i32, f32, vp]
     L.po_op_pack_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
-    L.po_op_qkv_rope.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i32, i32, i32, i32, vp]
+    L.po_op_qkv_rope.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i32, i32, i32, i32, f32, vp]
     L.po_op_quantize_rows.argtypes = [vp, vp, vp, i64, i32, vp]
     L.po_op_rmsnorm_quantize.argtypes = [vp, vp, vp, vp, i64, i32, f32, vp]
     L.po_op_linear_fp8.argtypes = [i32, vp, vp, vp, vp, vp, vp, i64, i32, i32, vp]
-    L.po_op_qkv_rope_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i32, i32, i32, i32, vp]
+    L.po_op_qkv_rope_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i32, i32, i32, i32, f32, vp]
     f64 = C.c_double
     L.po_sched_create.argtypes = [f64, C.POINTER(vp)]
     L.po_sched_destroy.argtypes = [vp]
@@ -454,7 +454,15 @@ def po_op_linear_fp8(a_codes, a_scales, w_codes, w_scales, residual=None, out=No
     return c
 
 
-def po_op_qkv_rope_fp8(a_codes, a_scales, w_codes, w_scales, bqkv, cos, sin, n_q_heads, n_kv_heads, head_dim, pos0=0):
+def attention_q_scale(head_dim: int) -> float:
+    """log2(e) / sqrt(head_dim) as the float32 the library uses: the factor between the rotated queries and what
+    po_op_attention expects with q_prescaled"""
+    import math
+    return float(np.float32(1.4426950408889634 / math.sqrt(head_dim)))
+
+
+def po_op_qkv_rope_fp8(a_codes, a_scales, w_codes, w_scales, bqkv, cos, sin, n_q_heads, n_kv_heads, head_dim, pos0=0,
+                       q_scale: float = 1.0):
     import torch
     M, K = a_codes.shape
     qd, kvd = n_q_heads * head_dim, n_kv_heads * head_dim
@@ -465,7 +473,7 @@ def po_op_qkv_rope_fp8(a_codes, a_scales, w_codes, w_scales, bqkv, cos, sin, n_q
     check(lib().po_op_qkv_rope_fp8(a_codes.data_ptr(), a_scales.data_ptr(), w_codes.data_ptr(), w_scales.data_ptr(),
                                    None if bqkv is None else bqkv.data_ptr(), q.data_ptr(), k.data_ptr(), vt.data_ptr(),
                                    ldv, cos.data_ptr(), sin.data_ptr(), pos0, M, n_q_heads, n_kv_heads, head_dim, K,
-                                   _stream()))
+                                   q_scale, _stream()))
     return q, k, vt
 
 
@@ -488,8 +496,9 @@ def po_op_gate_up_silu(a, wgu):
     return h
 
 
-def po_op_attention(q, k, v, out=None):
-    """q [N,Hq,hd], k/v [N,Hkv,hd] (rotated) -> o [N,Hq,hd]; out may be q itself."""
+def po_op_attention(q, k, v, out=None, q_prescaled: bool = False):
+    """q [N,Hq,hd], k/v [N,Hkv,hd] (rotated) -> o [N,Hq,hd]; out may be q itself.  q_prescaled: q holds the queries
+    times attention_q_scale(hd)."""
     import torch
     N, Hq, hd = q.shape
     Hkv = k.shape[1]
@@ -499,7 +508,8 @@ def po_op_attention(q, k, v, out=None):
         vt_bytes = (2 * Hkv * hd * ((N + 63) // 64 * 64) + 255) // 256 * 256
         scratch = torch.empty(vt_bytes + 4 * Hq * ((N + 255) // 256), dtype=torch.uint8, device=q.device)
     check(lib().po_op_attention(_dt(q), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
-                                None if scratch is None else scratch.data_ptr(), N, Hq, Hkv, hd, _stream()))
+                                None if scratch is None else scratch.data_ptr(), N, Hq, Hkv, hd, 1 if q_prescaled else 0,
+                                _stream()))
     return o
 
 
@@ -573,7 +583,7 @@ def po_op_pack_qkv(wq, wk, wv, n_q_heads: int, n_kv_heads: int, head_dim: int, b
 
 
 def po_op_qkv_rope(a, wqkv, bqkv, cos, sin, n_q_heads: int, n_kv_heads: int, head_dim: int, pos0: int = 0,
-                   vt=None):
+                   vt=None, q_scale: float = 1.0):
     """-> q [M, Hq*hd], k [M, Hkv*hd] (rotated), vt [Hkv*hd, ldv] with columns pos0..pos0+M-1 written"""
     import torch
     M, K = a.shape
@@ -583,7 +593,7 @@ def po_op_qkv_rope(a, wqkv, bqkv, cos, sin, n_q_heads: int, n_kv_heads: int, hea
         vt = torch.zeros((n_kv_heads * head_dim, (pos0 + M + 63) // 64 * 64), dtype=a.dtype, device=a.device)
     check(lib().po_op_qkv_rope(a.data_ptr(), wqkv.data_ptr(), None if bqkv is None else bqkv.data_ptr(),
                                q.data_ptr(), k.data_ptr(), vt.data_ptr(), vt.shape[1], cos.data_ptr(),
-                               sin.data_ptr(), pos0, M, n_q_heads, n_kv_heads, head_dim, K, _stream()))
+                               sin.data_ptr(), pos0, M, n_q_heads, n_kv_heads, head_dim, K, q_scale, _stream()))
     return q, k, vt
 
 

@@ -401,6 +401,13 @@ __device__ __forceinline__ float half_swap_sum(float x) {
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
+// PRE: the caller has multiplied Q by log2(e) / sqrt(hd) before rounding it to bf16 (the QKV projection's epilogue
+// does, in fp32: Q is rounded once, as before).  K Q^T then IS the exponent's argument, and no reference exponent is
+// subtracted at all: p = exp2(s) as it comes out of the matrix pipe, no multiply-add per score.  fp32 and bf16 hold
+// 2^-126 .. 2^127, attention scores of ordinary size are within +-40, and a row whose sum of p leaves 2^-60 .. 2^100
+// (scores far above or far below that) gives up and is recomputed by the running-maximum kernel, like an overflow
+// in the other form.
+template <bool PRE>
 __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const bf16_t* __restrict__ k,
                                                          const bf16_t* __restrict__ vt, int64_t ldv, bf16_t* o, int N,
                                                          int Hq, int Hkv, float sc_log2e, int nqt, int hpx, int* redo) {
@@ -542,9 +549,11 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
             }
         }
         if (31 > qw) { PO_MASK(sa, 0, 0); PO_MASK(sa, 0, 1); }
-        float m0, m1;
-        PO_BLOCKMAX(sa, 0, m0);
-        PO_BLOCKMAX(sa, 1, m1);
+        float m0 = 0.f, m1 = 0.f;
+        if (!PRE) {
+            PO_BLOCKMAX(sa, 0, m0);
+            PO_BLOCKMAX(sa, 1, m1);
+        }
         mb[0] = m0 * sc_log2e;
         mb[1] = m1 * sc_log2e;
     }
@@ -583,8 +592,8 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
     {                                                                                              \
         const int e_ = PO_JOB_E((n_) & 15);                                                        \
         const float mb_ = (e_ >> 4) ? mb1_ : mb0_;                                                 \
-        ea_[(n_) & 15][0] = fmaf(SC[e_ >> 4][e_ & 15], sc_log2e, -mb_);                            \
-        ea_[(n_) & 15][1] = fmaf(SC[e_ >> 4][(e_ & 15) + 1], sc_log2e, -mb_);                      \
+        ea_[(n_) & 15][0] = PRE ? SC[e_ >> 4][e_ & 15] : fmaf(SC[e_ >> 4][e_ & 15], sc_log2e, -mb_);           \
+        ea_[(n_) & 15][1] = PRE ? SC[e_ >> 4][(e_ & 15) + 1] : fmaf(SC[e_ >> 4][(e_ & 15) + 1], sc_log2e, -mb_); \
     }
 #define PO_ITER(i_, SC, SN, KST_, KA_, VST_, VA_, NKST_, NKA_, BAR_, DMA_T_, DMA_S_, DMA_J0_, MASK_)            \
     {                                                                                                           \
@@ -657,7 +666,9 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
             }                                                                                                   \
         }                                                                                                       \
         /* ---- renormalise when a row sum has grown past 2^40 (rare; see the note on the reference) */         \
-        if (__any(!(lrow[0] <= 0x1p40f) || !(lrow[1] <= 0x1p40f))) {                                            \
+        if (PRE) {                                                                                              \
+            if (__any(!(lrow[0] < 0x1p100f) || !(lrow[1] < 0x1p100f))) gave_up = 1;                             \
+        } else if (__any(!(lrow[0] <= 0x1p40f) || !(lrow[1] <= 0x1p40f))) {                                     \
             const float t0_ = half_swap_sum(lrow[0]), t1_ = half_swap_sum(lrow[1]);                             \
             if (__any(!(t0_ < 0x1p100f) || !(t1_ < 0x1p100f))) gave_up = 1;                                     \
             int e0_ = ilogbf(t0_), e1_ = ilogbf(t1_);                                                           \
@@ -729,6 +740,10 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
 #undef PO_MFMA_ACC
 #undef PO_MFMA_DRAIN
 
+    if (PRE && nkb_w > 0) {
+        // a row sum this small means the row's scores sit so far below zero that terms were flushed away
+        if (__any(!(half_swap_sum(lrow[0]) >= 0x1p-60f) || !(half_swap_sum(lrow[1]) >= 0x1p-60f))) gave_up = 1;
+    }
     // ---- did any wavefront give up?  (every wavefront has met the same number of barriers and arrives here)
     if (gave_up && lane == 0) *(volatile int*)lds_gave_up = 1;
     __syncthreads();
@@ -789,23 +804,28 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
 }
 
 void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
-                  int Hkv, int64_t q_row0, int* redo, hipStream_t s) {
+                  int Hkv, int64_t q_row0, int* redo, bool q_prescaled, hipStream_t s) {
     constexpr int SMEM = 2 * A64_NSTAGE * A64_TILE + 16;             // the ring and the give-up word
     constexpr int SMEM_REDO = 2 * 2 * BNK * 128 * 2;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)attn_fwd64_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+        (void)hipFuncSetAttribute((const void*)attn_fwd64_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+        (void)hipFuncSetAttribute((const void*)attn_fwd64_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
         (void)hipFuncSetAttribute((const void*)attn_fwd_kernel<128, 1, 8, false>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_REDO);
         attr_set = true;
     }
     const int nqt = (int)((N + 255) / 256);
     const int hpx = (Hq % 8 == 0) ? Hq / 8 : 0;
-    const float sc_log2e = (float)(1.4426950408889634 / sqrt(128.0));
+    const float sc_log2e = q_prescaled ? 1.0f : attention_q_scale(128);
     // workgroups enumerate query tiles from the last one down: fewer of them = only the last tiles
     const int nsel = nqt - (int)((q_row0 > 0 && q_row0 < N) ? q_row0 / 256 : 0);
-    hipLaunchKernelGGL(attn_fwd64_kernel, dim3((unsigned)(nsel * Hq)), dim3(256), SMEM, s, q, k, vt, ldv, o, (int)N, Hq,
-                       Hkv, sc_log2e, nqt, hpx, redo);
+    if (q_prescaled)
+        hipLaunchKernelGGL(attn_fwd64_kernel<true>, dim3((unsigned)(nsel * Hq)), dim3(256), SMEM, s, q, k, vt, ldv, o, (int)N,
+                           Hq, Hkv, sc_log2e, nqt, hpx, redo);
+    else
+        hipLaunchKernelGGL(attn_fwd64_kernel<false>, dim3((unsigned)(nsel * Hq)), dim3(256), SMEM, s, q, k, vt, ldv, o, (int)N,
+                           Hq, Hkv, sc_log2e, nqt, hpx, redo);
     // the (query tile, head) pairs given up above, by the running-maximum kernel with the same 256-row tiles
     // (8 wavefronts x 32 rows); item b = query tile * Hq + head
     hipLaunchKernelGGL((attn_fwd_kernel<128, 1, 8, false>), dim3((unsigned)std::min(nqt * Hq, 256)), dim3(512), SMEM_REDO, s, q, k, vt, ldv,
@@ -814,7 +834,7 @@ void launch_fwd64(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ld
 
 template <int HD, int QT, int NW>
 void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
-              int Hkv, int64_t q_row0, hipStream_t s) {
+              int Hkv, int64_t q_row0, bool q_prescaled, hipStream_t s) {
     constexpr int BMQ = NW * QT * 32;
     constexpr int SMEM = 2 * 2 * BNK * HD * 2;
     static bool attr_set = false;
@@ -825,7 +845,7 @@ void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, b
     }
     const int nqt = (int)((N + BMQ - 1) / BMQ);
     const int hpx = (Hq % 8 == 0) ? Hq / 8 : 0;
-    const float sc_log2e = (float)(1.4426950408889634 / sqrt((double)HD));
+    const float sc_log2e = q_prescaled ? 1.0f : attention_q_scale(HD);
     // workgroups enumerate query tiles from the last one down: fewer of them = only the last tiles
     const int nsel = nqt - (int)((q_row0 > 0 && q_row0 < N) ? q_row0 / BMQ : 0);
     hipLaunchKernelGGL((attn_fwd_kernel<HD, QT, NW, false>), dim3((unsigned)(nsel * Hq)), dim3(NW * 64), SMEM, s, q, k, vt,
@@ -835,7 +855,7 @@ void launch_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, b
 template <int HD>
 int launch_split_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N, int Hq,
                    int Hkv, int64_t q_row0, float* scratch, size_t scratch_bytes, bool launch, const bf16_t* k2,
-                   const bf16_t* vt2, int64_t ldv2, int64_t n2, hipStream_t s) {
+                   const bf16_t* vt2, int64_t ldv2, int64_t n2, bool q_prescaled, hipStream_t s) {
     constexpr int NW = 8, BMQ = NW * 32;
     constexpr int SMEM = 2 * 2 * BNK * HD * 2;
     const int64_t nq = N - q_row0;
@@ -857,7 +877,7 @@ int launch_split_t(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t l
     }
     float* opart = scratch;
     float* mlpart = scratch + o_bytes / sizeof(float);
-    const float sc_log2e = (float)(1.4426950408889634 / sqrt((double)HD));
+    const float sc_log2e = q_prescaled ? 1.0f : attention_q_scale(HD);
     hipLaunchKernelGGL((attn_fwd_kernel<HD, 1, NW, true>), dim3((unsigned)(nqt * Hq * n_split)), dim3(NW * 64), SMEM, s, q,
                        k, vt, ldv, o, (int)N, Hq, Hkv, sc_log2e, nqt, 0, (int)q_row0, n_split, opart, mlpart,
                        k2 ? k2 : k, vt2 ? vt2 : vt, vt2 ? ldv2 : ldv, (k2 && vt2) ? (int)(n2 / BNK) : 0, nullptr);
@@ -876,21 +896,23 @@ bool attention_mfma_supported(int Hq, int Hkv, int hd) {
 int launch_attention_mfma_split(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N,
                                 int Hq, int Hkv, int hd, int64_t q_row0, float* scratch, size_t scratch_bytes,
                                 bool launch, const bf16_t* k2, const bf16_t* vt2, int64_t ldv2, int64_t n2,
-                                hipStream_t s) {
+                                bool q_prescaled, hipStream_t s) {
     if (hd == 128)
-        return launch_split_t<128>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, k2, vt2, ldv2, n2, s);
+        return launch_split_t<128>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, k2, vt2, ldv2, n2,
+                                   q_prescaled, s);
     if (hd == 64)
-        return launch_split_t<64>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, k2, vt2, ldv2, n2, s);
+        return launch_split_t<64>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, scratch, scratch_bytes, launch, k2, vt2, ldv2, n2,
+                                  q_prescaled, s);
     return 0;
 }
 
 size_t attention_mfma_redo_bytes(int64_t N, int Hq) { return (size_t)((N + 255) / 256) * (size_t)Hq * sizeof(int); }
 
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o, int64_t N,
-                           int Hq, int Hkv, int hd, int64_t q_row0, int* redo, hipStream_t s) {
+                           int Hq, int Hkv, int hd, int64_t q_row0, int* redo, bool q_prescaled, hipStream_t s) {
     if (N <= 0) return;
-    if (hd == 128) launch_fwd64(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, redo, s);
-    else if (hd == 64) launch_t<64, 1, 8>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, s);
+    if (hd == 128) launch_fwd64(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, redo, q_prescaled, s);
+    else if (hd == 64) launch_t<64, 1, 8>(q, k, vt, ldv, o, N, Hq, Hkv, q_row0, q_prescaled, s);
 }
 
 }  // namespace po

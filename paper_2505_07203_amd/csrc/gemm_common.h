@@ -32,6 +32,8 @@ struct GemmParams {
     int qd, kvd, hd;     // EPI_QKV_ROPE: segment widths and head size
     const float* sa;     // FP8 kernel: scale per token row [M] and per output feature [N]
     const float* sw;
+    float q_scale;       // EPI_QKV_ROPE: factor on the rotated Q values before they are rounded (1, or the softmax
+                         // scale in log2 units when the attention kernel expects Q scaled; K and V are never scaled)
 };
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
@@ -63,6 +65,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmParams& p, int row, int
             // Q or K patch: sub-tile 0 holds rotary index i, sub-tile 1 holds i + hd/2 (the
             // weight rows were packed that way), so a pair sits in one lane, same register.
             const bool is_q = cb < p.qd;
+            const float qs = is_q ? p.q_scale : 1.0f;
             const int c = is_q ? cb : cb - p.qd;
             const int head = c / p.hd;
             const int patch = (c - head * p.hd) >> 6;
@@ -81,8 +84,8 @@ __device__ __forceinline__ void epilogue_patch(const GemmParams& p, int row, int
                 for (int e = 0; e < 4; ++e) {
                     float a = c0[4 * g4 + e], b = c1[4 * g4 + e];
                     if (bp) { a += bf2f(bp[8 * g4 + e]); b += bf2f(bp[32 + 8 * g4 + e]); }
-                    lo[e] = a * cv[e] - b * sv[e];
-                    hi[e] = b * cv[e] + a * sv[e];
+                    lo[e] = (a * cv[e] - b * sv[e]) * qs;
+                    hi[e] = (b * cv[e] + a * sv[e]) * qs;
                 }
                 *(uint2*)(drow + 8 * g4) = pack4(lo[0], lo[1], lo[2], lo[3]);
                 *(uint2*)(drow + half + 8 * g4) = pack4(hi[0], hi[1], hi[2], hi[3]);
@@ -346,6 +349,7 @@ __device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4
         const int cb = col_base;
         if (cb < p.qd + p.kvd) {
             const bool is_q = cb < p.qd;
+            const float qs = is_q ? p.q_scale : 1.0f;
             const int c = is_q ? cb : cb - p.qd;
             const int head = c / p.hd;
             const int patch = (c - head * p.hd) >> 6;
@@ -366,8 +370,8 @@ __device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4
                     for (int e = 0; e < 4; ++e) {
                         float a = acc[u][t][e], b = acc[u][t + 2][e];
                         if (p.bias) { a += bf2f(p.bias[cb + t * 16 + 4 * l4 + e]); b += bf2f(p.bias[cb + 32 + t * 16 + 4 * l4 + e]); }
-                        lo[e] = a * cv[e] - b * sv[e];
-                        hi[e] = b * cv[e] + a * sv[e];
+                        lo[e] = (a * cv[e] - b * sv[e]) * qs;
+                        hi[e] = (b * cv[e] + a * sv[e]) * qs;
                     }
                     *(uint2*)(drow + i0) = pack4(lo[0], lo[1], lo[2], lo[3]);
                     *(uint2*)(drow + half + i0) = pack4(hi[0], hi[1], hi[2], hi[3]);

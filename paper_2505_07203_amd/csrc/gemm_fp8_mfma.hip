@@ -230,6 +230,7 @@ GemmParams base_params(const unsigned char* A, int64_t lda, const float* sa, con
     memset(&p, 0, sizeof(p));
     p.A = (const bf16_t*)A; p.W = (const bf16_t*)W; p.lda = lda; p.ldw = ldw;      // byte pointers, byte pitches
     p.sa = sa; p.sw = sw;
+    p.q_scale = 1.0f;
     p.M = (int)M; p.N = N; p.K = K;
     p.mt = (int)((M + BM - 1) / BM);
     p.nt = (N + BN - 1) / BN;
@@ -277,8 +278,8 @@ int launch_gemm_fp8_splitk(int epi, const unsigned char* A, int64_t lda, const f
 int launch_gemm_fp8_qkv_rope_splitk(const unsigned char* A, int64_t lda, const float* sa, const unsigned char* Wqkv,
                                     int64_t ldw, const float* sw, const bf16_t* bias, bf16_t* Q, bf16_t* Kd, bf16_t* Vt,
                                     int64_t ldv, const float* rope_cos, const float* rope_sin, int64_t pos0,
-                                    const int32_t* row_pos, int64_t M, int qd, int kvd, int hd, int K, float* part,
-                                    size_t part_bytes, hipStream_t s) {
+                                    const int32_t* row_pos, int64_t M, int qd, int kvd, int hd, int K, float q_scale,
+                                    float* part, size_t part_bytes, hipStream_t s) {
     const int N = qd + 2 * kvd;
     if (M <= 0 || !gemm_fp8_supported(N, K) || (qd & 63) || (kvd & 63) || (hd & 63)) return 0;
     const int splits = pick_splits(M, N, K / BKB, part_bytes);
@@ -291,7 +292,7 @@ int launch_gemm_fp8_qkv_rope_splitk(const unsigned char* A, int64_t lda, const f
     GemmParams r = base_params(A, lda, sa, Wqkv, ldw, sw, M, N, K);
     r.bias = bias; r.dst = Q; r.dst_k = Kd; r.dst_vt = Vt; r.ldv = ldv;
     r.rope_cos = rope_cos; r.rope_sin = rope_sin; r.pos0 = pos0; r.row_pos = row_pos;
-    r.qd = qd; r.kvd = kvd; r.hd = hd;
+    r.qd = qd; r.kvd = kvd; r.hd = hd; r.q_scale = q_scale;
     launch_splitk_reduce_qkv(part, splits, r, s);
     return splits;
 }
@@ -299,9 +300,10 @@ int launch_gemm_fp8_qkv_rope_splitk(const unsigned char* A, int64_t lda, const f
 void launch_gemm_fp8_qkv_rope(const unsigned char* A, int64_t lda, const float* sa, const unsigned char* Wqkv, int64_t ldw,
                               const float* sw, const bf16_t* bias, bf16_t* Q, bf16_t* Kd, bf16_t* Vt, int64_t ldv,
                               const float* rope_cos, const float* rope_sin, int64_t pos0, const int32_t* row_pos,
-                              int64_t M, int qd, int kvd, int hd, int K, hipStream_t s) {
+                              int64_t M, int qd, int kvd, int hd, int K, float q_scale, hipStream_t s) {
     if (M <= 0) return;
     GemmParams p = base_params(A, lda, sa, Wqkv, ldw, sw, M, qd + 2 * kvd, K);
+    p.q_scale = q_scale;
     p.bias = bias; p.dst = Q; p.dst_k = Kd; p.dst_vt = Vt; p.ldv = ldv;
     p.rope_cos = rope_cos; p.rope_sin = rope_sin; p.pos0 = pos0; p.row_pos = row_pos;
     p.qd = qd; p.kvd = kvd; p.hd = hd;

@@ -240,8 +240,9 @@ __global__ void __launch_bounds__(256) splitk_reduce_qkv_kernel(const float* __r
         const int64_t pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
         const float cs = p.rope_cos[pos * half + i0], sn = p.rope_sin[pos * half + i0];
         bf16_t* drow = (is_q ? p.dst + (int64_t)row * p.qd : p.dst_k + (int64_t)row * p.kvd) + head * p.hd + i0;
-        drow[0] = f2bf(a * cs - b * sn);
-        drow[half] = f2bf(b * cs + a * sn);
+        const float qs = is_q ? p.q_scale : 1.0f;
+        drow[0] = f2bf((a * cs - b * sn) * qs);
+        drow[half] = f2bf((b * cs + a * sn) * qs);
     } else {
         const int f = cb - p.qd - p.kvd + j;
         bf16_t* dcol = p.dst_vt + p.pos0 + row;
@@ -285,6 +286,7 @@ GemmParams base_params(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ld
     memset(&p, 0, sizeof(p));
     p.A = A; p.W = W; p.lda = lda; p.ldw = ldw;
     p.M = (int)M; p.N = N; p.K = K;
+    p.q_scale = 1.0f;
     p.mt = (int)((M + BM - 1) / BM);
     p.nt = (N + BN - 1) / BN;
     return p;
@@ -342,7 +344,7 @@ void launch_splitk_reduce_qkv(const float* part, int splits, const GemmParams& r
 int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
                                 bf16_t* Q, bf16_t* Kd, bf16_t* Vt, int64_t ldv, const float* rope_cos,
                                 const float* rope_sin, int64_t pos0, const int32_t* row_pos, int64_t M, int qd, int kvd,
-                                int hd, int K, float* part, size_t part_bytes, bool launch, hipStream_t s) {
+                                int hd, int K, float q_scale, float* part, size_t part_bytes, bool launch, hipStream_t s) {
     const int N = qd + 2 * kvd;
     if (M <= 0 || !gemm_mfma_supported(N, K) || (qd & 63) || (kvd & 63) || (hd & 63)) return 0;
     const int splits = pick_splits(M, N, K / BK, part_bytes);
@@ -356,7 +358,7 @@ int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv
     GemmParams r = base_params(A, lda, Wqkv, ldw, M, N, K);
     r.bias = bias; r.dst = Q; r.dst_k = Kd; r.dst_vt = Vt; r.ldv = ldv;
     r.rope_cos = rope_cos; r.rope_sin = rope_sin; r.pos0 = pos0; r.row_pos = row_pos;
-    r.qd = qd; r.kvd = kvd; r.hd = hd;
+    r.qd = qd; r.kvd = kvd; r.hd = hd; r.q_scale = q_scale;
     launch_splitk_reduce_qkv(part, splits, r, s);
     return splits;
 }
@@ -395,9 +397,10 @@ int launch_gemm_mfma_splitk_residual(const bf16_t* A, int64_t lda, const bf16_t*
 void launch_gemm_qkv_rope(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
                           bf16_t* Q, bf16_t* Kd, bf16_t* Vt, int64_t ldv, const float* rope_cos,
                           const float* rope_sin, int64_t pos0, const int32_t* row_pos, int64_t M, int qd, int kvd,
-                          int hd, int K, hipStream_t s) {
+                          int hd, int K, float q_scale, hipStream_t s) {
     if (M <= 0) return;
     GemmParams p = base_params(A, lda, Wqkv, ldw, M, qd + 2 * kvd, K);
+    p.q_scale = q_scale;
     p.bias = bias; p.dst = Q; p.dst_k = Kd; p.dst_vt = Vt; p.ldv = ldv;
     p.rope_cos = rope_cos; p.rope_sin = rope_sin; p.pos0 = pos0; p.row_pos = row_pos;
     p.qd = qd; p.kvd = kvd; p.hd = hd;

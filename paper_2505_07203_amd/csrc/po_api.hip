@@ -305,6 +305,9 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
     const int C = dt == PO_BF16 ? (int)pick_chunk_rows(L.chunk, {{d, qd}, {2 * (int64_t)F, d}, {d, F}}) : L.chunk;
     const bool packed = segs.size() > 1;
     const int64_t n_seg = (int64_t)segs.size();
+    // bf16 path: the QKV epilogue hands the attention kernels Q times the softmax scale (in log2 units), applied in
+    // fp32 before Q's one rounding, so that K Q^T is the exponent's argument as it comes out of the matrix pipe
+    const float q_scale = attention_q_scale(hd);
 
     c->ev_used = 0;
     PO_HIP(hipMemcpyAsync(d_tok, tokens, (size_t)total * 4, hipMemcpyHostToDevice, s));
@@ -353,7 +356,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
             const int64_t q0 = (c->lazy_last_layer && l == m.n_layers - 1) ? total - 1 : p_reuse;
             if (launch_attention_mfma_split((const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)(ws + L.Vt), L.ldv, (bf16_t*)Q, total,
                                             m.n_q_heads, m.n_kv_heads, hd, q0, (float*)H, (size_t)L.chunk * F * esz, false,
-                                            nullptr, nullptr, 0, 0, s) > 1)
+                                            nullptr, nullptr, 0, 0, true, s) > 1)
                 p_direct = p_reuse / 64 * 64;
         }
         if (p_reuse > p_direct) {
@@ -383,12 +386,12 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                     launch_gemm_fp8_qkv_rope_splitk(Xn, d, sx, wqkv, d, (const float*)(c->w + o.s_wqkv), (const bf16_t*)bqkv,
                                                     (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
                                                     (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d,
-                                                    (float*)(H + h_used), h_bytes - h_used, s) > 1)
+                                                    q_scale, (float*)(H + h_used), h_bytes - h_used, s) > 1)
                     ++n_split_launches;
                 else
                     launch_gemm_fp8_qkv_rope(Xn, d, sx, wqkv, d, (const float*)(c->w + o.s_wqkv), (const bf16_t*)bqkv,
                                              (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
-                                             (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, s);
+                                             (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, q_scale, s);
             } else if (dt == PO_BF16) {
                 // one GEMM: RoPE applied to Q and K in the epilogue, V written as V^T (few rows: split over K,
                 // partials in the chunk buffer H behind the norm output if that sits there)
@@ -398,12 +401,12 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                     launch_gemm_qkv_rope_splitk((const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, (const bf16_t*)bqkv,
                                                   (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
                                                   (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d,
-                                                (float*)(H + h_used), h_bytes - h_used, true, s) > 1)
+                                                q_scale, (float*)(H + h_used), h_bytes - h_used, true, s) > 1)
                     ++n_split_launches;
                 else
                     launch_gemm_qkv_rope((const bf16_t*)Xn, d, (const bf16_t*)wqkv, d, (const bf16_t*)bqkv,
                                          (bf16_t*)(Q + (size_t)c0 * qd * esz), (bf16_t*)(K + (size_t)c0 * kvd * esz),
-                                         (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, s);
+                                         (bf16_t*)(ws + L.Vt), L.ldv, rc, rs, c0, d_row_pos, rows, qd, kvd, hd, d, q_scale, s);
             } else {
                 launch_gemm_basic(dt, Xn, d, wqkv, d, Q + (size_t)c0 * qd * esz, qd, bqkv, nullptr, 0, rows, qd, d, s);
                 launch_gemm_basic(dt, Xn, d, wqkv + (size_t)qd * d * esz, d, K + (size_t)c0 * kvd * esz, kvd,
@@ -455,12 +458,12 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                                                 m.n_q_heads, m.n_kv_heads, hd, q_row0, (float*)H,
                                                 (size_t)L.chunk * F * esz, true, p_direct ? (const bf16_t*)kc_l : nullptr,
                                                 p_direct ? (const bf16_t*)(kc_l + c->kv_v_off) : nullptr, c->kv_ldv, p_direct,
-                                                s) > 1)
+                                                true, s) > 1)
                     ++n_split_launches;
                 else
                     launch_attention_mfma((const bf16_t*)Qg, (const bf16_t*)(K + (size_t)g.start * kvd * esz),
                                           (const bf16_t*)(ws + L.Vt) + g.start, L.ldv, (bf16_t*)Qg, g.len, m.n_q_heads,
-                                          m.n_kv_heads, hd, q_row0, attn_redo, s);
+                                          m.n_kv_heads, hd, q_row0, attn_redo, true, s);
             } else {
                 launch_attention_basic(dt, Qg, K + (size_t)g.start * kvd * esz, V + (size_t)g.start * kvd * esz, Qg,
                                        g.len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
@@ -1320,8 +1323,9 @@ po_status po_op_pack_gate_up(int32_t dtype, const void* wg, const void* wu, void
 }
 
 po_status po_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* o, void* scratch,
-                          int64_t N, int32_t Hq, int32_t Hkv, int32_t hd, void* stream) {
+                          int64_t N, int32_t Hq, int32_t Hkv, int32_t hd, int32_t q_prescaled, void* stream) {
     if (bad_dtype(dtype) || !q || !k || !v || !o || N <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return PO_ERR_INVALID_ARG;
+    if ((q_prescaled != 0 && q_prescaled != 1) || (q_prescaled && dtype != PO_BF16)) return PO_ERR_INVALID_ARG;
     if (N > (int64_t)1 << 24) return PO_ERR_TOO_LONG;
     if (dtype == PO_BF16) {
         if (!attention_mfma_supported(Hq, Hkv, hd)) return PO_ERR_BAD_CONFIG;
@@ -1333,7 +1337,7 @@ po_status po_op_attention(int32_t dtype, const void* q, const void* k, const voi
         launch_fill_zero32(redo, attention_mfma_redo_bytes(N, Hq) / 4, (hipStream_t)stream);
         launch_v_transpose((const bf16_t*)v, (bf16_t*)scratch, N, Hkv * hd, ldv, (hipStream_t)stream);
         launch_attention_mfma((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)scratch, ldv, (bf16_t*)o, N, Hq, Hkv,
-                              hd, 0, redo, (hipStream_t)stream);
+                              hd, 0, redo, q_prescaled != 0, (hipStream_t)stream);
     } else {
         if (hd != 32 && hd != 64 && hd != 128) return PO_ERR_BAD_CONFIG;
         launch_attention_basic(dtype, q, k, v, o, N, Hq, Hkv, hd, 0, (hipStream_t)stream);
@@ -1354,7 +1358,7 @@ po_status po_op_attention_split(const void* q, const void* k, const void* v, voi
     launch_v_transpose((const bf16_t*)v, (bf16_t*)scratch_vt, N, Hkv * hd, ldv, (hipStream_t)stream);
     *splits_used = launch_attention_mfma_split((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)scratch_vt, ldv, (bf16_t*)o, N,
                                                Hq, Hkv, hd, q_row0, (float*)scratch_part, part_bytes, true, nullptr, nullptr, 0,
-                                               0, (hipStream_t)stream);
+                                               0, false, (hipStream_t)stream);
     PO_HIP(hipGetLastError());
     return PO_OK;
 }
@@ -1450,13 +1454,15 @@ po_status po_op_pack_qkv(const void* wq, const void* wk, const void* wv, void* w
 
 po_status po_op_qkv_rope(const void* a, const void* wqkv, const void* bqkv, void* q, void* k, void* vt, int64_t ldv,
                          const float* cos_t, const float* sin_t, int64_t pos0, int64_t M, int32_t Hq, int32_t Hkv,
-                         int32_t hd, int32_t K, void* stream) {
-    if (!a || !wqkv || !q || !k || !vt || !cos_t || !sin_t || M <= 0 || pos0 < 0 || Hq <= 0 || Hkv <= 0 || K <= 0)
+                         int32_t hd, int32_t K, float q_scale, void* stream) {
+    if (!a || !wqkv || !q || !k || !vt || !cos_t || !sin_t || M <= 0 || pos0 < 0 || Hq <= 0 || Hkv <= 0 || K <= 0 ||
+        !(q_scale > 0.f))
         return PO_ERR_INVALID_ARG;
     if ((hd != 64 && hd != 128) || !gemm_mfma_supported((Hq + 2 * Hkv) * hd, K)) return PO_ERR_BAD_CONFIG;
     if (ldv < pos0 + M || ldv % 8) return PO_ERR_INVALID_ARG;
     launch_gemm_qkv_rope((const bf16_t*)a, K, (const bf16_t*)wqkv, K, (const bf16_t*)bqkv, (bf16_t*)q, (bf16_t*)k,
-                         (bf16_t*)vt, ldv, cos_t, sin_t, pos0, nullptr, M, Hq * hd, Hkv * hd, hd, K, (hipStream_t)stream);
+                         (bf16_t*)vt, ldv, cos_t, sin_t, pos0, nullptr, M, Hq * hd, Hkv * hd, hd, K, q_scale,
+                         (hipStream_t)stream);
     PO_HIP(hipGetLastError());
     return PO_OK;
 }
@@ -1497,15 +1503,15 @@ po_status po_op_linear_fp8(int32_t epilogue, const void* a_codes, const float* a
 po_status po_op_qkv_rope_fp8(const void* a_codes, const float* a_scales, const void* w_codes, const float* w_scales,
                              const void* bqkv, void* q, void* k, void* vt, int64_t ldv, const float* cos_t,
                              const float* sin_t, int64_t pos0, int64_t M, int32_t Hq, int32_t Hkv, int32_t hd, int32_t K,
-                             void* stream) {
+                             float q_scale, void* stream) {
     if (!a_codes || !a_scales || !w_codes || !w_scales || !q || !k || !vt || !cos_t || !sin_t || M <= 0 || pos0 < 0 ||
-        Hq <= 0 || Hkv <= 0 || K <= 0)
+        Hq <= 0 || Hkv <= 0 || K <= 0 || !(q_scale > 0.f))
         return PO_ERR_INVALID_ARG;
     if ((hd != 64 && hd != 128) || !gemm_fp8_supported((Hq + 2 * Hkv) * hd, K)) return PO_ERR_BAD_CONFIG;
     if (ldv < pos0 + M || ldv % 8) return PO_ERR_INVALID_ARG;
     launch_gemm_fp8_qkv_rope((const unsigned char*)a_codes, K, a_scales, (const unsigned char*)w_codes, K, w_scales,
                              (const bf16_t*)bqkv, (bf16_t*)q, (bf16_t*)k, (bf16_t*)vt, ldv, cos_t, sin_t, pos0, nullptr, M,
-                             Hq * hd, Hkv * hd, hd, K, (hipStream_t)stream);
+                             Hq * hd, Hkv * hd, hd, K, q_scale, (hipStream_t)stream);
     PO_HIP(hipGetLastError());
     return PO_OK;
 }

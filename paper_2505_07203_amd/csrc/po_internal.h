@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libpo (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -66,10 +67,14 @@ void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, in
 // Vt is the base of V^T [kvd][ldv] and the call writes columns pos0 .. pos0+M-1.  GEMM row r is
 // rotated for sequence position row_pos[pos0 + r] (device array over buffer rows: several requests
 // packed into one buffer), or pos0 + r when row_pos is null.
+// q_scale: factor applied to the rotated Q values in fp32 before their one rounding to bf16 (1, or
+// attention_q_scale(hd) when the attention that follows is launched with q_prescaled; K and V are never scaled).
 void launch_gemm_qkv_rope(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
                           bf16_t* Q, bf16_t* K, bf16_t* Vt, int64_t ldv, const float* rope_cos,
                           const float* rope_sin, int64_t pos0, const int32_t* row_pos, int64_t M, int qd, int kvd,
-                          int hd, int Kdim, hipStream_t s);
+                          int hd, int Kdim, float q_scale, hipStream_t s);
+// the softmax scale in log2 units: p = exp2(q_scaled . k) = exp(q . k / sqrt(hd))
+static inline float attention_q_scale(int hd) { return (float)(1.4426950408889634 / sqrt((double)hd)); }
 // In place: within every head of `hd` rows (hd == 128 only; hd == 64 is already in order)
 // swap row blocks [32,64) and [64,96), so that rotary partners i and i + hd/2 sit 32 rows
 // apart inside one 64-row group.  row_elems = elements per row (1 for a bias vector).
@@ -88,8 +93,10 @@ void launch_v_transpose(const bf16_t* V, bf16_t* Vt, int64_t n, int kv_dim, int6
 // per 256-row query tile and head: the tiles whose scores leave the range of the fast kernel's fixed reference
 // exponent are marked there and recomputed by the running-maximum kernel in a second launch)
 size_t attention_mfma_redo_bytes(int64_t N, int Hq);
+// q_prescaled: q holds the rotated queries times attention_q_scale(hd) (launch_gemm_qkv_rope's q_scale); the
+// kernels then exponentiate K Q^T as it is.
 void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
-                           int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, int* redo, hipStream_t s);
+                           int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, int* redo, bool q_prescaled, hipStream_t s);
 // n 32-bit words of zeros (a kernel, not a memset node, so that it can be captured into a graph)
 void launch_fill_zero32(void* dst, size_t n_words, hipStream_t s);
 // The same for query rows [q_row0, N) when they are few and the keys many: the key tiles of a query tile are
@@ -101,7 +108,7 @@ void launch_fill_zero32(void* dst, size_t n_words, hipStream_t s);
 int launch_attention_mfma_split(const bf16_t* q, const bf16_t* k, const bf16_t* vt, int64_t ldv, bf16_t* o,
                                 int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, float* scratch,
                                 size_t scratch_bytes, bool launch, const bf16_t* k2, const bf16_t* vt2, int64_t ldv2,
-                                int64_t n2, hipStream_t s);
+                                int64_t n2, bool q_prescaled, hipStream_t s);
 bool gemm_mfma_supported(int N, int K);
 // C = A W^T + R for a GEMM with few rows, the reduction over K split between workgroups (a GEMM with few
 // output tiles leaves most of the chip idle and every workgroup streaming a whole K range of both operands):
@@ -115,7 +122,8 @@ bool gemm_mfma_supported(int N, int K);
 int launch_gemm_qkv_rope_splitk(const bf16_t* A, int64_t lda, const bf16_t* Wqkv, int64_t ldw, const bf16_t* bias,
                                 bf16_t* Q, bf16_t* Kd, bf16_t* Vt, int64_t ldv, const float* rope_cos,
                                 const float* rope_sin, int64_t pos0, const int32_t* row_pos, int64_t M, int qd,
-                                int kvd, int hd, int K, float* part, size_t part_bytes, bool launch, hipStream_t s);
+                                int kvd, int hd, int K, float q_scale, float* part, size_t part_bytes, bool launch,
+                                hipStream_t s);
 // launch_gemm_mfma(EPI_SILU_MUL) the same way; part must not overlap H's rows [0, M)
 int launch_gemm_mfma_splitk_silu(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* H, int64_t ldh,
                                  int64_t M, int N, int K, float* part, size_t part_bytes, bool launch, hipStream_t s);
@@ -138,7 +146,7 @@ void launch_gemm_fp8(int epi, const unsigned char* A, int64_t lda, const float* 
 void launch_gemm_fp8_qkv_rope(const unsigned char* A, int64_t lda, const float* sa, const unsigned char* Wqkv, int64_t ldw,
                               const float* sw, const bf16_t* bias, bf16_t* Q, bf16_t* K, bf16_t* Vt, int64_t ldv,
                               const float* rope_cos, const float* rope_sin, int64_t pos0, const int32_t* row_pos,
-                              int64_t M, int qd, int kvd, int hd, int Kdim, hipStream_t s);
+                              int64_t M, int qd, int kvd, int hd, int Kdim, float q_scale, hipStream_t s);
 // split-K forms of the two above for launches with few rows (see launch_gemm_mfma_splitk_residual): return the
 // number of splits used, 0 = nothing launched (not worth it, or part_bytes of scratch too small)
 int launch_gemm_fp8_splitk(int epi, const unsigned char* A, int64_t lda, const float* sa, const unsigned char* W,
@@ -147,8 +155,8 @@ int launch_gemm_fp8_splitk(int epi, const unsigned char* A, int64_t lda, const f
 int launch_gemm_fp8_qkv_rope_splitk(const unsigned char* A, int64_t lda, const float* sa, const unsigned char* Wqkv,
                                     int64_t ldw, const float* sw, const bf16_t* bias, bf16_t* Q, bf16_t* Kd, bf16_t* Vt,
                                     int64_t ldv, const float* rope_cos, const float* rope_sin, int64_t pos0,
-                                    const int32_t* row_pos, int64_t M, int qd, int kvd, int hd, int K, float* part,
-                                    size_t part_bytes, hipStream_t s);
+                                    const int32_t* row_pos, int64_t M, int qd, int kvd, int hd, int K, float q_scale,
+                                    float* part, size_t part_bytes, hipStream_t s);
 // q, scales = quantise(bf16(rmsnorm(x; g)))   (d % 8 == 0, d <= 8192)
 void launch_rmsnorm_quant(const bf16_t* x, const bf16_t* g, unsigned char* q, float* scales, int64_t rows, int d,
                           float eps, hipStream_t s);

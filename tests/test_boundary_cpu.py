@@ -159,8 +159,9 @@ def test_bad_arguments_rejected_before_any_launch():
     # single-kernel entry points validate too
     assert L.po_op_linear(B.PO_BF16, 4096, 4096, 4096, None, 8, 48, 64, None) == B.PO_ERR_BAD_CONFIG
     assert L.po_op_linear(3, 4096, 4096, 4096, None, 8, 64, 64, None) == B.PO_ERR_INVALID_ARG
-    assert L.po_op_attention(B.PO_BF16, 4096, 4096, 4096, 4096, 4096, 8, 4, 2, 96, None) == B.PO_ERR_BAD_CONFIG
-    assert L.po_op_attention(B.PO_BF16, 4096, 4096, 4096, 4096, 4096, 8, 4, 3, 128, None) == B.PO_ERR_INVALID_ARG
+    assert L.po_op_attention(B.PO_BF16, 4096, 4096, 4096, 4096, 4096, 8, 4, 2, 96, 0, None) == B.PO_ERR_BAD_CONFIG
+    assert L.po_op_attention(B.PO_F32, 4096, 4096, 4096, 4096, None, 8, 4, 2, 64, 1, None) == B.PO_ERR_INVALID_ARG
+    assert L.po_op_attention(B.PO_BF16, 4096, 4096, 4096, 4096, 4096, 8, 4, 3, 128, 0, None) == B.PO_ERR_INVALID_ARG
 
 
 def test_fp8_arenas():

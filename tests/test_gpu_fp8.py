@@ -275,21 +275,23 @@ def test_fp8_one_layer_full_width_step_by_step():
     wqkv, _ = B.po_op_pack_qkv(dev[I.KIND_WQ], dev[I.KIND_WK], dev[I.KIND_WV], Hq, Hkv, hd)
     qw, sw = B.po_op_quantize_rows(wqkv)
     cos, sin = B.po_op_rope_table(n, hd, cfg.rope_theta)
-    q, k, vt = B.po_op_qkv_rope_fp8(qa, sa, qw, sw, None, cos, sin, Hq, Hkv, hd, pos0=0)
+    c_att = B.attention_q_scale(hd)                   # the full path hands attention Q times the softmax scale
+    q, k, vt = B.po_op_qkv_rope_fp8(qa, sa, qw, sw, None, cos, sin, Hq, Hkv, hd, pos0=0, q_scale=c_att)
     pos = np.arange(n)
 
     def lin(name):
         wq_, ss = wq_oracle(name)
         return (aq @ wq_.T) * sa64[:, None] * ss[None, :]
-    close(host64(q).reshape(n, Hq, hd), O.rope(lin(I.KIND_WQ).reshape(n, Hq, hd), pos, cfg.rope_theta), 6e-3, "q")
+    close(host64(q).reshape(n, Hq, hd), O.rope(lin(I.KIND_WQ).reshape(n, Hq, hd), pos, cfg.rope_theta) * c_att, 6e-3, "q")
     close(host64(k).reshape(n, Hkv, hd), O.rope(lin(I.KIND_WK).reshape(n, Hkv, hd), pos, cfg.rope_theta), 6e-3, "k")
     v = vt[:, :n].T.contiguous()
     close(host64(v), lin(I.KIND_WV), 6e-3, "v")
 
     # ---- attention on the GPU's q, k, v
     q3, k3, v3 = q.view(n, Hq, hd), k.view(n, Hkv, hd), v.view(n, Hkv, hd)
-    o = B.po_op_attention(q3, k3, v3)
-    close(host64(o), O.causal_gqa_attention(host64(q3), host64(k3), host64(v3)), 1.5e-2, "attention")
+    o = B.po_op_attention(q3, k3, v3, q_prescaled=True)
+    close(host64(o), O.causal_gqa_attention(host64(q3) / np.float64(np.float32(c_att)), host64(k3), host64(v3)), 1.5e-2,
+          "attention")
 
     # ---- O-projection + residual from the GPU's codes of the attention output
     o2 = o.reshape(n, Hq * hd)

@@ -42,27 +42,41 @@ def host64(t) -> np.ndarray:
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
 
+def q_operand(qs32: np.ndarray, prescaled: bool):
+    """-> (device bf16 queries as the attention entry point takes them, the queries the definition sees, float64).
+    prescaled: the stored values are bf16(q * log2(e) / sqrt(hd)), the form the full path hands to attention; the
+    definition then sees those stored values divided by the scale."""
+    if not prescaled:
+        return bf16_dev(qs32)
+    c = np.float32(B.attention_q_scale(qs32.shape[-1]))
+    t, stored = bf16_dev(qs32 * c)
+    return t, stored / np.float64(c)
+
+
 # ------------------------------------------------------------------ attention, 32768 tokens
 
-def test_attention_32k_sampled_rows():
+@pytest.mark.parametrize("prescaled", [False, True], ids=["q", "q_prescaled"])
+def test_attention_32k_sampled_rows(prescaled):
     N, Hq, Hkv, hd = 32768, 32, 8, 128
     rng = np.random.default_rng(32768)
-    q, q64 = bf16_dev(rng.standard_normal((N, Hq, hd), dtype=np.float32))
+    q, q64 = q_operand(rng.standard_normal((N, Hq, hd), dtype=np.float32), prescaled)
     k, k64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
     v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
     rows = np.array([0, 1, 31, 32, 63, 64, 65, 127, 255, 256, 257, 319, 4095, 4096, 12345, 16383, 16384,
                      20000, 32511, 32512, 32575, 32703, 32766, 32767])
     ref = O.causal_gqa_attention(q64, k64, v64, query_rows=rows)
     del q64
-    got = host64(B.po_op_attention(q, k, v)[torch.from_numpy(rows).cuda()])
+    got = host64(B.po_op_attention(q, k, v, q_prescaled=prescaled)[torch.from_numpy(rows).cuda()])
     err = np.max(np.abs(got - ref), axis=(1, 2)) / np.max(np.abs(ref))
     print("attention N=32768, per sampled row:", " ".join(f"{r}:{e:.1e}" for r, e in zip(rows, err)))
     assert np.max(err) <= 1.5e-2
 
 
-def test_attention_large_scores_renormalise():
+@pytest.mark.parametrize("prescaled", [False, True], ids=["q", "q_prescaled"])
+def test_attention_large_scores_renormalise(prescaled):
     """Scores far above the first key block's maximum: the running sums pass the
-    renormalisation threshold many times."""
+    renormalisation threshold many times (with prescaled queries, which use no reference exponent, the rows whose
+    sums leave the float range are recomputed with a running maximum instead)."""
     N, Hq, Hkv, hd = 2048, 8, 2, 128
     rng = np.random.default_rng(7)
     qs = rng.standard_normal((N, Hq, hd), dtype=np.float32)
@@ -70,19 +84,20 @@ def test_attention_large_scores_renormalise():
     # growing key norm: later keys score higher and higher than the early ones
     ks *= (1.0 + 7.0 * np.arange(N, dtype=np.float32) / N)[:, None, None]
     qs *= 3.0
-    q, q64 = bf16_dev(qs)
+    q, q64 = q_operand(qs, prescaled)
     k, k64 = bf16_dev(ks)
     v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
     ref = O.causal_gqa_attention(q64, k64, v64)
-    got = host64(B.po_op_attention(q, k, v))
+    got = host64(B.po_op_attention(q, k, v, q_prescaled=prescaled))
     assert np.all(np.isfinite(got))
     err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
     print(f"attention with large scores: {err:.3e}")
     assert err <= 1.5e-2
 
 
+@pytest.mark.parametrize("prescaled", [False, True], ids=["q", "q_prescaled"])
 @pytest.mark.parametrize("nats", [70.0, 150.0, 400.0])
-def test_attention_outlier_key_mid_block(nats):
+def test_attention_outlier_key_mid_block(nats, prescaled):
     """One key, in the middle of a 32-key block, scores `nats` above everything before it for every query.
     70 nats (101 in log2 units) is inside what one block's exponentials hold: the row sums are renormalised.
     150 and 400 nats overflow the exponential against the reference taken from the first block: those query
@@ -95,55 +110,81 @@ def test_attention_outlier_key_mid_block(nats):
     ks = rng.standard_normal((N, Hkv, hd), dtype=np.float32)
     qs[:, :, 0] = 8.0
     ks[pos, :, 0] = np.float32(nats) * np.sqrt(np.float32(hd)) / 8.0
-    q, q64 = bf16_dev(qs)
+    q, q64 = q_operand(qs, prescaled)
     k, k64 = bf16_dev(ks)
     v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
     ref = O.causal_gqa_attention(q64, k64, v64)
     # the oracle itself: behind the outlier the softmax is that key alone
     assert np.max(np.abs(ref[pos:] - v64[pos][None].repeat(Hq // Hkv, axis=1))) < 1e-6
-    got = host64(B.po_op_attention(q, k, v))
+    got = host64(B.po_op_attention(q, k, v, q_prescaled=prescaled))
     assert np.all(np.isfinite(got))
     err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
     print(f"attention with a key {nats} nats above its predecessors: {err:.3e}")
     assert err <= 1.5e-2
     dq = q.clone()
-    B.po_op_attention(dq, k, v, out=dq)
+    B.po_op_attention(dq, k, v, out=dq, q_prescaled=prescaled)
     assert np.array_equal(host64(dq), got)
     # and the next call on ordinary inputs is unaffected (the give-up words were left clean)
     k2, k264 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
     ref2 = O.causal_gqa_attention(q64, k264, v64)
-    got2 = host64(B.po_op_attention(q, k2, v))
+    got2 = host64(B.po_op_attention(q, k2, v, q_prescaled=prescaled))
     assert np.max(np.abs(got2 - ref2)) / np.max(np.abs(ref2)) <= 1.5e-2
 
 
-def test_attention_128k_sampled_rows():
+@pytest.mark.parametrize("prescaled", [False, True], ids=["q", "q_prescaled"])
+@pytest.mark.parametrize("nats", [-45.0, -150.0])
+def test_attention_all_scores_far_below_zero(nats, prescaled):
+    """Every score of every row sits `nats` below zero (a common component of all keys against a common component
+    of all queries).  Softmax does not care; an implementation that exponentiates without a reference would flush
+    the probabilities to zero.  With prescaled queries the kernel's row sums fall below its floor and the tiles are
+    recomputed with a running maximum."""
+    N, Hq, Hkv, hd = 700, 8, 2, 128
+    rng = np.random.default_rng(int(-nats))
+    qs = rng.standard_normal((N, Hq, hd), dtype=np.float32)
+    ks = rng.standard_normal((N, Hkv, hd), dtype=np.float32)
+    qs[:, :, 0] = 8.0
+    ks[:, :, 0] = np.float32(nats) * np.sqrt(np.float32(hd)) / 8.0
+    q, q64 = q_operand(qs, prescaled)
+    k, k64 = bf16_dev(ks)
+    v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
+    ref = O.causal_gqa_attention(q64, k64, v64)
+    got = host64(B.po_op_attention(q, k, v, q_prescaled=prescaled))
+    assert np.all(np.isfinite(got))
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    print(f"attention with all scores {nats} nats: {err:.3e}")
+    assert err <= 1.5e-2
+
+
+@pytest.mark.parametrize("prescaled", [False, True], ids=["q", "q_prescaled"])
+def test_attention_128k_sampled_rows(prescaled):
     """The 131072-token workload's attention launch (32 query heads, 8 KV heads): rows of the first, middle
     and last query tiles against the definition evaluated for exactly those rows."""
     N, Hq, Hkv, hd = 131072, 32, 8, 128
     rng = np.random.default_rng(131072)
-    q, q64 = bf16_dev(rng.standard_normal((N, Hq, hd), dtype=np.float32))
+    q, q64 = q_operand(rng.standard_normal((N, Hq, hd), dtype=np.float32), prescaled)
     k, k64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
     v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
     rows = np.array([0, 1, 63, 64, 255, 256, 257, 511, 32767, 32768, 65535, 65536, 65537, 65599, 65791, 70001,
                      98304, 130815, 130816, 130879, 130880, 131007, 131070, 131071])
     ref = O.causal_gqa_attention(q64, k64, v64, query_rows=rows)
     del q64
-    got = host64(B.po_op_attention(q, k, v)[torch.from_numpy(rows).cuda()])
+    got = host64(B.po_op_attention(q, k, v, q_prescaled=prescaled)[torch.from_numpy(rows).cuda()])
     err = np.max(np.abs(got - ref), axis=(1, 2)) / np.max(np.abs(ref))
     print("attention N=131072, per sampled row:", " ".join(f"{r}:{e:.1e}" for r, e in zip(rows, err)))
     assert np.max(err) <= 1.5e-2
 
 
-def test_attention_qwen_heads_16k_sampled_rows():
+@pytest.mark.parametrize("prescaled", [False, True], ids=["q", "q_prescaled"])
+def test_attention_qwen_heads_16k_sampled_rows(prescaled):
     """Five query heads per KV head (40 and 8) over 16384 tokens: the Qwen-32B-shaped workload's launch."""
     N, Hq, Hkv, hd = 16384, 40, 8, 128
     rng = np.random.default_rng(16384)
-    q, q64 = bf16_dev(rng.standard_normal((N, Hq, hd), dtype=np.float32))
+    q, q64 = q_operand(rng.standard_normal((N, Hq, hd), dtype=np.float32), prescaled)
     k, k64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
     v, v64 = bf16_dev(rng.standard_normal((N, Hkv, hd), dtype=np.float32))
     rows = np.array([0, 31, 32, 255, 256, 1000, 4095, 4096, 8191, 8192, 12345, 16127, 16128, 16191, 16382, 16383])
     ref = O.causal_gqa_attention(q64, k64, v64, query_rows=rows)
-    got = host64(B.po_op_attention(q, k, v)[torch.from_numpy(rows).cuda()])
+    got = host64(B.po_op_attention(q, k, v, q_prescaled=prescaled)[torch.from_numpy(rows).cuda()])
     # every query head must have read ITS KV head: compare head by head
     err = np.max(np.abs(got - ref), axis=(0, 2)) / np.max(np.abs(ref))
     print("attention N=16384, 40/8 heads, per query head:", " ".join(f"{e:.1e}" for e in err))
@@ -222,7 +263,9 @@ def test_gemm_qkv_rope_benchmark_shape(shape):
     ref_v = a64[rows] @ v64.T
     cos, sin = B.po_op_rope_table(pos0 + M, hd, theta)
     wqkv, _ = B.po_op_pack_qkv(wq, wk, wv, Hq, Hkv, hd)
-    q, k, vt = B.po_op_qkv_rope(a, wqkv, None, cos, sin, Hq, Hkv, hd, pos0=pos0)
+    c = B.attention_q_scale(hd)
+    q, k, vt = B.po_op_qkv_rope(a, wqkv, None, cos, sin, Hq, Hkv, hd, pos0=pos0, q_scale=c)     # as the full path calls it
+    ref_q = ref_q * c
     gq = host64(q).reshape(M, Hq, hd)[rows]
     gk = host64(k).reshape(M, Hkv, hd)[rows]
     gv = host64(vt)[:, pos].T if vt.shape[1] > M else host64(vt)[:, rows].T

@@ -210,6 +210,16 @@ def test_op_attention(dtype, N, Hq, Hkv, hd):
     # in place over q, as the full path runs it
     B.po_op_attention(dq, to_dev(k), to_dev(v), out=dq)
     assert np.array_equal(from_dev(dq), got)
+    if dtype == I.BF16:
+        # the form the full path uses: queries stored as bf16(q * log2(e) / sqrt(hd)); the definition sees those
+        # stored values divided by the scale
+        c = np.float32(B.attention_q_scale(hd))
+        qp = I.f32_to_bf16_bits(I.bf16_bits_to_f32(q) * c)
+        ref2 = O.causal_gqa_attention(I.stored_to_f64(qp) / np.float64(c), I.stored_to_f64(k), I.stored_to_f64(v))
+        got2 = from_dev(B.po_op_attention(to_dev(qp), to_dev(k), to_dev(v), q_prescaled=True))
+        err2 = np.max(np.abs(got2 - ref2)) / np.max(np.abs(ref2))
+        print(f"    with prescaled queries: {err2:.3e}")
+        assert err2 <= tol
 
 
 @pytest.mark.parametrize("dtype", [I.F32, I.BF16])
@@ -295,6 +305,11 @@ def test_op_qkv_rope(Hq, Hkv, hd, K, M, pos0, bias):
     outside = np.ones(vt.shape[1], dtype=bool)
     outside[pos0:pos0 + M] = False
     assert np.all(from_dev(vt)[:, outside] == 0)
+    # the form the full path uses: Q times the softmax scale (log2 units) before its rounding; K and V as before
+    c = B.attention_q_scale(hd)
+    q2, k2, vt2 = B.po_op_qkv_rope(to_dev(a), wqkv, bqkv, cos, sin, Hq, Hkv, hd, pos0=pos0, q_scale=c)
+    assert np.max(np.abs(from_dev(q2) - q_ref * c)) <= 6e-3 * np.max(np.abs(q_ref * c))
+    assert np.array_equal(from_dev(k2), from_dev(k)) and np.array_equal(from_dev(vt2), from_dev(vt))
 
 
 def test_profile_run_measures_the_static_footprint():
