@@ -276,6 +276,8 @@ po_status po_sched_push(po_sched* s, int64_t id, const int32_t* tokens, int64_t 
 po_status po_sched_push_request(po_sched* s, int64_t id, const int32_t* tokens, int64_t len, const int32_t* cand_ids,
                                 int32_t n_cand, double arrival_time);
 int64_t po_sched_size(const po_sched* s);
+/* Takes the request with this id out of the queue without running it (PO_ERR_INVALID_ARG if there is none). */
+po_status po_sched_remove(po_sched* s, int64_t id);
 po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cached_tokens, double now,
                         int64_t* id, int64_t* n_cached_hit);
 /* The same against a cache of several entries: n_cached of a request is the best any entry
@@ -294,8 +296,10 @@ po_status po_sched_pick_multi(po_sched* s, const int32_t* const* cached_tokens, 
  * PO_ERR_INVALID_ARG and leaves the queue as it is.  *n_cand_used (may be NULL) receives the
  * number of log-probs written.  Other outputs as in po_prefill; *id receives the request's id
  * (-1, and nothing runs, when the queue is empty), *len and *reused_prefix_len (both may be
- * NULL) its length and the positions it did not compute.  A request whose run fails is NOT put
- * back: the error is returned with *id set. */
+ * NULL) its length and the positions it did not compute.  A request leaves the queue only once it
+ * has run: if the context refuses it (PO_ERR_TOO_LONG, PO_ERR_TOKEN_RANGE, ...) or its run fails, the
+ * error is returned with *id set and the request is still queued; drop it with po_sched_remove, or the
+ * next step picks it again. */
 po_status po_engine_step(po_ctx* ctx, po_sched* s, double now, const int32_t* cand_ids, int32_t n_cand,
                          float* out_logits, float* out_cand_logprobs, int32_t cand_capacity, int64_t* id,
                          int64_t* len, int64_t* reused_prefix_len, int32_t* n_cand_used);

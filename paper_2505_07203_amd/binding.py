@@ -40,7 +40,7 @@ EXPORTS = [
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
     "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_op_linear_split", "po_sched_push_request", "po_op_attention_split",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
-    "po_sched_size", "po_sched_pick", "po_op_rope_static", "po_op_mfma_peak", "po_op_stream_copy",
+    "po_sched_size", "po_sched_pick", "po_sched_remove", "po_op_rope_static", "po_op_mfma_peak", "po_op_stream_copy",
 ]
 
 
@@ -141,6 +141,7 @@ def lib() -> C.CDLL:
     L.po_sched_fit_jct_model.argtypes = [vp, vp, vp, vp, i32, C.POINTER(f64 * 3)]
     L.po_sched_push.argtypes = [vp, i64, vp, i64, f64]
     L.po_sched_size.argtypes = [vp]
+    L.po_sched_remove.argtypes = [vp, i64]
     L.po_sched_size.restype = i64
     L.po_sched_pick.argtypes = [vp, vp, i64, f64, C.POINTER(i64), C.POINTER(i64)]
     for name in EXPORTS:
@@ -630,6 +631,9 @@ class Scheduler:
 
     def po_sched_size(self) -> int:
         return int(lib().po_sched_size(self._h))
+
+    def po_sched_remove(self, rid: int) -> None:
+        check(lib().po_sched_remove(self._h, rid))
 
     def po_sched_pick(self, cached_tokens, now: float):
         """-> (id or -1, tokens of that request that hit the prefix cache)"""

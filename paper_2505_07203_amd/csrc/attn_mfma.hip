@@ -490,7 +490,8 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int j2 = 0; j2 < 2; ++j2) vofs[a][j2] = l31 * 128 + (((a * 4 + j2 * 2 + lhi) ^ swz8(l31)) << 4);
+        for (int j2 = 0; j2 < 2; ++j2)      // (the V^T half of LDS starts at 64 KiB: in the register, so that what is left is an immediate)
+            vofs[a][j2] = A64_VBASE + l31 * 128 + (((a * 4 + j2 * 2 + lhi) ^ swz8(l31)) << 4);
 
     f32x16 oacc[HT][2];
 #pragma unroll
@@ -500,6 +501,7 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[ht][qt][r] = 0.f;
     float mb[2], lrow[2] = {0.f, 0.f};      // reference exponents (log2 domain) and row sums per query tile
+    float lsum[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};       // PRE: the row sums as four partial sums each
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     int gave_up = 0;                        // wavefront-uniform: a row sum left the range the reference scheme covers
     int* const lds_gave_up = (int*)(smem + 2 * A64_NSTAGE * A64_TILE);     // one word behind the ring
@@ -592,8 +594,8 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
     {                                                                                              \
         const int e_ = PO_JOB_E((n_) & 15);                                                        \
         const float mb_ = (e_ >> 4) ? mb1_ : mb0_;                                                 \
-        ea_[(n_) & 15][0] = PRE ? SC[e_ >> 4][e_ & 15] : fmaf(SC[e_ >> 4][e_ & 15], sc_log2e, -mb_);           \
-        ea_[(n_) & 15][1] = PRE ? SC[e_ >> 4][(e_ & 15) + 1] : fmaf(SC[e_ >> 4][(e_ & 15) + 1], sc_log2e, -mb_); \
+        ea_[(n_) & 15][0] = fmaf(SC[e_ >> 4][e_ & 15], sc_log2e, -mb_);                            \
+        ea_[(n_) & 15][1] = fmaf(SC[e_ >> 4][(e_ & 15) + 1], sc_log2e, -mb_);                      \
     }
 #define PO_ITER(i_, SC, SN, KST_, KA_, VST_, VA_, NKST_, NKA_, BAR_, DMA_T_, DMA_S_, DMA_J0_, MASK_)            \
     {                                                                                                           \
@@ -635,11 +637,13 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
                 const int slot_ = 2 * c + qt;                    /* 0..31 over the iteration */                 \
                 {                                                                                               \
                     const int na_ = PO_JOB_AT(slot_ + 1), nb_ = PO_JOB_AT(slot_), nc_ = PO_JOB_AT(slot_ - 1);   \
-                    if (slot_ == 0) { PO_EXP_ARG(0, SC, mb0_, mb1_); }                                          \
-                    if (na_ > 0) { PO_EXP_ARG(na_, SC, mb0_, mb1_); }                                           \
+                    if (!PRE && slot_ == 0) { PO_EXP_ARG(0, SC, mb0_, mb1_); }                                  \
+                    if (!PRE && na_ > 0) { PO_EXP_ARG(na_, SC, mb0_, mb1_); }                                   \
                     if (nb_ >= 0) {                                                                             \
-                        ea_[nb_ & 15][0] = __builtin_amdgcn_exp2f(ea_[nb_ & 15][0]);                            \
-                        ea_[nb_ & 15][1] = __builtin_amdgcn_exp2f(ea_[nb_ & 15][1]);                            \
+                        /* PRE: the accumulator IS the exponent's argument */                                   \
+                        const int eb_ = PO_JOB_E(nb_ & 15);                                                     \
+                        ea_[nb_ & 15][0] = __builtin_amdgcn_exp2f(PRE ? SC[eb_ >> 4][eb_ & 15] : ea_[nb_ & 15][0]);       \
+                        ea_[nb_ & 15][1] = __builtin_amdgcn_exp2f(PRE ? SC[eb_ >> 4][(eb_ & 15) + 1] : ea_[nb_ & 15][1]); \
                     }                                                                                           \
                     if (nc_ >= 0) {                                                                             \
                         const int e_ = PO_JOB_E(nc_ & 15);                                                      \
@@ -651,14 +655,16 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
                     const int c_ = (c - 8) * 2 + qt;             /* 0..15 */                                    \
                     if (c_ == 8 || c_ == 9) {                                                                   \
                         const int sq_ = c_ - 8;                                                                 \
-                        /* four independent chains: a dependent dot product waits about 6 cycles */             \
+                        /* four independent chains: a dependent dot product waits about 6 cycles.  PRE: the     \
+                           four partial sums live across blocks (nothing looks at the row sum before the end) */\
                         float l_[4] = {lrow[sq_], 0.f, 0.f, 0.f};                                               \
                         _Pragma("unroll") for (int h2 = 0; h2 < 2; ++h2)                                        \
                         _Pragma("unroll") for (int e2 = 0; e2 < 4; ++e2) {                                      \
                             const bf16x2 pr2_ = {pf[sq_][h2][2 * e2], pf[sq_][h2][2 * e2 + 1]};                 \
-                            l_[e2] = __builtin_amdgcn_fdot2_f32_bf16(pr2_, ones, l_[e2], false);                \
+                            if (PRE) lsum[sq_][e2] = __builtin_amdgcn_fdot2_f32_bf16(pr2_, ones, lsum[sq_][e2], false); \
+                            else l_[e2] = __builtin_amdgcn_fdot2_f32_bf16(pr2_, ones, l_[e2], false);           \
                         }                                                                                       \
-                        lrow[sq_] = (l_[0] + l_[1]) + (l_[2] + l_[3]);                                          \
+                        if (!PRE) lrow[sq_] = (l_[0] + l_[1]) + (l_[2] + l_[3]);                                \
                     }                                                                                           \
                     if ((c_ & 3) == 3) { PO_DMA(DMA_T_, DMA_S_, (DMA_J0_) + (c_ >> 2)); }                       \
                 }                                                                                               \
@@ -666,9 +672,8 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
             }                                                                                                   \
         }                                                                                                       \
         /* ---- renormalise when a row sum has grown past 2^40 (rare; see the note on the reference) */         \
-        if (PRE) {                                                                                              \
-            if (__any(!(lrow[0] < 0x1p100f) || !(lrow[1] < 0x1p100f))) gave_up = 1;                             \
-        } else if (__any(!(lrow[0] <= 0x1p40f) || !(lrow[1] <= 0x1p40f))) {                                     \
+        /* (PRE: nothing to watch.  The sums only grow, an overflow stays an overflow: one look at the end does) */ \
+        if (!PRE && __any(!(lrow[0] <= 0x1p40f) || !(lrow[1] <= 0x1p40f))) {                                    \
             const float t0_ = half_swap_sum(lrow[0]), t1_ = half_swap_sum(lrow[1]);                             \
             if (__any(!(t0_ < 0x1p100f) || !(t1_ < 0x1p100f))) gave_up = 1;                                     \
             int e0_ = ilogbf(t0_), e1_ = ilogbf(t1_);                                                           \
@@ -698,7 +703,7 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
     {                                                                                              \
         const unsigned char* kst = smem + (s_) * A64_TILE;                                         \
         const unsigned char* kstn = smem + (((s_) + 1) & 3) * A64_TILE;                            \
-        const unsigned char* vst = smem + A64_VBASE + (s_) * A64_TILE;                             \
+        const unsigned char* vst = smem + (s_) * A64_TILE;                  /* (+ A64_VBASE, in vofs) */ \
         PO_ITER(2 * j, sa, sb, kst, 1, vst, 0, kstn, 0, 1, j + 3, ((s_) + 3) & 3, 0, M0_);         \
         PO_ITER(2 * j + 1, sb, sa, kstn, 0, vst, 1, kstn, 1, 0, j + 3, ((s_) + 3) & 3, 4, M1_);    \
     }
@@ -740,9 +745,13 @@ __global__ void __launch_bounds__(256) attn_fwd64_kernel(const bf16_t* q, const 
 #undef PO_MFMA_ACC
 #undef PO_MFMA_DRAIN
 
-    if (PRE && nkb_w > 0) {
-        // a row sum this small means the row's scores sit so far below zero that terms were flushed away
-        if (__any(!(half_swap_sum(lrow[0]) >= 0x1p-60f) || !(half_swap_sum(lrow[1]) >= 0x1p-60f))) gave_up = 1;
+    if (PRE) {
+        lrow[0] = (lsum[0][0] + lsum[0][1]) + (lsum[0][2] + lsum[0][3]);
+        lrow[1] = (lsum[1][0] + lsum[1][1]) + (lsum[1][2] + lsum[1][3]);
+        // a row sum of 2^100 or more (or infinite) means probabilities near or past the top of the float range; one
+        // below 2^-60 that the row's scores sit so far below zero that terms were flushed away
+        const float t0 = half_swap_sum(lrow[0]), t1 = half_swap_sum(lrow[1]);
+        if (nkb_w > 0 && __any(!(t0 >= 0x1p-60f) || !(t0 < 0x1p100f) || !(t1 >= 0x1p-60f) || !(t1 < 0x1p100f))) gave_up = 1;
     }
     // ---- did any wavefront give up?  (every wavefront has met the same number of barriers and arrives here)
     if (gave_up && lane == 0) *(volatile int*)lds_gave_up = 1;

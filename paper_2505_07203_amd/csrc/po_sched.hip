@@ -165,16 +165,31 @@ po_status po_engine_step(po_ctx* ctx, po_sched* s, double now, const int32_t* ca
     const bool own = cand_ids == nullptr;
     if (own) n_cand = (int32_t)s->queue[best].cand.size();
     if (out_cand_logprobs && n_cand > cand_capacity) return PO_ERR_INVALID_ARG;
-    po_sched::Req r = std::move(s->queue[best]);
-    s->queue.erase(s->queue.begin() + (std::ptrdiff_t)best);
+    // The request leaves the queue only once it has run: one that the context refuses (too long for it, a token id
+    // out of range) or whose run fails stays queued and is named in *id, so that the caller can drop it
+    // (po_sched_remove) or try again; nothing is lost on an error.
+    const po_sched::Req& r = s->queue[best];
     if (own) cand_ids = r.cand.empty() ? nullptr : r.cand.data();
     *id = r.id;
     if (len) *len = (int64_t)r.tokens.size();
+    const po_status st =
+        cached ? po_prefill_prefix(ctx, r.tokens.data(), (int64_t)r.tokens.size(), PO_KEEP_ALL, cand_ids, n_cand, out_logits,
+                                   out_cand_logprobs, reused_prefix_len)
+               : po_prefill(ctx, r.tokens.data(), (int64_t)r.tokens.size(), cand_ids, n_cand, out_logits, out_cand_logprobs);
+    if (st != PO_OK) return st;
     if (n_cand_used) *n_cand_used = out_cand_logprobs ? n_cand : 0;
-    if (cached)
-        return po_prefill_prefix(ctx, r.tokens.data(), (int64_t)r.tokens.size(), PO_KEEP_ALL, cand_ids, n_cand, out_logits,
-                                 out_cand_logprobs, reused_prefix_len);
-    return po_prefill(ctx, r.tokens.data(), (int64_t)r.tokens.size(), cand_ids, n_cand, out_logits, out_cand_logprobs);
+    s->queue.erase(s->queue.begin() + (std::ptrdiff_t)best);
+    return PO_OK;
+}
+
+po_status po_sched_remove(po_sched* s, int64_t id) {
+    if (!s) return PO_ERR_INVALID_ARG;
+    for (size_t i = 0; i < s->queue.size(); ++i)
+        if (s->queue[i].id == id) {
+            s->queue.erase(s->queue.begin() + (std::ptrdiff_t)i);
+            return PO_OK;
+        }
+    return PO_ERR_INVALID_ARG;
 }
 
 po_status po_sched_pick(po_sched* s, const int32_t* cached_tokens, int64_t n_cached_tokens, double now, int64_t* id,

@@ -584,14 +584,47 @@ def test_engine_step_matches_a_hand_driven_loop():
         assert sch.po_sched_size() == 1                                            # ... and the request stays queued
         rid, _, _, _, lp = ctx.po_engine_step(sch, 1.0, cand=[11, 12])             # the caller's list overrides
         assert rid == 3 and np.array_equal(lp, ctx.po_prefill(reqs[3], [11, 12], want_logits=False)[1])
-        # a request the context cannot run is dropped with an error, the queue moves on
+        # a request the context cannot run is reported and stays queued (see the next test)
         sch = B.Scheduler(0.0)
         sch.po_sched_push(7, np.zeros(ctx.max_input_len + 1, dtype=np.int32), 0.0)
         sch.po_sched_push(8, reqs[0], 0.0)
         with pytest.raises(B.PoError):
             ctx.po_engine_step(sch, 0.0, cand)          # shortest first: request 8 runs ...
             ctx.po_engine_step(sch, 0.0, cand)          # ... then 7 fails
-        assert sch.po_sched_size() == 0
+        assert sch.po_sched_size() == 1
+    finally:
+        ctx.po_destroy()
+
+
+def test_engine_step_keeps_a_refused_request_queued():
+    """A request the context cannot run (longer than its maximum input length; a token id out of range) is
+    reported and stays in the queue: nothing is lost, the caller drops it with po_sched_remove and the loop goes on."""
+    cfg = I.TINY.replace(dtype=I.BF16, ffn_dim=704)
+    ctx = make_ctx(cfg, 31, 256, 64)
+    try:
+        sch = B.Scheduler(0.0)                          # shortest first: the good request would run first ...
+        good = I.make_tokens(cfg, 3, 100)
+        too_long = I.make_tokens(cfg, 4, 300)
+        bad_id = I.make_tokens(cfg, 5, 50).copy()
+        bad_id[7] = cfg.vocab_size
+        sch.po_sched_push(1, bad_id, 0.0)               # ... so the shortest one is the one with the bad token id
+        sch.po_sched_push(2, good, 0.0)
+        sch.po_sched_push(3, too_long, 0.0)
+        with pytest.raises(B.PoError) as e:
+            ctx.po_engine_step(sch, 1.0, I.label_ids(cfg))
+        assert e.value.status == B.PO_ERR_TOKEN_RANGE and sch.po_sched_size() == 3
+        sch.po_sched_remove(1)
+        rid, n, _, _, lp = ctx.po_engine_step(sch, 1.0, I.label_ids(cfg))
+        assert (rid, n) == (2, 100) and sch.po_sched_size() == 1
+        _, lp_ref = ctx.po_prefill(good, I.label_ids(cfg), want_logits=False)
+        assert np.array_equal(lp, lp_ref)
+        with pytest.raises(B.PoError) as e:
+            ctx.po_engine_step(sch, 2.0, I.label_ids(cfg))
+        assert e.value.status == B.PO_ERR_TOO_LONG and sch.po_sched_size() == 1
+        sch.po_sched_remove(3)
+        with pytest.raises(B.PoError):
+            sch.po_sched_remove(3)
+        assert ctx.po_engine_step(sch, 3.0, I.label_ids(cfg))[0] == -1
     finally:
         ctx.po_destroy()
 
