@@ -66,15 +66,29 @@ def read_counters(d):
     return out
 
 
+def short_name(name):
+    """A kernel's demangled name without return type, namespaces and argument list (template arguments kept)."""
+    for drop in ("void ", "(anonymous namespace)::", "po::"):
+        name = name.replace(drop, "")
+    depth = 0
+    for i, ch in enumerate(name):
+        if ch == "<":
+            depth += 1
+        elif ch == ">":
+            depth -= 1
+        elif ch == "(" and depth == 0:
+            return name[:i]
+    return name
+
+
 def read_stats(d):
-    """-> {class: (calls, average ns)} from the kernel-trace statistics"""
-    out = {}
+    """-> [(short kernel name, class or '', calls, average ns, min ns, max ns)] from the kernel-trace statistics"""
+    out = []
     for f in glob.glob(os.path.join(d, "**", "*kernel_stats.csv"), recursive=True):
         with open(f, newline="") as fh:
             for row in csv.DictReader(fh):
-                cls = classify(row["Name"])
-                if cls:
-                    out[cls] = (int(row["Calls"]), float(row["AverageNs"]))
+                out.append((short_name(row["Name"]), classify(row["Name"]) or "", int(row["Calls"]),
+                            float(row["AverageNs"]), float(row["MinNs"]), float(row["MaxNs"])))
     return out
 
 
@@ -89,23 +103,36 @@ def main():
     ap.add_argument("--fetch")
     ap.add_argument("--write")
     ap.add_argument("--sq")
-    ap.add_argument("--bench-flags", default="--steps 1 --warmup 0 --copy-calibration --no-cpu-baseline --no-phase-timing --no-clock-sample --no-extras")
+    common = "--copy-calibration --no-cpu-baseline --no-phase-timing --no-clock-sample --no-extras"
+    ap.add_argument("--bench-flags", default="--steps 1 --warmup 0 " + common,
+                    help="bench.py flags of the counter passes (one prefill: counter collection serialises dispatches)")
+    ap.add_argument("--trace-flags", default="--steps 3 --warmup 1 " + common,
+                    help="bench.py flags of the kernel-trace pass")
+    ap.add_argument("--tag", default="", help="suffix of the summaries' file names, e.g. fp8 for a run with --fp8")
+    ap.add_argument("--stem", default="", help="file-name stem of the summaries (default prefill_<workload>[_<tag>])")
+    ap.add_argument("--trace-cmd", default="", help="the whole traced command, when it is not a --workload run of bench.py")
     ap.add_argument("--out-dir", default=os.path.join(os.path.dirname(HERE), "profiles"))
     a = ap.parse_args()
     os.makedirs(a.out_dir, exist_ok=True)
+    stem = a.stem or f"prefill_{a.workload}" + (f"_{a.tag}" if a.tag else "")
+    trace_cmd = a.trace_cmd or f"python3 bench.py --workload {a.workload} {a.trace_flags}"
     cmd = f"python3 bench.py --workload {a.workload} {a.bench_flags}"
     if a.trace:
         st = read_stats(a.trace)
-        path = os.path.join(a.out_dir, f"prefill_{a.workload}_kernel_trace.txt")
+        path = os.path.join(a.out_dir, stem + "_kernel_trace.txt")
         with open(path, "w") as f:
-            f.write(f"rocprofv3 kernel trace summary: whole prefill path, workload {a.workload}\n")
-            f.write(f"command (from the repository root, on the MI355X box):\n  rocprofv3 --kernel-trace --stats --output-format csv -d <dir> -- {cmd}\n")
-            f.write("then: python3 -m paper_2505_07203_amd.pmc_summary --trace <dir>\n\n")
-            f.write(f"{'kernel class':18s} {'function':40s} {'calls':>6s} {'average us':>12s} {'total ms':>10s}\n")
-            tot = sum(c * ns for c, ns in st.values())
-            for cls, (calls, ns) in sorted(st.items(), key=lambda kv: -kv[1][0] * kv[1][1]):
-                f.write(f"{cls:18s} {CLASSES[cls]:40s} {calls:6d} {ns / 1e3:12.1f} {calls * ns / 1e6:10.2f}\n")
-            f.write(f"\nsum over the kernels above: {tot / 1e6:.2f} ms\n")
+            f.write(f"rocprofv3 kernel trace summary: {trace_cmd}\n")
+            f.write("command (from the repository root, on the MI355X box):\n  rocprofv3 --kernel-trace --stats "
+                    f"--output-format csv -d <dir> -- {trace_cmd}\n")
+            f.write("then: python3 -m paper_2505_07203_amd.pmc_summary --trace <dir> [--stem / --tag / --trace-cmd / "
+                    "--trace-flags as above]\n")
+            f.write("(every prefill of the run is in the table, warm-up included, and the kernels of the model load; microseconds)\n\n")
+            f.write(f"{'kernel':44s} {'class':16s} {'calls':>6s} {'average us':>11s} {'min us':>9s} {'max us':>9s} {'total ms':>9s} {'%':>6s}\n")
+            tot = sum(c * ns for _, _, c, ns, _, _ in st)
+            for name, cls, calls, ns, lo, hi in sorted(st, key=lambda r: -r[2] * r[3]):
+                f.write(f"{name[:44]:44s} {cls:16s} {calls:6d} {ns / 1e3:11.1f} {lo / 1e3:9.1f} {hi / 1e3:9.1f} "
+                        f"{calls * ns / 1e6:9.2f} {100.0 * calls * ns / tot:6.2f}\n")
+            f.write(f"\nsum over all kernels: {tot / 1e6:.2f} ms\n")
         print("wrote", path)
     if a.fetch and a.write:
         fe, wr = read_counters(a.fetch), read_counters(a.write)
@@ -114,7 +141,7 @@ def main():
         cal_w = mean(wr["copy_calibration"]["WRITE_SIZE"])
         kib = float(1 << 20)                                  # the calibration kernel moves 2^20 KiB each way
         ff, fw = kib / cal_f, kib / cal_w
-        path = os.path.join(a.out_dir, f"prefill_{a.workload}_pmc_counters.txt")
+        path = os.path.join(a.out_dir, stem + "_pmc_counters.txt")
         with open(path, "w") as f:
             f.write(f"rocprofv3 counter summary: whole prefill path, workload {a.workload}\n")
             f.write("commands (from the repository root, on the MI355X box; one pass per run, counters only):\n")
