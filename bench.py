@@ -121,6 +121,38 @@ def cpu_baseline_full_tiny():
             "sample": "the whole configuration (weights generated inside the timed region)"}
 
 
+def cpu_baseline_full_request():
+    """The oracle timed IN FULL on the shortest request of the 16-request mix (all 32 layers at the 8B width): minutes
+    of CPU time, so only on request (--cpu-baseline-request)."""
+    import helpers as H
+    from paper_2505_07203_amd import inputs as I
+    w = I.WORKLOADS["llama8b_mixed16"]
+    lens = [int(n) for n in I.workload_lengths("llama8b_mixed16")]
+    i = min(range(len(lens)), key=lambda j: lens[j])
+    tokens = I.make_tokens(w["cfg"], w["tseed"], int(lens[i]), request=i)
+    t0 = time.perf_counter()
+    H.oracle_prefill(w["cfg"], w["wseed"], tokens, cand=I.label_ids(w["cfg"]))
+    dt = time.perf_counter() - t0
+    return {"workload": "llama8b_mixed16", "request": i, "tokens": lens[i], "value": lens[i] / dt, "unit": "tokens/s",
+            "seconds": dt, "kind": "oracle", "sample": "one whole request, all layers (weights generated inside the timed region)"}
+
+
+def cpu_baseline_recorded():
+    """What tests/golden/make_golden.py recorded when it ran the oracle over the WHOLE 16-request mix (all layers, exact
+    mode): read from the fixture, not measured now, and on that machine's cores."""
+    path = os.path.join(ROOT, "tests", "golden", "llama8b_mixed16.json")
+    try:
+        with open(path) as f:
+            g = json.load(f)
+        toks = sum(r["len"] for r in g["requests"])
+        return {"workload": "llama8b_mixed16", "tokens": toks, "value": toks / g["oracle_layer_seconds_exact_mode"],
+                "unit": "tokens/s", "seconds": g["oracle_layer_seconds_exact_mode"], "cores": g.get("host_cores"),
+                "kind": "oracle, recorded", "sample": "all 16 requests x 32 layers, layer time of the exact evaluation as "
+                "recorded in tests/golden/llama8b_mixed16.json when the fixture was written"}
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def micro_peaks(B, torch):
     """Measured micro-peaks beside the nominal ones: matrix-instruction loops on random bf16 operands (no memory
     traffic inside the loop; the rate is what the board's power limit grants) and a 1 GiB streaming copy."""
@@ -303,6 +335,8 @@ def main():
     ap.add_argument("--workload", default="llama8b_32k")
     ap.add_argument("--layers", type=int, default=0, help="debug: override the layer count (invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-request", action="store_true",
+                    help="also time the oracle in full on the shortest request of the 16-request mix (minutes of CPU time)")
     ap.add_argument("--no-phase-timing", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the untimed extras: micro-peaks (matrix loop, streaming copy) and the footprint sweep")
@@ -520,7 +554,9 @@ def main():
         out["micro_peak"] = micro_peaks(B, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w["wseed"], w["tseed"], lens, 2, 4096)
-        out["cpu_baseline_full"] = cpu_baseline_full_tiny()
+        out["cpu_baseline_full"] = [cpu_baseline_full_tiny(), cpu_baseline_recorded()]
+        if args.cpu_baseline_request:
+            out["cpu_baseline_full"].append(cpu_baseline_full_request())
     print(json.dumps(out))
 
 
