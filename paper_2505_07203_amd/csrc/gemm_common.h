@@ -336,13 +336,13 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 // the row so that the writes, lane = row, and the reads, lanes along a row, are free of bank conflicts) and leave
 // as 16 bytes per lane covering whole row segments; QKV keeps a per-lane path (rotary pairs, V^T).
 // smem: at least 8 KiB per wavefront, free to overwrite (callers synchronise the workgroup before).
-template <int EPI>
-__device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4 (&acc)[8][4], unsigned char* smem,
+template <int EPI, int MU>
+__device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4 (&acc)[MU][4], unsigned char* smem,
                                                 int m0, int n0, int wave, int lane) {
     const int l15 = lane & 15, l4 = lane >> 4;
     const int wm = wave >> 2, wn = wave & 3;
     unsigned char* stg = smem + wave * 8192;
-    const int row_base = m0 + wm * 128, col_base = n0 + wn * 64;
+    const int row_base = m0 + wm * (MU * 16), col_base = n0 + wn * 64;
     if (col_base >= p.N) return;                       // (N is a multiple of 64: a patch is wholly in or out)
     if (EPI == EPI_QKV_ROPE) {
         const int half = p.hd >> 1;
@@ -354,7 +354,7 @@ __device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4
             const int head = c / p.hd;
             const int patch = (c - head * p.hd) >> 6;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < MU; ++u) {
                 const int row = row_base + u * 16 + l15;
                 if (row >= p.M) continue;
                 const int64_t pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
@@ -382,7 +382,7 @@ __device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4
             // V patch: stored transposed, V^T[feature][position]; consecutive lanes are consecutive positions
             const int f0 = cb - p.qd - p.kvd;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < MU; ++u) {
                 const int row = row_base + u * 16 + l15;
                 if (row >= p.M) continue;
                 bf16_t* dcol = p.dst_vt + p.pos0 + row;
@@ -403,7 +403,7 @@ __device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4
         // register quad), then 8 consecutive features per lane, 8 rows per pass
         const int col = col_base + (lane & 7) * 8;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < MU; ++u) {
 #pragma unroll
             for (int t = 0; t < 4; ++t)
                 *(f32x4*)(stg + l15 * 256 + (((t * 4 + l4) ^ l15) << 4)) = acc[u][t];
@@ -450,7 +450,7 @@ __device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4
         // banks: swizzle with row / 2), then 8 features per lane, 8 rows per pass
         const int col = col_base + (lane & 7) * 8;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < MU; ++u) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 float v[4] = {acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]};
@@ -482,7 +482,7 @@ __device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4
         // features per lane: one pass stores all 16 rows, 64 contiguous bytes each
         const int col = col_base / 2 + (lane & 3) * 8;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < MU; ++u) {
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const f32x4& g = acc[u][t];

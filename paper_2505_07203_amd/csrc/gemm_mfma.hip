@@ -3,7 +3,7 @@
 //   C[M, N] = A[M, K] * W[N, K]^T        A: activations (token-major), W: weights in the
 //                                        checkpoint layout [out, in]; both K-contiguous.
 //
-// What bounds it: the board's power limit.  These GEMMs keep the matrix pipe busy 80-85 % of their cycles, and
+// What bounds it: the board's power limit.  These GEMMs keep the matrix pipe busy 64-72 % of their cycles (counters), and
 // the clock the board grants (1.6-1.9 GHz of a nominal 2.4) falls with every joule spent per flop, so the design
 // minimises energy per flop, not instruction slots:
 //  * v_mfma_f32_16x16x32_bf16.  A bare loop of it on random operands sustains 2.1-2.2 PFLOP/s on this board at
@@ -61,22 +61,30 @@ constexpr int NUNIT = 5;                           // ring of five units: the wh
 constexpr int SMEM_BYTES = NUNIT * UNIT_BYTES;
 constexpr int NT_BF16 = 512;                       // eight wavefronts (the FP8 kernel keeps gemm::NTHREADS = 256)
 
-template <int EPI>
+// MU = 16-row groups per wavefront patch: 8 (256-row block tile, the form described above) or 4 (128-row block tile:
+// wavefront patches of 64 x 64, a slice is two phases of 16 MFMAs with the hand-over barrier behind the first, the A
+// unit is half full).  Every output element still is ONE fp32 accumulator running over K in steps of 32 in the same
+// order, so the two forms give the same bits, and the launcher may pick by tile count alone: launches whose 256-row
+// tiles would leave compute units idle (short requests, N of 4096-5120) take the 128-row form.
+template <int EPI, int MU>
 __global__ void __launch_bounds__(NT_BF16) gemm_bf16_mfma_kernel(const GemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int BM_ = 32 * MU;                   // block tile rows
+    constexpr int NA = MU / 2;                     // global->LDS loads per wavefront for an A unit (W: always 4)
 
     const int total = p.mt * p.nt;
     const int per_xcd = (total + 7) >> 3;
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int li = xcd * per_xcd + local;
     if (local >= per_xcd || li >= total) return;
-    const int group_sz = GROUP_M * p.nt;
+    constexpr int GM = MU == 8 ? GROUP_M : 2 * GROUP_M;       // M-tiles per group: 1024 rows either way
+    const int group_sz = GM * p.nt;
     const int g = li / group_sz;
     const int within = li - g * group_sz;
-    const int gm_this = min(GROUP_M, p.mt - g * GROUP_M);
+    const int gm_this = min(GM, p.mt - g * GM);
     const int tn = within / gm_this;
-    const int tm = g * GROUP_M + (within - tn * gm_this);
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int tm = g * GM + (within - tn * gm_this);
+    const int m0 = tm * BM_, n0 = tn * BN;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -91,30 +99,37 @@ __global__ void __launch_bounds__(NT_BF16) gemm_bf16_mfma_kernel(const GemmParam
         (void*)(p.A + (int64_t)m0 * p.lda + k0), 0, (int)(uint32_t)(a_bytes > 0xffffffffull ? 0xffffffffull : a_bytes), 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(p.W + (int64_t)n0 * p.ldw + k0), 0, (int)(uint32_t)(w_bytes > 0xffffffffull ? 0xffffffffull : w_bytes), 0x00020000);
-    uint32_t voa[4], vow[4];
+    uint32_t voa[4] = {0, 0, 0, 0}, vow[4];      // (voa: NA entries used)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = (wave * 4 + i) * 8 + (lane >> 3);
         const int lseg = (lane & 7) ^ ((row >> 1) & 7);
-        voa[i] = (uint32_t)row * (uint32_t)(p.lda * 2) + lseg * 16;
         vow[i] = (uint32_t)row * (uint32_t)(p.ldw * 2) + lseg * 16;
     }
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int row = (wave * NA + i) * 8 + (lane >> 3);
+        const int lseg = (lane & 7) ^ ((row >> 1) & 7);
+        voa[i] = (uint32_t)row * (uint32_t)(p.lda * 2) + lseg * 16;
+    }
     const int KT = p.K / BK;
-    // load i_ (0..3) of this wavefront's share of the A (is_w_ = 0) or W unit of slice slice_, into ring position pos_
+    // load i_ (W: 0..3, A: 0..NA-1) of this wavefront's share of the A (is_w_ = 0) or W unit of slice slice_, into ring
+    // position pos_
 #define PO_DMA(is_w_, slice_, pos_, i_)                                                                              \
     {                                                                                                                  \
-        unsigned char* d_ = smem + (pos_) * UNIT_BYTES + (wave * 4 + (i_)) * 1024;                                     \
+        unsigned char* d_ = smem + (pos_) * UNIT_BYTES + (wave * ((is_w_) ? 4 : NA) + (i_)) * 1024;                    \
         __builtin_amdgcn_raw_ptr_buffer_load_lds((is_w_) ? rw : ra, (__attribute__((address_space(3))) void*)d_, 16,   \
-                                                 (is_w_) ? vow[(i_)] : voa[(i_)], min((slice_), KT - 1) * (BK * 2), 0, 0); \
+                                                 (is_w_) ? vow[(i_)] : voa[(i_)],                    \
+                                                 min((slice_), KT - 1) * (BK * 2), 0, 0);                              \
     }
     int f_off[2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) f_off[ks] = l15 * 128 + (((ks * 4 + l4) ^ ((l15 >> 1) & 7)) << 4);
-    const int a_base = wm * 128 * 128, w_base = wn * 64 * 128;
+    const int a_base = wm * (MU * 16) * 128, w_base = wn * 64 * 128;
 
-    f32x4 acc[8][4];
+    f32x4 acc[MU][4];
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
+    for (int u = 0; u < MU; ++u)
 #pragma unroll
         for (int t = 0; t < 4; ++t) acc[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -122,8 +137,9 @@ __global__ void __launch_bounds__(NT_BF16) gemm_bf16_mfma_kernel(const GemmParam
 #pragma unroll
     for (int u4 = 0; u4 < 4; ++u4)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) PO_DMA(u4 & 1, u4 >> 1, u4, i)
-    asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");      // slice 0 has landed
+        for (int i = 0; i < ((u4 & 1) ? 4 : NA); ++i) PO_DMA(u4 & 1, u4 >> 1, u4, i)
+    if (MU == 8) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");      // slice 0 has landed
+    else asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
     bf16x8 A0[4], A1[4], W0[4], W1[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -147,7 +163,7 @@ __global__ void __launch_bounds__(NT_BF16) gemm_bf16_mfma_kernel(const GemmParam
         } else if (m < nra_ + nrw_) {                                                                                 \
             WN[(m - nra_) & 3] = *(const bf16x8*)((uw_) + ((m - nra_) & 3) * 2048 + f_off[rwk_]);  \
             __builtin_amdgcn_sched_barrier(0);                                                                        \
-        } else if ((DMA_) && m < nra_ + nrw_ + 4) {                                                                   \
+        } else if ((DMA_) && m < nra_ + nrw_ + ((dw_) ? 4 : NA)) {                                                    \
             PO_DMA(dw_, ds_, dp_, (m - nra_ - nrw_) & 3)                                         \
             __builtin_amdgcn_sched_barrier(0);                                                                        \
         }                                                                                                             \
@@ -161,16 +177,25 @@ __global__ void __launch_bounds__(NT_BF16) gemm_bf16_mfma_kernel(const GemmParam
         const unsigned char* uw = smem + pw * UNIT_BYTES + w_base;
         const unsigned char* ua1 = smem + pa1 * UNIT_BYTES + a_base;
         const unsigned char* uw1 = smem + pw1 * UNIT_BYTES + w_base;
-        // phase 0: k-step 0, rows 0-63 | reads A(k0, rows 64-127) and W(k1)
-        PO_PHASE(A0, W0, 0, 1, A1, ua, 1, 0, 1, W1, uw, 1, 0, 0, 0, 0)
-        // phase 1: k-step 0, rows 64-127 | reads A(k1, rows 0-63); loads A(s+2) into the position W(s-1) left
-        PO_PHASE(A1, W0, 1, 1, A0, ua, 0, 1, 0, W1, uw, 1, 1, 0, s + 2, (pa + 4 >= NUNIT ? pa + 4 - NUNIT : pa + 4))
-        // phase 2: k-step 1, rows 0-63 | reads A(k1, rows 64-127)
-        PO_PHASE(A0, W1, 0, 1, A1, ua, 1, 1, 0, W0, uw, 0, 0, 0, 0, 0)
-        // hand-over: slice s+1 has landed (all but the 4 youngest loads), every LDS read of slice s is done
-        asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        // phase 3: k-step 1, rows 64-127 | reads W(k0) and A(k0, rows 0-63) of slice s+1; loads W(s+2) into A(s)'s position
-        PO_PHASE(A1, W1, 1, 1, A0, ua1, 0, 0, 1, W0, uw1, 0, 1, 1, s + 2, pa)
+        if constexpr (MU == 8) {
+            // phase 0: k-step 0, rows 0-63 | reads A(k0, rows 64-127) and W(k1)
+            PO_PHASE(A0, W0, 0, 1, A1, ua, 1, 0, 1, W1, uw, 1, 0, 0, 0, 0)
+            // phase 1: k-step 0, rows 64-127 | reads A(k1, rows 0-63); loads A(s+2) into the position W(s-1) left
+            PO_PHASE(A1, W0, 1, 1, A0, ua, 0, 1, 0, W1, uw, 1, 1, 0, s + 2, (pa + 4 >= NUNIT ? pa + 4 - NUNIT : pa + 4))
+            // phase 2: k-step 1, rows 0-63 | reads A(k1, rows 64-127)
+            PO_PHASE(A0, W1, 0, 1, A1, ua, 1, 1, 0, W0, uw, 0, 0, 0, 0, 0)
+            // hand-over: slice s+1 has landed (all but the 4 youngest loads), every LDS read of slice s is done
+            asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            // phase 3: k-step 1, rows 64-127 | reads W(k0) and A(k0, rows 0-63) of slice s+1; loads W(s+2) into A(s)'s position
+            PO_PHASE(A1, W1, 1, 1, A0, ua1, 0, 0, 1, W0, uw1, 0, 1, 1, s + 2, pa)
+        } else {
+            // phase 0: k-step 0 | reads A(k1) and W(k1); loads A(s+2) into the position W(s-1) left
+            PO_PHASE(A0, W0, 0, 1, A1, ua, 0, 1, 1, W1, uw, 1, 1, 0, s + 2, (pa + 4 >= NUNIT ? pa + 4 - NUNIT : pa + 4))
+            // hand-over: slice s+1 has landed (all but the NA youngest loads), every LDS read of slice s is done
+            asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            // phase 1: k-step 1 | reads A(k0) and W(k0) of slice s+1; loads W(s+2) into A(s)'s position
+            PO_PHASE(A1, W1, 0, 1, A0, ua1, 0, 0, 1, W0, uw1, 0, 1, 1, s + 2, pa)
+        }
         pa = pa1;
     }
 #undef PO_PHASE
@@ -180,9 +205,9 @@ __global__ void __launch_bounds__(NT_BF16) gemm_bf16_mfma_kernel(const GemmParam
     if (EPI == EPI_PARTIAL) {
         GemmParams q = p;
         q.dst = (bf16_t*)((float*)p.dst + (int64_t)blockIdx.y * p.ldr);
-        tile_epilogue16<EPI>(q, acc, smem, m0, n0, wave, lane);
+        tile_epilogue16<EPI, MU>(q, acc, smem, m0, n0, wave, lane);
     } else {
-        tile_epilogue16<EPI>(p, acc, smem, m0, n0, wave, lane);
+        tile_epilogue16<EPI, MU>(p, acc, smem, m0, n0, wave, lane);
     }
 }
 
@@ -268,17 +293,37 @@ __global__ void __launch_bounds__(256) splitk_reduce_silu_kernel(const float* __
     H[(int64_t)row * ldh + f] = f2bf(silu_f(g) * u);
 }
 
-template <int EPI>
-void launch_t(const GemmParams& p, hipStream_t s, int splits = 1) {
+// 256-row or 128-row block tiles: the cheaper by rounds of tiles over the 256 compute units, a 128-row tile counted
+// as 0.66 of a 256-row one.  Measured: 0.51-0.55 in launches of one round (O- and down projections of up to 2048
+// rows: 185 against 248 us at 1920 rows), 0.63-0.68 in launches of many rounds (gate/up: every tile streams a whole W
+// slice for half the rows), where the 256-row form stays the better one unless it wastes most of a round.  Same bits
+// either way.
+constexpr double COST_128_ROW_TILE = 0.66;
+double cost_256(int64_t M, int N) { return (double)((((M + 255) / 256) * ((N + BN - 1) / BN) + 255) / 256); }
+double cost_128(int64_t M, int N) {
+    return COST_128_ROW_TILE * (double)((((M + 127) / 128) * ((N + BN - 1) / BN) + 255) / 256);
+}
+bool prefer_128_row_tiles(int64_t M, int N) { return cost_128(M, N) < cost_256(M, N); }
+
+template <int E2, int M2>
+void launch_mu(GemmParams p, hipStream_t s, int splits) {
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI>,
+        (void)hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<E2, M2>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
         attr_set = true;
     }
+    p.mt = (p.M + 32 * M2 - 1) / (32 * M2);
     const int total = p.mt * p.nt;
     const int per_xcd = (total + 7) / 8;
-    hipLaunchKernelGGL(gemm_bf16_mfma_kernel<EPI>, dim3((unsigned)(per_xcd * 8), (unsigned)splits), dim3(NT_BF16), SMEM_BYTES, s, p);
+    hipLaunchKernelGGL((gemm_bf16_mfma_kernel<E2, M2>), dim3((unsigned)(per_xcd * 8), (unsigned)splits), dim3(NT_BF16),
+                       SMEM_BYTES, s, p);
+}
+
+template <int EPI>
+void launch_t(const GemmParams& p, hipStream_t s, int splits = 1) {
+    if (EPI != EPI_PARTIAL && prefer_128_row_tiles(p.M, p.N)) launch_mu<EPI, 4>(p, s, splits);
+    else launch_mu<EPI, 8>(p, s, splits);
 }
 
 GemmParams base_params(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, int64_t M, int N, int K) {
@@ -296,6 +341,8 @@ GemmParams base_params(const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ld
 
 // K must be a multiple of 64 (whole slices), N of 64 (the epilogues work on 64-column patches).
 bool gemm_mfma_supported(int N, int K) { return K > 0 && K % 64 == 0 && N > 0 && N % 64 == 0; }
+
+double gemm_mfma_launch_cost(int64_t M, int N) { return prefer_128_row_tiles(M, N) ? cost_128(M, N) : cost_256(M, N); }
 
 void launch_gemm_mfma(int epi, const bf16_t* A, int64_t lda, const bf16_t* W, int64_t ldw, bf16_t* C, int64_t ldc,
                       const bf16_t* bias, const bf16_t* R, int64_t ldr, int64_t M, int N, int K, hipStream_t s) {

@@ -230,33 +230,26 @@ struct PhaseTimer {
     }
 };
 
-// Rows per launch of a chunk loop.  The MFMA GEMM works in 256 x 256 tiles, one per CU at a time, so a
-// launch costs ceil(tiles / 256) rounds of its K-loop: among the multiples of 256 rows up to max_rows this
-// picks the one with the least such cost per row, summed over the GEMMs of the loop (ties: the larger).
-// Results do not depend on the choice (row results are independent of the other rows of a launch); only
-// the buffers' capacity (max_rows) binds it.
+// Rows per launch of a chunk loop.  The MFMA GEMM works in tiles of 256 (or 128) rows x 256 columns, one per CU at a
+// time, so a launch costs whole rounds of tiles over the 256 CUs (gemm_mfma_launch_cost): among max_rows and the
+// multiples of 256 rows below it this picks the one with the least such cost per row, summed over the GEMMs of the loop (ties:
+// the larger).  Results do not depend on the choice (row results are independent of the other rows of a launch);
+// only the buffers' capacity (max_rows) binds it.
 struct GemmCols {
     int64_t n_cols, k;
 };
 int64_t pick_chunk_rows(int64_t max_rows, std::initializer_list<GemmCols> gemms) {
     if (max_rows < 512) return max_rows;
+    auto cost_per_row = [&](int64_t rows) {
+        double cost = 0;
+        for (const GemmCols& g : gemms) cost += gemm_mfma_launch_cost(rows, (int)g.n_cols) * (double)g.k;
+        return cost / (double)rows;
+    };
     int64_t best = max_rows;
-    double best_cost = -1;
+    double best_cost = cost_per_row(max_rows);
     for (int64_t m = max_rows / 256; m >= 1; --m) {
-        double cost = 0;
-        for (const GemmCols& g : gemms) {
-            const int64_t tiles = m * ((g.n_cols + 255) / 256);
-            cost += (double)((tiles + 255) / 256) * (double)g.k;
-        }
-        cost /= (double)m;
-        if (best_cost < 0 || cost < best_cost * (1 - 1e-9)) { best_cost = cost; best = m * 256; }
-    }
-    // (a capacity that is not a multiple of 256 is kept when no multiple below it does better per row)
-    if (max_rows % 256) {
-        double cost = 0;
-        const int64_t mt = (max_rows + 255) / 256;
-        for (const GemmCols& g : gemms) cost += (double)((mt * ((g.n_cols + 255) / 256) + 255) / 256) * (double)g.k;
-        if (cost / ((double)max_rows / 256.0) <= best_cost) best = max_rows;
+        const double cost = cost_per_row(m * 256);
+        if (cost < best_cost * (1 - 1e-9)) { best_cost = cost; best = m * 256; }
     }
     return best;
 }

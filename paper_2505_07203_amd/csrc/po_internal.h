@@ -110,6 +110,9 @@ int launch_attention_mfma_split(const bf16_t* q, const bf16_t* k, const bf16_t* 
                                 size_t scratch_bytes, bool launch, const bf16_t* k2, const bf16_t* vt2, int64_t ldv2,
                                 int64_t n2, bool q_prescaled, hipStream_t s);
 bool gemm_mfma_supported(int N, int K);
+// Time of one bf16 GEMM launch of M rows x N columns in units of (one 256 x 256 tile's K loop): rounds of tiles over
+// the compute units with the tile height the launcher will pick.
+double gemm_mfma_launch_cost(int64_t M, int N);
 // C = A W^T + R for a GEMM with few rows, the reduction over K split between workgroups (a GEMM with few
 // output tiles leaves most of the chip idle and every workgroup streaming a whole K range of both operands):
 // split s of `splits` writes its fp32 partial tile sums to part[s][M][N], a second kernel adds them up in

@@ -275,6 +275,41 @@ def test_gemm_qkv_rope_benchmark_shape(shape):
         assert e <= 6e-3, (name, e)
 
 
+def test_gemm_tile_heights_give_the_same_bits():
+    """The bf16 GEMM picks 128-row or 256-row block tiles by how many tiles a launch has.  Every output is one fp32
+    accumulator running over K in the same order in both forms, so the rows of a short launch (128-row tiles) must
+    equal, bit for bit, the same rows inside a long launch (256-row tiles) -- what the chunk, prefix-cache and packing
+    invariances of the path rest on (Section 4.2: chunking leaves the result unchanged).  All three fused epilogues,
+    a ragged row count included."""
+    rng = np.random.default_rng(77)
+    big, small = 4096, 1100                                          # 16 x 16 tiles of 256 rows; 9 x 16 tiles of 128
+    a, _ = bf16_dev(rng.standard_normal((big, 4096), dtype=np.float32))
+    w, _ = bf16_dev(rng.standard_normal((4096, 4096), dtype=np.float32) * 0.02)
+    r, _ = bf16_dev(rng.standard_normal((big, 4096), dtype=np.float32))
+    full = B.po_op_linear(a, w, residual=r)
+    part = B.po_op_linear(a[:small].contiguous(), w, residual=r[:small].contiguous())
+    assert torch.equal(full[:small], part)
+    # gate/up + SiLU-multiply: 256 rows x 112 column tiles take the 128-row form, 4096 rows the 256-row form
+    wg, _ = bf16_dev(rng.standard_normal((14336, 4096), dtype=np.float32) * 0.02)
+    wu, _ = bf16_dev(rng.standard_normal((14336, 4096), dtype=np.float32) * 0.02)
+    wgu = B.po_op_pack_gate_up(wg, wu)
+    full = B.po_op_gate_up_silu(a, wgu)
+    part = B.po_op_gate_up_silu(a[:200].contiguous(), wgu)
+    assert torch.equal(full[:200], part)
+    # QKV + RoPE + transposed V: 1000 rows x 24 column tiles against 8192 rows
+    Hq, Hkv, hd = 32, 8, 128
+    a8, _ = bf16_dev(rng.standard_normal((8192, 4096), dtype=np.float32))
+    wq, _ = bf16_dev(rng.standard_normal((Hq * hd, 4096), dtype=np.float32) * 0.02)
+    wk, _ = bf16_dev(rng.standard_normal((Hkv * hd, 4096), dtype=np.float32) * 0.02)
+    wv, _ = bf16_dev(rng.standard_normal((Hkv * hd, 4096), dtype=np.float32) * 0.02)
+    cos, sin = B.po_op_rope_table(8192, hd, 500000.0)
+    wqkv, _ = B.po_op_pack_qkv(wq, wk, wv, Hq, Hkv, hd)
+    c = B.attention_q_scale(hd)
+    q, k, vt = B.po_op_qkv_rope(a8, wqkv, None, cos, sin, Hq, Hkv, hd, pos0=0, q_scale=c)
+    q2, k2, vt2 = B.po_op_qkv_rope(a8[:1000].contiguous(), wqkv, None, cos, sin, Hq, Hkv, hd, pos0=0, q_scale=c)
+    assert torch.equal(q[:1000], q2) and torch.equal(k[:1000], k2) and torch.equal(vt[:, :1000], vt2[:, :1000])
+
+
 # ------------------------------------------------------------------ whole path at 32768 tokens
 
 def test_full_path_32k_bitwise_properties():
