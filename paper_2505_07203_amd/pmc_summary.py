@@ -28,9 +28,9 @@ KERNEL_SOURCES = ("gemm_mfma.hip", "gemm_common.h", "attn_mfma.hip", "kernels_ba
 # kernel class -> substring of the kernel's demangled name
 CLASSES = collections.OrderedDict([
     ("attention", "attn_fwd64_kernel"),
-    ("gate_up", "gemm_bf16_mfma_kernel<2>"),
-    ("residual", "gemm_bf16_mfma_kernel<1>"),
-    ("qkv", "gemm_bf16_mfma_kernel<3>"),
+    ("gate_up", "gemm_bf16_mfma_kernel<2, "),          # either tile height
+    ("residual", "gemm_bf16_mfma_kernel<1, "),
+    ("qkv", "gemm_bf16_mfma_kernel<3, "),
     ("attention_redo", "attn_fwd_kernel<128, 1, 8, false>"),
     ("rmsnorm", "rmsnorm_bf16_vec_kernel"),
     ("lm_head", "lm_head_kernel"),
