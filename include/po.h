@@ -325,6 +325,16 @@ po_status po_set_lazy_last_layer(po_ctx* ctx, int32_t on);
  * nor between a request run alone and the same rows computed as part of a larger chunk. */
 po_status po_set_few_rows_split(po_ctx* ctx, int32_t on);
 
+/* Float32 contexts only (PO_ERR_BAD_CONFIG otherwise); off by default.  When on, every tensor the forward pass keeps
+ * between two operators -- both normalised activations, the rotated Q and K, V, the attention output, the gated MLP
+ * intermediate, the residual stream after each update, the normalised last row -- is rounded to the nearest bf16 value
+ * (ties to even) as soon as it is written; arithmetic inside an operator and the logits stay float32.  This is what a
+ * bf16 model's storage does to the definition's result with no other source of error, measured by comparing a run
+ * with the mode on against one with it off: the yardstick for the bf16 path at configurations too large for a
+ * float64 CPU run (Section 4.2 of the paper claims only that chunking changes nothing; storage precision is the
+ * model's own).  Host call, takes effect from the next request. */
+po_status po_set_storage_rounding(po_ctx* ctx, int32_t on);
+
 /* When on, po_prefill brackets the attention and GEMM launches with HIP events on its stream
  * so that po_get_stats can split the time per kernel class (adds event overhead; off by
  * default). */

@@ -38,7 +38,7 @@ EXPORTS = [
     "po_kv_cache_bytes", "po_attach_kv_cache", "po_prefill_prefix", "po_prefill_packed",
     "po_op_quantize_rows", "po_op_rmsnorm_quantize", "po_op_linear_fp8", "po_op_qkv_rope_fp8",
     "po_attach_kv_cache_slots", "po_kv_cache_match", "po_kv_cache_slot", "po_sched_pick_multi",
-    "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_op_linear_split", "po_sched_push_request", "po_op_attention_split",
+    "po_profile_jct", "po_engine_step", "po_set_few_rows_split", "po_set_storage_rounding", "po_op_linear_split", "po_sched_push_request", "po_op_attention_split",
     "po_sched_create", "po_sched_destroy", "po_sched_set_jct_model", "po_sched_fit_jct_model", "po_sched_push",
     "po_sched_size", "po_sched_pick", "po_sched_remove", "po_op_rope_static", "po_op_mfma_peak", "po_op_stream_copy",
 ]
@@ -101,6 +101,7 @@ def lib() -> C.CDLL:
     L.po_kv_cache_match.argtypes = [vp, vp, i64, C.POINTER(i64)]
     L.po_kv_cache_slot.argtypes = [vp, i32, vp, i64, C.POINTER(i64)]
     L.po_set_few_rows_split.argtypes = [vp, i32]
+    L.po_set_storage_rounding.argtypes = [vp, i32]
     L.po_engine_step.argtypes = [vp, vp, C.c_double, vp, i32, vp, vp, i32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64),
                                  C.POINTER(i32)]
     L.po_sched_push_request.argtypes = [vp, i64, vp, i64, vp, i32, C.c_double]
@@ -337,6 +338,9 @@ class Context:
     def po_set_few_rows_split(self, on: bool) -> None:
         check(lib().po_set_few_rows_split(self._h, 1 if on else 0))
 
+    def po_set_storage_rounding(self, on: bool) -> None:
+        check(lib().po_set_storage_rounding(self._h, 1 if on else 0))
+
     def po_set_lazy_last_layer(self, on: bool) -> None:
         check(lib().po_set_lazy_last_layer(self._h, 1 if on else 0))
 
@@ -363,9 +367,15 @@ class Context:
             pass
 
     # -- convenience: load a whole synthetic model from the seeded generator ----------------
-    def load_synthetic(self, seed: int, threads: int = 8) -> None:
+    def load_synthetic(self, seed: int, threads: int = 8, values_of=None) -> None:
+        """Seeded random-init weights of this context's configuration.  values_of=inputs.BF16 on a float32 context
+        loads the bf16 model's weight VALUES (generated and rounded as for the bf16 model, handed over as float32):
+        the same model evaluated in float32."""
         from . import inputs as I
-        for kind, layer, arr in I.iter_model_tensors(self.cfg, seed, threads=threads):
+        gen_cfg = self.cfg if values_of is None else self.cfg.replace(dtype=values_of)
+        for kind, layer, arr in I.iter_model_tensors(gen_cfg, seed, threads=threads):
+            if values_of is not None and self.cfg.dtype == I.F32 and arr.dtype == np.uint16:
+                arr = I.bf16_bits_to_f32(arr)
             self.po_load_tensor(kind, layer, arr)
         if not self.po_is_loaded():
             raise RuntimeError("model not fully loaded")

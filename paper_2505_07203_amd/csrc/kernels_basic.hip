@@ -464,6 +464,17 @@ void launch_fill_zero32(void* dst, size_t n_words, hipStream_t s) {
     hipLaunchKernelGGL(fill_zero32_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, s, (uint32_t*)dst, n_words);
 }
 
+// x[i] = float(bf16(x[i])), round to nearest even: what storing a float32 tensor as bf16 and reading it back does.
+__global__ void __launch_bounds__(256) round_bf16_f32_kernel(float* x, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) x[i] = bf2f(f2bf(x[i]));
+}
+
+void launch_round_bf16_f32(float* x, int64_t n, hipStream_t s) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(round_bf16_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, n);
+}
+
 void launch_vt_pad_zero(bf16_t* Vt, int rows, int64_t ldv, int64_t n, hipStream_t s) {
     const int pad = (int)(round_up64(n, 64) - n);
     if (pad <= 0 || rows <= 0) return;

@@ -175,6 +175,7 @@ struct po_ctx {
     hipEvent_t ev_start, ev_stop;
     bool phase_timing;
     bool split_few_rows;              // requests of few rows: split reductions for occupancy (not bit-identical)
+    bool store_round;                 // float32 contexts: tensors kept between operators are rounded to bf16 values
     bool lazy_last_layer;             // last layer: queries, attention rows and MLP only where the last token needs them
     // prefix K/V cache (caller-provided device memory): per layer K [cap, kvd], then V^T [kvd, ldvc]
     // (bf16) or V [cap, kvd] (fp32); see kv_slots
@@ -301,6 +302,9 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
     // bf16 path: the QKV epilogue hands the attention kernels Q times the softmax scale (in log2 units), applied in
     // fp32 before Q's one rounding, so that K Q^T is the exponent's argument as it comes out of the matrix pipe
     const float q_scale = attention_q_scale(hd);
+    // float32 path, second evaluation mode: every tensor kept between operators takes bf16 values (Section 4.2's
+    // claim is about chunking only; this mode measures what bf16 storage alone does at shapes no CPU run reaches)
+    const bool sr = dt == PO_F32 && c->store_round;
 
     c->ev_used = 0;
     PO_HIP(hipMemcpyAsync(d_tok, tokens, (size_t)total * 4, hipMemcpyHostToDevice, s));
@@ -371,6 +375,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                                      rows, d, m.rms_eps, s);
             else
                 launch_rmsnorm(dt, X + (size_t)c0 * d * esz, c->w + o.attn_norm, Xn, rows, d, m.rms_eps, s);
+            if (sr) launch_round_bf16_f32((float*)Xn, rows * d, s);
             PhaseTimer pt(c, PO_K_QKV);
             if (fp8) {
                 const size_t h_bytes = (size_t)L.chunk * F * esz;
@@ -406,6 +411,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                                   bqkv ? bqkv + (size_t)qd * esz : nullptr, nullptr, 0, rows, kvd, d, s);
                 launch_gemm_basic(dt, Xn, d, wqkv + (size_t)(qd + kvd) * d * esz, d, V + (size_t)c0 * kvd * esz, kvd,
                                   bqkv ? bqkv + (size_t)(qd + kvd) * esz : nullptr, nullptr, 0, rows, kvd, d, s);
+                if (sr) launch_round_bf16_f32((float*)(V + (size_t)c0 * kvd * esz), rows * kvd, s);
             }
         }
         if (dt == PO_F32) {
@@ -415,6 +421,10 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                 const size_t t0 = (size_t)p_reuse * (hd / 2);
                 launch_rope(dt, Q + (size_t)r0 * qd * esz, qd, rc + t0, rs + t0, nr, m.n_q_heads, hd, s);
                 launch_rope(dt, K + (size_t)r0 * kvd * esz, kvd, rc + t0, rs + t0, nr, m.n_kv_heads, hd, s);
+                if (sr) {
+                    launch_round_bf16_f32((float*)(Q + (size_t)r0 * qd * esz), nr * qd, s);
+                    launch_round_bf16_f32((float*)(K + (size_t)r0 * kvd * esz), nr * kvd, s);
+                }
             }
         }
         // Section 5.1: keep the K/V of the prefix, discard the suffix's with the layer.  Into the slot the
@@ -460,6 +470,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
             } else {
                 launch_attention_basic(dt, Qg, K + (size_t)g.start * kvd * esz, V + (size_t)g.start * kvd * esz, Qg,
                                        g.len, m.n_q_heads, m.n_kv_heads, hd, q_row0, s);
+                if (sr) launch_round_bf16_f32((float*)Qg, g.len * qd, s);     // (rows below q_row0 hold rounded Q: unchanged)
             }
         }
         // ---- position-wise part after attention, chunk by chunk, residual stream in place
@@ -564,14 +575,18 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                     PhaseTimer pt(c, PO_K_RESIDUAL);
                     launch_gemm_basic(dt, Oc, qd, c->w + o.wo, qd, Xc, d, nullptr, Xc, d, rows, d, qd, s);
                 }
+                if (sr) launch_round_bf16_f32((float*)Xc, rows * d, s);
                 launch_rmsnorm(dt, Xc, c->w + o.mlp_norm, Xn, rows, d, m.rms_eps, s);
+                if (sr) launch_round_bf16_f32((float*)Xn, rows * d, s);
                 {
                     PhaseTimer pt(c, PO_K_GATE_UP);
                     launch_gemm_basic(dt, Xn, d, c->w + o.wgu, d, GU, 2 * F, nullptr, nullptr, 0, rows, 2 * F, d, s);
                     launch_silu_mul(dt, GU, H, rows, F, s);
+                    if (sr) launch_round_bf16_f32((float*)H, rows * F, s);
                 }
                 PhaseTimer pt(c, PO_K_RESIDUAL);
                 launch_gemm_basic(dt, H, F, c->w + o.wd, F, Xc, d, nullptr, Xc, d, rows, d, F, s);
+                if (sr) launch_round_bf16_f32((float*)Xc, rows * d, s);
             }
         }
     }
@@ -580,6 +595,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
     for (int64_t j = 0; j < n_seg; ++j) {
         const int64_t r = gathered ? j : segs[j].start + segs[j].len - 1;
         launch_rmsnorm(dt, X + (size_t)r * d * esz, c->w + L.final_norm, ws + L.xn_last, 1, d, m.rms_eps, s);
+        if (sr) launch_round_bf16_f32((float*)(ws + L.xn_last), d, s);
         // nobody asked for the whole distribution: only the acceptable tokens' rows of the LM head
         const bool cand_only = !out_logits && n_cand > 0;
         launch_lm_head(dt, ws + L.xn_last, c->w + L.lm_head, d_logits, m.vocab_size, d,
@@ -701,6 +717,7 @@ po_status po_create(const po_model_config* cfg, int64_t max_input_len, int32_t m
     c->kv_tick = 0;
     c->kv_src = c->kv_dst = 0;
     c->split_few_rows = false;
+    c->store_round = false;
     c->ev_used = 0;
     memset(&c->stats, 0, sizeof(c->stats));
     c->stats.weights_bytes = c->lay.weights_bytes;
@@ -1202,6 +1219,13 @@ po_status po_profile_jct(po_ctx* c, int64_t max_len, int64_t step, int64_t* n_in
     }
     for (auto& sl : c->kv_slots) sl.tokens.clear();                          // the fake prefix serves nobody
     return st;
+}
+
+po_status po_set_storage_rounding(po_ctx* c, int32_t on) {
+    if (!c) return PO_ERR_INVALID_ARG;
+    if (c->cfg.dtype != PO_F32) return PO_ERR_BAD_CONFIG;
+    c->store_round = on != 0;
+    return PO_OK;
 }
 
 po_status po_set_few_rows_split(po_ctx* c, int32_t on) {

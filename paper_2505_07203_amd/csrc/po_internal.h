@@ -99,6 +99,7 @@ void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, i
                            int64_t N, int Hq, int Hkv, int hd, int64_t q_row0, int* redo, bool q_prescaled, hipStream_t s);
 // n 32-bit words of zeros (a kernel, not a memset node, so that it can be captured into a graph)
 void launch_fill_zero32(void* dst, size_t n_words, hipStream_t s);
+void launch_round_bf16_f32(float* x, int64_t n, hipStream_t s);
 // The same for query rows [q_row0, N) when they are few and the keys many: the key tiles of a query tile are
 // divided between workgroups (fp32 partial results in `scratch`, merged by a second kernel).  Sums are formed
 // in a different order than in launch_attention_mfma: equal to rounding, not bit for bit.  Returns the
