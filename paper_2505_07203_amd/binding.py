@@ -381,6 +381,24 @@ class Context:
             raise RuntimeError("model not fully loaded")
 
 
+def load_synthetic_models(contexts, seed: int, threads: int = 8, values_of=None) -> None:
+    """Context.load_synthetic for several contexts of ONE model shape at once (say a bf16 context and a float32
+    context that evaluates the same weight values): every tensor is generated once and handed to each context, which
+    halves the host time of tests that compare two evaluation paths."""
+    from . import inputs as I
+    ref = contexts[0].cfg
+    gen_cfg = ref if values_of is None else ref.replace(dtype=values_of)
+    for kind, layer, arr in I.iter_model_tensors(gen_cfg, seed, threads=threads):
+        for c in contexts:
+            a = arr
+            if c.cfg.dtype == I.F32 and arr.dtype == np.uint16:
+                a = I.bf16_bits_to_f32(arr)
+            c.po_load_tensor(kind, layer, a)
+    for c in contexts:
+        if not c.po_is_loaded():
+            raise RuntimeError("model not fully loaded")
+
+
 # ---- single-kernel entry points on torch device tensors (pointers only) ---------------------
 
 def _dt(t) -> int:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpo.so")
 SOURCES = ["po_api.hip", "kernels_basic.hip", "gemm_mfma.hip", "attn_mfma.hip", "po_sched.hip", "fp8_kernels.hip",
-           "gemm_fp8_mfma.hip", "peak_kernels.hip"]
+           "gemm_fp8_mfma.hip", "peak_kernels.hip", "f32_mfma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result"]

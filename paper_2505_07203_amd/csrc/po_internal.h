@@ -100,6 +100,13 @@ void launch_attention_mfma(const bf16_t* q, const bf16_t* k, const bf16_t* vt, i
 // n 32-bit words of zeros (a kernel, not a memset node, so that it can be captured into a graph)
 void launch_fill_zero32(void* dst, size_t n_words, hipStream_t s);
 void launch_round_bf16_f32(float* x, int64_t n, hipStream_t s);
+// float32 GEMM on the float32 matrix instruction; false (nothing launched) when K, the leading dimensions or the
+// pointers do not allow 16-byte loads
+bool launch_gemm_f32_mfma(const float* A, int64_t lda, const float* W, int64_t ldw, float* C, int64_t ldc, const float* bias,
+                          const float* R, int64_t ldr, int64_t M, int N, int K, hipStream_t s);
+// float32 attention on the float32 matrix instruction; false (nothing launched) when hd is neither 64 nor 128
+bool launch_attention_f32_mfma(const float* q, const float* k, const float* v, float* o, int64_t N, int Hq, int Hkv, int hd,
+                               int64_t q_row0, hipStream_t s);
 // The same for query rows [q_row0, N) when they are few and the keys many: the key tiles of a query tile are
 // divided between workgroups (fp32 partial results in `scratch`, merged by a second kernel).  Sums are formed
 // in a different order than in launch_attention_mfma: equal to rounding, not bit for bit.  Returns the

@@ -12,8 +12,8 @@ BOTH, the rule of the stored fixtures, and name the same top-1 whenever the two 
 a lead of at least 5 % of the range each.  Section 4.2 of the paper claims only that chunking changes nothing, which
 the bitwise tests cover; storage precision is the model's own.
 
-These tests print progress lines past pytest's capture: each runs one to three minutes, most of it weight generation
-on the host and the float32 kernels.
+These tests print progress lines past pytest's capture: each runs up to a minute, most of it weight generation on the
+host.
 """
 import os
 import sys
@@ -38,24 +38,29 @@ def _need_gpu():
         pytest.skip("needs a GPU")
 
 
-def _run(cfg, wseed, tokens, cand, chunk, say, what, both_modes=False):
-    """-> [(logits, candidate log-probs)] of one prefill; float32 contexts with both_modes: nothing rounded, then bf16
-    storage rounding"""
+def _run(cfg, wseed, tokens, cand, chunk, say, both_modes):
+    """-> [(logits, candidate log-probs)] of the bf16 path, the float32 path and (both_modes) the float32 path with
+    bf16 storage rounding, all on the same weight values: the two contexts live side by side and every tensor is
+    generated once"""
     t0 = time.perf_counter()
-    ctx = B.Context(cfg, len(tokens), chunk)
+    ctxs = [B.Context(cfg, len(tokens), chunk), B.Context(cfg.replace(dtype=I.F32), len(tokens), chunk)]
     out = []
     try:
-        ctx.load_synthetic(wseed, threads=16, values_of=I.BF16)         # (the bf16 model's weights for both paths)
-        say(f"{what}: weights loaded, {time.perf_counter() - t0:.0f} s")
-        for mode in ((False, True) if both_modes else (False,)):
+        B.load_synthetic_models(ctxs, wseed, threads=16, values_of=I.BF16)
+        say(f"weights loaded into both contexts, {time.perf_counter() - t0:.0f} s")
+        for what, ctx, mode in (("bf16 path", ctxs[0], False), ("float32 path", ctxs[1], False),
+                                ("float32 path with bf16 storage rounding", ctxs[1], True)):
+            if mode and not both_modes:
+                continue
             if mode:
                 ctx.po_set_storage_rounding(True)
             t0 = time.perf_counter()
             z, lp = ctx.po_prefill(tokens, cand, want_logits=True)
-            say(f"{what}{' with bf16 storage rounding' if mode else ''}: prefill done, {time.perf_counter() - t0:.1f} s")
+            say(f"{what}: prefill done, {time.perf_counter() - t0:.1f} s")
             out.append((z.astype(np.float64), lp.astype(np.float64)))
     finally:
-        ctx.po_destroy()
+        for ctx in ctxs:
+            ctx.po_destroy()
         torch.cuda.empty_cache()
     return out
 
@@ -79,10 +84,10 @@ def test_bf16_path_against_float32_path(workload, req, layers, capsys):
     n = int(I.workload_lengths(workload)[req])
     tokens = I.make_tokens(cfg, w["tseed"], n, request=req)
     cand = I.label_ids(cfg)
-    (z16, lp16), = _run(cfg, w["wseed"], tokens, cand, w["chunk"], say, "bf16 path")
     deep = cfg.n_layers > 4
-    runs = _run(cfg.replace(dtype=I.F32), w["wseed"], tokens, cand, w["chunk"], say, "float32 path", both_modes=deep)
-    (z32, lp32), (z32s, lp32s) = runs if deep else (runs[0], runs[0])     # shallow stack: the plain 2e-2 bar, one mode
+    runs = _run(cfg, w["wseed"], tokens, cand, w["chunk"], say, both_modes=deep)
+    (z16, lp16), (z32, lp32) = runs[:2]
+    z32s, lp32s = runs[2] if deep else runs[1]                            # shallow stack: the plain 2e-2 bar, one mode
     for z in (z16, z32, z32s):
         assert np.all(np.isfinite(z))
     scale = float(np.max(np.abs(z32)))

@@ -72,6 +72,23 @@ def test_attention_32k_sampled_rows(prescaled):
     assert np.max(err) <= 1.5e-2
 
 
+def test_attention_float32_32k_sampled_rows():
+    """The float32 path's attention (the float32 matrix instruction) at the benchmark's length and head layout: it
+    stands in for the float64 definition at whole configurations, so it is held to float32 rounding here."""
+    N, Hq, Hkv, hd = 32768, 32, 8, 128
+    rng = np.random.default_rng(32769)
+    q, k, v = (rng.standard_normal((N, h, hd), dtype=np.float32) for h in (Hq, Hkv, Hkv))
+    rows = np.array([0, 1, 31, 32, 33, 63, 64, 127, 128, 129, 255, 4095, 4096, 12345, 16383, 16384, 20000, 32639, 32640,
+                     32671, 32672, 32735, 32766, 32767])
+    ref = O.causal_gqa_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), query_rows=rows)
+    dq = torch.from_numpy(q).cuda()
+    got = B.po_op_attention(dq, torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda())
+    got = got[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    err = np.max(np.abs(got - ref), axis=(1, 2)) / np.max(np.abs(ref))
+    print("float32 attention N=32768, per sampled row:", " ".join(f"{r}:{e:.1e}" for r, e in zip(rows, err)))
+    assert np.max(err) <= 2e-5
+
+
 @pytest.mark.parametrize("prescaled", [False, True], ids=["q", "q_prescaled"])
 def test_attention_large_scores_renormalise(prescaled):
     """Scores far above the first key block's maximum: the running sums pass the

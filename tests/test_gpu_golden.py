@@ -116,8 +116,13 @@ def test_against_stored_oracle(path):
     cand = doc["cand_ids"]
     lens = [r["len"] for r in doc["requests"]]
     ctx = B.Context(cfg, max(lens), doc["mlp_chunk"])
+    # single-request bf16 fixtures are also run through the float32 path (below): its context is loaded alongside,
+    # from the same generated tensors
+    ctx32 = None
+    if not f32 and len(doc["requests"]) == 1:
+        ctx32 = B.Context(cfg.replace(dtype=I.F32), max(lens), doc["mlp_chunk"])
     try:
-        ctx.load_synthetic(doc["wseed"], threads=16)
+        B.load_synthetic_models([ctx] + ([ctx32] if ctx32 else []), doc["wseed"], threads=16)
         singles = []
 
         def _storage_dev(r):
@@ -162,18 +167,20 @@ def test_against_stored_oracle(path):
             zp, lpp = ctx.po_prefill_packed(toks, cand, want_logits=True)
             for i, (z, lp) in enumerate(singles):
                 assert np.array_equal(zp[i], z) and np.array_equal(lpp[i], lp), (doc["case"], i)
+    except BaseException:
+        if ctx32:
+            ctx32.po_destroy()
+        raise
     finally:
         ctx.po_destroy()
-    if not f32 and len(doc["requests"]) == 1:
+    if ctx32:
         # The float32 path in its two evaluation modes against the oracle's two evaluations of the same fixture: nothing
         # rounded against "exact", every tensor kept between operators rounded to bf16 (po_set_storage_rounding)
         # against "stored_bf16".  This anchors test_gpu_fullconfig.py, where the same two modes stand in for the
         # oracle at configurations no float64 CPU run reaches, at full depth (2048 / 1024 tokens) and at full length
-        # (32768, 131072, 16384 tokens on 1-2 layers).
-        c32 = cfg.replace(dtype=I.F32)
-        ctx = B.Context(c32, max(lens), doc["mlp_chunk"])
+        # (32768, 131072, 16384 tokens on 1-2 layers).  The context holds the bf16 model's weight values.
+        ctx = ctx32
         try:
-            ctx.load_synthetic(doc["wseed"], threads=16, values_of=I.BF16)        # the bf16 model's weight values
             r = doc["requests"][0]
             t = I.make_tokens(cfg, doc["tseed"], r["len"], request=0)
             z, lp = ctx.po_prefill(t, cand, want_logits=True)

@@ -196,7 +196,9 @@ def test_op_gate_up_silu(dtype, M, F, K):
 
 @pytest.mark.parametrize("dtype,N,Hq,Hkv,hd", [(I.BF16, 1, 4, 2, 128), (I.BF16, 63, 4, 4, 64), (I.BF16, 257, 8, 2, 128),
                                                 (I.BF16, 1000, 16, 2, 64), (I.BF16, 640, 5, 1, 128),
-                                                (I.F32, 200, 4, 2, 64), (I.F32, 70, 2, 1, 128)])
+                                                (I.F32, 200, 4, 2, 64), (I.F32, 70, 2, 1, 128), (I.F32, 1, 4, 2, 128),
+                                                (I.F32, 333, 8, 2, 128), (I.F32, 129, 4, 4, 64), (I.F32, 1000, 5, 1, 128),
+                                                (I.F32, 97, 2, 2, 32)])
 def test_op_attention(dtype, N, Hq, Hkv, hd):
     rng = np.random.default_rng(N)
     q, k, v = (rand_stored(rng, (N, h, hd), dtype) for h in (Hq, Hkv, Hkv))
