@@ -160,7 +160,7 @@ def _oracle_fp8(cfg, wseed, tokens):
     return z_s, z_e, z_b
 
 
-@pytest.mark.parametrize("cfg,n,chunk", [(FP8_SMALL, 300, 256), (FP8_SMALL_128, 513, 512), (FP8_WIDE, 700, 512)])
+@pytest.mark.parametrize("cfg,n,chunk", [(FP8_SMALL, 300, 256), (FP8_SMALL_128, 513, 512), (FP8_WIDE, 320, 256)])
 def test_fp8_full_path_against_the_oracle(cfg, n, chunk):
     """Tolerance: a per-token dynamic scale and a 4-bit significand turn any 2^-9 difference in an activation
     into code flips, so two correct evaluations differ by more than the bf16 bar.  The distance between the

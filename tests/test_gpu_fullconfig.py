@@ -72,8 +72,8 @@ def _dist(za, zb, scale):
 @pytest.mark.parametrize("workload,req,layers", [
     ("llama8b_32k", 0, None),        # the benchmark configuration in full: 32 layers x 32768 tokens
     ("qwen32b_8x16k", 0, None),      # one of its 8 requests in full: 64 layers x 16384 tokens
-    ("llama8b_128k", 0, 4),          # 4 layers x 131072 tokens, all query rows
-], ids=["llama8b_32k_full", "qwen32b_16k_full_depth", "llama8b_128k_4_layers"])
+    ("llama8b_128k", 0, None),       # the long-input configuration in full: 32 layers x 131072 tokens
+], ids=["llama8b_32k_full", "qwen32b_16k_full_depth", "llama8b_128k_full"])
 def test_bf16_path_against_float32_path(workload, req, layers, capsys):
     def say(msg):
         with capsys.disabled():
