@@ -2,6 +2,8 @@
 #pragma once
 #include "po_internal.h"
 
+#include <type_traits>
+
 namespace po {
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
@@ -36,7 +38,9 @@ struct GemmParams {
                          // scale in log2 units when the attention kernel expects Q scaled; K and V are never scaled)
 };
 
-__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+// g * sigmoid(g).  The reciprocal is the hardware's (v_rcp_f32, 1 ulp) instead of an IEEE division: the division expands
+// to ten dependent instructions per value, 64 values per lane in a gate/up tile's epilogue, which no MFMA overlaps.
+__device__ __forceinline__ float silu_f(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
 
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
     uint2 w;
@@ -347,55 +351,84 @@ __device__ __forceinline__ void tile_epilogue16(const GemmParams& p, const f32x4
     if (EPI == EPI_QKV_ROPE) {
         const int half = p.hd >> 1;
         const int cb = col_base;
+        // (bias or not, whole patch or ragged: decided once per patch, wavefront-uniform, outside the unrolled loops --
+        //  a test per element costs a scalar branch each, hundreds per patch, in a part of the kernel no MFMA overlaps)
         if (cb < p.qd + p.kvd) {
             const bool is_q = cb < p.qd;
             const float qs = is_q ? p.q_scale : 1.0f;
             const int c = is_q ? cb : cb - p.qd;
             const int head = c / p.hd;
             const int patch = (c - head * p.hd) >> 6;
+            auto qk_patch = [&](auto has_bias) {
+                constexpr bool HB = decltype(has_bias)::value;
+                float ba[2][4], bb[2][4];
+                if (HB) {
 #pragma unroll
-            for (int u = 0; u < MU; ++u) {
-                const int row = row_base + u * 16 + l15;
-                if (row >= p.M) continue;
-                const int64_t pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
-                bf16_t* drow = (is_q ? p.dst + (int64_t)row * p.qd : p.dst_k + (int64_t)row * p.kvd) + head * p.hd;
+                    for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int i0 = patch * 32 + t * 16 + 4 * l4;             // rotary index of register 0
-                    const float4 cs = *(const float4*)(p.rope_cos + pos * half + i0);
-                    const float4 sn = *(const float4*)(p.rope_sin + pos * half + i0);
-                    const float cv[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
-                    float lo[4], hi[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float a = acc[u][t][e], b = acc[u][t + 2][e];
-                        if (p.bias) { a += bf2f(p.bias[cb + t * 16 + 4 * l4 + e]); b += bf2f(p.bias[cb + 32 + t * 16 + 4 * l4 + e]); }
-                        lo[e] = (a * cv[e] - b * sv[e]) * qs;
-                        hi[e] = (b * cv[e] + a * sv[e]) * qs;
-                    }
-                    *(uint2*)(drow + i0) = pack4(lo[0], lo[1], lo[2], lo[3]);
-                    *(uint2*)(drow + half + i0) = pack4(hi[0], hi[1], hi[2], hi[3]);
+                        for (int e = 0; e < 4; ++e) {
+                            ba[t][e] = bf2f(p.bias[cb + t * 16 + 4 * l4 + e]);
+                            bb[t][e] = bf2f(p.bias[cb + 32 + t * 16 + 4 * l4 + e]);
+                        }
                 }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        } else {
-            // V patch: stored transposed, V^T[feature][position]; consecutive lanes are consecutive positions
-            const int f0 = cb - p.qd - p.kvd;
 #pragma unroll
-            for (int u = 0; u < MU; ++u) {
-                const int row = row_base + u * 16 + l15;
-                if (row >= p.M) continue;
-                bf16_t* dcol = p.dst_vt + p.pos0 + row;
+                for (int u = 0; u < MU; ++u) {
+                    const int row = row_base + u * 16 + l15;
+                    if (row >= p.M) continue;
+                    const int64_t pos = p.row_pos ? (int64_t)p.row_pos[p.pos0 + row] : p.pos0 + row;
+                    bf16_t* drow = (is_q ? p.dst + (int64_t)row * p.qd : p.dst_k + (int64_t)row * p.kvd) + head * p.hd;
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const int i0 = patch * 32 + t * 16 + 4 * l4;             // rotary index of register 0
+                        const float4 cs = *(const float4*)(p.rope_cos + pos * half + i0);
+                        const float4 sn = *(const float4*)(p.rope_sin + pos * half + i0);
+                        const float cv[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
+                        float lo[4], hi[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float a = acc[u][t][e], b = acc[u][t + 2][e];
+                            if (HB) { a += ba[t][e]; b += bb[t][e]; }
+                            lo[e] = (a * cv[e] - b * sv[e]) * qs;
+                            hi[e] = (b * cv[e] + a * sv[e]) * qs;
+                        }
+                        *(uint2*)(drow + i0) = pack4(lo[0], lo[1], lo[2], lo[3]);
+                        *(uint2*)(drow + half + i0) = pack4(hi[0], hi[1], hi[2], hi[3]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            if (p.bias) qk_patch(std::true_type{});
+            else qk_patch(std::false_type{});
+        } else {
+            // V patch: stored transposed, V^T[feature][position]; consecutive lanes are consecutive positions.  One
+            // address per (tile column, register) and lane; the eight row groups of the patch are fixed offsets from it.
+            const int f0 = cb - p.qd - p.kvd;
+            bf16_t* const dbase = p.dst_vt + p.pos0 + row_base + l15;
+            auto v_patch = [&](auto has_bias, auto whole) {
+                constexpr bool HB = decltype(has_bias)::value, WHOLE = decltype(whole)::value;
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int f = f0 + t * 16 + 4 * l4 + e;
-                        float v = acc[u][t][e];
-                        if (p.bias) v += bf2f(p.bias[p.qd + p.kvd + f]);
-                        dcol[(int64_t)f * p.ldv] = f2bf(v);
+                        bf16_t* const dp = dbase + (int64_t)f * p.ldv;
+                        float bv = 0.f;
+                        if (HB) bv = bf2f(p.bias[p.qd + p.kvd + f]);
+#pragma unroll
+                        for (int u = 0; u < MU; ++u) {
+                            float v = acc[u][t][e];
+                            if (HB) v += bv;
+                            if (WHOLE || row_base + u * 16 + l15 < p.M) dp[u * 16] = f2bf(v);
+                        }
                     }
-                __builtin_amdgcn_sched_barrier(0);
+            };
+            const bool whole = row_base + MU * 16 <= p.M;
+            if (p.bias) {
+                if (whole) v_patch(std::true_type{}, std::true_type{});
+                else v_patch(std::true_type{}, std::false_type{});
+            } else {
+                if (whole) v_patch(std::false_type{}, std::true_type{});
+                else v_patch(std::false_type{}, std::false_type{});
             }
         }
     } else if (EPI == EPI_RESIDUAL || EPI == EPI_PARTIAL) {
