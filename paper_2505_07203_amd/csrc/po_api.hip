@@ -493,6 +493,18 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                 pw1 = n_seg;
             }
         }
+        // bf16 path: the O-projection has no intermediate of its own (it reads the attention output, which lies in the
+        // Q buffer, and adds into the residual stream in place), so it needs no chunking to stay small; it runs over all
+        // rows in one launch.  Same bits (a row's result does not depend on the launch it is in); what it saves is the
+        // end of eight one-round launches per layer, where every tile reads its residual rows and writes its output at
+        // the same moment.
+        const bool oproj_whole = dt == PO_BF16 && !fp8 && !c->split_few_rows && pw1 - pw0 > C;
+        if (oproj_whole) {
+            PhaseTimer pt(c, PO_K_RESIDUAL);
+            unsigned char* Xa = X + (size_t)pw0 * d * esz;
+            launch_gemm_mfma(EPI_RESIDUAL, (const bf16_t*)(Q + (size_t)pw0 * qd * esz), qd, (const bf16_t*)(c->w + o.wo), qd,
+                             (bf16_t*)Xa, d, nullptr, (const bf16_t*)Xa, d, pw1 - pw0, d, qd, s);
+        }
         for (int64_t c0 = pw0; c0 < pw1; c0 += C) {
             const int64_t rows = (pw1 - c0 < C) ? pw1 - c0 : C;
             unsigned char* Xc = X + (size_t)c0 * d * esz;
@@ -538,7 +550,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
                 // only d output columns split their reduction over K so that the whole chip streams the
                 // weights; scratch = the part of the chunk buffer H that this chunk's rows leave free
                 const size_t h_bytes = (size_t)L.chunk * F * esz;
-                {
+                if (!oproj_whole) {
                     PhaseTimer pt(c, PO_K_RESIDUAL);
                     if (c->split_few_rows &&
                         launch_gemm_mfma_splitk_residual((const bf16_t*)Oc, qd, (const bf16_t*)(c->w + o.wo), qd, (bf16_t*)Xc, d,
