@@ -111,6 +111,7 @@ def main():
     ap.add_argument("--tag", default="", help="suffix of the summaries' file names, e.g. fp8 for a run with --fp8")
     ap.add_argument("--stem", default="", help="file-name stem of the summaries (default prefill_<workload>[_<tag>])")
     ap.add_argument("--trace-cmd", default="", help="the whole traced command, when it is not a --workload run of bench.py")
+    ap.add_argument("--trace-log", default="", help="stdout of the traced command: its JSON line is quoted under the table")
     ap.add_argument("--out-dir", default=os.path.join(os.path.dirname(HERE), "profiles"))
     a = ap.parse_args()
     os.makedirs(a.out_dir, exist_ok=True)
@@ -124,8 +125,8 @@ def main():
             f.write(f"rocprofv3 kernel trace summary: {trace_cmd}\n")
             f.write("command (from the repository root, on the MI355X box):\n  rocprofv3 --kernel-trace --stats "
                     f"--output-format csv -d <dir> -- {trace_cmd}\n")
-            f.write("then: python3 -m paper_2505_07203_amd.pmc_summary --trace <dir> [--stem / --tag / --trace-cmd / "
-                    "--trace-flags as above]\n")
+            f.write("then: python3 -m paper_2505_07203_amd.pmc_summary --trace <dir> [--trace-log <stdout of that run>] "
+                    "[--stem / --tag / --trace-cmd / --trace-flags as above]\n")
             f.write("(every prefill of the run is in the table, warm-up included, and the kernels of the model load; microseconds)\n\n")
             f.write(f"{'kernel':44s} {'class':16s} {'calls':>6s} {'average us':>11s} {'min us':>9s} {'max us':>9s} {'total ms':>9s} {'%':>6s}\n")
             tot = sum(c * ns for _, _, c, ns, _, _ in st)
@@ -133,6 +134,17 @@ def main():
                 f.write(f"{name[:44]:44s} {cls:16s} {calls:6d} {ns / 1e3:11.1f} {lo / 1e3:9.1f} {hi / 1e3:9.1f} "
                         f"{calls * ns / 1e6:9.2f} {100.0 * calls * ns / tot:6.2f}\n")
             f.write(f"\nsum over all kernels: {tot / 1e6:.2f} ms\n")
+            if a.trace_log:
+                # what the traced command itself printed (bench.py's JSON line), for the throughput under the profiler
+                import json
+                with open(a.trace_log) as lf:
+                    lines = [l for l in lf if l.startswith('{"metric"')]
+                if lines:
+                    d = json.loads(lines[-1])
+                    e, h = d.get("end_to_end", {}), d.get("peak_hbm_bytes", {})
+                    f.write(f"\nthe traced run's own bench line: {d['value']:.0f} {d['unit']}, {d['ms_per_step']:.1f} ms per step, "
+                            f"{e.get('frac_of_bf16_mfma_peak', float('nan')):.3f} of the nominal bf16 peak, weights "
+                            f"{h.get('weights_arena', 0) / 1e9:.2f} GB + workspace {h.get('workspace_arena', 0) / 1e9:.2f} GB\n")
         print("wrote", path)
     if a.fetch and a.write:
         fe, wr = read_counters(a.fetch), read_counters(a.write)
