@@ -1,7 +1,9 @@
 // Bandwidth-bound and fp32-path kernels of libpo (gfx950): embedding gather, RMSNorm,
-// rotary table + rotation, a plain fp32-accumulating tiled GEMM, SiLU-multiply, the
-// fp32-path attention, the last-row LM head, candidate log-probs, weight packing and the
-// V transpose used by the bf16 attention.  Templated on the storage type (float | bf16).
+// rotary table + rotation, a plain fp32-accumulating tiled GEMM, SiLU-multiply, a plain
+// attention (one thread per query row), the last-row LM head, candidate log-probs, weight
+// packing and the V transpose used by the bf16 attention.  Templated on the storage type
+// (float | bf16).  The float32 path takes the plain GEMM and attention only for shapes the
+// float32 matrix-instruction kernels (f32_mfma.hip) do not cover.
 #include "po_internal.h"
 
 namespace po {
