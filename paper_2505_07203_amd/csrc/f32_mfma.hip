@@ -1,4 +1,4 @@
-// Float32-path kernels on the float32 matrix instruction (gfx950): causal GQA attention and the plain GEMM.
+// Float32-path kernels on the float32 matrix instruction (gfx950): causal GQA attention and the GEMM.
 // Operands, products and sums are float32 throughout (v_mfma_f32_32x32x2_f32); nothing is rounded to a narrower
 // type.  The float32 path is the one that is held to 1e-4 against the float64 definition and that stands in for it
 // at configurations no CPU run reaches, so what matters here is that every output is one float32 dot product in a
@@ -20,7 +20,7 @@ __device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c) {
 // in tiles of 32 staged in LDS (K rows padded by 4 floats, V rows as they are).  Per tile a wavefront forms
 // S^T[key][query] = K Q^T with 64 (hd 128) matrix instructions, so that a lane owns ONE query column -- lane l and
 // lane l ^ 32 share it, 16 keys each -- and the online softmax needs one exchange with the partner lane per tile;
-// the rounded probabilities never leave their registers: register r of S^T is exactly the B operand of step r of
+// the probabilities never leave their registers: register r of S^T is exactly the B operand of step r of
 // O^T[hd][query] += V^T P^T when the V fragment of that step is read at the key that register r holds.
 // The contraction index of Q K^T is split between the lane halves (half h takes elements [h hd/2, (h+1) hd/2)), so
 // that a lane's K fragment is contiguous in LDS (16-byte reads).
