@@ -296,7 +296,11 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
     // rows per launch of the position-wise loops: the chunk buffers' capacity, or less where that wastes
     // fewer CU rounds (bf16 path; e.g. d = 5120 gives 20 column tiles: 12 row tiles fill 240 CUs in one
     // round where 16 would take two)
-    const int C = dt == PO_BF16 ? (int)pick_chunk_rows(L.chunk, {{d, qd}, {2 * (int64_t)F, d}, {d, F}}) : L.chunk;
+    // (the plain bf16 path runs the O-projection outside the chunk loop, see below: it does not weigh in there)
+    const bool oproj_apart = dt == PO_BF16 && !fp8 && !c->split_few_rows;
+    const int C = dt != PO_BF16 ? L.chunk
+                  : oproj_apart ? (int)pick_chunk_rows(L.chunk, {{2 * (int64_t)F, d}, {d, F}})
+                                : (int)pick_chunk_rows(L.chunk, {{d, qd}, {2 * (int64_t)F, d}, {d, F}});
     const bool packed = segs.size() > 1;
     const int64_t n_seg = (int64_t)segs.size();
     // bf16 path: the QKV epilogue hands the attention kernels Q times the softmax scale (in log2 units), applied in
@@ -498,7 +502,7 @@ po_status run_rows(po_ctx* c, const int32_t* tokens, int64_t total, const std::v
         // rows in one launch.  Same bits (a row's result does not depend on the launch it is in); what it saves is the
         // end of eight one-round launches per layer, where every tile reads its residual rows and writes its output at
         // the same moment.
-        const bool oproj_whole = dt == PO_BF16 && !fp8 && !c->split_few_rows && pw1 - pw0 > C;
+        const bool oproj_whole = oproj_apart && pw1 - pw0 > C;
         if (oproj_whole) {
             PhaseTimer pt(c, PO_K_RESIDUAL);
             unsigned char* Xa = X + (size_t)pw0 * d * esz;
