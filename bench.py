@@ -215,12 +215,14 @@ def footprint_sweep(B, I, cfg, chunk, main_ctx, main_len):
 
 
 def sample_shader_clock(run_step, n_steps=2):
-    """Shader clock (MHz) reported by rocm-smi while `run_step` keeps the GPU busy; outside the timed region.
-    -> median of the samples, or None when the tool is not there."""
+    """Shader clock (MHz, rocm-smi) and package power (W, the driver's hwmon sensor) while `run_step` keeps the GPU busy;
+    outside the timed region.  -> (median clock, {median power, power cap}), each None when its source is not there."""
     import re
     import subprocess
     import threading
-    samples, stop = [], threading.Event()
+    import glob
+    clocks, watts, stop = [], [], threading.Event()
+    hwmon = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")[:1]
 
     def poll():
         while not stop.is_set():
@@ -229,7 +231,10 @@ def sample_shader_clock(run_step, n_steps=2):
                 for line in r.stdout.splitlines():
                     m = re.search(r"sclk clock level.*\((\d+)Mhz\)", line)
                     if m:
-                        samples.append(int(m.group(1)))
+                        clocks.append(int(m.group(1)))
+                for f in hwmon:                 # (the driver's own sensor file, microwatts; rocm-smi prints no power here)
+                    with open(f) as fh:
+                        watts.append(float(fh.read().strip()) / 1e6)
             except Exception:
                 return
             time.sleep(0.15)
@@ -239,8 +244,18 @@ def sample_shader_clock(run_step, n_steps=2):
         run_step()
     stop.set()
     th.join(timeout=10)
-    busy = sorted(samples[1:]) if len(samples) > 2 else sorted(samples)
-    return busy[len(busy) // 2] if busy else None
+
+    def median_busy(v):
+        busy = sorted(v[1:]) if len(v) > 2 else sorted(v)
+        return busy[len(busy) // 2] if busy else None
+    cap = None
+    for f in glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap")[:1]:
+        try:
+            with open(f) as fh:
+                cap = float(fh.read().strip()) / 1e6
+        except Exception:
+            pass
+    return median_busy(clocks), {"during_untimed_steps": median_busy(watts), "cap": cap}
 
 
 def serve(args, cfg, w, B, I):
@@ -460,7 +475,7 @@ def main():
         torch.cuda.synchronize()
         ms_per_step_with_events = 1e3 * (time.perf_counter() - t1) / split_steps
         ctx.po_set_phase_timing(False)
-    sclk = None if args.no_clock_sample else sample_shader_clock(step)
+    sclk, watts = (None, {"during_untimed_steps": None, "cap": None}) if args.no_clock_sample else sample_shader_clock(step)
     tokens = sum(lens)
     value = tokens * args.steps / elapsed
     lin_f, att_f = flop_model(cfg, lens)
@@ -507,6 +522,7 @@ def main():
         "load_seconds": load_s,
         # the nominal MFMA peak assumes 2400 MHz; the board runs this load at its power limit, below that
         "shader_clock_mhz": {"during_untimed_steps": sclk, "nominal": 2400},
+        "board_power_w": watts,
     }
     if sum(k_ms.values()) > 0:
         # `roofline` is the kernel with the largest share of the step; the others follow
