@@ -6,12 +6,14 @@
 // What bounds it: the board's power limit.  These GEMMs keep the matrix pipe busy 64-72 % of their cycles (counters), and
 // the clock the board grants (1.6-1.9 GHz of a nominal 2.4) falls with every joule spent per flop, so the design
 // minimises energy per flop, not instruction slots:
-//  * v_mfma_f32_16x16x32_bf16.  A bare loop of it on random operands sustains 2.1-2.2 PFLOP/s on this board at
-//    two wavefronts per SIMD, against 1.7-1.9 for 32x32x16 (and only 1.5 when a single wavefront per SIMD issues
-//    it), so the workgroup is eight wavefronts, two per SIMD, arranged 2 x 4 over a 256 x 256 block tile: each owns
-//    a 128-row x 64-column patch of 8 x 4 tiles (128 fp32 accumulators per lane) and reads 12 fragments per 32
-//    MFMAs.  The second wavefront of a SIMD also fills the issue gaps of the first, so memory instructions simply
-//    sit one behind each MFMA.
+//  * v_mfma_f32_16x16x32_bf16.  A bare loop of it on random operands sustains 2.1-2.2 PFLOP/s on this board, against
+//    1.9 for 32x32x16 (both power-limited, with one wavefront per SIMD as with two).  The workgroup is eight
+//    wavefronts, two per SIMD, arranged 2 x 4 over a 256 x 256 block tile: each owns a 128-row x 64-column patch of
+//    8 x 4 tiles (128 fp32 accumulators per lane) and reads 12 fragments per 32 MFMAs.  The second wavefront of a
+//    SIMD is there for the waits, not for the issue rate: it multiplies while the first waits for a fragment or at
+//    the hand-over barrier, and it halves the time of the epilogue.  (A four-wavefront form with 128 x 128 patches,
+//    16 fragment reads per 64 MFMAs, was built on the same ring and gives the same bits: 2-18 % slower.)  Memory
+//    instructions simply sit one behind each MFMA.
 //  * K is consumed in slices of 64, so that a row of an operand slice is one whole 128-byte cache line: eight
 //    lanes of a load fetch one line.  Operand slices go straight from global memory into LDS (buffer_load ... lds,
 //    16 bytes per lane, no staging registers; copies of this kernel that stage them through registers, with the

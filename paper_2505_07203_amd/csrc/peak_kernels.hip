@@ -13,7 +13,10 @@ namespace {
 
 // Every wavefront loads one A and one B fragment (16 bytes per lane each) from `operands` and multiplies them
 // `iters` times into independent accumulators: KIND 0 = 8 accumulators of v_mfma_f32_32x32x16_bf16, KIND 1 = 32
-// of v_mfma_f32_16x16x32_bf16 (262 144 and 524 288 flop per wavefront and iteration).
+// of v_mfma_f32_16x16x32_bf16 (262 144 and 524 288 flop per wavefront and iteration).  The MFMAs are written as
+// instructions on accumulation registers: from the builtin the compiler makes a loop that copies accumulators and
+// pads with s_nop, which a single wavefront per SIMD cannot hide (it then reads 0.61 of the pipe's rate for the
+// 16x16x32 instruction where the instruction loop reads 0.93-0.95, the same as two wavefronts per SIMD).
 template <int NT, int KIND>
 __global__ void __launch_bounds__(NT) mfma_peak_kernel(const uint4* __restrict__ operands, float* sink, int iters) {
     const size_t i = ((size_t)blockIdx.x * NT + threadIdx.x) * 2;
@@ -28,8 +31,9 @@ __global__ void __launch_bounds__(NT) mfma_peak_kernel(const uint4* __restrict__
             for (int r = 0; r < 16; ++r) c[j][r] = 0.f;
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[j], 0, 0, 0);
+            for (int j = 0; j < 8; ++j) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c[j]) : "v"(a), "v"(b));
         }
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");      // (the compiler does not know the instruction's latency)
 #pragma unroll
         for (int j = 0; j < 8; ++j) s += c[j][0];
     } else {
@@ -40,8 +44,9 @@ __global__ void __launch_bounds__(NT) mfma_peak_kernel(const uint4* __restrict__
             for (int r = 0; r < 4; ++r) c[j][r] = 0.f;
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int j = 0; j < 32; ++j) c[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c[j], 0, 0, 0);
+            for (int j = 0; j < 32; ++j) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c[j]) : "v"(a), "v"(b));
         }
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
         for (int j = 0; j < 32; ++j) s += c[j][0];
     }
