@@ -12,8 +12,8 @@ BOTH, the rule of the stored fixtures, and name the same top-1 whenever the two 
 a lead of at least 5 % of the range each.  Section 4.2 of the paper claims only that chunking changes nothing, which
 the bitwise tests cover; storage precision is the model's own.
 
-These tests print progress lines past pytest's capture: each runs up to a minute, most of it weight generation on the
-host.
+These tests print progress lines past pytest's capture: the 32768- and 16384-token cases run up to a minute each, most of
+it weight generation on the host; the 131072-token case a little over two minutes (two float32 passes of a minute each).
 """
 import os
 import sys
