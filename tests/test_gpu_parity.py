@@ -164,7 +164,10 @@ def test_llama8b_width_two_layers_bf16():
 
 @pytest.mark.parametrize("dtype,M,N,K", [(I.BF16, 300, 320, 256), (I.BF16, 1000, 4096 + 64, 512), (I.BF16, 1, 64, 64),
                                           (I.BF16, 70, 128, 192), (I.BF16, 70, 192, 320), (I.BF16, 33, 64, 640),   # 3, 5, 10 slices
-                                          (I.F32, 130, 100, 72)])
+                                          (I.F32, 130, 100, 72),
+                                          # float32 matrix-instruction GEMM: several tiles and slices, ragged M / N / K, N not a
+                                          # multiple of 4 (element-wise stores), K not a multiple of 4 (the plain kernel)
+                                          (I.F32, 300, 388, 256), (I.F32, 257, 130, 100), (I.F32, 129, 90, 688), (I.F32, 65, 64, 70)])
 def test_op_linear(dtype, M, N, K):
     rng = np.random.default_rng(M + N)
     a, w, r = rand_stored(rng, (M, K), dtype), rand_stored(rng, (N, K), dtype, 0.05), rand_stored(rng, (M, N), dtype)
