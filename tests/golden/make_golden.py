@@ -53,6 +53,7 @@ CASES = {
     "llama8b_L1_N131072": ("llama8b_128k", 1, [131072], True),
     "qwen32b_L64_N1024": ("qwen32b_8x16k", None, [1024], False),
     "qwen32b_L2_N16384": ("qwen32b_8x16k", 2, [16384], False),
+    "qwen32b_L16_N16384": ("qwen32b_8x16k", 16, [16384], False),   # a quarter of the depth at a request's full length
     # a full configuration (16 requests of 256..8192 tokens)
     "llama8b_mixed16": ("llama8b_mixed16", None, None, False),
     # full depth and width in float32
